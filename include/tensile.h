@@ -1,0 +1,198 @@
+/* tensile.h - batched evaluation of GPU-memory footprint timelines over a tensor
+ * access sequence (TAS) for candidate swap/recompute plans, on one AMD MI355X.
+ *
+ * This is the data-parallel core of the plan generation of TENSILE (arXiv
+ * 2105.13336): the GPU memory peak analysis (section IV-B, Alg. 1), which the
+ * paper re-runs after every scheduled tensor, the choice of the candidate
+ * tensor among those resident at the peak (section IV-C) and the greedy loop
+ * around them (Alg. 2, Alg. 3).  All quantities are integers; results are
+ * exact.
+ *
+ * Step model.  The paper's time axis is continuous; here it is indexed by
+ * steps t in [0,T), one operator-execution slot each, in execution order
+ * (section III-A "Workload").  Tensor i is resident from the step of its
+ * tensor-generating access, alloc_step[i], through free_step[i], the step of
+ * its last tensor-using access (activity analysis, section IV-E), or
+ * alloc_step[i] if nobody reads it.  Its touch points are p_0 = alloc_step[i],
+ * p_1.. = its access steps.
+ *   MF0[t]  = base_bytes + sum_i size[i] * [alloc_step[i] <= t <= free_step[i]]      (Eq. 1, no events)
+ * A plan is a set of intervals (tensor i, out o, in r, kind): tensor i is NOT
+ * resident during steps o+1 .. r-1.  o is the last step the bytes are still
+ * there (end of the swap-out, or of the using access if later - situation 4 of
+ * section IV-B; release after an access for recomputation - situation 5); r is
+ * the step the bytes are back (the swap-in's finishing point - situation 3).
+ *   MF_b[t] = MF0[t] - sum_{(i,o,r) in plan b} size[i] * [o < t < r]                 (Eq. 1)
+ *   peak_b  = max_t MF_b[t]                                                          (Eq. 2)
+ *   argmax_b = the smallest t attaining it (Alg. 1 updates on a strict '>').
+ * An interval that cannot be applied (i outside [0,N), o < 0, r > T, r <= o)
+ * is skipped by every entry point; an endpoint at r == T is dropped.  Offsets
+ * in plan_offsets are clamped to [0, n_intervals].  Apart from that, plan
+ * semantics (interval inside one gap of its tensor, one interval per gap) are
+ * NOT checked on the fast path: the arithmetic above is applied as written and
+ * min_resident < 0 is the cheap tell-tale; tensile_validate_plans checks them.
+ *
+ * Conventions.  Every function returns TENSILE_OK (0) or a negative error
+ * code, never throws or aborts; tensile_last_error() gives a thread-local
+ * message for the last failure.  "HOST" / "DEVICE" says where a pointer must
+ * live.  Device buffers are caller-owned (any HIP allocation, e.g. a torch
+ * tensor's data_ptr()).  eval/score are asynchronous: they enqueue on the
+ * given HIP stream (hipStream_t passed as void*, NULL = the default stream) and
+ * return.  They use scratch memory owned by the TAS handle, sized on first use
+ * (that call may allocate and synchronise): calls that share a handle must be
+ * ordered on one stream or serialised by the caller.
+ */
+#ifndef TENSILE_H
+#define TENSILE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TENSILE_OK 0
+#define TENSILE_E_INVAL (-1)    /* NULL pointer, non-positive size, inconsistent arguments        */
+#define TENSILE_E_RANGE (-2)    /* an index or step outside its range in a TAS description         */
+#define TENSILE_E_NOMEM (-3)    /* host or device allocation failed                                */
+#define TENSILE_E_HIP (-4)      /* a HIP runtime call failed (message has the HIP error string)    */
+#define TENSILE_E_CAPACITY (-5) /* an output buffer of the stated capacity is too small            */
+
+/* Thread-local description of the last error on this thread ("" if none). */
+const char *tensile_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int tensile_version(void);
+
+/* ------------------------------------------------------------------ TAS */
+
+typedef struct tensile_tas tensile_tas; /* opaque; owns device copies and scratch */
+
+/* Problem statement of section III-A in structure-of-arrays form.  All
+ * pointers are HOST pointers; the arrays are copied, the caller keeps them. */
+typedef struct {
+    int32_t T, N, J;               /* steps, tensors, jobs (J >= 1)                                  */
+    const int64_t *size_bytes;     /* [N]   > 0                                                      */
+    const int32_t *alloc_step;     /* [N]   in [0,T)                                                 */
+    const int32_t *free_step;      /* [N]   == last access step, or alloc_step if no access          */
+    const int64_t *access_offsets; /* [N+1] CSR over tensors into access_steps, offsets[0] == 0      */
+    const int32_t *access_steps;   /* per tensor strictly increasing, every one > alloc_step, < T    */
+    const int32_t *job_id;         /* [N] in [0,J), or NULL (all job 0)                              */
+    const int64_t *step_ns;        /* [T] operator latency > 0, or NULL: no timing, transfers free   */
+    int64_t base_bytes;            /* initial space of the runtime libraries (section IV-B sit. 1)   */
+    int64_t link_bytes_per_us;     /* host link bandwidth (64 GB/s = 64000); > 0 if step_ns != NULL  */
+} tensile_tas_desc;
+
+/* Validates the description (E_INVAL / E_RANGE name the first violation in
+ * tensile_last_error), copies it to the current HIP device and builds there:
+ * MF0[T] (same scatter + scan kernels as plan evaluation), the cumulative
+ * latency C[T+1], the transfer times x_i = ceil(size_i*1000/link_bytes_per_us)
+ * ns, and for every gap between touch points its earliest feasible swap-out
+ * step (section IV-C: swap-out as early as possible after the previous access,
+ * swap-in as late as possible before the next one, the two must not overlap).
+ * Synchronous.  *out is NULL on failure. */
+int tensile_tas_load(const tensile_tas_desc *desc, tensile_tas **out);
+
+/* Releases the handle and everything it owns (synchronises the device). NULL is allowed. */
+void tensile_tas_free(tensile_tas *tas);
+
+/* Peak and earliest peak step of the unscheduled timeline MF0 (either output may be NULL). */
+int tensile_tas_info(const tensile_tas *tas, int64_t *unscheduled_peak, int32_t *argmax);
+
+/* Copies MF0 into a HOST buffer of T words (synchronous). */
+int tensile_tas_base_timeline(const tensile_tas *tas, int64_t *mf0_host);
+
+/* ---------------------------------------------------------------- plans */
+
+/* A batch of B plans in CSR form.  DEVICE pointers, caller-owned, read-only.
+ * Intervals of plan b are entries plan_offsets[b] .. plan_offsets[b+1]-1, in
+ * any order. */
+typedef struct {
+    int32_t B;                   /* plans, >= 0                                                     */
+    int64_t n_intervals;         /* length of the four interval arrays (host-known)                 */
+    const int64_t *plan_offsets; /* [B+1]                                                           */
+    const int32_t *iv_tensor;    /* [n_intervals] tensor index                                      */
+    const int32_t *iv_out;       /* [n_intervals] o: last resident step                             */
+    const int32_t *iv_in;        /* [n_intervals] r: step the bytes are back                        */
+    const uint8_t *iv_kind;      /* [n_intervals] 0 swap, 1 recompute; may be NULL (all swap).      *
+                                  * The kind does not change the footprint (Alg. 1 treats a release  *
+                                  * for recomputation like a swap-out).                              */
+} tensile_plans;
+
+/* Memory peak analysis of B plans at once (Eq. 1, Eq. 2, Alg. 1).
+ *   resident     DEVICE [B*T] row-major, t fastest: MF_b[t]; may be NULL (peaks only)
+ *   peak         DEVICE [B]   max_t MF_b[t]
+ *   argmax       DEVICE [B]   earliest t with MF_b[t] == peak[b]
+ *   min_resident DEVICE [B]   min_t MF_b[t]; may be NULL
+ * Asynchronous on hip_stream.  B == 0 is a no-op. */
+int tensile_eval_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *resident, int64_t *peak,
+                       int32_t *argmax, int64_t *min_resident, void *hip_stream);
+
+/* Per-tensor candidate scores for every plan (section IV-C: the candidates are
+ * the tensors resident and idle at the peak; the paper orders them by size,
+ * this returns the exact peak reduction, which is the size when the peak is
+ * isolated).  For plan b with t* = argmax[b], P = peak[b], tensor i:
+ *   1. gap g with p_g < t* < p_{g+1}; none -> 0 (not resident, or in use at t*)
+ *   2. plan b already has an applicable interval of i with p_g <= o and r <= p_{g+1} -> 0
+ *   3. o_i = min{ o >= p_g : C[o+1] - C[p_g+1] >= x_i }   (swap-out as early as possible)
+ *   4. r_i = p_{g+1}                                     (swap-in as late as possible)
+ *   5. feasible iff o_i exists, C[o_i+1] + x_i <= C[r_i] and o_i < t* < r_i; else 0
+ *   6. score = P - max( max_{t<=o_i} MF_b[t], max_{t>=r_i} MF_b[t], P - size_i )
+ *            = P - peak(plan b + (i, o_i, r_i)),  0 <= score <= size_i.
+ * Exclusive use of the link is not considered here (only transfer duration);
+ * tensile_greedy_plan places transfers on the link.
+ *   resident, peak, argmax  DEVICE, as produced by tensile_eval_plans for the same plans
+ *   score    DEVICE [B*N]
+ *   win_out  DEVICE [B*N] o_i, or -1 where steps 1, 2 or 5 reject; may be NULL
+ *   win_in   DEVICE [B*N] r_i, or -1; may be NULL
+ * Asynchronous on hip_stream. */
+int tensile_score_candidates(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident,
+                             const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
+                             int32_t *win_in, void *hip_stream);
+
+/* Slow semantic check of a batch (synchronous; copies the plans to the host).
+ * Valid means: applicable (see top), p_g <= o and r <= p_{g+1} for one gap g of
+ * the tensor (section IV-C: a swap may not overlap the tensor's own accesses;
+ * swap-in not later than the using access), and at most one interval per
+ * (plan, tensor, gap).  *first_bad (HOST) receives the index of the first
+ * offending interval or -1; *reason (HOST, may be NULL) 1 = not applicable,
+ * 2 = not inside one gap, 3 = second interval in a gap, 4 = bad plan_offsets. */
+int tensile_validate_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *first_bad, int32_t *reason);
+
+/* --------------------------------------------------------------- greedy */
+
+/* Hyper-parameters of the complete scheduling algorithm (Alg. 3). */
+typedef struct {
+    int32_t max_iters;      /* at most this many new intervals (<= 0: no limit)                      */
+    int32_t min_iters;      /* the stall rule applies only after this many iterations (paper: 100)   */
+    int32_t stop_at_budget; /* non-zero: stop as soon as peak <= budget_bytes                        */
+    const int64_t *msr_num; /* HOST [J] max swapping rate of job j = msr_num[j]/msr_den (section     *
+                             * IV-C); a tensor of job j is a candidate while                         *
+                             * swapped[j]*msr_den <= msr_num[j]*max(1, total swapped). NULL = off.   */
+    int64_t msr_den;
+} tensile_greedy_opts;
+
+/* Swap phase of Alg. 3 with the placement of Alg. 2, one interval per
+ * iteration: evaluate the current plan (tensile_eval_plans, B = 1), score the
+ * candidates (tensile_score_candidates), order them by (score desc, size desc,
+ * tensor asc), and for each in turn place the swap-out on the earliest run of
+ * consecutive free link steps after p_g whose duration covers x_i and the
+ * swap-in on the latest such run before p_{g+1} (the link carries one transfer
+ * at a time, section IV-C); accept the first candidate whose placed window
+ * (o', d+1) still has o' < t* < d+1.  Stops when no candidate is accepted, at
+ * max_iters, at capacity, at the budget if asked, or when, after min_iters
+ * iterations, the last three lowered the peak by less than 0.05 %.
+ * Synchronous; uses the default stream.
+ *   capacity    length of the four HOST interval arrays
+ *   n_initial   the first n_initial entries are an existing plan to extend (kept; their
+ *               transfers are not entered into the link timeline)
+ *   n_intervals HOST out: total number of intervals (>= n_initial)
+ *   peak_trace  HOST [capacity - n_initial + 1] or NULL: peak before each new interval, last = final
+ *   final_peak  HOST out */
+int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes, const tensile_greedy_opts *opts,
+                        int32_t capacity, int32_t n_initial, int32_t *iv_tensor, int32_t *iv_out, int32_t *iv_in,
+                        uint8_t *iv_kind, int32_t *n_intervals, int64_t *peak_trace, int64_t *final_peak);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TENSILE_H */

@@ -1,0 +1,112 @@
+// Internal declarations shared by the translation units of libtensile.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "tensile.h"
+
+namespace tensile {
+
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+int hip_fail(hipError_t e, const char *what);
+
+#define TS_HIP(call)                                               \
+    do {                                                           \
+        hipError_t e_ = (call);                                    \
+        if (e_ != hipSuccess) return ::tensile::hip_fail(e_, #call); \
+    } while (0)
+
+// Device buffer that frees itself; plain pointer semantics otherwise.
+template <typename T>
+struct DevBuf {
+    T *p = nullptr;
+    size_t n = 0;
+    DevBuf() = default;
+    DevBuf(const DevBuf &) = delete;
+    DevBuf &operator=(const DevBuf &) = delete;
+    ~DevBuf() { release(); }
+    void release() {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+        n = 0;
+    }
+    // (Re)allocate to hold at least `count` elements; contents are not kept.
+    hipError_t reserve(size_t count) {
+        if (count <= n) return hipSuccess;
+        release();
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&p), (count ? count : 1) * sizeof(T));
+        if (e == hipSuccess) n = count;
+        else p = nullptr;
+        return e;
+    }
+    hipError_t upload(const T *host, size_t count) {
+        hipError_t e = reserve(count);
+        if (e != hipSuccess || count == 0) return e;
+        return hipMemcpy(p, host, count * sizeof(T), hipMemcpyHostToDevice);
+    }
+};
+
+// Launch geometry of the evaluation kernel (see eval.hip).
+constexpr int kEvalThreads = 256;
+constexpr int kEvalTile = 4096;   // steps per LDS difference tile
+
+// Arguments of the fused scatter + scan + reduce kernel.
+struct EvalArgs {
+    int32_t T, N, B;
+    int32_t o_min;                 // smallest admissible out step (0 for plans, -1 when building MF0)
+    int64_t n_intervals;
+    const int64_t *plan_offsets;
+    const int32_t *iv_tensor, *iv_out, *iv_in;
+    const int64_t *size;           // [N]
+    const int64_t *MF0;            // [T]
+    int64_t *resident;             // [B*T] or null
+    int32_t S;                     // segments per plan
+    int32_t tiles_per_seg;
+    int64_t *out_max;              // S == 1: peak[B]; else partials [B*S]
+    int32_t *out_arg;
+    int64_t *out_min;              // may be null when S == 1
+};
+
+struct Scratch {
+    DevBuf<int64_t> part_max, part_min;
+    DevBuf<int32_t> part_arg;
+    DevBuf<int64_t> rowmax;        // score: one T-word row per resident workgroup
+    int32_t rowmax_slots = 0;
+};
+
+}  // namespace tensile
+
+// The opaque handle of the C ABI.
+struct tensile_tas {
+    int32_t T = 0, N = 0, J = 1, G = 0;
+    int device = 0;
+    bool timed = false;
+    int64_t base_bytes = 0, link_bytes_per_us = 0;
+    int64_t unscheduled_peak = 0;
+    int32_t unscheduled_argmax = 0;
+    int num_cus = 256;
+    // device copies
+    tensile::DevBuf<int64_t> d_size, d_MF0, d_C, d_x, d_touch_off;
+    tensile::DevBuf<int32_t> d_touch, d_gp, d_gq, d_gtensor, d_gwin;
+    // host copies used by the greedy driver and the validator
+    std::vector<int64_t> h_size, h_C, h_x, h_touch_off;
+    std::vector<int32_t> h_touch, h_job;
+    mutable tensile::Scratch scratch;
+};
+
+namespace tensile {
+
+// eval.hip
+int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, int32_t *argmax, int64_t *min_resident,
+                hipStream_t stream);
+// score.hip
+int launch_score(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident, const int64_t *peak,
+                 const int32_t *argmax, int64_t *score, int32_t *win_out, int32_t *win_in, hipStream_t stream);
+// tas.hip
+int build_times(tensile_tas *tas, const int64_t *d_step_ns);
+
+}  // namespace tensile

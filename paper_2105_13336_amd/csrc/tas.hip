@@ -1,0 +1,407 @@
+// TAS handle: validation of the description, device copies, and the per-TAS
+// tables every plan evaluation shares (unscheduled timeline MF0, cumulative
+// latency C, transfer times x, earliest swap-out step per gap).  Also the C-ABI
+// entry points that are thin argument checks around the kernels.
+#include "common.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <new>
+#include <unordered_set>
+
+namespace tensile {
+
+namespace {
+thread_local std::string g_last_error;
+}
+
+void set_error(const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+}
+
+int hip_fail(hipError_t e, const char *what) {
+    set_error("HIP error %d (%s) in %s", static_cast<int>(e), hipGetErrorString(e), what);
+    return e == hipErrorOutOfMemory ? TENSILE_E_NOMEM : TENSILE_E_HIP;
+}
+
+namespace {
+
+// x_i = ceil(size_i * 1000 / link_bytes_per_us) ns; 0 without timing information
+__global__ void transfer_time_kernel(int32_t N, const int64_t *size, int64_t link_bytes_per_us, int64_t *x) {
+    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    x[i] = link_bytes_per_us > 0 ? (size[i] * 1000 + link_bytes_per_us - 1) / link_bytes_per_us : 0;
+}
+
+// C[0] = 0, C[t+1] = C[t] + step_ns[t]; one workgroup, 1024 steps per iteration.
+__global__ __launch_bounds__(256) void cumulative_latency_kernel(int32_t T, const int64_t *step_ns, int64_t *C) {
+    __shared__ int64_t wave_tot[2][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int64_t carry = 0;
+    int buf = 0;
+    if (tid == 0) C[0] = 0;
+    for (int32_t t0 = 0; t0 < T; t0 += 1024) {
+        const int32_t t = t0 + tid * 4;
+        int64_t v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (t + j < T && step_ns) ? step_ns[t + j] : 0;
+#pragma unroll
+        for (int j = 1; j < 4; ++j) v[j] += v[j - 1];
+        int64_t incl = v[3];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int64_t y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        if (lane == 63) wave_tot[buf][wave] = incl;
+        __syncthreads();
+        int64_t pre = carry + incl - v[3];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const int64_t tw = wave_tot[buf][w];
+            if (w < wave) pre += tw;
+            carry += tw;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (t + j < T) C[t + j + 1] = pre + v[j];
+        buf ^= 1;
+    }
+}
+
+// Earliest feasible swap-out step of every gap (p, q) of tensor i:
+//   o = min{ o >= p : C[o+1] - C[p+1] >= x_i }, kept only if C[o+1] + x_i <= C[q]
+// (the swap-in, which ends at the start of step q, may not begin before the
+// swap-out has ended); -1 otherwise.  C is strictly increasing when timed.
+__global__ void gap_window_kernel(int32_t G, int32_t T, const int32_t *gp, const int32_t *gq, const int32_t *gtensor,
+                                  const int64_t *C, const int64_t *x, int32_t *gwin) {
+    const int32_t g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= G) return;
+    const int32_t p = gp[g], q = gq[g];
+    const int64_t xi = x[gtensor[g]];
+    const int64_t target = C[p + 1] + xi;
+    int32_t lo = p, hi = T;          // first o in [p, T) with C[o+1] >= target; T = none
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if (C[mid + 1] >= target) hi = mid;
+        else lo = mid + 1;
+    }
+    int32_t o = lo;
+    if (o >= T || C[o + 1] + xi > C[q]) o = -1;
+    gwin[g] = o;
+}
+
+__global__ void fill_kernel(int64_t n, int64_t value, int64_t *dst) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = value;
+}
+
+__global__ void lifetime_intervals_kernel(int32_t N, const int64_t *size, const int32_t *alloc, const int32_t *free_step,
+                                          int64_t *neg_size, int32_t *iv_tensor, int32_t *iv_out, int32_t *iv_in) {
+    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    neg_size[i] = -size[i];
+    iv_tensor[i] = i;
+    iv_out[i] = alloc[i] - 1;     // "absent" during alloc .. free with a negated size = present
+    iv_in[i] = free_step[i] + 1;
+}
+
+int validate_desc(const tensile_tas_desc *d) {
+    if (!d) { set_error("tas_load: desc is NULL"); return TENSILE_E_INVAL; }
+    if (d->T <= 0) { set_error("tas_load: T = %d must be positive", d->T); return TENSILE_E_INVAL; }
+    if (d->T == INT32_MAX) { set_error("tas_load: T too large"); return TENSILE_E_INVAL; }
+    if (d->N < 0) { set_error("tas_load: N = %d is negative", d->N); return TENSILE_E_INVAL; }
+    if (d->J < 1) { set_error("tas_load: J = %d must be at least 1", d->J); return TENSILE_E_INVAL; }
+    if (d->N > 0 && (!d->size_bytes || !d->alloc_step || !d->free_step || !d->access_offsets)) {
+        set_error("tas_load: a required array is NULL");
+        return TENSILE_E_INVAL;
+    }
+    if (d->base_bytes < 0) { set_error("tas_load: base_bytes is negative"); return TENSILE_E_INVAL; }
+    if (d->step_ns && d->link_bytes_per_us <= 0) {
+        set_error("tas_load: link_bytes_per_us must be positive when step_ns is given");
+        return TENSILE_E_INVAL;
+    }
+    if (d->N > 0 && d->access_offsets[0] != 0) { set_error("tas_load: access_offsets[0] != 0"); return TENSILE_E_INVAL; }
+    int64_t total = 0;    // the sum of all sizes bounds every footprint: keep it inside int64
+    for (int32_t i = 0; i < d->N; ++i) {
+        if (d->size_bytes[i] <= 0) { set_error("tas_load: size_bytes[%d] <= 0", i); return TENSILE_E_INVAL; }
+        if (d->size_bytes[i] > (INT64_MAX / 1000) - 1) { set_error("tas_load: size_bytes[%d] too large", i); return TENSILE_E_RANGE; }
+        if (__builtin_add_overflow(total, d->size_bytes[i], &total) || total > INT64_MAX - d->base_bytes) {
+            set_error("tas_load: the sizes sum past int64");
+            return TENSILE_E_RANGE;
+        }
+        const int32_t al = d->alloc_step[i], fr = d->free_step[i];
+        if (al < 0 || al >= d->T) { set_error("tas_load: alloc_step[%d] = %d outside [0,T)", i, al); return TENSILE_E_RANGE; }
+        if (fr < al || fr >= d->T) { set_error("tas_load: free_step[%d] = %d outside [alloc,T)", i, fr); return TENSILE_E_RANGE; }
+        const int64_t a0 = d->access_offsets[i], a1 = d->access_offsets[i + 1];
+        if (a1 < a0) { set_error("tas_load: access_offsets not monotone at %d", i); return TENSILE_E_INVAL; }
+        if (a1 > a0 && !d->access_steps) { set_error("tas_load: access_steps is NULL"); return TENSILE_E_INVAL; }
+        int32_t prev = al;
+        for (int64_t k = a0; k < a1; ++k) {
+            const int32_t s = d->access_steps[k];
+            if (s <= prev || s >= d->T) {
+                set_error("tas_load: access %lld of tensor %d (step %d) not after the previous touch point or >= T",
+                          static_cast<long long>(k - a0), i, s);
+                return TENSILE_E_RANGE;
+            }
+            prev = s;
+        }
+        if (prev != fr) { set_error("tas_load: free_step[%d] = %d is not the last touch point %d", i, fr, prev); return TENSILE_E_RANGE; }
+        if (d->job_id && (d->job_id[i] < 0 || d->job_id[i] >= d->J)) {
+            set_error("tas_load: job_id[%d] outside [0,J)", i);
+            return TENSILE_E_RANGE;
+        }
+    }
+    if (d->step_ns) {
+        int64_t sum = 0;
+        for (int32_t t = 0; t < d->T; ++t) {
+            if (d->step_ns[t] <= 0) { set_error("tas_load: step_ns[%d] <= 0", t); return TENSILE_E_INVAL; }
+            if (__builtin_add_overflow(sum, d->step_ns[t], &sum)) { set_error("tas_load: step_ns sums past int64"); return TENSILE_E_RANGE; }
+        }
+        if (d->N > 0 && sum > INT64_MAX / 4) { set_error("tas_load: total latency too large"); return TENSILE_E_RANGE; }
+    }
+    return TENSILE_OK;
+}
+
+int build(tensile_tas *h, const tensile_tas_desc *d) {
+    const int32_t T = d->T, N = d->N;
+    TS_HIP(hipGetDevice(&h->device));
+    hipDeviceProp_t prop;
+    TS_HIP(hipGetDeviceProperties(&prop, h->device));
+    h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    h->T = T; h->N = N; h->J = d->J;
+    h->timed = d->step_ns != nullptr;
+    h->base_bytes = d->base_bytes;
+    h->link_bytes_per_us = h->timed ? d->link_bytes_per_us : 0;
+
+    // host copies: sizes, touch points (alloc then accesses), jobs
+    h->h_size.assign(d->size_bytes, d->size_bytes + N);
+    h->h_job.assign(static_cast<size_t>(N), 0);
+    if (d->job_id) h->h_job.assign(d->job_id, d->job_id + N);
+    h->h_touch_off.resize(static_cast<size_t>(N) + 1);
+    const int64_t n_acc = N > 0 ? d->access_offsets[N] : 0;
+    h->h_touch.resize(static_cast<size_t>(n_acc + N));
+    std::vector<int32_t> gp, gq, gt;
+    for (int32_t i = 0; i < N; ++i) {
+        const int64_t a0 = d->access_offsets[i], a1 = d->access_offsets[i + 1];
+        int64_t w = a0 + i;
+        h->h_touch_off[i] = w;
+        h->h_touch[w++] = d->alloc_step[i];
+        for (int64_t k = a0; k < a1; ++k) {
+            const int32_t prev = h->h_touch[w - 1], s = d->access_steps[k];
+            if (s - prev >= 2) {          // a shorter gap has no step strictly inside
+                gp.push_back(prev);
+                gq.push_back(s);
+                gt.push_back(i);
+            }
+            h->h_touch[w++] = s;
+        }
+    }
+    h->h_touch_off[N] = n_acc + N;
+    if (gp.size() > static_cast<size_t>(INT32_MAX)) { set_error("tas_load: too many gaps"); return TENSILE_E_RANGE; }
+    h->G = static_cast<int32_t>(gp.size());
+
+    TS_HIP(h->d_size.upload(h->h_size.data(), N));
+    TS_HIP(h->d_touch_off.upload(h->h_touch_off.data(), static_cast<size_t>(N) + 1));
+    TS_HIP(h->d_touch.upload(h->h_touch.data(), h->h_touch.size()));
+    TS_HIP(h->d_gp.upload(gp.data(), gp.size()));
+    TS_HIP(h->d_gq.upload(gq.data(), gq.size()));
+    TS_HIP(h->d_gtensor.upload(gt.data(), gt.size()));
+    TS_HIP(h->d_gwin.reserve(gp.size()));
+    TS_HIP(h->d_MF0.reserve(T));
+    TS_HIP(h->d_C.reserve(static_cast<size_t>(T) + 1));
+    TS_HIP(h->d_x.reserve(N));
+
+    // ---- MF0 with the evaluation kernel: start from the constant base_bytes and
+    // "evict" every tensor with a negated size over its lifetime [alloc, free].
+    {
+        DevBuf<int64_t> base, neg, offs, peak, mn;
+        DevBuf<int32_t> alloc, fr, it, io, ir, arg;
+        TS_HIP(base.reserve(T));
+        TS_HIP(neg.reserve(N));
+        TS_HIP(alloc.upload(d->alloc_step, N));
+        TS_HIP(fr.upload(d->free_step, N));
+        TS_HIP(it.reserve(N)); TS_HIP(io.reserve(N)); TS_HIP(ir.reserve(N));
+        const int64_t h_offs[2] = {0, N};
+        TS_HIP(offs.upload(h_offs, 2));
+        TS_HIP(peak.reserve(1)); TS_HIP(mn.reserve(1)); TS_HIP(arg.reserve(1));
+        hipLaunchKernelGGL(fill_kernel, dim3((T + 255) / 256), dim3(256), 0, 0, static_cast<int64_t>(T), d->base_bytes, base.p);
+        if (N > 0)
+            hipLaunchKernelGGL(lifetime_intervals_kernel, dim3((N + 255) / 256), dim3(256), 0, 0, N, h->d_size.p, alloc.p,
+                               fr.p, neg.p, it.p, io.p, ir.p);
+        TS_HIP(hipGetLastError());
+        EvalArgs a{};
+        a.T = T; a.N = N; a.B = 1; a.o_min = -1; a.n_intervals = N;
+        a.plan_offsets = offs.p; a.iv_tensor = it.p; a.iv_out = io.p; a.iv_in = ir.p;
+        a.size = neg.p; a.MF0 = base.p; a.resident = h->d_MF0.p;
+        int rc = launch_eval(h, a, peak.p, arg.p, mn.p, nullptr);
+        if (rc != TENSILE_OK) return rc;
+        TS_HIP(hipMemcpy(&h->unscheduled_peak, peak.p, sizeof(int64_t), hipMemcpyDeviceToHost));
+        TS_HIP(hipMemcpy(&h->unscheduled_argmax, arg.p, sizeof(int32_t), hipMemcpyDeviceToHost));
+    }
+
+    // ---- C, x, per-gap windows
+    {
+        DevBuf<int64_t> step;
+        if (h->timed) TS_HIP(step.upload(d->step_ns, T));
+        hipLaunchKernelGGL(cumulative_latency_kernel, dim3(1), dim3(256), 0, 0, T, h->timed ? step.p : nullptr, h->d_C.p);
+        if (N > 0)
+            hipLaunchKernelGGL(transfer_time_kernel, dim3((N + 255) / 256), dim3(256), 0, 0, N, h->d_size.p,
+                               h->link_bytes_per_us, h->d_x.p);
+        if (h->G > 0)
+            hipLaunchKernelGGL(gap_window_kernel, dim3((h->G + 255) / 256), dim3(256), 0, 0, h->G, T, h->d_gp.p, h->d_gq.p,
+                               h->d_gtensor.p, h->d_C.p, h->d_x.p, h->d_gwin.p);
+        TS_HIP(hipGetLastError());
+        TS_HIP(hipDeviceSynchronize());
+    }
+    h->h_C.resize(static_cast<size_t>(T) + 1);
+    h->h_x.resize(static_cast<size_t>(N));
+    TS_HIP(hipMemcpy(h->h_C.data(), h->d_C.p, (static_cast<size_t>(T) + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (N > 0) TS_HIP(hipMemcpy(h->h_x.data(), h->d_x.p, static_cast<size_t>(N) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    return TENSILE_OK;
+}
+
+int check_plans(const tensile_tas *tas, const tensile_plans *plans, const char *who) {
+    if (!tas || !plans) { set_error("%s: NULL handle or plans", who); return TENSILE_E_INVAL; }
+    if (plans->B < 0 || plans->n_intervals < 0) { set_error("%s: negative B or n_intervals", who); return TENSILE_E_INVAL; }
+    if (plans->B > 0 && !plans->plan_offsets) { set_error("%s: plan_offsets is NULL", who); return TENSILE_E_INVAL; }
+    if (plans->n_intervals > 0 && (!plans->iv_tensor || !plans->iv_out || !plans->iv_in)) {
+        set_error("%s: an interval array is NULL", who);
+        return TENSILE_E_INVAL;
+    }
+    return TENSILE_OK;
+}
+
+}  // namespace
+}  // namespace tensile
+
+using namespace tensile;
+
+extern "C" {
+
+const char *tensile_last_error(void) { return g_last_error.c_str(); }
+
+int tensile_version(void) { return 100; }
+
+int tensile_tas_load(const tensile_tas_desc *desc, tensile_tas **out) {
+    if (!out) { set_error("tas_load: out is NULL"); return TENSILE_E_INVAL; }
+    *out = nullptr;
+    int rc = validate_desc(desc);
+    if (rc != TENSILE_OK) return rc;
+    tensile_tas *h = new (std::nothrow) tensile_tas();
+    if (!h) { set_error("tas_load: out of host memory"); return TENSILE_E_NOMEM; }
+    try {
+        rc = build(h, desc);
+    } catch (const std::bad_alloc &) {
+        set_error("tas_load: out of host memory");
+        rc = TENSILE_E_NOMEM;
+    }
+    if (rc != TENSILE_OK) {
+        delete h;
+        return rc;
+    }
+    *out = h;
+    return TENSILE_OK;
+}
+
+void tensile_tas_free(tensile_tas *tas) {
+    if (!tas) return;
+    (void)hipDeviceSynchronize();
+    delete tas;
+}
+
+int tensile_tas_info(const tensile_tas *tas, int64_t *unscheduled_peak, int32_t *argmax) {
+    if (!tas) { set_error("tas_info: NULL handle"); return TENSILE_E_INVAL; }
+    if (unscheduled_peak) *unscheduled_peak = tas->unscheduled_peak;
+    if (argmax) *argmax = tas->unscheduled_argmax;
+    return TENSILE_OK;
+}
+
+int tensile_tas_base_timeline(const tensile_tas *tas, int64_t *mf0_host) {
+    if (!tas || !mf0_host) { set_error("tas_base_timeline: NULL argument"); return TENSILE_E_INVAL; }
+    TS_HIP(hipMemcpy(mf0_host, tas->d_MF0.p, static_cast<size_t>(tas->T) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    return TENSILE_OK;
+}
+
+int tensile_eval_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *resident, int64_t *peak,
+                       int32_t *argmax, int64_t *min_resident, void *hip_stream) {
+    int rc = check_plans(tas, plans, "eval_plans");
+    if (rc != TENSILE_OK) return rc;
+    if (plans->B == 0) return TENSILE_OK;
+    if (!peak || !argmax) { set_error("eval_plans: peak and argmax are required"); return TENSILE_E_INVAL; }
+    EvalArgs a{};
+    a.T = tas->T; a.N = tas->N; a.B = plans->B; a.o_min = 0; a.n_intervals = plans->n_intervals;
+    a.plan_offsets = plans->plan_offsets;
+    a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;
+    a.size = tas->d_size.p; a.MF0 = tas->d_MF0.p; a.resident = resident;
+    return launch_eval(tas, a, peak, argmax, min_resident, static_cast<hipStream_t>(hip_stream));
+}
+
+int tensile_score_candidates(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident,
+                             const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
+                             int32_t *win_in, void *hip_stream) {
+    int rc = check_plans(tas, plans, "score_candidates");
+    if (rc != TENSILE_OK) return rc;
+    if (plans->B == 0) return TENSILE_OK;
+    if (!resident || !peak || !argmax || !score) {
+        set_error("score_candidates: resident, peak, argmax and score are required");
+        return TENSILE_E_INVAL;
+    }
+    return launch_score(tas, plans, resident, peak, argmax, score, win_out, win_in, static_cast<hipStream_t>(hip_stream));
+}
+
+int tensile_validate_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *first_bad, int32_t *reason) {
+    int rc = check_plans(tas, plans, "validate_plans");
+    if (rc != TENSILE_OK) return rc;
+    if (!first_bad) { set_error("validate_plans: first_bad is NULL"); return TENSILE_E_INVAL; }
+    *first_bad = -1;
+    if (reason) *reason = 0;
+    const int32_t B = plans->B;
+    const int64_t K = plans->n_intervals;
+    try {
+        std::vector<int64_t> offs(static_cast<size_t>(B) + 1);
+        std::vector<int32_t> it(K), io(K), ir(K);
+        if (B > 0) TS_HIP(hipMemcpy(offs.data(), plans->plan_offsets, offs.size() * 8, hipMemcpyDeviceToHost));
+        if (K > 0) {
+            TS_HIP(hipMemcpy(it.data(), plans->iv_tensor, K * 4, hipMemcpyDeviceToHost));
+            TS_HIP(hipMemcpy(io.data(), plans->iv_out, K * 4, hipMemcpyDeviceToHost));
+            TS_HIP(hipMemcpy(ir.data(), plans->iv_in, K * 4, hipMemcpyDeviceToHost));
+        }
+        auto fail = [&](int64_t k, int32_t why) {
+            *first_bad = k;
+            if (reason) *reason = why;
+            return TENSILE_OK;
+        };
+        std::unordered_set<int64_t> used;
+        for (int32_t b = 0; b < B; ++b) {
+            if (offs[b] < 0 || offs[b + 1] < offs[b] || offs[b + 1] > K) return fail(offs[b] < 0 ? 0 : offs[b], 4);
+            used.clear();
+            for (int64_t k = offs[b]; k < offs[b + 1]; ++k) {
+                const int32_t i = it[k], o = io[k], r = ir[k];
+                if (i < 0 || i >= tas->N || o < 0 || r > tas->T || r <= o) return fail(k, 1);
+                // gap with p_g <= o < p_{g+1}
+                const int32_t *tp = tas->h_touch.data();
+                int64_t lo = tas->h_touch_off[i], hi = tas->h_touch_off[i + 1];
+                const int64_t first = lo, last = hi;
+                while (lo < hi) {
+                    const int64_t mid = (lo + hi) >> 1;
+                    if (tp[mid] <= o) lo = mid + 1;
+                    else hi = mid;
+                }
+                if (lo == first || lo == last || r > tp[lo]) return fail(k, 2);
+                if (!used.insert(lo).second) return fail(k, 3);
+            }
+        }
+    } catch (const std::bad_alloc &) {
+        set_error("validate_plans: out of host memory");
+        return TENSILE_E_NOMEM;
+    }
+    return TENSILE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,373 @@
+"""HIP path vs the CPU oracle, bit-exact (all quantities are integers), through
+the C ABI.  Small cases compare every element; the full-size configurations run
+in the launch configuration the benchmark times and compare sampled plans row
+by row plus the per-plan reductions."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("needs a GPU", allow_module_level=True)
+
+import paper_2105_13336_amd as P  # noqa: E402
+from oracle import oracle as O  # noqa: E402
+from workloads import (CONFIGS, make_config_plans, make_plans, make_tas, plans_from_lists, small_random_tas,  # noqa: E402
+                       tas_from_lists)
+from workloads.plans import Plans  # noqa: E402
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def upload(pl: Plans) -> P.DevicePlans:
+    return P.DevicePlans.from_numpy(pl.plan_offsets, pl.iv_tensor, pl.iv_out, pl.iv_in, pl.iv_kind)
+
+
+def gpu_eval(h, dp, want_resident=True, want_min=True):
+    B = dp.B
+    res = torch.empty((B, h.T), dtype=torch.int64, device="cuda") if want_resident else None
+    peak = torch.empty(B, dtype=torch.int64, device="cuda")
+    arg = torch.empty(B, dtype=torch.int32, device="cuda")
+    mn = torch.empty(B, dtype=torch.int64, device="cuda") if want_min else None
+    P.tensile_eval_plans(h, dp, res, peak, arg, mn)
+    torch.cuda.synchronize()
+    return res, peak, arg, mn
+
+
+def gpu_score(h, dp, res, peak, arg):
+    B, N = dp.B, h.N
+    sc = torch.empty((B, N), dtype=torch.int64, device="cuda")
+    wo = torch.empty((B, N), dtype=torch.int32, device="cuda")
+    wi = torch.empty((B, N), dtype=torch.int32, device="cuda")
+    P.tensile_score_candidates(h, dp, res, peak, arg, sc, wo, wi)
+    torch.cuda.synchronize()
+    return sc, wo, wi
+
+
+def check_eval(tas, pl, h=None, rows=None, label=""):
+    """Full comparison of the batch ``pl`` (or of the plan rows ``rows`` of it)."""
+    own = h is None
+    h = h or P.tas_load(tas)
+    res, peak, arg, mn = gpu_eval(h, upload(pl))
+    sel = pl if rows is None else pl.select(rows)
+    r0, p0, a0, m0 = O.eval_plans(tas, sel)
+    idx = slice(None) if rows is None else torch.as_tensor(np.asarray(rows), device="cuda")
+    assert np.array_equal(peak[idx].cpu().numpy(), p0), label + " peak"
+    assert np.array_equal(arg[idx].cpu().numpy(), a0), label + " argmax"
+    assert np.array_equal(mn[idx].cpu().numpy(), m0), label + " min"
+    assert np.array_equal(res[idx].cpu().numpy(), r0), label + " resident"
+    if own:
+        h.close()
+    return res, peak, arg, mn
+
+
+# ------------------------------------------------------------------ tas_load
+
+@pytest.mark.parametrize("idx", [0, 1, 2])
+def test_tas_load_tables(idx, configs_small):
+    tas = configs_small[idx]
+    say(f"tas_load config {idx}")
+    h = P.tas_load(tas)
+    MF0 = O.base_timeline(tas)
+    assert np.array_equal(P.tensile_tas_base_timeline(h), MF0)
+    assert P.tensile_tas_info(h) == (int(MF0.max()), int(np.argmax(MF0)))
+    h.close()
+
+
+def test_tas_load_base_bytes_and_many_tiles():
+    tas = small_random_tas(11, N=300, T=20011, max_acc=3, base_bytes=12345)
+    say("tas_load T=20011")
+    h = P.tas_load(tas)
+    assert np.array_equal(P.tensile_tas_base_timeline(h), O.base_timeline(tas))
+    h.close()
+
+
+# ---------------------------------------------------------------------- eval
+
+@pytest.mark.parametrize("idx,B", [(0, None), (1, 512), (2, 96)])
+def test_eval_elementwise(idx, B, configs_small):
+    tas = configs_small[idx]
+    pl = make_config_plans(idx, tas, B=B)
+    say(f"eval config {idx} B={pl.B} K={pl.n_intervals}")
+    check_eval(tas, pl, label=f"c{idx}")
+
+
+@pytest.mark.parametrize("T,B,segs", [(1, 3, 0), (2, 2, 0), (7, 5, 0), (4095, 4, 0), (4096, 4, 0), (4097, 4, 0),
+                                      (12289, 9, 0), (12291, 2, 0), (20011, 3, 3), (20011, 17, 2), (50001, 2, 0)])
+def test_eval_shapes_and_segments(T, B, segs, monkeypatch):
+    """Odd and even T (8- and 16-byte stores), ragged tails, one tile, tile edges, several
+    tiles per segment and several segments per plan (finalize kernel)."""
+    if segs:
+        monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", str(segs))
+    N = max(1, min(400, T // 2))
+    tas = small_random_tas(1000 + T, N=N, T=T, max_acc=4 if T > 8 else 1, base_bytes=7)
+    pl = make_plans(tas, B, 5, p_swap=0.7)
+    say(f"eval T={T} B={B} segs={segs} K={pl.n_intervals}")
+    check_eval(tas, pl, label=f"T={T}")
+
+
+def test_eval_optional_outputs_and_empty_batches(configs_small):
+    tas = configs_small[1]
+    h = P.tas_load(tas)
+    pl = make_config_plans(1, tas, B=16)
+    dp = upload(pl)
+    say("eval optional outputs")
+    _, p0, a0, m0 = O.eval_plans(tas, pl, want_resident=False)
+    res, peak, arg, mn = gpu_eval(h, dp, want_resident=False, want_min=False)
+    assert res is None and mn is None
+    assert np.array_equal(peak.cpu().numpy(), p0) and np.array_equal(arg.cpu().numpy(), a0)
+    # B == 0: nothing happens
+    empty = upload(plans_from_lists([]))
+    P.tensile_eval_plans(h, empty, None, peak, arg, None)
+    # plans without any interval
+    none = upload(plans_from_lists([[], [], []]))
+    res, peak, arg, mn = gpu_eval(h, none)
+    MF0 = O.base_timeline(tas)
+    assert np.array_equal(res.cpu().numpy(), np.tile(MF0, (3, 1)))
+    assert peak.tolist() == [int(MF0.max())] * 3 and arg.tolist() == [int(np.argmax(MF0))] * 3
+    h.close()
+
+
+def test_eval_inapplicable_intervals_and_clamped_offsets():
+    tas = tas_from_lists(8, [5, 7], [0, 1], [[6], [7]])
+    good = [(0, 1, 5, 0)]
+    bad = [(2, 1, 5, 0), (-1, 1, 5, 0), (0, -1, 5, 0), (0, 1, 9, 0), (0, 5, 5, 0), (0, 5, 3, 0), (1, 3, 8, 0), (0, 2, 3, 0)]
+    pl = plans_from_lists([good, good + bad, bad])
+    say("eval inapplicable intervals")
+    check_eval(tas, pl)
+    pl2 = plans_from_lists([good, good])
+    pl2 = Plans(2, np.array([-5, 1, 99], dtype=np.int64), pl2.iv_tensor, pl2.iv_out, pl2.iv_in, pl2.iv_kind)
+    check_eval(tas, pl2)
+
+
+def test_eval_order_invariance(configs_small):
+    """Permuting the intervals of a plan changes nothing (the scatter uses atomics)."""
+    tas = configs_small[1]
+    pl = make_config_plans(1, tas, B=1)
+    t, o, r, k = pl.plan(0)
+    rng = np.random.default_rng(3)
+    plans = []
+    for _ in range(6):
+        perm = rng.permutation(len(t))
+        plans.append(list(zip(t[perm].tolist(), o[perm].tolist(), r[perm].tolist())))
+    say("eval order invariance")
+    res, peak, arg, mn = check_eval(tas, plans_from_lists(plans))
+    assert torch.equal(res[0], res[5]) and len(set(peak.tolist())) == 1
+
+
+def test_eval_heavy_collisions():
+    """Many intervals sharing the same endpoints (LDS atomic contention) and giant sizes."""
+    N, T = 3000, 5000
+    tas = tas_from_lists(T, [(1 << 31) - (i % 7) for i in range(N)], [0] * N, [[T - 1]] * N)
+    ivs = [(i, 10 + (i % 3), 4000 + (i % 2)) for i in range(N)]
+    say("eval collisions")
+    check_eval(tas, plans_from_lists([ivs, ivs[:1500], []]))
+
+
+# --------------------------------------------------------------------- score
+
+def check_score(tas, pl, rows=None, h=None, label=""):
+    own = h is None
+    h = h or P.tas_load(tas)
+    dp = upload(pl)
+    res, peak, arg, mn = gpu_eval(h, dp)
+    sc, wo, wi = gpu_score(h, dp, res, peak, arg)
+    rows = list(range(pl.B)) if rows is None else list(rows)
+    r0, p0, a0, m0 = O.eval_plans(tas, pl.select(rows))
+    s0, o0, i0 = O.score_plans(tas, pl.select(rows), r0, p0, a0)
+    idx = torch.as_tensor(np.asarray(rows), device="cuda")
+    assert np.array_equal(sc[idx].cpu().numpy(), s0), label + " score"
+    assert np.array_equal(wo[idx].cpu().numpy(), o0), label + " win_out"
+    assert np.array_equal(wi[idx].cpu().numpy(), i0), label + " win_in"
+    if own:
+        h.close()
+    return int((o0 >= 0).sum())
+
+
+@pytest.mark.parametrize("idx,B,rows", [(0, None, None), (1, 300, range(0, 300, 7)), (2, 40, range(0, 40, 5))])
+def test_score_configs(idx, B, rows, configs_small):
+    tas = configs_small[idx]
+    pl = make_config_plans(idx, tas, B=B)
+    say(f"score config {idx} B={pl.B}")
+    assert check_score(tas, pl, rows, label=f"c{idx}") > 10
+
+
+@pytest.mark.parametrize("seed,timed,T", [(1, True, 60), (2, False, 60), (3, True, 3000), (4, True, 9001)])
+def test_score_random(seed, timed, T):
+    tas = small_random_tas(200 + seed, N=min(500, T // 2), T=T, max_acc=5, timed=timed, link_bytes_per_us=400_000)
+    pl = make_plans(tas, 24, seed, p_swap=0.25)
+    say(f"score random seed={seed} T={T}")
+    assert check_score(tas, pl) > 0
+
+
+def test_score_optional_windows_and_blocking():
+    tas = tas_from_lists(10, [10, 3], [0, 6], [[4, 9], [7]])
+    pl = plans_from_lists([[], [(0, 1, 3)], [(0, 7, 9)], [(0, 4, 9)], [(5, 1, 2), (0, -3, 2)]])
+    say("score blocking")
+    check_score(tas, pl)
+    h = P.tas_load(tas)
+    dp = upload(pl)
+    res, peak, arg, mn = gpu_eval(h, dp)
+    sc = torch.empty((pl.B, 2), dtype=torch.int64, device="cuda")
+    P.tensile_score_candidates(h, dp, res, peak, arg, sc, None, None)
+    torch.cuda.synchronize()
+    assert sc.tolist() == [[3, 0], [3, 0], [0, 0], [0, 0], [3, 0]]
+    h.close()
+
+
+# -------------------------------------------------------------------- greedy
+
+def same_greedy(g, o):
+    for f in ("iv_tensor", "iv_out", "iv_in", "iv_kind", "peak_trace"):
+        assert np.array_equal(g[f], o[f]), f
+    assert g["final_peak"] == o["final_peak"]
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_greedy_matches_oracle(idx, configs_small):
+    tas = configs_small[idx]
+    say(f"greedy config {idx}")
+    h = P.tas_load(tas)
+    o = O.greedy(tas, 0)
+    g = P.tensile_greedy_plan(h, 0, capacity=len(o["iv_tensor"]) + 8)
+    same_greedy(g, o)
+    # the emitted plan passes the semantic validator
+    dp = P.DevicePlans.from_numpy(np.array([0, len(g["iv_tensor"])]), g["iv_tensor"], g["iv_out"], g["iv_in"], g["iv_kind"])
+    assert P.tensile_validate_plans(h, dp) == (-1, 0)
+    h.close()
+
+
+def test_greedy_options(configs_small):
+    tas = configs_small[1]
+    h = P.tas_load(tas)
+    say("greedy options")
+    same_greedy(P.tensile_greedy_plan(h, 0, max_iters=7, capacity=64), O.greedy(tas, 0, max_iters=7))
+    budget = int(P.tensile_tas_info(h)[0] * 60 // 100)
+    same_greedy(P.tensile_greedy_plan(h, budget, stop_at_budget=True, capacity=4096),
+                O.greedy(tas, budget, stop_at_budget=True))
+    same_greedy(P.tensile_greedy_plan(h, 0, min_iters=0, capacity=4096), O.greedy(tas, 0, min_iters=0))
+    # capacity reached
+    g = P.tensile_greedy_plan(h, 0, capacity=5)
+    assert len(g["iv_tensor"]) == 5
+    # extend an existing plan
+    first = O.greedy(tas, 0, max_iters=4)
+    init = (first["iv_tensor"], first["iv_out"], first["iv_in"], first["iv_kind"])
+    same_greedy(P.tensile_greedy_plan(h, 0, max_iters=6, capacity=64, initial=init),
+                O.greedy(tas, 0, max_iters=6, initial=init))
+    h.close()
+
+
+def test_greedy_rate_limit_and_link():
+    tas = tas_from_lists(8, [50, 40, 100, 30], [1, 2, 4, 2], [[7], [6], [5], [6]], jobs=[0, 1, 0, 1])
+    tas.J = 2
+    h = P.tas_load(tas)
+    say("greedy rate limit")
+    for num, den in (([1, 0], 1), ([1, 1], 2)):
+        same_greedy(P.tensile_greedy_plan(h, 0, msr_num=num, msr_den=den, capacity=16),
+                    O.greedy(tas, 0, msr_num=np.array(num), msr_den=den))
+    h.close()
+    tas = tas_from_lists(12, [20, 20, 100], [0, 0, 5], [[11], [11], [6]], step_ns=[10] * 12, link_bytes_per_us=1000)
+    h = P.tas_load(tas)
+    g = P.tensile_greedy_plan(h, 0, capacity=16)
+    same_greedy(g, O.greedy(tas, 0))
+    assert list(zip(g["iv_tensor"].tolist(), g["iv_out"].tolist(), g["iv_in"].tolist())) == [(0, 2, 11), (1, 4, 9)]
+    h.close()
+
+
+def test_greedy_random_timed():
+    for seed in range(4):
+        tas = small_random_tas(500 + seed, N=120, T=400, max_acc=5, timed=True, link_bytes_per_us=300_000)
+        say(f"greedy random {seed}")
+        h = P.tas_load(tas)
+        same_greedy(P.tensile_greedy_plan(h, 0, capacity=2048), O.greedy(tas, 0))
+        h.close()
+
+
+# ------------------------------------------------------------------ validate
+
+def test_validate_plans(configs_small):
+    tas = configs_small[1]
+    h = P.tas_load(tas)
+    pl = make_config_plans(1, tas, B=8)
+    say("validate")
+    assert P.tensile_validate_plans(h, upload(pl)) == (-1, 0)
+    k = int(pl.plan_offsets[3]) + 2
+    bad = Plans(pl.B, pl.plan_offsets, pl.iv_tensor.copy(), pl.iv_out.copy(), pl.iv_in.copy(), pl.iv_kind)
+    bad.iv_in[k] = bad.iv_out[k]                    # empty or reversed window
+    assert P.tensile_validate_plans(h, upload(bad)) == (k, 1)
+    bad.iv_in[k] = tas.T                            # reaches past the next access
+    assert P.tensile_validate_plans(h, upload(bad)) == (k, 2)
+    dup = Plans(pl.B, pl.plan_offsets, pl.iv_tensor.copy(), pl.iv_out.copy(), pl.iv_in.copy(), pl.iv_kind)
+    dup.iv_tensor[k], dup.iv_out[k], dup.iv_in[k] = dup.iv_tensor[k - 1], dup.iv_out[k - 1], dup.iv_in[k - 1]
+    assert P.tensile_validate_plans(h, upload(dup)) == (k, 3)
+    h.close()
+
+
+def test_argument_errors(configs_small):
+    tas = configs_small[0]
+    h = P.tas_load(tas)
+    dp = upload(make_config_plans(0, tas, B=4))
+    peak = torch.empty(4, dtype=torch.int64, device="cuda")
+    arg = torch.empty(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(P.TensileError):
+        P.tensile_eval_plans(h, dp, None, peak.cpu(), arg)                  # host tensor
+    with pytest.raises(P.TensileError):
+        P.tensile_eval_plans(h, dp, None, peak[:2], arg)                    # too short
+    with pytest.raises(P.TensileError):
+        P.tensile_eval_plans(h, dp, None, None, arg)                        # required output missing
+    h.close()
+    with pytest.raises(P.TensileError):
+        P.tensile_tas_info(h)                                               # freed handle
+
+
+# ------------------------------------------------- full-size configurations
+
+@pytest.mark.parametrize("idx,n_rows,n_score", [(1, 256, 24), (2, 128, 8), (3, 96, 4), (4, 6, 2)])
+def test_full_size_config(idx, n_rows, n_score):
+    """Whole batch on the GPU in the benchmark's launch configuration; the oracle recomputes
+    sampled plans one by one (rows spread over the batch, including the first and the last)."""
+    cfg = CONFIGS[idx]
+    say(f"full-size config {idx}: building TAS and {cfg.B} plans")
+    tas = make_tas(idx)
+    pl = make_config_plans(idx, tas)
+    say(f"  N={tas.N} T={tas.T} K={pl.n_intervals}; uploading")
+    h = P.tas_load(tas)
+    dp = upload(pl)
+    res, peak, arg, mn = gpu_eval(h, dp)
+    say("  eval done; comparing sampled rows")
+    rows = np.unique(np.linspace(0, cfg.B - 1, n_rows).astype(np.int64))
+    sel = pl.select(rows)
+    r0, p0, a0, m0 = O.eval_plans(tas, sel)
+    idxs = torch.as_tensor(rows, device="cuda")
+    assert np.array_equal(peak[idxs].cpu().numpy(), p0) and np.array_equal(arg[idxs].cpu().numpy(), a0)
+    assert np.array_equal(mn[idxs].cpu().numpy(), m0)
+    assert np.array_equal(res[idxs].cpu().numpy(), r0)
+    # properties that hold for every plan of the batch
+    assert torch.equal(res.max(dim=1).values, peak) and torch.equal(res.min(dim=1).values, mn)
+    first_max = (res == peak[:, None]).to(torch.int8).argmax(dim=1).to(torch.int32)
+    assert torch.equal(first_max, arg)
+    MF0 = torch.from_numpy(O.base_timeline(tas)).cuda()
+    assert bool((res <= MF0[None, :]).all()) and bool((mn >= 0).all()) and bool((res[:, -1] == MF0[-1]).all())
+    del first_max
+    say("  scoring the whole batch")
+    sc = torch.empty((cfg.B, tas.N), dtype=torch.int64, device="cuda")
+    wo = torch.empty((cfg.B, tas.N), dtype=torch.int32, device="cuda")
+    wi = torch.empty((cfg.B, tas.N), dtype=torch.int32, device="cuda")
+    P.tensile_score_candidates(h, dp, res, peak, arg, sc, wo, wi)
+    torch.cuda.synchronize()
+    srows = rows[:: max(1, len(rows) // n_score)][:n_score]
+    pos = [int(np.searchsorted(rows, r)) for r in srows]
+    s0, o0, i0 = O.score_plans(tas, sel, r0, p0, a0, rows=pos)
+    sidx = torch.as_tensor(srows, device="cuda")
+    assert np.array_equal(sc[sidx].cpu().numpy(), s0) and np.array_equal(wo[sidx].cpu().numpy(), o0)
+    assert np.array_equal(wi[sidx].cpu().numpy(), i0)
+    size = torch.from_numpy(tas.size_bytes).cuda()
+    assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
+    h.close()
