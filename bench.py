@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched plan evaluator on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic plans:
+``tensile_eval_plans`` (difference-array scatter, prefix scan, max/argmax/min,
+footprint rows written) followed by ``tensile_score_candidates`` on the same
+batch, inputs already resident in HBM.  The workload is configuration 3 (four
+jobs merged on one timeline, 16,384 plans), the one the bandwidth target is
+stated for.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
+    ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-planner leg")
+    ap.add_argument("--eval-only", action="store_true", help="steps run tensile_eval_plans alone (profiling aid)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build evaluates plans on ONE GPU (plans are independent; no multi-GPU path is built); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2105_13336_amd as P
+    from workloads import CONFIGS, make_config_plans, make_tas, plans_hash, tas_hash
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[args.config]
+    t0 = time.time()
+    tas = make_tas(args.config)
+    pl = make_config_plans(args.config, tas)
+    B, T, N, K = pl.B, tas.T, tas.N, pl.n_intervals
+    log(f"{cfg.name}: B={B} T={T} N={N} intervals={K} tas_hash={tas_hash(tas):016x} plans_hash={plans_hash(pl):016x} "
+        f"(generated in {time.time() - t0:.1f}s)")
+
+    h = P.tas_load(tas)
+    dp = P.DevicePlans.from_numpy(pl.plan_offsets, pl.iv_tensor, pl.iv_out, pl.iv_in, pl.iv_kind)
+    res = torch.empty((B, T), dtype=torch.int64, device="cuda")
+    peak = torch.empty(B, dtype=torch.int64, device="cuda")
+    arg = torch.empty(B, dtype=torch.int32, device="cuda")
+    mn = torch.empty(B, dtype=torch.int64, device="cuda")
+    sc = torch.empty((B, N), dtype=torch.int64, device="cuda")
+    wo = torch.empty((B, N), dtype=torch.int32, device="cuda")
+    wi = torch.empty((B, N), dtype=torch.int32, device="cuda")
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        P.tensile_eval_plans(h, dp, res, peak, arg, mn)
+        if events is not None:
+            events[1].record()
+        if not args.eval_only:
+            P.tensile_score_candidates(h, dp, res, peak, arg, sc, wo, wi)
+            if events is not None:
+                events[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    ms_per_step = (t_end - t_start) * 1e3 / args.steps
+    eval_ms = [e[0].elapsed_time(e[1]) for e in evs]
+    score_ms = [e[1].elapsed_time(e[2]) for e in evs] if not args.eval_only else [0.0]
+    eval_avg, score_avg = float(np.mean(eval_ms)), float(np.mean(score_ms))
+    plan_timesteps = float(B) * float(T)
+    value = plan_timesteps / (ms_per_step * 1e-3)
+
+    # algorithmic bytes of one eval launch: footprint rows out, intervals in (tensor, out, in: 12 B each;
+    # the kind byte does not enter the footprint), offsets in, per-plan results out, MF0 and sizes once
+    eval_bytes = 8.0 * B * T + 12.0 * K + 8.0 * (B + 1) + 20.0 * B + 8.0 * T + 8.0 * N
+    achieved = eval_bytes / (eval_avg * 1e-3) / 1e9
+    # scoring: footprint rows in, scores and windows out, intervals in
+    score_bytes = 8.0 * B * T + 16.0 * B * N + 12.0 * K + 12.0 * B
+
+    out = {
+        "metric": "plan-timesteps evaluated/sec (eval_plans + score_candidates per step) and % of peak HBM GB/s",
+        "value": value, "unit": "plan-timesteps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {cfg.name}", "B": B, "T": T, "N": N, "intervals": K,
+                   "step": "eval_plans" if args.eval_only else "eval_plans+score_candidates"},
+        "roofline": {"kernel": "eval_kernel (tensile_eval_plans)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": eval_bytes, "avg_launch_ms": eval_avg},
+        "rows": {
+            "eval_plans": {"ms": eval_avg, "ms_min": float(np.min(eval_ms)),
+                           "plan_timesteps_per_s": plan_timesteps / (eval_avg * 1e-3)},
+            "score_candidates": {"ms": score_avg, "algorithmic_GBps": score_bytes / max(score_avg, 1e-9) / 1e6,
+                                 "frac_of_hbm_peak": score_bytes / max(score_avg, 1e-9) / 1e6 / HBM_PEAK_GBS},
+        },
+    }
+
+    if not args.no_greedy:
+        iters = 48
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        g = P.tensile_greedy_plan(h, 0, max_iters=iters, capacity=iters)
+        tg = time.perf_counter() - tg
+        out["rows"]["greedy_plan"] = {"iterations": int(len(g["iv_tensor"])), "s": tg,
+                                      "iterations_per_s": len(g["iv_tensor"]) / tg,
+                                      "peak_before": int(g["peak_trace"][0]), "peak_after": int(g["final_peak"])}
+
+    if not args.no_cpu:
+        from oracle import oracle as O
+        ns = min(B, 384)
+        sample = pl.select(np.arange(ns))
+        log(f"cpu baseline: oracle on the first {ns} plans")
+        MF0 = O.base_timeline(tas)
+        tc0 = time.perf_counter()
+        r0, p0, a0, m0 = O.eval_plans(tas, sample, MF0=MF0)
+        tc1 = time.perf_counter()
+        nsc = ns if args.eval_only else min(ns, 384)
+        if not args.eval_only:
+            O.score_plans(tas, sample, r0, p0, a0, rows=range(nsc))
+        tc2 = time.perf_counter()
+        cpu_s = (tc1 - tc0) + (tc2 - tc1) * (ns / nsc if not args.eval_only else 0.0)
+        out["cpu_baseline"] = {"value": ns * float(T) / cpu_s, "unit": "plan-timesteps/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {ns} of {B} plans of the same batch, same step "
+                                         f"({'eval' if args.eval_only else 'eval + score'}), single thread",
+                               "eval_only_value": ns * float(T) / (tc1 - tc0), "seconds": cpu_s}
+        # the GPU rows of the sample agree with what the oracle just computed
+        assert np.array_equal(peak[:ns].cpu().numpy(), p0) and np.array_equal(arg[:ns].cpu().numpy(), a0)
+        assert np.array_equal(res[:8].cpu().numpy(), r0[:8])
+    h.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
