@@ -51,7 +51,7 @@ struct DevBuf {
 };
 
 // Launch geometry of the evaluation kernel (see eval.hip).
-constexpr int kEvalThreads = 256;
+constexpr int kEvalThreads = 512;
 constexpr int kEvalTile = 4096;   // steps per LDS difference tile
 
 // Arguments of the fused scatter + scan + reduce kernel.
@@ -62,7 +62,9 @@ struct EvalArgs {
     const int64_t *plan_offsets;
     const int32_t *iv_tensor, *iv_out, *iv_in;
     const int64_t *size;           // [N]
-    const int64_t *MF0;            // [T]
+    const uint32_t *size_units;    // [N] size >> size_shift when that is exact and fits 32 bits, else null
+    int32_t size_shift;
+    const int64_t *MF0;            // [T rounded up to whole tiles], zero padded
     int64_t *resident;             // [B*T] or null
     int32_t S;                     // segments per plan
     int32_t tiles_per_seg;
@@ -91,6 +93,8 @@ struct tensile_tas {
     int num_cus = 256;
     // device copies
     tensile::DevBuf<int64_t> d_size, d_MF0, d_C, d_x, d_touch_off;
+    tensile::DevBuf<uint32_t> d_size_units;   // empty when the sizes do not fit (see EvalArgs)
+    int32_t size_shift = 0;
     tensile::DevBuf<int32_t> d_touch, d_gp, d_gq, d_gtensor, d_gwin;
     // host copies used by the greedy driver and the validator
     std::vector<int64_t> h_size, h_C, h_x, h_touch_off;

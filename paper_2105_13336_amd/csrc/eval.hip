@@ -9,12 +9,15 @@
 // the plan's intervals while it scans them for the first tile (an interval
 // contributes -size if its out+1 lies before the segment and +size if its in
 // step does), so segments of one plan need no communication and no look-back.
-// Per tile every thread walks the plan's interval list (coalesced int32 loads,
-// served by L2 after the first touch) and adds the endpoints that fall into the
-// tile with 64-bit LDS atomics.  Each of the four wavefronts then owns a
-// contiguous quarter of the tile: one pass sums the quarters (to get each
-// wave's starting carry), one pass scans 256 steps at a time (4 per lane + a
-// wave scan), adds MF0 and writes 32 contiguous bytes per lane.
+// The plan's intervals are read once, coalesced, into registers (endpoints and
+// size; R per thread, chosen on the host from the average plan length; a longer
+// plan re-reads its tail from memory).  Per tile every thread tests its
+// registers against the tile's range and adds the endpoints that fall into it
+// with 64-bit LDS atomics.  Each of the eight wavefronts then owns a contiguous
+// eighth of the tile and scans it 256 steps at a time (4 per lane + a DPP wave
+// scan) with a wave-local carry; after the waves have exchanged their totals
+// each adds its offset and MF0 (loaded while the scan runs) and writes 32
+// contiguous bytes per lane.  Two barriers per tile.
 //
 // Workgroup ids are decoded so that all segments of a plan run on the same XCD
 // (ids are dealt round-robin to the 8 XCDs, each with its own L2): the plan's
@@ -33,20 +36,33 @@ constexpr int kVpt = 4;                        // steps per lane per chunk
 constexpr int kChunk = 64 * kVpt;              // steps per wave per scan step
 static_assert(kQuarter % kChunk == 0, "tile must split into whole chunks");
 
-__device__ __forceinline__ int64_t wave_sum(int64_t v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
+// One DPP move of a 64-bit value (two 32-bit halves); lanes without a source, or
+// masked off, receive 0, so the caller can add the result unconditionally.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ int64_t dpp_or_zero(int64_t x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(x), kCtrl, kRowMask, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(x >> 32), kCtrl, kRowMask, 0xf, true);
+    return (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
 }
 
-// inclusive scan over the 64 lanes
-__device__ __forceinline__ int64_t wave_scan_add(int64_t v, int lane) {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        int64_t y = __shfl_up(v, d, 64);
-        if (lane >= d) v += y;
-    }
-    return v;
+// Inclusive add-scan over the 64 lanes: shifts by 1, 2, 4, 8 inside each row of
+// 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3, then lane 31
+// to rows 2 and 3.
+__device__ __forceinline__ int64_t wave_scan_add(int64_t x) {
+    x += dpp_or_zero<0x111, 0xf>(x);   // row_shr:1
+    x += dpp_or_zero<0x112, 0xf>(x);   // row_shr:2
+    x += dpp_or_zero<0x114, 0xf>(x);   // row_shr:4
+    x += dpp_or_zero<0x118, 0xf>(x);   // row_shr:8
+    x += dpp_or_zero<0x142, 0xa>(x);   // row_bcast:15 into rows 1, 3
+    x += dpp_or_zero<0x143, 0xc>(x);   // row_bcast:31 into rows 2, 3
+    return x;
+}
+
+// value of lane 63, as a wave-uniform scalar
+__device__ __forceinline__ int64_t last_lane(int64_t x) {
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(x), 63);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(x >> 32), 63);
+    return (static_cast<int64_t>(hi) << 32) | lo;
 }
 
 struct Best {
@@ -63,40 +79,63 @@ __device__ __forceinline__ void best_merge(Best &a, int64_t mx, int32_t arg, int
     if (mn < a.mn) a.mn = mn;
 }
 
+typedef long long ll2 __attribute__((ext_vector_type(2)));
+
 template <bool kVec16, bool kNonTemporal>
-__device__ __forceinline__ void store4(int64_t *dst, const int64_t (&v)[kVpt], int32_t n_valid) {
-    if (n_valid >= kVpt) {
-        if constexpr (kVec16) {
-            typedef long long ll2 __attribute__((ext_vector_type(2)));
-            ll2 a = {v[0], v[1]}, b = {v[2], v[3]};
-            if constexpr (kNonTemporal) {
-                __builtin_nontemporal_store(a, reinterpret_cast<ll2 *>(dst));
-                __builtin_nontemporal_store(b, reinterpret_cast<ll2 *>(dst) + 1);
-            } else {
-                reinterpret_cast<ll2 *>(dst)[0] = a;
-                reinterpret_cast<ll2 *>(dst)[1] = b;
-            }
+__device__ __forceinline__ void store4(int64_t *dst, const int64_t (&v)[kVpt]) {
+    if constexpr (kVec16) {
+        const ll2 a = {v[0], v[1]}, b = {v[2], v[3]};
+        if constexpr (kNonTemporal) {
+            __builtin_nontemporal_store(a, reinterpret_cast<ll2 *>(dst));
+            __builtin_nontemporal_store(b, reinterpret_cast<ll2 *>(dst) + 1);
         } else {
-#pragma unroll
-            for (int j = 0; j < kVpt; ++j) {
-                if constexpr (kNonTemporal) __builtin_nontemporal_store(v[j], dst + j);
-                else dst[j] = v[j];
-            }
+            reinterpret_cast<ll2 *>(dst)[0] = a;
+            reinterpret_cast<ll2 *>(dst)[1] = b;
         }
     } else {
 #pragma unroll
-        for (int j = 0; j < kVpt; ++j)
-            if (j < n_valid) dst[j] = v[j];
+        for (int j = 0; j < kVpt; ++j) {
+            if constexpr (kNonTemporal) __builtin_nontemporal_store(v[j], dst + j);
+            else dst[j] = v[j];
+        }
     }
 }
 
-template <bool kVec16, bool kNonTemporal>
-__global__ __launch_bounds__(kEvalThreads) void eval_kernel(const EvalArgs a) {
-    __shared__ int64_t delta[kEvalTile];
+// Sizes are kept in registers either as int64 (kNarrow == false) or, when every
+// size is a multiple of 2^size_shift and fits 32 bits after the shift, as uint32
+// units (one register less per interval).
+template <bool kNarrow>
+struct SizeReg;
+template <>
+struct SizeReg<false> {
+    typedef int64_t type;
+    static __device__ __forceinline__ type load(const EvalArgs &a, int32_t i) { return a.size[i]; }
+    static __device__ __forceinline__ int64_t bytes(const EvalArgs &, type s) { return s; }
+};
+template <>
+struct SizeReg<true> {
+    typedef uint32_t type;
+    static __device__ __forceinline__ type load(const EvalArgs &a, int32_t i) { return a.size_units[i]; }
+    static __device__ __forceinline__ int64_t bytes(const EvalArgs &a, type s) {
+        return static_cast<int64_t>(static_cast<uint64_t>(s) << a.size_shift);
+    }
+};
+
+__device__ __forceinline__ void opaque(uint32_t &x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void opaque(int64_t &x) { asm volatile("" : "+v"(x)); }
+
+__device__ __forceinline__ void lds_add(int64_t *p, int64_t v) {
+    atomicAdd(reinterpret_cast<unsigned long long *>(p), static_cast<unsigned long long>(v));
+}
+
+template <int R, bool kNarrow, bool kVec16, bool kNonTemporal>
+__device__ __forceinline__ void eval_body(const EvalArgs &a) {
+    __shared__ __attribute__((aligned(16))) int64_t delta[kEvalTile];
     __shared__ int64_t wave_tot[kWaves];
     __shared__ int64_t carry_part[kWaves];
     __shared__ int64_t red_mx[kWaves], red_mn[kWaves];
     __shared__ int32_t red_arg[kWaves];
+    typedef SizeReg<kNarrow> SR;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // XCD-aware decode: block w runs on XCD w % 8; give XCD x the plans = x (mod 8)
@@ -121,92 +160,151 @@ __global__ __launch_bounds__(kEvalThreads) void eval_kernel(const EvalArgs a) {
 
     for (int j = tid; j < kEvalTile; j += kEvalThreads) delta[j] = 0;
 
-    int64_t carry = 0;   // running sum of the deltas before the current tile (same in every thread)
+    // ---- the plan's first R*threads intervals live in registers for the whole segment:
+    // (first step without the bytes, first step with them again, size); an interval that
+    // cannot be applied, or a slot past the end of the list, gets endpoints no tile contains.
+    int32_t e0[R], e1[R];
+    typename SR::type sz[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int64_t k = k0 + static_cast<int64_t>(j) * kEvalThreads + tid;
+        int32_t i = -1, o = 0, r = 0;
+        if (k < k1) {
+            i = a.iv_tensor[k];
+            o = a.iv_out[k];
+            r = a.iv_in[k];
+        }
+        const bool ok = static_cast<uint32_t>(i) < static_cast<uint32_t>(a.N) && o >= a.o_min && r <= a.T && r > o;
+        e0[j] = ok ? o + 1 : INT32_MAX;
+        e1[j] = ok ? r : INT32_MAX;
+        sz[j] = ok ? SR::load(a, i) : 0;
+    }
+    const int64_t k_over = k0 + static_cast<int64_t>(R) * kEvalThreads;   // the rest is re-read per tile
+
+    // ---- running sum of the deltas before the segment
+    int64_t carry = 0;   // wave-uniform: sum of the deltas before the current tile
+    if (seg_lo > 0) {
+        int64_t c = 0;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int64_t s = SR::bytes(a, sz[j]);
+            c += (e1[j] < seg_lo ? s : 0) - (e0[j] < seg_lo ? s : 0);
+        }
+        for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
+            const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
+            if (static_cast<uint32_t>(i) >= static_cast<uint32_t>(a.N) || o < a.o_min || r > a.T || r <= o) continue;
+            const int64_t s = a.size[i];
+            c += (r < seg_lo ? s : 0) - (o + 1 < seg_lo ? s : 0);
+        }
+        c = last_lane(wave_scan_add(c));
+        if (lane == 0) carry_part[wave] = c;
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < kWaves; ++v) carry += carry_part[v];
+    }
+
     Best best{INT64_MIN, INT64_MAX, INT32_MAX};
     int64_t *row = a.resident ? a.resident + static_cast<int64_t>(plan) * a.T : nullptr;
+    const int my = wave * kQuarter + lane * kVpt;   // this lane's first step inside a chunk-0 tile part
+    __syncthreads();                                // the zero fill of delta is complete
 
     for (int32_t tile_lo = seg_lo; tile_lo < seg_hi; tile_lo += kEvalTile) {
         const int32_t tile_hi = tile_lo + kEvalTile < seg_hi ? tile_lo + kEvalTile : seg_hi;
-        const bool first = tile_lo == seg_lo;
-        __syncthreads();   // delta is all zero here (initial fill, or re-zeroed by the scan below)
+        const uint32_t tile_n = static_cast<uint32_t>(tile_hi - tile_lo);
+        // delta is all zero here: initially by the fill above, later because the scan below
+        // re-zeroes what it reads before its barrier.
 
         // ---- scatter: endpoints of this plan that fall into [tile_lo, tile_hi)
-        int64_t carry_local = 0;
-        for (int64_t k = k0 + tid; k < k1; k += kEvalThreads) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const uint32_t u0 = static_cast<uint32_t>(e0[j] - tile_lo), u1 = static_cast<uint32_t>(e1[j] - tile_lo);
+            // keep the compact register form across tiles: without this the widened and the
+            // negated size are hoisted out of the tile loop and held in six registers per interval
+            typename SR::type s = sz[j];
+            opaque(s);
+            if (u0 < tile_n) lds_add(&delta[u0], -SR::bytes(a, s));
+            if (u1 < tile_n) lds_add(&delta[u1], SR::bytes(a, s));
+        }
+        for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
             const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
             if (static_cast<uint32_t>(i) >= static_cast<uint32_t>(a.N) || o < a.o_min || r > a.T || r <= o) continue;
-            const int32_t e0 = o + 1;   // -size from here on
-            const int32_t e1 = r;       // +size from here on
-            const bool in0 = e0 >= tile_lo && e0 < tile_hi;
-            const bool in1 = e1 >= tile_lo && e1 < tile_hi;
-            const bool before0 = first && e0 < seg_lo;
-            const bool before1 = first && e1 < seg_lo;
-            if (in0 | in1 | before0 | before1) {
+            const uint32_t u0 = static_cast<uint32_t>(o + 1 - tile_lo), u1 = static_cast<uint32_t>(r - tile_lo);
+            if ((u0 < tile_n) | (u1 < tile_n)) {
                 const int64_t s = a.size[i];
-                if (in0) atomicAdd(reinterpret_cast<unsigned long long *>(&delta[e0 - tile_lo]),
-                                   static_cast<unsigned long long>(-s));
-                if (in1) atomicAdd(reinterpret_cast<unsigned long long *>(&delta[e1 - tile_lo]),
-                                   static_cast<unsigned long long>(s));
-                carry_local += (before1 ? s : 0) - (before0 ? s : 0);
+                if (u0 < tile_n) lds_add(&delta[u0], -s);
+                if (u1 < tile_n) lds_add(&delta[u1], s);
             }
         }
-        if (first) {
-            carry_local = wave_sum(carry_local);
-            if (lane == 0) carry_part[wave] = carry_local;
-        }
         __syncthreads();
-        if (first) {
+
+        // ---- MF0 of this lane's steps (the array is padded to whole tiles), in flight during the scan
+        ll2 mf[kQuarter / kChunk][2];
 #pragma unroll
-            for (int v = 0; v < kWaves; ++v) carry += carry_part[v];
+        for (int c = 0; c < kQuarter / kChunk; ++c) {
+            const ll2 *src = reinterpret_cast<const ll2 *>(a.MF0 + tile_lo + my + c * kChunk);
+            mf[c][0] = src[0];
+            mf[c][1] = src[1];
         }
 
-        // ---- each wave sums its quarter of the tile (lane-strided reads: no bank conflicts)
-        const int qbase = wave * kQuarter;
-        int64_t qs = 0;
+        // ---- scan this wave's part of the tile with a wave-local carry; re-zero what was read
+        int64_t v[kQuarter / kChunk][kVpt];
+        int64_t wave_run = 0;
 #pragma unroll
-        for (int j = 0; j < kQuarter / 64; ++j) qs += delta[qbase + j * 64 + lane];
-        qs = wave_sum(qs);
-        if (lane == 0) wave_tot[wave] = qs;
+        for (int c = 0; c < kQuarter / kChunk; ++c) {
+            ll2 *src = reinterpret_cast<ll2 *>(&delta[my + c * kChunk]);
+            const ll2 x0 = src[0], x1 = src[1];
+            src[0] = ll2{0, 0};
+            src[1] = ll2{0, 0};
+            v[c][0] = x0[0];
+            v[c][1] = v[c][0] + x0[1];
+            v[c][2] = v[c][1] + x1[0];
+            v[c][3] = v[c][2] + x1[1];
+            const int64_t incl = wave_scan_add(v[c][3]);
+            const int64_t excl = incl - v[c][3] + wave_run;
+#pragma unroll
+            for (int j = 0; j < kVpt; ++j) v[c][j] += excl;
+            wave_run += last_lane(incl);
+        }
+        if (lane == 0) wave_tot[wave] = wave_run;
         __syncthreads();
-        int64_t wave_carry = carry;
+        int64_t off = carry;
 #pragma unroll
-        for (int v = 0; v < kWaves; ++v) {
-            const int64_t tv = wave_tot[v];
-            if (v < wave) wave_carry += tv;
+        for (int u = 0; u < kWaves; ++u) {
+            const int64_t tv = wave_tot[u];
+            if (u < wave) off += tv;
             carry += tv;
         }
 
-        // ---- scan the quarter, 256 steps at a time; re-zero what was read
-#pragma unroll 1
+        // ---- add MF0 and the carries, reduce, store
+#pragma unroll
         for (int c = 0; c < kQuarter / kChunk; ++c) {
-            const int base = qbase + c * kChunk + lane * kVpt;
-            const int32_t t0 = tile_lo + base;
-            if (tile_lo + qbase + c * kChunk >= tile_hi) break;   // wave-uniform: nothing left in this tile
-            int64_t v[kVpt];
-#pragma unroll
-            for (int j = 0; j < kVpt; ++j) {
-                v[j] = delta[base + j];
-                delta[base + j] = 0;
-            }
-#pragma unroll
-            for (int j = 1; j < kVpt; ++j) v[j] += v[j - 1];
-            const int64_t incl = wave_scan_add(v[kVpt - 1], lane);
-            const int64_t excl = incl - v[kVpt - 1] + wave_carry;
-            wave_carry += __shfl(incl, 63, 64);
-            const int32_t n_valid = t0 >= tile_hi ? 0 : (tile_hi - t0 < kVpt ? tile_hi - t0 : kVpt);
-            if (n_valid > 0) {
+            const int32_t t0 = tile_lo + my + c * kChunk;
+            v[c][0] += off + mf[c][0][0];
+            v[c][1] += off + mf[c][0][1];
+            v[c][2] += off + mf[c][1][0];
+            v[c][3] += off + mf[c][1][1];
+            if (t0 + kVpt <= tile_hi) {
 #pragma unroll
                 for (int j = 0; j < kVpt; ++j) {
-                    if (j < n_valid) {
-                        v[j] += excl + a.MF0[t0 + j];
-                        if (v[j] > best.mx) {
-                            best.mx = v[j];
+                    if (v[c][j] > best.mx) {
+                        best.mx = v[c][j];
+                        best.arg = t0 + j;
+                    }
+                    if (v[c][j] < best.mn) best.mn = v[c][j];
+                }
+                if (row) store4<kVec16, kNonTemporal>(row + t0, v[c]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < kVpt; ++j) {
+                    if (t0 + j < tile_hi) {
+                        if (v[c][j] > best.mx) {
+                            best.mx = v[c][j];
                             best.arg = t0 + j;
                         }
-                        if (v[j] < best.mn) best.mn = v[j];
+                        if (v[c][j] < best.mn) best.mn = v[c][j];
+                        if (row) row[t0 + j] = v[c][j];
                     }
                 }
-                if (row) store4<kVec16, kNonTemporal>(row + t0, v, n_valid);
             }
         }
     }
@@ -226,12 +324,23 @@ __global__ __launch_bounds__(kEvalThreads) void eval_kernel(const EvalArgs a) {
     __syncthreads();
     if (tid == 0) {
 #pragma unroll
-        for (int v = 1; v < kWaves; ++v) best_merge(best, red_mx[v], red_arg[v], red_mn[v]);
+        for (int u = 1; u < kWaves; ++u) best_merge(best, red_mx[u], red_arg[u], red_mn[u]);
         const int64_t slot = static_cast<int64_t>(plan) * a.S + seg;
         a.out_max[slot] = best.mx;
         a.out_arg[slot] = best.arg;
         if (a.out_min) a.out_min[slot] = best.mn;
     }
+}
+
+// Two workgroups per CU (four waves per SIMD) need at most 128 VGPRs; up to 12 intervals per
+// thread fit without spilling.  The 16-interval variant is left to the register allocator.
+template <int R, bool kNarrow, bool kVec16, bool kNonTemporal>
+__global__ __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void eval_kernel(const EvalArgs a) {
+    eval_body<R, kNarrow, kVec16, kNonTemporal>(a);
+}
+template <bool kNarrow, bool kVec16, bool kNonTemporal>
+__global__ __launch_bounds__(kEvalThreads) void eval_kernel_r16(const EvalArgs a) {
+    eval_body<16, kNarrow, kVec16, kNonTemporal>(a);
 }
 
 // Combine the per-segment partials of each plan; segments are in time order, so
@@ -307,11 +416,43 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     }
     const bool vec16 = a.resident && (a.T % 2 == 0) && (reinterpret_cast<uintptr_t>(a.resident) % 16 == 0);
     const bool nt = env_int("TENSILE_EVAL_NT", 1) != 0;
+    const bool narrow = a.size_units != nullptr;
+    // intervals per thread kept in registers: sized for the average plan with some slack
+    // (plans longer than R*threads re-read their tail from memory in every tile)
+    const int64_t avg_k = (a.n_intervals + a.B - 1) / a.B;
+    int64_t r_need = (avg_k + avg_k / 4 + kEvalThreads - 1) / kEvalThreads;
+    const int r_forced = env_int("TENSILE_EVAL_R", 0);   // tuning knob
+    if (r_forced > 0) r_need = r_forced;
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kEvalThreads);
-    if (vec16 && nt) hipLaunchKernelGGL((eval_kernel<true, true>), grid, block, 0, stream, a);
-    else if (vec16) hipLaunchKernelGGL((eval_kernel<true, false>), grid, block, 0, stream, a);
-    else if (nt) hipLaunchKernelGGL((eval_kernel<false, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((eval_kernel<false, false>), grid, block, 0, stream, a);
+#define TS_LAUNCH_EVAL2(R, NARROW)                                                                                  \
+    do {                                                                                                            \
+        if (vec16 && nt) hipLaunchKernelGGL((eval_kernel<R, NARROW, true, true>), grid, block, 0, stream, a);       \
+        else if (vec16) hipLaunchKernelGGL((eval_kernel<R, NARROW, true, false>), grid, block, 0, stream, a);       \
+        else if (nt) hipLaunchKernelGGL((eval_kernel<R, NARROW, false, true>), grid, block, 0, stream, a);          \
+        else hipLaunchKernelGGL((eval_kernel<R, NARROW, false, false>), grid, block, 0, stream, a);                 \
+    } while (0)
+#define TS_LAUNCH_EVAL(R)                        \
+    do {                                         \
+        if (narrow) TS_LAUNCH_EVAL2(R, true);    \
+        else TS_LAUNCH_EVAL2(R, false);          \
+    } while (0)
+    if (r_need <= 4) TS_LAUNCH_EVAL(4);
+    else if (r_need <= 8) TS_LAUNCH_EVAL(8);
+    else if (r_need <= 12) TS_LAUNCH_EVAL(12);
+    else {
+#define TS_LAUNCH_R16(NARROW)                                                                                     \
+    do {                                                                                                          \
+        if (vec16 && nt) hipLaunchKernelGGL((eval_kernel_r16<NARROW, true, true>), grid, block, 0, stream, a);    \
+        else if (vec16) hipLaunchKernelGGL((eval_kernel_r16<NARROW, true, false>), grid, block, 0, stream, a);    \
+        else if (nt) hipLaunchKernelGGL((eval_kernel_r16<NARROW, false, true>), grid, block, 0, stream, a);       \
+        else hipLaunchKernelGGL((eval_kernel_r16<NARROW, false, false>), grid, block, 0, stream, a);              \
+    } while (0)
+        if (narrow) TS_LAUNCH_R16(true);
+        else TS_LAUNCH_R16(false);
+#undef TS_LAUNCH_R16
+    }
+#undef TS_LAUNCH_EVAL
+#undef TS_LAUNCH_EVAL2
     TS_HIP(hipGetLastError());
     if (S > 1) {
         const int threads = 256;

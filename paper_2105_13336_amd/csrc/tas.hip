@@ -4,6 +4,7 @@
 // entry points that are thin argument checks around the kernels.
 #include "common.h"
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <new>
@@ -213,7 +214,23 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
     TS_HIP(h->d_gq.upload(gq.data(), gq.size()));
     TS_HIP(h->d_gtensor.upload(gt.data(), gt.size()));
     TS_HIP(h->d_gwin.reserve(gp.size()));
-    TS_HIP(h->d_MF0.reserve(T));
+    const size_t T_pad = (static_cast<size_t>(T) + kEvalTile - 1) / kEvalTile * kEvalTile;
+    TS_HIP(h->d_MF0.reserve(T_pad));
+    TS_HIP(hipMemset(h->d_MF0.p, 0, T_pad * sizeof(int64_t)));
+    {   // sizes as 32-bit multiples of their common power of two, when they fit
+        uint64_t all = 0, mx = 0;
+        for (int32_t i = 0; i < N; ++i) {
+            all |= static_cast<uint64_t>(d->size_bytes[i]);
+            mx = std::max<uint64_t>(mx, static_cast<uint64_t>(d->size_bytes[i]));
+        }
+        const int shift = all ? __builtin_ctzll(all) : 0;
+        if (N > 0 && (mx >> shift) <= 0xffffffffULL) {
+            std::vector<uint32_t> units(static_cast<size_t>(N));
+            for (int32_t i = 0; i < N; ++i) units[i] = static_cast<uint32_t>(static_cast<uint64_t>(d->size_bytes[i]) >> shift);
+            TS_HIP(h->d_size_units.upload(units.data(), units.size()));
+            h->size_shift = shift;
+        }
+    }
     TS_HIP(h->d_C.reserve(static_cast<size_t>(T) + 1));
     TS_HIP(h->d_x.reserve(N));
 
@@ -222,7 +239,8 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
     {
         DevBuf<int64_t> base, neg, offs, peak, mn;
         DevBuf<int32_t> alloc, fr, it, io, ir, arg;
-        TS_HIP(base.reserve(T));
+        TS_HIP(base.reserve(T_pad));
+        TS_HIP(hipMemset(base.p, 0, T_pad * sizeof(int64_t)));
         TS_HIP(neg.reserve(N));
         TS_HIP(alloc.upload(d->alloc_step, N));
         TS_HIP(fr.upload(d->free_step, N));
@@ -238,7 +256,7 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
         EvalArgs a{};
         a.T = T; a.N = N; a.B = 1; a.o_min = -1; a.n_intervals = N;
         a.plan_offsets = offs.p; a.iv_tensor = it.p; a.iv_out = io.p; a.iv_in = ir.p;
-        a.size = neg.p; a.MF0 = base.p; a.resident = h->d_MF0.p;
+        a.size = neg.p; a.size_units = nullptr; a.MF0 = base.p; a.resident = h->d_MF0.p;
         int rc = launch_eval(h, a, peak.p, arg.p, mn.p, nullptr);
         if (rc != TENSILE_OK) return rc;
         TS_HIP(hipMemcpy(&h->unscheduled_peak, peak.p, sizeof(int64_t), hipMemcpyDeviceToHost));
@@ -338,7 +356,8 @@ int tensile_eval_plans(const tensile_tas *tas, const tensile_plans *plans, int64
     a.T = tas->T; a.N = tas->N; a.B = plans->B; a.o_min = 0; a.n_intervals = plans->n_intervals;
     a.plan_offsets = plans->plan_offsets;
     a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;
-    a.size = tas->d_size.p; a.MF0 = tas->d_MF0.p; a.resident = resident;
+    a.size = tas->d_size.p; a.size_units = tas->d_size_units.p; a.size_shift = tas->size_shift;
+    a.MF0 = tas->d_MF0.p; a.resident = resident;
     return launch_eval(tas, a, peak, argmax, min_resident, static_cast<hipStream_t>(hip_stream));
 }
 
