@@ -64,7 +64,8 @@ struct EvalArgs {
     const int64_t *size;           // [N]
     const uint32_t *size_units;    // [N] size >> size_shift when that is exact and fits 32 bits, else null
     int32_t size_shift;
-    const int64_t *MF0;            // [T rounded up to whole tiles], zero padded
+    const int64_t *MF0;            // [T] unscheduled timeline (read at segment starts only)
+    const int64_t *dMF0;           // [T rounded up to whole tiles] MF0[t] - MF0[t-1], dMF0[0] = MF0[0], zero padded
     int64_t *resident;             // [B*T] or null
     int32_t S;                     // segments per plan
     int32_t tiles_per_seg;
@@ -92,7 +93,7 @@ struct tensile_tas {
     int32_t unscheduled_argmax = 0;
     int num_cus = 256;
     // device copies
-    tensile::DevBuf<int64_t> d_size, d_MF0, d_C, d_x, d_touch_off;
+    tensile::DevBuf<int64_t> d_size, d_MF0, d_dMF0, d_C, d_x, d_touch_off;
     tensile::DevBuf<uint32_t> d_size_units;   // empty when the sizes do not fit (see EvalArgs)
     int32_t size_shift = 0;
     tensile::DevBuf<int32_t> d_touch, d_gp, d_gq, d_gtensor, d_gwin;

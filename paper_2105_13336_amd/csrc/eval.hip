@@ -1,23 +1,41 @@
 // Memory peak analysis of a batch of plans (Eq. 1, Eq. 2 and Alg. 1 of the paper)
 // as one fused kernel: difference-array scatter of the interval endpoints into an
-// LDS tile, prefix scan over the steps, add the unscheduled timeline, store the
-// footprint row, and reduce (max, earliest argmax, min) on the way.
+// LDS tile, prefix scan over the steps, store the footprint row, and reduce
+// (max, earliest argmax, min) on the way.
 //
-// Work decomposition.  A workgroup owns one (plan, segment): `tiles_per_seg`
-// consecutive tiles of kEvalTile steps.  The running sum that enters a segment
-// is the sum of the deltas before it, which the workgroup takes straight from
-// the plan's intervals while it scans them for the first tile (an interval
+// Work decomposition.  A workgroup (512 threads) owns one (plan, segment):
+// `tiles_per_seg` consecutive tiles of kEvalTile steps.  The running sum that
+// enters a segment is MF0 just before it plus the plan's deltas before it, which
+// the workgroup takes straight from the plan's intervals (an interval
 // contributes -size if its out+1 lies before the segment and +size if its in
 // step does), so segments of one plan need no communication and no look-back.
-// The plan's intervals are read once, coalesced, into registers (endpoints and
-// size; R per thread, chosen on the host from the average plan length; a longer
-// plan re-reads its tail from memory).  Per tile every thread tests its
-// registers against the tile's range and adds the endpoints that fall into it
-// with 64-bit LDS atomics.  Each of the eight wavefronts then owns a contiguous
-// eighth of the tile and scans it 256 steps at a time (4 per lane + a DPP wave
-// scan) with a wave-local carry; after the waves have exchanged their totals
-// each adds its offset and MF0 (loaded while the scan runs) and writes 32
-// contiguous bytes per lane.  Two barriers per tile.
+//
+// The kernel is bound by instruction issue as much as by HBM (the chip issues
+// about 39 lane-instructions per 8-byte element at full HBM speed and 64-bit
+// integer adds take two), so the per-element work is kept small:
+//  * The LDS tile is initialised with the DIFFERENCES of the unscheduled
+//    timeline, dMF0[t] = MF0[t] - MF0[t-1], not with zeros: the scan then yields
+//    the footprint itself and no separate "+ MF0" pass is needed.  The next
+//    tile's dMF0 is loaded while the current tile is processed and written into
+//    the cells as the scan reads them.
+//  * The plan's intervals are read once into registers (endpoints and size; R
+//    per thread, chosen on the host from the average plan length; a longer plan
+//    re-reads its tail from memory per tile).  Threads take CONSECUTIVE
+//    intervals, so when a plan lists its intervals roughly in time order (plans
+//    are usually built tensor by tensor) a wavefront's endpoints cluster in time
+//    and the wavefront skips the scatter of tiles its endpoints cannot touch.
+//    The result does not depend on the order.
+//  * Each lane owns 8 consecutive steps of the tile: 7 local adds, one DPP wave
+//    scan per 8 steps, one exchange of wave totals through LDS (two barriers per
+//    tile), one add of the offset.
+//  * Stores want 16 contiguous bytes per lane per instruction (a wavefront then
+//    writes 1 KB of whole lines; 64 bytes per lane at a 64-byte stride reaches
+//    only about 60 % of the streaming-store rate), so each wavefront transposes
+//    its 512 results through a private LDS staging area.  Both the tile and the
+//    staging area skew every group of four lanes by one 16-byte granule, which
+//    makes the lane-contiguous and the striped access patterns conflict-free.
+//  * max/min are reduced over the lane's 8 values first; the argmax is located
+//    only when the lane's maximum improves.
 //
 // Workgroup ids are decoded so that all segments of a plan run on the same XCD
 // (ids are dealt round-robin to the 8 XCDs, each with its own L2): the plan's
@@ -31,10 +49,14 @@ namespace tensile {
 namespace {
 
 constexpr int kWaves = kEvalThreads / 64;
-constexpr int kQuarter = kEvalTile / kWaves;   // steps per wave per tile
-constexpr int kVpt = 4;                        // steps per lane per chunk
-constexpr int kChunk = 64 * kVpt;              // steps per wave per scan step
-static_assert(kQuarter % kChunk == 0, "tile must split into whole chunks");
+constexpr int kVpt = kEvalTile / kEvalThreads;   // steps per lane per tile
+static_assert(kVpt == 8, "the scan below is written for 8 steps per lane");
+// LDS layouts are skewed: 16-byte granule g lives at granule g + (g >> 4), i.e. cell u at
+// u + 2 * (u >> 5).  A lane's four granules stay contiguous (they never straddle a multiple of 16).
+constexpr int kTileCells = kEvalTile + 2 * (kEvalTile >> 5);          // 4352
+constexpr int kStageCells = 64 * kVpt + 2 * ((64 * kVpt) >> 5) + 2;    // 546 per wave, rounded up below
+constexpr int kStageStride = (kStageCells + 7) / 8 * 8;               // 552
+__device__ __forceinline__ uint32_t skew(uint32_t u) { return u + ((u >> 5) << 1); }
 
 // One DPP move of a 64-bit value (two 32-bit halves); lanes without a source, or
 // masked off, receive 0, so the caller can add the result unconditionally.
@@ -81,26 +103,6 @@ __device__ __forceinline__ void best_merge(Best &a, int64_t mx, int32_t arg, int
 
 typedef long long ll2 __attribute__((ext_vector_type(2)));
 
-template <bool kVec16, bool kNonTemporal>
-__device__ __forceinline__ void store4(int64_t *dst, const int64_t (&v)[kVpt]) {
-    if constexpr (kVec16) {
-        const ll2 a = {v[0], v[1]}, b = {v[2], v[3]};
-        if constexpr (kNonTemporal) {
-            __builtin_nontemporal_store(a, reinterpret_cast<ll2 *>(dst));
-            __builtin_nontemporal_store(b, reinterpret_cast<ll2 *>(dst) + 1);
-        } else {
-            reinterpret_cast<ll2 *>(dst)[0] = a;
-            reinterpret_cast<ll2 *>(dst)[1] = b;
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < kVpt; ++j) {
-            if constexpr (kNonTemporal) __builtin_nontemporal_store(v[j], dst + j);
-            else dst[j] = v[j];
-        }
-    }
-}
-
 // Sizes are kept in registers either as int64 (kNarrow == false) or, when every
 // size is a multiple of 2^size_shift and fits 32 bits after the shift, as uint32
 // units (one register less per interval).
@@ -128,9 +130,14 @@ __device__ __forceinline__ void lds_add(int64_t *p, int64_t v) {
     atomicAdd(reinterpret_cast<unsigned long long *>(p), static_cast<unsigned long long>(v));
 }
 
+__device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o, int32_t r) {
+    return static_cast<uint32_t>(i) < static_cast<uint32_t>(a.N) && o >= a.o_min && r <= a.T && r > o;
+}
+
 template <int R, bool kNarrow, bool kVec16, bool kNonTemporal>
 __device__ __forceinline__ void eval_body(const EvalArgs &a) {
-    __shared__ __attribute__((aligned(16))) int64_t delta[kEvalTile];
+    __shared__ __attribute__((aligned(16))) int64_t delta[kTileCells];
+    __shared__ __attribute__((aligned(16))) int64_t stage_all[kWaves * kStageStride];
     __shared__ int64_t wave_tot[kWaves];
     __shared__ int64_t carry_part[kWaves];
     __shared__ int64_t red_mx[kWaves], red_mn[kWaves];
@@ -157,155 +164,195 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     if (seg_lo64 >= a.T) return;   // cannot happen with the host's choice of S; keeps indexing safe
     const int32_t seg_lo = static_cast<int32_t>(seg_lo64);
     const int32_t seg_hi = static_cast<int32_t>(seg_lo64 + seg_len < a.T ? seg_lo64 + seg_len : a.T);
+    const int my = tid * kVpt;                  // this lane's first step of the tile
+    const int my_cell = my + 2 * (tid >> 2);    // ... and where it lives in the skewed tile
+    int64_t *stage = stage_all + wave * kStageStride;
 
-    for (int j = tid; j < kEvalTile; j += kEvalThreads) delta[j] = 0;
+    // ---- first tile's cells: differences of the unscheduled timeline (dMF0 is padded to whole tiles)
+    ll2 fill[kVpt / 2];
+#pragma unroll
+    for (int j = 0; j < kVpt / 2; ++j) fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + seg_lo + my)[j];
 
-    // ---- the plan's first R*threads intervals live in registers for the whole segment:
-    // (first step without the bytes, first step with them again, size); an interval that
-    // cannot be applied, or a slot past the end of the list, gets endpoints no tile contains.
+    // ---- the plan's first R*threads intervals live in registers for the whole segment, R
+    // consecutive ones per thread: (first step without the bytes, first step with them again,
+    // size).  An interval that cannot be applied, or a slot past the end of the list, gets
+    // endpoints no tile contains.  [lo_t, hi_t] spans this thread's endpoints.
     int32_t e0[R], e1[R];
     typename SR::type sz[R];
+    int32_t lo_t = INT32_MAX, hi_t = -1;
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const int64_t k = k0 + static_cast<int64_t>(j) * kEvalThreads + tid;
+        const int64_t k = k0 + static_cast<int64_t>(tid) * R + j;
         int32_t i = -1, o = 0, r = 0;
         if (k < k1) {
             i = a.iv_tensor[k];
             o = a.iv_out[k];
             r = a.iv_in[k];
         }
-        const bool ok = static_cast<uint32_t>(i) < static_cast<uint32_t>(a.N) && o >= a.o_min && r <= a.T && r > o;
+        const bool ok = applies(a, i, o, r);
         e0[j] = ok ? o + 1 : INT32_MAX;
         e1[j] = ok ? r : INT32_MAX;
         sz[j] = ok ? SR::load(a, i) : 0;
+        if (ok) {
+            lo_t = o + 1 < lo_t ? o + 1 : lo_t;
+            hi_t = r > hi_t ? r : hi_t;
+        }
     }
     const int64_t k_over = k0 + static_cast<int64_t>(R) * kEvalThreads;   // the rest is re-read per tile
 
-    // ---- running sum of the deltas before the segment
-    int64_t carry = 0;   // wave-uniform: sum of the deltas before the current tile
+#pragma unroll
+    for (int j = 0; j < kVpt / 2; ++j) reinterpret_cast<ll2 *>(&delta[my_cell])[j] = fill[j];
+
+    // ---- footprint just before the segment: MF0 there plus the plan's deltas before it
+    int64_t carry = 0;   // same value in every thread
     if (seg_lo > 0) {
         int64_t c = 0;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const int64_t s = SR::bytes(a, sz[j]);
+            typename SR::type s32 = sz[j];
+            opaque(s32);
+            const int64_t s = SR::bytes(a, s32);
             c += (e1[j] < seg_lo ? s : 0) - (e0[j] < seg_lo ? s : 0);
         }
         for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
             const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
-            if (static_cast<uint32_t>(i) >= static_cast<uint32_t>(a.N) || o < a.o_min || r > a.T || r <= o) continue;
+            if (!applies(a, i, o, r)) continue;
             const int64_t s = a.size[i];
             c += (r < seg_lo ? s : 0) - (o + 1 < seg_lo ? s : 0);
         }
         c = last_lane(wave_scan_add(c));
         if (lane == 0) carry_part[wave] = c;
         __syncthreads();
+        carry = a.MF0[seg_lo - 1];
 #pragma unroll
         for (int v = 0; v < kWaves; ++v) carry += carry_part[v];
     }
 
     Best best{INT64_MIN, INT64_MAX, INT32_MAX};
     int64_t *row = a.resident ? a.resident + static_cast<int64_t>(plan) * a.T : nullptr;
-    const int my = wave * kQuarter + lane * kVpt;   // this lane's first step inside a chunk-0 tile part
-    __syncthreads();                                // the zero fill of delta is complete
+    __syncthreads();   // the first tile's cells are in place
 
     for (int32_t tile_lo = seg_lo; tile_lo < seg_hi; tile_lo += kEvalTile) {
         const int32_t tile_hi = tile_lo + kEvalTile < seg_hi ? tile_lo + kEvalTile : seg_hi;
         const uint32_t tile_n = static_cast<uint32_t>(tile_hi - tile_lo);
-        // delta is all zero here: initially by the fill above, later because the scan below
-        // re-zeroes what it reads before its barrier.
+        // delta holds dMF0 of this tile: written before the loop, or by the scan of the previous
+        // tile ahead of its barrier.
 
-        // ---- scatter: endpoints of this plan that fall into [tile_lo, tile_hi)
+        // next tile's dMF0, in flight while this tile is processed (zeros after the last tile)
+        const bool more = tile_lo + kEvalTile < seg_hi;
 #pragma unroll
-        for (int j = 0; j < R; ++j) {
-            const uint32_t u0 = static_cast<uint32_t>(e0[j] - tile_lo), u1 = static_cast<uint32_t>(e1[j] - tile_lo);
-            // keep the compact register form across tiles: without this the widened and the
-            // negated size are hoisted out of the tile loop and held in six registers per interval
-            typename SR::type s = sz[j];
-            opaque(s);
-            if (u0 < tile_n) lds_add(&delta[u0], -SR::bytes(a, s));
-            if (u1 < tile_n) lds_add(&delta[u1], SR::bytes(a, s));
+        for (int j = 0; j < kVpt / 2; ++j)
+            fill[j] = more ? reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kEvalTile + my)[j] : ll2{0, 0};
+
+        // ---- scatter: endpoints of this plan that fall into [tile_lo, tile_hi); a wavefront none
+        // of whose lanes holds an endpoint in the tile's range skips its registers
+        const bool mine = hi_t >= tile_lo && lo_t < tile_hi;
+        if (__builtin_amdgcn_ballot_w64(mine) != 0) {
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const uint32_t u0 = static_cast<uint32_t>(e0[j] - tile_lo), u1 = static_cast<uint32_t>(e1[j] - tile_lo);
+                // keep the compact register form across tiles: without this the widened and the
+                // negated size are hoisted out of the tile loop and held in six registers per interval
+                typename SR::type s = sz[j];
+                opaque(s);
+                if (u0 < tile_n) lds_add(&delta[skew(u0)], -SR::bytes(a, s));
+                if (u1 < tile_n) lds_add(&delta[skew(u1)], SR::bytes(a, s));
+            }
         }
         for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
             const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
-            if (static_cast<uint32_t>(i) >= static_cast<uint32_t>(a.N) || o < a.o_min || r > a.T || r <= o) continue;
+            if (!applies(a, i, o, r)) continue;
             const uint32_t u0 = static_cast<uint32_t>(o + 1 - tile_lo), u1 = static_cast<uint32_t>(r - tile_lo);
             if ((u0 < tile_n) | (u1 < tile_n)) {
                 const int64_t s = a.size[i];
-                if (u0 < tile_n) lds_add(&delta[u0], -s);
-                if (u1 < tile_n) lds_add(&delta[u1], s);
+                if (u0 < tile_n) lds_add(&delta[skew(u0)], -s);
+                if (u1 < tile_n) lds_add(&delta[skew(u1)], s);
             }
         }
         __syncthreads();
 
-        // ---- MF0 of this lane's steps (the array is padded to whole tiles), in flight during the scan
-        ll2 mf[kQuarter / kChunk][2];
+        // ---- local scan of this lane's 8 cells; the cells receive the next tile's dMF0
+        int64_t v[kVpt];
+        {
+            ll2 *cell = reinterpret_cast<ll2 *>(&delta[my_cell]);
 #pragma unroll
-        for (int c = 0; c < kQuarter / kChunk; ++c) {
-            const ll2 *src = reinterpret_cast<const ll2 *>(a.MF0 + tile_lo + my + c * kChunk);
-            mf[c][0] = src[0];
-            mf[c][1] = src[1];
+            for (int j = 0; j < kVpt / 2; ++j) {
+                const ll2 x = cell[j];
+                cell[j] = fill[j];
+                v[2 * j] = x[0];
+                v[2 * j + 1] = x[1];
+            }
         }
-
-        // ---- scan this wave's part of the tile with a wave-local carry; re-zero what was read
-        int64_t v[kQuarter / kChunk][kVpt];
-        int64_t wave_run = 0;
 #pragma unroll
-        for (int c = 0; c < kQuarter / kChunk; ++c) {
-            ll2 *src = reinterpret_cast<ll2 *>(&delta[my + c * kChunk]);
-            const ll2 x0 = src[0], x1 = src[1];
-            src[0] = ll2{0, 0};
-            src[1] = ll2{0, 0};
-            v[c][0] = x0[0];
-            v[c][1] = v[c][0] + x0[1];
-            v[c][2] = v[c][1] + x1[0];
-            v[c][3] = v[c][2] + x1[1];
-            const int64_t incl = wave_scan_add(v[c][3]);
-            const int64_t excl = incl - v[c][3] + wave_run;
-#pragma unroll
-            for (int j = 0; j < kVpt; ++j) v[c][j] += excl;
-            wave_run += last_lane(incl);
-        }
-        if (lane == 0) wave_tot[wave] = wave_run;
+        for (int j = 1; j < kVpt; ++j) v[j] += v[j - 1];
+        const int64_t incl = wave_scan_add(v[kVpt - 1]);
+        if (lane == 63) wave_tot[wave] = incl;
         __syncthreads();
-        int64_t off = carry;
+        int64_t base = carry + incl - v[kVpt - 1];
 #pragma unroll
         for (int u = 0; u < kWaves; ++u) {
             const int64_t tv = wave_tot[u];
-            if (u < wave) off += tv;
+            if (u < wave) base += tv;
             carry += tv;
         }
+#pragma unroll
+        for (int j = 0; j < kVpt; ++j) v[j] += base;
 
-        // ---- add MF0 and the carries, reduce, store
+        // ---- reduce
+        const int32_t t0 = tile_lo + my;
+        if (t0 + kVpt <= tile_hi) {
+            int64_t cm = v[0], cn = v[0];
 #pragma unroll
-        for (int c = 0; c < kQuarter / kChunk; ++c) {
-            const int32_t t0 = tile_lo + my + c * kChunk;
-            v[c][0] += off + mf[c][0][0];
-            v[c][1] += off + mf[c][0][1];
-            v[c][2] += off + mf[c][1][0];
-            v[c][3] += off + mf[c][1][1];
-            if (t0 + kVpt <= tile_hi) {
+            for (int j = 1; j < kVpt; ++j) {
+                cm = v[j] > cm ? v[j] : cm;
+                cn = v[j] < cn ? v[j] : cn;
+            }
+            if (cm > best.mx) {
+                best.mx = cm;
 #pragma unroll
-                for (int j = 0; j < kVpt; ++j) {
-                    if (v[c][j] > best.mx) {
-                        best.mx = v[c][j];
+                for (int j = kVpt - 1; j >= 0; --j)
+                    if (v[j] == cm) best.arg = t0 + j;
+            }
+            best.mn = cn < best.mn ? cn : best.mn;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kVpt; ++j) {
+                if (t0 + j < tile_hi) {
+                    if (v[j] > best.mx) {
+                        best.mx = v[j];
                         best.arg = t0 + j;
                     }
-                    if (v[c][j] < best.mn) best.mn = v[c][j];
-                }
-                if (row) store4<kVec16, kNonTemporal>(row + t0, v[c]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < kVpt; ++j) {
-                    if (t0 + j < tile_hi) {
-                        if (v[c][j] > best.mx) {
-                            best.mx = v[c][j];
-                            best.arg = t0 + j;
-                        }
-                        if (v[c][j] < best.mn) best.mn = v[c][j];
-                        if (row) row[t0 + j] = v[c][j];
-                    }
+                    if (v[j] < best.mn) best.mn = v[j];
                 }
             }
+        }
+
+        // ---- store: transpose the wave's 512 results through its staging area so that every
+        // store instruction writes 16 contiguous bytes per lane
+        if (row) {
+            ll2 *mine_out = reinterpret_cast<ll2 *>(stage + lane * kVpt + 2 * (lane >> 2));
+#pragma unroll
+            for (int j = 0; j < kVpt / 2; ++j) mine_out[j] = ll2{v[2 * j], v[2 * j + 1]};
+            __builtin_amdgcn_wave_barrier();
+            const int32_t wave_t0 = tile_lo + wave * (64 * kVpt);
+#pragma unroll
+            for (int j = 0; j < kVpt / 2; ++j) {
+                const int g = j * 64 + lane;                         // granule in time order
+                const ll2 x = *reinterpret_cast<const ll2 *>(stage + 2 * (g + (g >> 4)));
+                const int32_t t = wave_t0 + 2 * g;
+                if (t + 2 <= tile_hi) {
+                    if constexpr (kVec16) {
+                        if constexpr (kNonTemporal) __builtin_nontemporal_store(x, reinterpret_cast<ll2 *>(row + t));
+                        else *reinterpret_cast<ll2 *>(row + t) = x;
+                    } else {
+                        row[t] = x[0];
+                        row[t + 1] = x[1];
+                    }
+                } else if (t < tile_hi) {
+                    row[t] = x[0];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     }
 
@@ -415,12 +462,12 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
         a.out_min = sc.part_min.p;
     }
     const bool vec16 = a.resident && (a.T % 2 == 0) && (reinterpret_cast<uintptr_t>(a.resident) % 16 == 0);
-    const bool nt = env_int("TENSILE_EVAL_NT", 1) != 0;
+    const bool nt = env_int("TENSILE_EVAL_NT", 0) != 0;   // plain stores measure faster than nontemporal ones
     const bool narrow = a.size_units != nullptr;
     // intervals per thread kept in registers: sized for the average plan with some slack
     // (plans longer than R*threads re-read their tail from memory in every tile)
     const int64_t avg_k = (a.n_intervals + a.B - 1) / a.B;
-    int64_t r_need = (avg_k + avg_k / 4 + kEvalThreads - 1) / kEvalThreads;
+    int64_t r_need = (avg_k + avg_k / 8 + kEvalThreads - 1) / kEvalThreads;
     const int r_forced = env_int("TENSILE_EVAL_R", 0);   // tuning knob
     if (r_forced > 0) r_need = r_forced;
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kEvalThreads);
@@ -436,10 +483,6 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
         if (narrow) TS_LAUNCH_EVAL2(R, true);    \
         else TS_LAUNCH_EVAL2(R, false);          \
     } while (0)
-    if (r_need <= 4) TS_LAUNCH_EVAL(4);
-    else if (r_need <= 8) TS_LAUNCH_EVAL(8);
-    else if (r_need <= 12) TS_LAUNCH_EVAL(12);
-    else {
 #define TS_LAUNCH_R16(NARROW)                                                                                     \
     do {                                                                                                          \
         if (vec16 && nt) hipLaunchKernelGGL((eval_kernel_r16<NARROW, true, true>), grid, block, 0, stream, a);    \
@@ -447,10 +490,12 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
         else if (nt) hipLaunchKernelGGL((eval_kernel_r16<NARROW, false, true>), grid, block, 0, stream, a);       \
         else hipLaunchKernelGGL((eval_kernel_r16<NARROW, false, false>), grid, block, 0, stream, a);              \
     } while (0)
-        if (narrow) TS_LAUNCH_R16(true);
-        else TS_LAUNCH_R16(false);
+    if (r_need <= 4) TS_LAUNCH_EVAL(4);
+    else if (r_need <= 8) TS_LAUNCH_EVAL(8);
+    else if (r_need <= 12) TS_LAUNCH_EVAL(12);
+    else if (narrow) TS_LAUNCH_R16(true);
+    else TS_LAUNCH_R16(false);
 #undef TS_LAUNCH_R16
-    }
 #undef TS_LAUNCH_EVAL
 #undef TS_LAUNCH_EVAL2
     TS_HIP(hipGetLastError());

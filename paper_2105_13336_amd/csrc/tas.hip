@@ -97,6 +97,12 @@ __global__ void gap_window_kernel(int32_t G, int32_t T, const int32_t *gp, const
     gwin[g] = o;
 }
 
+// d[t] = MF0[t] - MF0[t-1], d[0] = MF0[0]
+__global__ void difference_kernel(int32_t T, const int64_t *MF0, int64_t *d) {
+    const int32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < T) d[t] = t > 0 ? MF0[t] - MF0[t - 1] : MF0[0];
+}
+
 __global__ void fill_kernel(int64_t n, int64_t value, int64_t *dst) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = value;
@@ -215,8 +221,9 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
     TS_HIP(h->d_gtensor.upload(gt.data(), gt.size()));
     TS_HIP(h->d_gwin.reserve(gp.size()));
     const size_t T_pad = (static_cast<size_t>(T) + kEvalTile - 1) / kEvalTile * kEvalTile;
-    TS_HIP(h->d_MF0.reserve(T_pad));
-    TS_HIP(hipMemset(h->d_MF0.p, 0, T_pad * sizeof(int64_t)));
+    TS_HIP(h->d_MF0.reserve(T));
+    TS_HIP(h->d_dMF0.reserve(T_pad));
+    TS_HIP(hipMemset(h->d_dMF0.p, 0, T_pad * sizeof(int64_t)));
     {   // sizes as 32-bit multiples of their common power of two, when they fit
         uint64_t all = 0, mx = 0;
         for (int32_t i = 0; i < N; ++i) {
@@ -237,10 +244,12 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
     // ---- MF0 with the evaluation kernel: start from the constant base_bytes and
     // "evict" every tensor with a negated size over its lifetime [alloc, free].
     {
-        DevBuf<int64_t> base, neg, offs, peak, mn;
+        DevBuf<int64_t> base, dbase, neg, offs, peak, mn;
         DevBuf<int32_t> alloc, fr, it, io, ir, arg;
-        TS_HIP(base.reserve(T_pad));
-        TS_HIP(hipMemset(base.p, 0, T_pad * sizeof(int64_t)));
+        TS_HIP(base.reserve(T));
+        TS_HIP(dbase.reserve(T_pad));     // differences of the constant timeline: base_bytes, 0, 0, ...
+        TS_HIP(hipMemset(dbase.p, 0, T_pad * sizeof(int64_t)));
+        TS_HIP(hipMemcpy(dbase.p, &d->base_bytes, sizeof(int64_t), hipMemcpyHostToDevice));
         TS_HIP(neg.reserve(N));
         TS_HIP(alloc.upload(d->alloc_step, N));
         TS_HIP(fr.upload(d->free_step, N));
@@ -256,11 +265,13 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
         EvalArgs a{};
         a.T = T; a.N = N; a.B = 1; a.o_min = -1; a.n_intervals = N;
         a.plan_offsets = offs.p; a.iv_tensor = it.p; a.iv_out = io.p; a.iv_in = ir.p;
-        a.size = neg.p; a.size_units = nullptr; a.MF0 = base.p; a.resident = h->d_MF0.p;
+        a.size = neg.p; a.size_units = nullptr; a.MF0 = base.p; a.dMF0 = dbase.p; a.resident = h->d_MF0.p;
         int rc = launch_eval(h, a, peak.p, arg.p, mn.p, nullptr);
         if (rc != TENSILE_OK) return rc;
         TS_HIP(hipMemcpy(&h->unscheduled_peak, peak.p, sizeof(int64_t), hipMemcpyDeviceToHost));
         TS_HIP(hipMemcpy(&h->unscheduled_argmax, arg.p, sizeof(int32_t), hipMemcpyDeviceToHost));
+        hipLaunchKernelGGL(difference_kernel, dim3((T + 255) / 256), dim3(256), 0, 0, T, h->d_MF0.p, h->d_dMF0.p);
+        TS_HIP(hipGetLastError());
     }
 
     // ---- C, x, per-gap windows
@@ -357,7 +368,7 @@ int tensile_eval_plans(const tensile_tas *tas, const tensile_plans *plans, int64
     a.plan_offsets = plans->plan_offsets;
     a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;
     a.size = tas->d_size.p; a.size_units = tas->d_size_units.p; a.size_shift = tas->size_shift;
-    a.MF0 = tas->d_MF0.p; a.resident = resident;
+    a.MF0 = tas->d_MF0.p; a.dMF0 = tas->d_dMF0.p; a.resident = resident;
     return launch_eval(tas, a, peak, argmax, min_resident, static_cast<hipStream_t>(hip_stream));
 }
 
