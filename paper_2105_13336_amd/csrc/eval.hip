@@ -80,6 +80,13 @@ __device__ __forceinline__ int64_t wave_scan_add(int64_t x) {
     return x;
 }
 
+// value of lane `src` (wave-uniform index), as a wave-uniform scalar
+__device__ __forceinline__ int64_t lane_value(int64_t x, int src) {
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(x), src);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(x >> 32), src);
+    return (static_cast<int64_t>(hi) << 32) | lo;
+}
+
 // value of lane 63, as a wave-uniform scalar
 __device__ __forceinline__ int64_t last_lane(int64_t x) {
     const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(x), 63);
@@ -127,7 +134,10 @@ __device__ __forceinline__ void opaque(uint32_t &x) { asm volatile("" : "+v"(x))
 __device__ __forceinline__ void opaque(int64_t &x) { asm volatile("" : "+v"(x)); }
 
 __device__ __forceinline__ void lds_add(int64_t *p, int64_t v) {
-    atomicAdd(reinterpret_cast<unsigned long long *>(p), static_cast<unsigned long long>(v));
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void lds_sub(int64_t *p, int64_t v) {
+    __hip_atomic_fetch_sub(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 __device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o, int32_t r) {
@@ -145,6 +155,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     typedef SizeReg<kNarrow> SR;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // the same number, known to be wave-uniform
     // XCD-aware decode: block w runs on XCD w % 8; give XCD x the plans = x (mod 8)
     const int64_t w = blockIdx.x;
     const int32_t xcd = static_cast<int32_t>(w & 7);
@@ -177,25 +188,53 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     // consecutive ones per thread: (first step without the bytes, first step with them again,
     // size).  An interval that cannot be applied, or a slot past the end of the list, gets
     // endpoints no tile contains.  [lo_t, hi_t] spans this thread's endpoints.
-    int32_t e0[R], e1[R];
+    // e0/e1 hold the endpoints in the skewed cell numbering of the LDS tile (skew is monotone and
+    // additive over multiples of 32, so skew(e) - skew(tile_lo) is the cell inside the tile)
+    uint32_t e0[R], e1[R];
     typename SR::type sz[R];
     int32_t lo_t = INT32_MAX, hi_t = -1;
+    if (k1 > k0) {   // block-uniform
+        // all loads are unconditional (indices clamped into the plan's list, tensor index
+        // clamped to 0) and issued back to back, then waited for once
+        const int32_t *pt = a.iv_tensor + k0, *po = a.iv_out + k0, *pr = a.iv_in + k0;
+        const uint32_t len = k1 - k0 < R * kEvalThreads ? static_cast<uint32_t>(k1 - k0) : R * kEvalThreads;
+        int32_t ti[R], vo[R], vr[R];
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        const int64_t k = k0 + static_cast<int64_t>(tid) * R + j;
-        int32_t i = -1, o = 0, r = 0;
-        if (k < k1) {
-            i = a.iv_tensor[k];
-            o = a.iv_out[k];
-            r = a.iv_in[k];
+        for (int j = 0; j < R; ++j) {
+            const uint32_t k = tid * R + j;
+            const uint32_t kc = k < len ? k : len - 1;
+            ti[j] = pt[kc];
+            vo[j] = po[kc];
+            vr[j] = pr[kc];
         }
-        const bool ok = applies(a, i, o, r);
-        e0[j] = ok ? o + 1 : INT32_MAX;
-        e1[j] = ok ? r : INT32_MAX;
-        sz[j] = ok ? SR::load(a, i) : 0;
-        if (ok) {
-            lo_t = o + 1 < lo_t ? o + 1 : lo_t;
-            hi_t = r > hi_t ? r : hi_t;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const bool ok = tid * R + j < len && applies(a, ti[j], vo[j], vr[j]);
+            ti[j] = ok ? ti[j] : -1;
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j) sz[j] = SR::load(a, ti[j] < 0 ? 0 : ti[j]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            if (ti[j] < 0) {
+                sz[j] = 0;
+                e0[j] = UINT32_MAX;
+                e1[j] = UINT32_MAX;
+            } else {
+                lo_t = vo[j] + 1 < lo_t ? vo[j] + 1 : lo_t;
+                hi_t = vr[j] > hi_t ? vr[j] : hi_t;
+                e0[j] = skew(static_cast<uint32_t>(vo[j] + 1));
+                e1[j] = skew(static_cast<uint32_t>(vr[j]));
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            e0[j] = UINT32_MAX;
+            e1[j] = UINT32_MAX;
+            sz[j] = 0;
         }
     }
     const int64_t k_over = k0 + static_cast<int64_t>(R) * kEvalThreads;   // the rest is re-read per tile
@@ -212,7 +251,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
             typename SR::type s32 = sz[j];
             opaque(s32);
             const int64_t s = SR::bytes(a, s32);
-            c += (e1[j] < seg_lo ? s : 0) - (e0[j] < seg_lo ? s : 0);
+            c += (e1[j] < skew(seg_lo) ? s : 0) - (e0[j] < skew(seg_lo) ? s : 0);
         }
         for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
             const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
@@ -248,15 +287,17 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
         // of whose lanes holds an endpoint in the tile's range skips its registers
         const bool mine = hi_t >= tile_lo && lo_t < tile_hi;
         if (__builtin_amdgcn_ballot_w64(mine) != 0) {
+            const uint32_t base_cell = skew(static_cast<uint32_t>(tile_lo)), n_cell = skew(tile_n);
 #pragma unroll
             for (int j = 0; j < R; ++j) {
-                const uint32_t u0 = static_cast<uint32_t>(e0[j] - tile_lo), u1 = static_cast<uint32_t>(e1[j] - tile_lo);
-                // keep the compact register form across tiles: without this the widened and the
-                // negated size are hoisted out of the tile loop and held in six registers per interval
+                const uint32_t u0 = e0[j] - base_cell, u1 = e1[j] - base_cell;
+                // keep the compact register form across tiles: without this the widened (and a
+                // negated) size is hoisted out of the tile loop and held in extra registers
                 typename SR::type s = sz[j];
                 opaque(s);
-                if (u0 < tile_n) lds_add(&delta[skew(u0)], -SR::bytes(a, s));
-                if (u1 < tile_n) lds_add(&delta[skew(u1)], SR::bytes(a, s));
+                const int64_t bytes = SR::bytes(a, s);
+                if (u0 < n_cell) lds_sub(&delta[u0], bytes);
+                if (u1 < n_cell) lds_add(&delta[u1], bytes);
             }
         }
         for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
@@ -288,13 +329,15 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
         const int64_t incl = wave_scan_add(v[kVpt - 1]);
         if (lane == 63) wave_tot[wave] = incl;
         __syncthreads();
-        int64_t base = carry + incl - v[kVpt - 1];
-#pragma unroll
-        for (int u = 0; u < kWaves; ++u) {
-            const int64_t tv = wave_tot[u];
-            if (u < wave) base += tv;
-            carry += tv;
-        }
+        // prefix over the eight wave totals: lanes 0-7 scan them, then every lane picks the
+        // sum of the waves before its own and the tile total by lane index
+        int64_t tot = wave_tot[lane & (kWaves - 1)];
+        tot += dpp_or_zero<0x111, 0xf>(tot);
+        tot += dpp_or_zero<0x112, 0xf>(tot);
+        tot += dpp_or_zero<0x114, 0xf>(tot);
+        const int64_t before = wave_u > 0 ? lane_value(tot, wave_u - 1) : 0;
+        const int64_t base = carry + before + incl - v[kVpt - 1];
+        carry += lane_value(tot, kWaves - 1);
 #pragma unroll
         for (int j = 0; j < kVpt; ++j) v[j] += base;
 
@@ -334,22 +377,27 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
 #pragma unroll
             for (int j = 0; j < kVpt / 2; ++j) mine_out[j] = ll2{v[2 * j], v[2 * j + 1]};
             __builtin_amdgcn_wave_barrier();
-            const int32_t wave_t0 = tile_lo + wave * (64 * kVpt);
+            const int32_t wave_t0 = tile_lo + wave_u * (64 * kVpt);
+            const ll2 *src = reinterpret_cast<const ll2 *>(stage) + lane + (lane >> 4);   // + 68 granules per j
+            if (kVec16 && tile_n == kEvalTile) {   // whole tile: no bounds checks (block-uniform)
+                ll2 *dst = reinterpret_cast<ll2 *>(row + wave_t0) + lane;
 #pragma unroll
-            for (int j = 0; j < kVpt / 2; ++j) {
-                const int g = j * 64 + lane;                         // granule in time order
-                const ll2 x = *reinterpret_cast<const ll2 *>(stage + 2 * (g + (g >> 4)));
-                const int32_t t = wave_t0 + 2 * g;
-                if (t + 2 <= tile_hi) {
-                    if constexpr (kVec16) {
-                        if constexpr (kNonTemporal) __builtin_nontemporal_store(x, reinterpret_cast<ll2 *>(row + t));
-                        else *reinterpret_cast<ll2 *>(row + t) = x;
-                    } else {
+                for (int j = 0; j < kVpt / 2; ++j) {
+                    const ll2 x = src[68 * j];
+                    if constexpr (kNonTemporal) __builtin_nontemporal_store(x, dst + 64 * j);
+                    else dst[64 * j] = x;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < kVpt / 2; ++j) {
+                    const ll2 x = src[68 * j];
+                    const int32_t t = wave_t0 + 2 * (j * 64 + lane);
+                    if (t + 2 <= tile_hi) {
                         row[t] = x[0];
                         row[t + 1] = x[1];
+                    } else if (t < tile_hi) {
+                        row[t] = x[0];
                     }
-                } else if (t < tile_hi) {
-                    row[t] = x[0];
                 }
             }
             __builtin_amdgcn_wave_barrier();
