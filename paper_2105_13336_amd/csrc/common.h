@@ -65,8 +65,9 @@ struct EvalArgs {
     const uint32_t *size_units;    // [N] size >> size_shift when that is exact and fits 32 bits, else null
     int32_t size_shift;
     const int64_t *MF0;            // [T] unscheduled timeline (read at segment starts only)
-    const int64_t *dMF0;           // [T rounded up to whole tiles] MF0[t] - MF0[t-1], dMF0[0] = MF0[0], zero padded
+    const int64_t *dMF0;           // MF0[t] - MF0[t-1], dMF0[0] = MF0[0]; zero padded to whole tiles plus one tile
     int64_t *resident;             // [B*T] or null
+    int64_t tail_threshold;        // plans with more intervals than this belong to the tail kernel
     int32_t S;                     // segments per plan
     int32_t tiles_per_seg;
     int64_t *out_max;              // S == 1: peak[B]; else partials [B*S]

@@ -18,6 +18,10 @@
 //    the footprint itself and no separate "+ MF0" pass is needed.  The next
 //    tile's dMF0 is loaded while the current tile is processed and written into
 //    the cells as the scan reads them.
+//  * The memory counter of a wavefront retires loads and stores in order, so a
+//    load issued after a tile's stores can only be waited for together with
+//    them.  The stores of a tile are therefore issued one iteration late, right
+//    after the loads of that iteration, from the staging area.
 //  * The plan's intervals are read once into registers (endpoints and size; R
 //    per thread, chosen on the host from the average plan length; a longer plan
 //    re-reads its tail from memory per tile).  Threads take CONSECUTIVE
@@ -43,6 +47,7 @@
 #include "common.h"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace tensile {
 
@@ -144,8 +149,18 @@ __device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o,
     return static_cast<uint32_t>(i) < static_cast<uint32_t>(a.N) && o >= a.o_min && r <= a.T && r > o;
 }
 
-template <int R, bool kNarrow, bool kVec16, bool kNonTemporal>
+// kTail == false: the common kernel.  It only takes plans whose intervals all fit the registers
+// (at most R per thread) and has no memory loads in its tile loop besides the dMF0 prefetch, so
+// the compiler can wait for that prefetch with an exact counter value instead of draining every
+// outstanding store.  kTail == true: the kernel for the remaining (longer) plans, which re-reads
+// the intervals beyond the registers from memory for every tile.  Both are launched for every
+// batch; a workgroup whose plan belongs to the other kernel exits at once.
+// kOut: 0 = no footprint rows are written (peaks only), 1 = rows written with 8-byte stores
+// (odd T or unaligned buffer), 2 = with 16-byte stores.  A compile-time property so that
+// every path through the tile loop issues the same memory operations.
+template <int R, bool kTail, bool kNarrow, int kOut>
 __device__ __forceinline__ void eval_body(const EvalArgs &a) {
+    constexpr bool kStore = kOut != 0, kVec16 = kOut == 2;
     __shared__ __attribute__((aligned(16))) int64_t delta[kTileCells];
     __shared__ __attribute__((aligned(16))) int64_t stage_all[kWaves * kStageStride];
     __shared__ int64_t wave_tot[kWaves];
@@ -169,6 +184,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     if (k0 < 0) k0 = 0;
     if (k1 > a.n_intervals) k1 = a.n_intervals;
     if (k1 < k0) k1 = k0;
+    if ((k1 - k0 > a.tail_threshold) != kTail) return;   // block-uniform: the other kernel's plan
 
     const int64_t seg_len = static_cast<int64_t>(a.tiles_per_seg) * kEvalTile;
     const int64_t seg_lo64 = seg * seg_len;
@@ -253,11 +269,13 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
             const int64_t s = SR::bytes(a, s32);
             c += (e1[j] < skew(seg_lo) ? s : 0) - (e0[j] < skew(seg_lo) ? s : 0);
         }
-        for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
-            const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
-            if (!applies(a, i, o, r)) continue;
-            const int64_t s = a.size[i];
-            c += (r < seg_lo ? s : 0) - (o + 1 < seg_lo ? s : 0);
+        if constexpr (kTail) {
+            for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
+                const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
+                if (!applies(a, i, o, r)) continue;
+                const int64_t s = a.size[i];
+                c += (r < seg_lo ? s : 0) - (o + 1 < seg_lo ? s : 0);
+            }
         }
         c = last_lane(wave_scan_add(c));
         if (lane == 0) carry_part[wave] = c;
@@ -268,20 +286,55 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     }
 
     Best best{INT64_MIN, INT64_MAX, INT32_MAX};
-    int64_t *row = a.resident ? a.resident + static_cast<int64_t>(plan) * a.T : nullptr;
+    int64_t *row = kStore ? a.resident + static_cast<int64_t>(plan) * a.T : nullptr;
     __syncthreads();   // the first tile's cells are in place
 
-    for (int32_t tile_lo = seg_lo; tile_lo < seg_hi; tile_lo += kEvalTile) {
+    // Stores of one tile from the wave's staging area: 16 contiguous bytes per lane per
+    // instruction.  `full` (block-uniform) = whole tile and 16-byte aligned rows: no bounds checks.
+    auto store_tile = [&](int32_t t_lo, int32_t t_hi) {
+        const int32_t wave_t0 = t_lo + wave_u * (64 * kVpt);
+        const ll2 *src = reinterpret_cast<const ll2 *>(stage) + lane + (lane >> 4);   // + 68 granules per j
+        if (kVec16 && t_hi - t_lo == kEvalTile) {
+            ll2 *dst = reinterpret_cast<ll2 *>(row + wave_t0) + lane;
+#pragma unroll
+            for (int j = 0; j < kVpt / 2; ++j) {
+                dst[64 * j] = src[68 * j];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kVpt / 2; ++j) {
+                const ll2 x = src[68 * j];
+                const int32_t t = wave_t0 + 2 * (j * 64 + lane);
+                if (t + 2 <= t_hi) {
+                    row[t] = x[0];
+                    row[t + 1] = x[1];
+                } else if (t < t_hi) {
+                    row[t] = x[0];
+                }
+            }
+        }
+    };
+
+    // One tile.  The memory operations of an iteration are, in this order: the loads of the next
+    // tile's dMF0, then the stores of the PREVIOUS tile (software pipelining: its results wait in
+    // the staging area).  The scan, which needs the loads, can then wait until only those stores
+    // are outstanding instead of draining them.  The first tile has no previous one and is a
+    // separate instantiation so that this holds on every path.
+    auto do_tile = [&](int32_t tile_lo, auto first_tag) {
+        constexpr bool kFirst = decltype(first_tag)::value;
         const int32_t tile_hi = tile_lo + kEvalTile < seg_hi ? tile_lo + kEvalTile : seg_hi;
         const uint32_t tile_n = static_cast<uint32_t>(tile_hi - tile_lo);
         // delta holds dMF0 of this tile: written before the loop, or by the scan of the previous
-        // tile ahead of its barrier.
-
-        // next tile's dMF0, in flight while this tile is processed (zeros after the last tile)
-        const bool more = tile_lo + kEvalTile < seg_hi;
+        // tile ahead of its barrier.  dMF0 has one whole tile of padding past the end, so the load
+        // of the "next" tile is unconditional (what it brings is never scanned in that case).
 #pragma unroll
         for (int j = 0; j < kVpt / 2; ++j)
-            fill[j] = more ? reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kEvalTile + my)[j] : ll2{0, 0};
+            fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kEvalTile + my)[j];
+        if constexpr (!kFirst && kStore) {
+            __builtin_amdgcn_wave_barrier();
+            store_tile(tile_lo - kEvalTile, tile_lo);
+            __builtin_amdgcn_wave_barrier();
+        }
 
         // ---- scatter: endpoints of this plan that fall into [tile_lo, tile_hi); a wavefront none
         // of whose lanes holds an endpoint in the tile's range skips its registers
@@ -300,14 +353,16 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
                 if (u1 < n_cell) lds_add(&delta[u1], bytes);
             }
         }
-        for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
-            const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
-            if (!applies(a, i, o, r)) continue;
-            const uint32_t u0 = static_cast<uint32_t>(o + 1 - tile_lo), u1 = static_cast<uint32_t>(r - tile_lo);
-            if ((u0 < tile_n) | (u1 < tile_n)) {
-                const int64_t s = a.size[i];
-                if (u0 < tile_n) lds_add(&delta[skew(u0)], -s);
-                if (u1 < tile_n) lds_add(&delta[skew(u1)], s);
+        if constexpr (kTail) {
+            for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
+                const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
+                if (!applies(a, i, o, r)) continue;
+                const uint32_t u0 = static_cast<uint32_t>(o + 1 - tile_lo), u1 = static_cast<uint32_t>(r - tile_lo);
+                if ((u0 < tile_n) | (u1 < tile_n)) {
+                    const int64_t s = a.size[i];
+                    if (u0 < tile_n) lds_add(&delta[skew(u0)], -s);
+                    if (u1 < tile_n) lds_add(&delta[skew(u1)], s);
+                }
             }
         }
         __syncthreads();
@@ -370,38 +425,24 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
             }
         }
 
-        // ---- store: transpose the wave's 512 results through its staging area so that every
-        // store instruction writes 16 contiguous bytes per lane
-        if (row) {
+        // ---- park the results in the wave's staging area (lane-contiguous, skewed); they are
+        // stored at the top of the next iteration, or after the loop
+        if constexpr (kStore) {
             ll2 *mine_out = reinterpret_cast<ll2 *>(stage + lane * kVpt + 2 * (lane >> 2));
 #pragma unroll
             for (int j = 0; j < kVpt / 2; ++j) mine_out[j] = ll2{v[2 * j], v[2 * j + 1]};
-            __builtin_amdgcn_wave_barrier();
-            const int32_t wave_t0 = tile_lo + wave_u * (64 * kVpt);
-            const ll2 *src = reinterpret_cast<const ll2 *>(stage) + lane + (lane >> 4);   // + 68 granules per j
-            if (kVec16 && tile_n == kEvalTile) {   // whole tile: no bounds checks (block-uniform)
-                ll2 *dst = reinterpret_cast<ll2 *>(row + wave_t0) + lane;
-#pragma unroll
-                for (int j = 0; j < kVpt / 2; ++j) {
-                    const ll2 x = src[68 * j];
-                    if constexpr (kNonTemporal) __builtin_nontemporal_store(x, dst + 64 * j);
-                    else dst[64 * j] = x;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < kVpt / 2; ++j) {
-                    const ll2 x = src[68 * j];
-                    const int32_t t = wave_t0 + 2 * (j * 64 + lane);
-                    if (t + 2 <= tile_hi) {
-                        row[t] = x[0];
-                        row[t + 1] = x[1];
-                    } else if (t < tile_hi) {
-                        row[t] = x[0];
-                    }
-                }
-            }
-            __builtin_amdgcn_wave_barrier();
         }
+    };
+
+    do_tile(seg_lo, std::true_type{});
+    int32_t last_lo = seg_lo;
+    for (int32_t tile_lo = seg_lo + kEvalTile; tile_lo < seg_hi; tile_lo += kEvalTile) {
+        do_tile(tile_lo, std::false_type{});
+        last_lo = tile_lo;
+    }
+    if constexpr (kStore) {
+        __builtin_amdgcn_wave_barrier();
+        store_tile(last_lo, seg_hi);
     }
 
     // ---- (max, earliest argmax, min) of the segment
@@ -428,14 +469,15 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
 }
 
 // Two workgroups per CU (four waves per SIMD) need at most 128 VGPRs; up to 12 intervals per
-// thread fit without spilling.  The 16-interval variant is left to the register allocator.
-template <int R, bool kNarrow, bool kVec16, bool kNonTemporal>
+// thread fit without spilling.  The tail kernel keeps 16 and is left to the register allocator.
+template <int R, bool kNarrow, int kOut>
 __global__ __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void eval_kernel(const EvalArgs a) {
-    eval_body<R, kNarrow, kVec16, kNonTemporal>(a);
+    eval_body<R, false, kNarrow, kOut>(a);
 }
-template <bool kNarrow, bool kVec16, bool kNonTemporal>
-__global__ __launch_bounds__(kEvalThreads) void eval_kernel_r16(const EvalArgs a) {
-    eval_body<16, kNarrow, kVec16, kNonTemporal>(a);
+constexpr int kTailR = 16;
+template <bool kNarrow, int kOut>
+__global__ __launch_bounds__(kEvalThreads) void eval_tail_kernel(const EvalArgs a) {
+    eval_body<kTailR, true, kNarrow, kOut>(a);
 }
 
 // Combine the per-segment partials of each plan; segments are in time order, so
@@ -509,43 +551,37 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
         a.out_arg = sc.part_arg.p;
         a.out_min = sc.part_min.p;
     }
-    const bool vec16 = a.resident && (a.T % 2 == 0) && (reinterpret_cast<uintptr_t>(a.resident) % 16 == 0);
-    const bool nt = env_int("TENSILE_EVAL_NT", 0) != 0;   // plain stores measure faster than nontemporal ones
+    const int out = !a.resident ? 0
+                    : ((a.T % 2 == 0) && (reinterpret_cast<uintptr_t>(a.resident) % 16 == 0)) ? 2 : 1;
     const bool narrow = a.size_units != nullptr;
-    // intervals per thread kept in registers: sized for the average plan with some slack
-    // (plans longer than R*threads re-read their tail from memory in every tile)
+    // intervals per thread kept in registers by the common kernel: sized for the average plan
+    // with some slack; longer plans are left to the tail kernel
     const int64_t avg_k = (a.n_intervals + a.B - 1) / a.B;
     int64_t r_need = (avg_k + avg_k / 8 + kEvalThreads - 1) / kEvalThreads;
     const int r_forced = env_int("TENSILE_EVAL_R", 0);   // tuning knob
     if (r_forced > 0) r_need = r_forced;
+    const int r_fast = r_need <= 4 ? 4 : r_need <= 8 ? 8 : 12;
+    a.tail_threshold = static_cast<int64_t>(r_fast) * kEvalThreads;
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kEvalThreads);
-#define TS_LAUNCH_EVAL2(R, NARROW)                                                                                  \
-    do {                                                                                                            \
-        if (vec16 && nt) hipLaunchKernelGGL((eval_kernel<R, NARROW, true, true>), grid, block, 0, stream, a);       \
-        else if (vec16) hipLaunchKernelGGL((eval_kernel<R, NARROW, true, false>), grid, block, 0, stream, a);       \
-        else if (nt) hipLaunchKernelGGL((eval_kernel<R, NARROW, false, true>), grid, block, 0, stream, a);          \
-        else hipLaunchKernelGGL((eval_kernel<R, NARROW, false, false>), grid, block, 0, stream, a);                 \
+#define TS_LAUNCH_OUT(KERNEL, ...)                                                                   \
+    do {                                                                                             \
+        if (out == 2) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 2>), grid, block, 0, stream, a);       \
+        else if (out == 1) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 1>), grid, block, 0, stream, a);  \
+        else hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 0>), grid, block, 0, stream, a);                \
     } while (0)
-#define TS_LAUNCH_EVAL(R)                        \
-    do {                                         \
-        if (narrow) TS_LAUNCH_EVAL2(R, true);    \
-        else TS_LAUNCH_EVAL2(R, false);          \
+#define TS_LAUNCH_EVAL(R)                                   \
+    do {                                                    \
+        if (narrow) TS_LAUNCH_OUT(eval_kernel, R, true);    \
+        else TS_LAUNCH_OUT(eval_kernel, R, false);          \
     } while (0)
-#define TS_LAUNCH_R16(NARROW)                                                                                     \
-    do {                                                                                                          \
-        if (vec16 && nt) hipLaunchKernelGGL((eval_kernel_r16<NARROW, true, true>), grid, block, 0, stream, a);    \
-        else if (vec16) hipLaunchKernelGGL((eval_kernel_r16<NARROW, true, false>), grid, block, 0, stream, a);    \
-        else if (nt) hipLaunchKernelGGL((eval_kernel_r16<NARROW, false, true>), grid, block, 0, stream, a);       \
-        else hipLaunchKernelGGL((eval_kernel_r16<NARROW, false, false>), grid, block, 0, stream, a);              \
-    } while (0)
-    if (r_need <= 4) TS_LAUNCH_EVAL(4);
-    else if (r_need <= 8) TS_LAUNCH_EVAL(8);
-    else if (r_need <= 12) TS_LAUNCH_EVAL(12);
-    else if (narrow) TS_LAUNCH_R16(true);
-    else TS_LAUNCH_R16(false);
-#undef TS_LAUNCH_R16
+    if (r_fast == 4) TS_LAUNCH_EVAL(4);
+    else if (r_fast == 8) TS_LAUNCH_EVAL(8);
+    else TS_LAUNCH_EVAL(12);
+    TS_HIP(hipGetLastError());
+    if (narrow) TS_LAUNCH_OUT(eval_tail_kernel, true);
+    else TS_LAUNCH_OUT(eval_tail_kernel, false);
 #undef TS_LAUNCH_EVAL
-#undef TS_LAUNCH_EVAL2
+#undef TS_LAUNCH_OUT
     TS_HIP(hipGetLastError());
     if (S > 1) {
         const int threads = 256;

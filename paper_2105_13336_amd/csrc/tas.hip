@@ -220,7 +220,8 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
     TS_HIP(h->d_gq.upload(gq.data(), gq.size()));
     TS_HIP(h->d_gtensor.upload(gt.data(), gt.size()));
     TS_HIP(h->d_gwin.reserve(gp.size()));
-    const size_t T_pad = (static_cast<size_t>(T) + kEvalTile - 1) / kEvalTile * kEvalTile;
+    // whole tiles plus one: the evaluation kernel prefetches one tile ahead unconditionally
+    const size_t T_pad = ((static_cast<size_t>(T) + kEvalTile - 1) / kEvalTile + 1) * kEvalTile;
     TS_HIP(h->d_MF0.reserve(T));
     TS_HIP(h->d_dMF0.reserve(T_pad));
     TS_HIP(hipMemset(h->d_dMF0.p, 0, T_pad * sizeof(int64_t)));
