@@ -161,7 +161,10 @@ __device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o,
 template <int R, bool kTail, bool kNarrow, int kOut>
 __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     constexpr bool kStore = kOut != 0, kVec16 = kOut == 2;
-    __shared__ __attribute__((aligned(16))) int64_t delta[kTileCells];
+    // the tile, followed by 64 "trash" cells: a lane whose endpoint lies outside the tile adds to
+    // trash[lane] instead (never read), which keeps the scatter free of branches and of
+    // execution-mask changes
+    __shared__ __attribute__((aligned(16))) int64_t delta[kTileCells + 64];
     __shared__ __attribute__((aligned(16))) int64_t stage_all[kWaves * kStageStride];
     __shared__ int64_t wave_tot[kWaves];
     __shared__ int64_t carry_part[kWaves];
@@ -341,6 +344,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
         const bool mine = hi_t >= tile_lo && lo_t < tile_hi;
         if (__builtin_amdgcn_ballot_w64(mine) != 0) {
             const uint32_t base_cell = skew(static_cast<uint32_t>(tile_lo)), n_cell = skew(tile_n);
+            const uint32_t trash = kTileCells + lane;
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const uint32_t u0 = e0[j] - base_cell, u1 = e1[j] - base_cell;
@@ -349,8 +353,8 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
                 typename SR::type s = sz[j];
                 opaque(s);
                 const int64_t bytes = SR::bytes(a, s);
-                if (u0 < n_cell) lds_sub(&delta[u0], bytes);
-                if (u1 < n_cell) lds_add(&delta[u1], bytes);
+                lds_sub(&delta[u0 < n_cell ? u0 : trash], bytes);
+                lds_add(&delta[u1 < n_cell ? u1 : trash], bytes);
             }
         }
         if constexpr (kTail) {
@@ -399,11 +403,31 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
         // ---- reduce
         const int32_t t0 = tile_lo + my;
         if (t0 + kVpt <= tile_hi) {
-            int64_t cm = v[0], cn = v[0];
+            // The lane's 8 values almost always share their upper 32 bits; then max and min are
+            // those of the (unsigned) lower halves, single instructions without a condition code.
+            int64_t cm, cn;
+            {
+                const int32_t h0 = static_cast<int32_t>(v[0] >> 32);
+                uint32_t diff = 0, lmx = static_cast<uint32_t>(v[0]), lmn = lmx;
 #pragma unroll
-            for (int j = 1; j < kVpt; ++j) {
-                cm = v[j] > cm ? v[j] : cm;
-                cn = v[j] < cn ? v[j] : cn;
+                for (int j = 1; j < kVpt; ++j) {
+                    diff |= static_cast<uint32_t>(static_cast<int32_t>(v[j] >> 32) ^ h0);
+                    const uint32_t l = static_cast<uint32_t>(v[j]);
+                    lmx = l > lmx ? l : lmx;
+                    lmn = l < lmn ? l : lmn;
+                }
+                if (__builtin_amdgcn_ballot_w64(diff != 0) == 0) {   // wave-uniform
+                    cm = (static_cast<int64_t>(h0) << 32) | lmx;
+                    cn = (static_cast<int64_t>(h0) << 32) | lmn;
+                } else {
+                    cm = v[0];
+                    cn = v[0];
+#pragma unroll
+                    for (int j = 1; j < kVpt; ++j) {
+                        cm = v[j] > cm ? v[j] : cm;
+                        cn = v[j] < cn ? v[j] : cn;
+                    }
+                }
             }
             if (cm > best.mx) {
                 best.mx = cm;
