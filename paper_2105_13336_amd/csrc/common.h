@@ -51,8 +51,8 @@ struct DevBuf {
 };
 
 // Launch geometry of the evaluation kernel (see eval.hip).
-constexpr int kEvalThreads = 512;
-constexpr int kEvalTile = 4096;   // steps per LDS difference tile
+constexpr int kEvalThreads = 1024;
+constexpr int kEvalTile = 8192;   // steps per LDS difference tile
 
 // Arguments of the fused scatter + scan + reduce kernel.
 struct EvalArgs {

@@ -55,7 +55,7 @@ namespace {
 
 constexpr int kWaves = kEvalThreads / 64;
 constexpr int kVpt = kEvalTile / kEvalThreads;   // steps per lane per tile
-static_assert(kVpt == 8, "the scan below is written for 8 steps per lane");
+static_assert(kWaves <= 16 && kVpt == 8, "the scan below is written for 8 steps per lane");
 // LDS layouts are skewed: 16-byte granule g lives at granule g + (g >> 4), i.e. cell u at
 // u + 2 * (u >> 5).  A lane's four granules stay contiguous (they never straddle a multiple of 16).
 constexpr int kTileCells = kEvalTile + 2 * (kEvalTile >> 5);          // 4352
@@ -292,37 +292,33 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     int64_t *row = kStore ? a.resident + static_cast<int64_t>(plan) * a.T : nullptr;
     __syncthreads();   // the first tile's cells are in place
 
-    // Stores of one tile from the wave's staging area: 16 contiguous bytes per lane per
-    // instruction.  `full` (block-uniform) = whole tile and 16-byte aligned rows: no bounds checks.
-    auto store_tile = [&](int32_t t_lo, int32_t t_hi) {
+    // One quarter (granule row j of 4) of a tile's stores from the wave's staging area: 16
+    // contiguous bytes per lane, 1 KB per wavefront.  A whole tile with 16-byte aligned rows
+    // (block-uniform) needs no bounds checks.
+    auto store_part = [&](int32_t t_lo, int32_t t_hi, int j) {
         const int32_t wave_t0 = t_lo + wave_u * (64 * kVpt);
-        const ll2 *src = reinterpret_cast<const ll2 *>(stage) + lane + (lane >> 4);   // + 68 granules per j
+        const ll2 x = (reinterpret_cast<const ll2 *>(stage) + lane + (lane >> 4))[68 * j];
         if (kVec16 && t_hi - t_lo == kEvalTile) {
-            ll2 *dst = reinterpret_cast<ll2 *>(row + wave_t0) + lane;
-#pragma unroll
-            for (int j = 0; j < kVpt / 2; ++j) {
-                dst[64 * j] = src[68 * j];
-            }
+            (reinterpret_cast<ll2 *>(row + wave_t0) + lane)[64 * j] = x;   // plain store: nontemporal ones measured slower
         } else {
-#pragma unroll
-            for (int j = 0; j < kVpt / 2; ++j) {
-                const ll2 x = src[68 * j];
-                const int32_t t = wave_t0 + 2 * (j * 64 + lane);
-                if (t + 2 <= t_hi) {
-                    row[t] = x[0];
-                    row[t + 1] = x[1];
-                } else if (t < t_hi) {
-                    row[t] = x[0];
-                }
+            const int32_t t = wave_t0 + 2 * (j * 64 + lane);
+            if (t + 2 <= t_hi) {
+                row[t] = x[0];
+                row[t + 1] = x[1];
+            } else if (t < t_hi) {
+                row[t] = x[0];
             }
         }
     };
 
-    // One tile.  The memory operations of an iteration are, in this order: the loads of the next
-    // tile's dMF0, then the stores of the PREVIOUS tile (software pipelining: its results wait in
-    // the staging area).  The scan, which needs the loads, can then wait until only those stores
-    // are outstanding instead of draining them.  The first tile has no previous one and is a
-    // separate instantiation so that this holds on every path.
+    // One tile.  The results of a tile are parked in the staging area and stored during the NEXT
+    // iteration (software pipelining), one quarter after each phase.  Two reasons: (1) the loads
+    // of the next tile's dMF0 come first in the iteration, so the scan can wait for them with an
+    // exact counter value while younger stores stay in flight; (2) all wavefronts of a CU share
+    // one in-order memory pipeline that drains at the CU's share of the HBM write rate: a burst
+    // of every wavefront's stores at one point of the iteration backs it up and the wavefronts
+    // behind arrive late at the next barrier.  The first tile has no previous one and is a
+    // separate instantiation so that the same operations are issued on every path.
     auto do_tile = [&](int32_t tile_lo, auto first_tag) {
         constexpr bool kFirst = decltype(first_tag)::value;
         const int32_t tile_hi = tile_lo + kEvalTile < seg_hi ? tile_lo + kEvalTile : seg_hi;
@@ -333,10 +329,10 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
 #pragma unroll
         for (int j = 0; j < kVpt / 2; ++j)
             fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kEvalTile + my)[j];
-        if constexpr (!kFirst && kStore) {
+        constexpr bool kPrev = !kFirst && kStore;
+        if constexpr (kPrev) {
             __builtin_amdgcn_wave_barrier();
-            store_tile(tile_lo - kEvalTile, tile_lo);
-            __builtin_amdgcn_wave_barrier();
+            store_part(tile_lo - kEvalTile, tile_lo, 0);
         }
 
         // ---- scatter: endpoints of this plan that fall into [tile_lo, tile_hi); a wavefront none
@@ -369,6 +365,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
                 }
             }
         }
+        if constexpr (kPrev) store_part(tile_lo - kEvalTile, tile_lo, 1);
         __syncthreads();
 
         // ---- local scan of this lane's 8 cells; the cells receive the next tile's dMF0
@@ -387,6 +384,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
         for (int j = 1; j < kVpt; ++j) v[j] += v[j - 1];
         const int64_t incl = wave_scan_add(v[kVpt - 1]);
         if (lane == 63) wave_tot[wave] = incl;
+        if constexpr (kPrev) store_part(tile_lo - kEvalTile, tile_lo, 2);
         __syncthreads();
         // prefix over the eight wave totals: lanes 0-7 scan them, then every lane picks the
         // sum of the waves before its own and the tile total by lane index
@@ -394,6 +392,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
         tot += dpp_or_zero<0x111, 0xf>(tot);
         tot += dpp_or_zero<0x112, 0xf>(tot);
         tot += dpp_or_zero<0x114, 0xf>(tot);
+        if constexpr (kWaves > 8) tot += dpp_or_zero<0x118, 0xf>(tot);
         const int64_t before = wave_u > 0 ? lane_value(tot, wave_u - 1) : 0;
         const int64_t base = carry + before + incl - v[kVpt - 1];
         carry += lane_value(tot, kWaves - 1);
@@ -450,7 +449,11 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
         }
 
         // ---- park the results in the wave's staging area (lane-contiguous, skewed); they are
-        // stored at the top of the next iteration, or after the loop
+        // stored during the next iteration, or after the loop
+        if constexpr (kPrev) {
+            store_part(tile_lo - kEvalTile, tile_lo, 3);
+            __builtin_amdgcn_wave_barrier();
+        }
         if constexpr (kStore) {
             ll2 *mine_out = reinterpret_cast<ll2 *>(stage + lane * kVpt + 2 * (lane >> 2));
 #pragma unroll
@@ -466,7 +469,8 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     }
     if constexpr (kStore) {
         __builtin_amdgcn_wave_barrier();
-        store_tile(last_lo, seg_hi);
+#pragma unroll
+        for (int j = 0; j < kVpt / 2; ++j) store_part(last_lo, seg_hi, j);
     }
 
     // ---- (max, earliest argmax, min) of the segment
@@ -498,7 +502,10 @@ template <int R, bool kNarrow, int kOut>
 __global__ __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void eval_kernel(const EvalArgs a) {
     eval_body<R, false, kNarrow, kOut>(a);
 }
-constexpr int kTailR = 16;
+// intervals per thread held in registers: three sizes for the common kernel (2048, 4096 and
+// 6144 intervals per plan), 8192 for the tail kernel
+constexpr int kRSmall = 2048 / kEvalThreads, kRMid = 4096 / kEvalThreads, kRBig = 6144 / kEvalThreads;
+constexpr int kTailR = 8192 / kEvalThreads;
 template <bool kNarrow, int kOut>
 __global__ __launch_bounds__(kEvalThreads) void eval_tail_kernel(const EvalArgs a) {
     eval_body<kTailR, true, kNarrow, kOut>(a);
@@ -584,7 +591,7 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     int64_t r_need = (avg_k + avg_k / 8 + kEvalThreads - 1) / kEvalThreads;
     const int r_forced = env_int("TENSILE_EVAL_R", 0);   // tuning knob
     if (r_forced > 0) r_need = r_forced;
-    const int r_fast = r_need <= 4 ? 4 : r_need <= 8 ? 8 : 12;
+    const int r_fast = r_need <= kRSmall ? kRSmall : r_need <= kRMid ? kRMid : kRBig;
     a.tail_threshold = static_cast<int64_t>(r_fast) * kEvalThreads;
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kEvalThreads);
 #define TS_LAUNCH_OUT(KERNEL, ...)                                                                   \
@@ -598,9 +605,9 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
         if (narrow) TS_LAUNCH_OUT(eval_kernel, R, true);    \
         else TS_LAUNCH_OUT(eval_kernel, R, false);          \
     } while (0)
-    if (r_fast == 4) TS_LAUNCH_EVAL(4);
-    else if (r_fast == 8) TS_LAUNCH_EVAL(8);
-    else TS_LAUNCH_EVAL(12);
+    if (r_fast == kRSmall) TS_LAUNCH_EVAL(kRSmall);
+    else if (r_fast == kRMid) TS_LAUNCH_EVAL(kRMid);
+    else TS_LAUNCH_EVAL(kRBig);
     TS_HIP(hipGetLastError());
     if (narrow) TS_LAUNCH_OUT(eval_tail_kernel, true);
     else TS_LAUNCH_OUT(eval_tail_kernel, false);
