@@ -78,8 +78,8 @@ struct EvalArgs {
 struct Scratch {
     DevBuf<int64_t> part_max, part_min;
     DevBuf<int32_t> part_arg;
-    DevBuf<int64_t> rowmax;        // score: one T-word row per resident workgroup
-    int32_t rowmax_slots = 0;
+    DevBuf<int64_t> rowmax;        // score: chunk-maxima tables, one set per resident workgroup
+    DevBuf<int32_t> cand_map;      // score: tensor -> candidate gap, one array per resident workgroup
 };
 
 }  // namespace tensile

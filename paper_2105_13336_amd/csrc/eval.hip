@@ -45,6 +45,7 @@
 // (ids are dealt round-robin to the 8 XCDs, each with its own L2): the plan's
 // interval list is then fetched from HBM once and re-read from that L2.
 #include "common.h"
+#include "wave_ops.h"
 
 #include <cstdlib>
 #include <type_traits>
@@ -62,42 +63,6 @@ constexpr int kTileCells = kEvalTile + 2 * (kEvalTile >> 5);          // 4352
 constexpr int kStageCells = 64 * kVpt + 2 * ((64 * kVpt) >> 5) + 2;    // 546 per wave, rounded up below
 constexpr int kStageStride = (kStageCells + 7) / 8 * 8;               // 552
 __device__ __forceinline__ uint32_t skew(uint32_t u) { return u + ((u >> 5) << 1); }
-
-// One DPP move of a 64-bit value (two 32-bit halves); lanes without a source, or
-// masked off, receive 0, so the caller can add the result unconditionally.
-template <int kCtrl, int kRowMask>
-__device__ __forceinline__ int64_t dpp_or_zero(int64_t x) {
-    const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(x), kCtrl, kRowMask, 0xf, true);
-    const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(x >> 32), kCtrl, kRowMask, 0xf, true);
-    return (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
-}
-
-// Inclusive add-scan over the 64 lanes: shifts by 1, 2, 4, 8 inside each row of
-// 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3, then lane 31
-// to rows 2 and 3.
-__device__ __forceinline__ int64_t wave_scan_add(int64_t x) {
-    x += dpp_or_zero<0x111, 0xf>(x);   // row_shr:1
-    x += dpp_or_zero<0x112, 0xf>(x);   // row_shr:2
-    x += dpp_or_zero<0x114, 0xf>(x);   // row_shr:4
-    x += dpp_or_zero<0x118, 0xf>(x);   // row_shr:8
-    x += dpp_or_zero<0x142, 0xa>(x);   // row_bcast:15 into rows 1, 3
-    x += dpp_or_zero<0x143, 0xc>(x);   // row_bcast:31 into rows 2, 3
-    return x;
-}
-
-// value of lane `src` (wave-uniform index), as a wave-uniform scalar
-__device__ __forceinline__ int64_t lane_value(int64_t x, int src) {
-    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(x), src);
-    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(x >> 32), src);
-    return (static_cast<int64_t>(hi) << 32) | lo;
-}
-
-// value of lane 63, as a wave-uniform scalar
-__device__ __forceinline__ int64_t last_lane(int64_t x) {
-    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(x), 63);
-    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(x >> 32), 63);
-    return (static_cast<int64_t>(hi) << 32) | lo;
-}
 
 struct Best {
     int64_t mx, mn;
