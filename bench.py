@@ -23,6 +23,23 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "eval_kernel_c3_hbm_traffic.txt")
+
+
+def measured_traffic(config: int):
+    """HBM bytes per eval launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
+    workload (the summary under profiles/ gives the commands); None for other workloads."""
+    if config != 3 or not os.path.exists(TRAFFIC_FILE):
+        return None
+    vals = {}
+    with open(TRAFFIC_FILE) as f:
+        for line in f:
+            if "=" in line and not line.startswith("#"):
+                k, v = line.split("=", 1)
+                vals[k.strip()] = float(v.split()[0])
+    if "fetch_bytes_per_launch" in vals and "write_bytes_per_launch" in vals:
+        return vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"]
+    return None
 
 
 def log(msg: str) -> None:
@@ -36,6 +53,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
+    ap.add_argument("--cpu-plans", type=int, default=1536, help="plans in the oracle's sample (about 10-20 s of CPU work)")
     ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-planner leg")
     ap.add_argument("--eval-only", action="store_true", help="steps run tensile_eval_plans alone (profiling aid)")
     args = ap.parse_args()
@@ -113,7 +131,7 @@ def main() -> int:
         "config": {"workload": f"configs[{args.config}] {cfg.name}", "B": B, "T": T, "N": N, "intervals": K,
                    "step": "eval_plans" if args.eval_only else "eval_plans+score_candidates"},
         "roofline": {"kernel": "eval_kernel (tensile_eval_plans)", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.config),
                      "algorithmic_bytes": eval_bytes, "avg_launch_ms": eval_avg},
         "rows": {
             "eval_plans": {"ms": eval_avg, "ms_min": float(np.min(eval_ms)),
@@ -135,25 +153,26 @@ def main() -> int:
 
     if not args.no_cpu:
         from oracle import oracle as O
-        ns = min(B, 384)
+        ns = min(B, args.cpu_plans)
         sample = pl.select(np.arange(ns))
         log(f"cpu baseline: oracle on the first {ns} plans")
         MF0 = O.base_timeline(tas)
         tc0 = time.perf_counter()
         r0, p0, a0, m0 = O.eval_plans(tas, sample, MF0=MF0)
         tc1 = time.perf_counter()
-        nsc = ns if args.eval_only else min(ns, 384)
         if not args.eval_only:
-            O.score_plans(tas, sample, r0, p0, a0, rows=range(nsc))
+            s0, o0, i0 = O.score_plans(tas, sample, r0, p0, a0)
         tc2 = time.perf_counter()
-        cpu_s = (tc1 - tc0) + (tc2 - tc1) * (ns / nsc if not args.eval_only else 0.0)
+        cpu_s = tc2 - tc0
         out["cpu_baseline"] = {"value": ns * float(T) / cpu_s, "unit": "plan-timesteps/s", "cores": 1, "kind": "oracle",
                                "sample": f"first {ns} of {B} plans of the same batch, same step "
                                          f"({'eval' if args.eval_only else 'eval + score'}), single thread",
                                "eval_only_value": ns * float(T) / (tc1 - tc0), "seconds": cpu_s}
-        # the GPU rows of the sample agree with what the oracle just computed
+        # the GPU results for the sample agree with what the oracle just computed
         assert np.array_equal(peak[:ns].cpu().numpy(), p0) and np.array_equal(arg[:ns].cpu().numpy(), a0)
         assert np.array_equal(res[:8].cpu().numpy(), r0[:8])
+        if not args.eval_only:
+            assert np.array_equal(sc[:ns].cpu().numpy(), s0) and np.array_equal(wo[:ns].cpu().numpy(), o0)
     h.close()
     print(json.dumps(out), flush=True)
     return 0

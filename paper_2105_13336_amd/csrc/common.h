@@ -68,6 +68,8 @@ struct EvalArgs {
     const int64_t *dMF0;           // MF0[t] - MF0[t-1], dMF0[0] = MF0[0]; zero padded to whole tiles plus one tile
     int64_t *resident;             // [B*T] or null
     int64_t tail_threshold;        // plans with more intervals than this belong to the tail kernel
+    unsigned long long *tail_flag; // set to `epoch` by the common kernel when it leaves a plan to the tail kernel
+    unsigned long long epoch;      // number of this launch (per handle)
     int32_t S;                     // segments per plan
     int32_t tiles_per_seg;
     int64_t *out_max;              // S == 1: peak[B]; else partials [B*S]
@@ -78,6 +80,8 @@ struct EvalArgs {
 struct Scratch {
     DevBuf<int64_t> part_max, part_min;
     DevBuf<int32_t> part_arg;
+    DevBuf<unsigned long long> tail_flag;   // eval: see EvalArgs::tail_flag
+    unsigned long long epoch = 0;
     DevBuf<int64_t> rowmax;        // score: chunk-maxima tables, one set per resident workgroup
     DevBuf<int32_t> cand_map;      // score: tensor -> candidate gap, one array per resident workgroup
 };

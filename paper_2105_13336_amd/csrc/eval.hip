@@ -124,7 +124,7 @@ __device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o,
 // (odd T or unaligned buffer), 2 = with 16-byte stores.  A compile-time property so that
 // every path through the tile loop issues the same memory operations.
 template <int R, bool kTail, bool kNarrow, int kOut>
-__device__ __forceinline__ void eval_body(const EvalArgs &a) {
+__device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     constexpr bool kStore = kOut != 0, kVec16 = kOut == 2;
     // the tile, followed by 64 "trash" cells: a lane whose endpoint lies outside the tile adds to
     // trash[lane] instead (never read), which keeps the scatter free of branches and of
@@ -140,7 +140,6 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // the same number, known to be wave-uniform
     // XCD-aware decode: block w runs on XCD w % 8; give XCD x the plans = x (mod 8)
-    const int64_t w = blockIdx.x;
     const int32_t xcd = static_cast<int32_t>(w & 7);
     const int64_t q = w >> 3;
     const int64_t plan64 = (q / a.S) * 8 + xcd;
@@ -152,7 +151,10 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
     if (k0 < 0) k0 = 0;
     if (k1 > a.n_intervals) k1 = a.n_intervals;
     if (k1 < k0) k1 = k0;
-    if ((k1 - k0 > a.tail_threshold) != kTail) return;   // block-uniform: the other kernel's plan
+    if ((k1 - k0 > a.tail_threshold) != kTail) {   // block-uniform: the other kernel's plan
+        if (!kTail && tid == 0) atomicMax(a.tail_flag, a.epoch);   // tell the tail kernel it has work
+        return;
+    }
 
     const int64_t seg_len = static_cast<int64_t>(a.tiles_per_seg) * kEvalTile;
     const int64_t seg_lo64 = seg * seg_len;
@@ -333,9 +335,13 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
         if constexpr (kPrev) store_part(tile_lo - kEvalTile, tile_lo, 1);
         __syncthreads();
 
-        // ---- local scan of this lane's 8 cells; the cells receive the next tile's dMF0
+        // ---- local scan of this lane's 8 cells; the cells receive the next tile's dMF0.  In the
+        // ragged last tile of a row a wavefront whose 512 steps all lie past the end has nothing
+        // to scan (wave-uniform): it only reports a zero total.
+        const bool wave_live = tile_lo + wave_u * (64 * kVpt) < tile_hi;
         int64_t v[kVpt];
-        {
+        int64_t incl = 0;
+        if (wave_live) {
             ll2 *cell = reinterpret_cast<ll2 *>(&delta[my_cell]);
 #pragma unroll
             for (int j = 0; j < kVpt / 2; ++j) {
@@ -344,14 +350,18 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
                 v[2 * j] = x[0];
                 v[2 * j + 1] = x[1];
             }
-        }
 #pragma unroll
-        for (int j = 1; j < kVpt; ++j) v[j] += v[j - 1];
-        const int64_t incl = wave_scan_add(v[kVpt - 1]);
+            for (int j = 1; j < kVpt; ++j) v[j] += v[j - 1];
+            incl = wave_scan_add(v[kVpt - 1]);
+        }
         if (lane == 63) wave_tot[wave] = incl;
         if constexpr (kPrev) store_part(tile_lo - kEvalTile, tile_lo, 2);
         __syncthreads();
-        // prefix over the eight wave totals: lanes 0-7 scan them, then every lane picks the
+        if (!wave_live) {   // (the ragged tile is the last one of its row: no later tile needs carry)
+            if constexpr (kPrev) store_part(tile_lo - kEvalTile, tile_lo, 3);
+            return;
+        }
+        // prefix over the wave totals: the first lanes scan them, then every lane picks the
         // sum of the waves before its own and the tile total by lane index
         int64_t tot = wave_tot[lane & (kWaves - 1)];
         tot += dpp_or_zero<0x111, 0xf>(tot);
@@ -465,15 +475,22 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a) {
 // thread fit without spilling.  The tail kernel keeps 16 and is left to the register allocator.
 template <int R, bool kNarrow, int kOut>
 __global__ __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void eval_kernel(const EvalArgs a) {
-    eval_body<R, false, kNarrow, kOut>(a);
+    eval_body<R, false, kNarrow, kOut>(a, blockIdx.x);
 }
 // intervals per thread held in registers: three sizes for the common kernel (2048, 4096 and
 // 6144 intervals per plan), 8192 for the tail kernel
 constexpr int kRSmall = 2048 / kEvalThreads, kRMid = 4096 / kEvalThreads, kRBig = 6144 / kEvalThreads;
 constexpr int kTailR = 8192 / kEvalThreads;
+// The tail kernel runs after the common one on the same stream with a small persistent grid.
+// It does nothing unless the common kernel met a plan it had to leave (flag == this launch's
+// epoch); then its workgroups walk all (plan, segment) pairs and take the long plans.
 template <bool kNarrow, int kOut>
-__global__ __launch_bounds__(kEvalThreads) void eval_tail_kernel(const EvalArgs a) {
-    eval_body<kTailR, true, kNarrow, kOut>(a);
+__global__ __launch_bounds__(kEvalThreads) void eval_tail_kernel(const EvalArgs a, const int64_t n_logical) {
+    if (*a.tail_flag != a.epoch) return;
+    for (int64_t w = blockIdx.x; w < n_logical; w += gridDim.x) {
+        eval_body<kTailR, true, kNarrow, kOut>(a, w);
+        __syncthreads();   // LDS is reused by the next logical workgroup
+    }
 }
 
 // Combine the per-segment partials of each plan; segments are in time order, so
@@ -558,6 +575,15 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     if (r_forced > 0) r_need = r_forced;
     const int r_fast = r_need <= kRSmall ? kRSmall : r_need <= kRMid ? kRMid : kRBig;
     a.tail_threshold = static_cast<int64_t>(r_fast) * kEvalThreads;
+    {
+        Scratch &sc = tas->scratch;
+        if (!sc.tail_flag.p) {
+            TS_HIP(sc.tail_flag.reserve(1));
+            TS_HIP(hipMemset(sc.tail_flag.p, 0, sizeof(unsigned long long)));
+        }
+        a.tail_flag = sc.tail_flag.p;
+        a.epoch = ++sc.epoch;
+    }
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kEvalThreads);
 #define TS_LAUNCH_OUT(KERNEL, ...)                                                                   \
     do {                                                                                             \
@@ -574,10 +600,20 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     else if (r_fast == kRMid) TS_LAUNCH_EVAL(kRMid);
     else TS_LAUNCH_EVAL(kRBig);
     TS_HIP(hipGetLastError());
-    if (narrow) TS_LAUNCH_OUT(eval_tail_kernel, true);
-    else TS_LAUNCH_OUT(eval_tail_kernel, false);
 #undef TS_LAUNCH_EVAL
 #undef TS_LAUNCH_OUT
+    {
+        const dim3 tgrid(static_cast<uint32_t>(blocks < tas->num_cus ? blocks : tas->num_cus));
+#define TS_LAUNCH_TAIL(NARROW)                                                                                      \
+    do {                                                                                                            \
+        if (out == 2) hipLaunchKernelGGL((eval_tail_kernel<NARROW, 2>), tgrid, block, 0, stream, a, blocks);        \
+        else if (out == 1) hipLaunchKernelGGL((eval_tail_kernel<NARROW, 1>), tgrid, block, 0, stream, a, blocks);   \
+        else hipLaunchKernelGGL((eval_tail_kernel<NARROW, 0>), tgrid, block, 0, stream, a, blocks);                 \
+    } while (0)
+        if (narrow) TS_LAUNCH_TAIL(true);
+        else TS_LAUNCH_TAIL(false);
+#undef TS_LAUNCH_TAIL
+    }
     TS_HIP(hipGetLastError());
     if (S > 1) {
         const int threads = 256;
