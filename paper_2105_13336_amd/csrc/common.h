@@ -101,7 +101,12 @@ struct tensile_tas {
     tensile::DevBuf<int64_t> d_size, d_MF0, d_dMF0, d_C, d_x, d_touch_off;
     tensile::DevBuf<uint32_t> d_size_units;   // empty when the sizes do not fit (see EvalArgs)
     int32_t size_shift = 0;
-    tensile::DevBuf<int32_t> d_touch, d_gp, d_gq, d_gtensor, d_gwin;
+    tensile::DevBuf<int32_t> d_touch;
+    // candidate gaps {p, q, o, tensor} filed under every bucket of 2^bucket_shift steps that (o, q) overlaps
+    tensile::DevBuf<int4> d_cand;
+    tensile::DevBuf<int64_t> d_cand_size;     // size of each entry's tensor
+    tensile::DevBuf<int32_t> d_bucket_off;    // [n_buckets + 1]
+    int32_t bucket_shift = 0;
     // host copies used by the greedy driver and the validator
     std::vector<int64_t> h_size, h_C, h_x, h_touch_off;
     std::vector<int32_t> h_touch, h_job;

@@ -175,6 +175,44 @@ int validate_desc(const tensile_tas_desc *d) {
     return TENSILE_OK;
 }
 
+// A gap (p, q) with earliest swap-out step o >= 0 is a scoring candidate at the peak steps
+// t* with o < t* < q.  File it under every bucket of 2^shift steps that o+1 .. q-1 overlaps;
+// the bucket width starts at 256 steps and doubles while the index would hold more than
+// about 16 entries per gap.
+int build_candidate_index(tensile_tas *h, const std::vector<int32_t> &gp, const std::vector<int32_t> &gq,
+                          const std::vector<int32_t> &gt, const std::vector<int32_t> &gwin) {
+    const size_t G = gp.size();
+    const int32_t T = h->T;
+    int32_t shift = 8;
+    uint64_t entries;
+    for (;; ++shift) {
+        entries = 0;
+        for (size_t g = 0; g < G; ++g)
+            if (gwin[g] >= 0 && gwin[g] + 1 <= gq[g] - 1) entries += ((gq[g] - 1) >> shift) - ((gwin[g] + 1) >> shift) + 1;
+        if (entries <= 16 * static_cast<uint64_t>(G) + 4096 || (int64_t{1} << shift) >= T) break;
+    }
+    if (entries > static_cast<uint64_t>(INT32_MAX)) { set_error("tas_load: candidate index too large"); return TENSILE_E_RANGE; }
+    const int32_t n_buckets = ((T - 1) >> shift) + 1;
+    std::vector<int32_t> off(static_cast<size_t>(n_buckets) + 1, 0);
+    for (size_t g = 0; g < G; ++g)
+        if (gwin[g] >= 0 && gwin[g] + 1 <= gq[g] - 1)
+            for (int32_t b = (gwin[g] + 1) >> shift; b <= (gq[g] - 1) >> shift; ++b) ++off[b + 1];
+    for (int32_t b = 0; b < n_buckets; ++b) off[b + 1] += off[b];
+    std::vector<int4> cand(static_cast<size_t>(off[n_buckets]));
+    std::vector<int32_t> fill(off.begin(), off.end() - 1);
+    for (size_t g = 0; g < G; ++g)
+        if (gwin[g] >= 0 && gwin[g] + 1 <= gq[g] - 1)
+            for (int32_t b = (gwin[g] + 1) >> shift; b <= (gq[g] - 1) >> shift; ++b)
+                cand[fill[b]++] = make_int4(gp[g], gq[g], gwin[g], gt[g]);
+    std::vector<int64_t> cand_size(cand.size());
+    for (size_t e = 0; e < cand.size(); ++e) cand_size[e] = h->h_size[cand[e].w];
+    h->bucket_shift = shift;
+    TS_HIP(h->d_cand.upload(cand.data(), cand.size()));
+    TS_HIP(h->d_cand_size.upload(cand_size.data(), cand_size.size()));
+    TS_HIP(h->d_bucket_off.upload(off.data(), off.size()));
+    return TENSILE_OK;
+}
+
 int build(tensile_tas *h, const tensile_tas_desc *d) {
     const int32_t T = d->T, N = d->N;
     TS_HIP(hipGetDevice(&h->device));
@@ -216,10 +254,6 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
     TS_HIP(h->d_size.upload(h->h_size.data(), N));
     TS_HIP(h->d_touch_off.upload(h->h_touch_off.data(), static_cast<size_t>(N) + 1));
     TS_HIP(h->d_touch.upload(h->h_touch.data(), h->h_touch.size()));
-    TS_HIP(h->d_gp.upload(gp.data(), gp.size()));
-    TS_HIP(h->d_gq.upload(gq.data(), gq.size()));
-    TS_HIP(h->d_gtensor.upload(gt.data(), gt.size()));
-    TS_HIP(h->d_gwin.reserve(gp.size()));
     // whole tiles plus one: the evaluation kernel prefetches one tile ahead unconditionally
     const size_t T_pad = ((static_cast<size_t>(T) + kEvalTile - 1) / kEvalTile + 1) * kEvalTile;
     TS_HIP(h->d_MF0.reserve(T));
@@ -283,11 +317,20 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
         if (N > 0)
             hipLaunchKernelGGL(transfer_time_kernel, dim3((N + 255) / 256), dim3(256), 0, 0, N, h->d_size.p,
                                h->link_bytes_per_us, h->d_x.p);
+        DevBuf<int32_t> d_gp, d_gq, d_gt, d_gwin;
+        TS_HIP(d_gp.upload(gp.data(), gp.size()));
+        TS_HIP(d_gq.upload(gq.data(), gq.size()));
+        TS_HIP(d_gt.upload(gt.data(), gt.size()));
+        TS_HIP(d_gwin.reserve(gp.size()));
         if (h->G > 0)
-            hipLaunchKernelGGL(gap_window_kernel, dim3((h->G + 255) / 256), dim3(256), 0, 0, h->G, T, h->d_gp.p, h->d_gq.p,
-                               h->d_gtensor.p, h->d_C.p, h->d_x.p, h->d_gwin.p);
+            hipLaunchKernelGGL(gap_window_kernel, dim3((h->G + 255) / 256), dim3(256), 0, 0, h->G, T, d_gp.p, d_gq.p,
+                               d_gt.p, h->d_C.p, h->d_x.p, d_gwin.p);
         TS_HIP(hipGetLastError());
         TS_HIP(hipDeviceSynchronize());
+        std::vector<int32_t> gwin(gp.size());
+        if (h->G > 0) TS_HIP(hipMemcpy(gwin.data(), d_gwin.p, gwin.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+        int rc = build_candidate_index(h, gp, gq, gt, gwin);
+        if (rc != TENSILE_OK) return rc;
     }
     h->h_C.resize(static_cast<size_t>(T) + 1);
     h->h_x.resize(static_cast<size_t>(N));
