@@ -82,8 +82,36 @@ struct Scratch {
     DevBuf<int32_t> part_arg;
     DevBuf<unsigned long long> tail_flag;   // eval: see EvalArgs::tail_flag
     unsigned long long epoch = 0;
-    DevBuf<int64_t> rowmax;        // score: chunk-maxima tables, one set per resident workgroup
-    DevBuf<int32_t> cand_map;      // score: tensor -> candidate gap, one array per resident workgroup
+    DevBuf<int64_t> score_tab;     // score: per-workgroup sub-span maxima when they do not fit in LDS
+};
+
+// Geometry the scoring kernel shares with the index built at load time (see score.hip).
+constexpr int kScoreThreads = 1024;
+constexpr int kScoreWaves = kScoreThreads / 64;
+constexpr int kScoreMini = 256;    // steps one wavefront takes up at a time (4 consecutive steps per lane)
+
+// Candidate index: every gap (p, q) with a feasible earliest swap-out step o, filed under each
+// bucket of 2^shift steps that o+1 .. q-1 overlaps.  Per bucket (entries e0 .. e1-1, local
+// index = e - e0):
+//   cand / cand_size / cand_o   the entries sorted by o
+//   qord                        {q, local index} sorted by q
+//   wave_ptr[2][kScoreWaves+1]  first local position with o (resp. q) >= w * span, both orders
+//   hash_dir / hash_slots       open-addressing table tensor -> {tensor, p, q, local | last << 31}
+//   filter                      one bit per (tensor mod filter_bits): some entry has this tensor
+struct CandIndex {
+    int32_t shift = 0, n_buckets = 0;
+    int32_t span = kScoreMini;     // steps per wavefront: ceil(T / kScoreWaves) rounded up to kScoreMini
+    int32_t filter_words = 0;      // words per bucket, a power of two
+    int32_t max_bucket = 0;        // entries in the largest bucket
+    DevBuf<int32_t> bucket_off;    // [n_buckets + 1]
+    DevBuf<int4> cand;
+    DevBuf<int64_t> cand_size;
+    DevBuf<int32_t> cand_o;
+    DevBuf<int2> qord;
+    DevBuf<int32_t> wave_ptr;      // [n_buckets][2][kScoreWaves + 1]
+    DevBuf<int2> hash_dir;         // [n_buckets] {first slot, log2(slots)}
+    DevBuf<int4> hash_slots;
+    DevBuf<uint32_t> filter;       // [n_buckets][filter_words]
 };
 
 }  // namespace tensile
@@ -102,11 +130,7 @@ struct tensile_tas {
     tensile::DevBuf<uint32_t> d_size_units;   // empty when the sizes do not fit (see EvalArgs)
     int32_t size_shift = 0;
     tensile::DevBuf<int32_t> d_touch;
-    // candidate gaps {p, q, o, tensor} filed under every bucket of 2^bucket_shift steps that (o, q) overlaps
-    tensile::DevBuf<int4> d_cand;
-    tensile::DevBuf<int64_t> d_cand_size;     // size of each entry's tensor
-    tensile::DevBuf<int32_t> d_bucket_off;    // [n_buckets + 1]
-    int32_t bucket_shift = 0;
+    tensile::CandIndex index;
     // host copies used by the greedy driver and the validator
     std::vector<int64_t> h_size, h_C, h_x, h_touch_off;
     std::vector<int32_t> h_touch, h_job;

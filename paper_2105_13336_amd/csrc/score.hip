@@ -1,43 +1,40 @@
 // Candidate scoring (section IV-C of the paper): for every plan, how much would
 // evicting each tensor that is resident and idle at the peak lower the peak,
-// given the earliest swap-out / latest swap-in the host link's speed allows.
-//
-// score = P - max( max MF[0..o], max MF[q..T), P - size ) needs running maxima of
-// the plan's footprint row at scattered positions (o, q).  Writing a full row of
-// running maxima would double the traffic of the pass, so the maxima are kept at
-// a granularity of kChunk = 8 steps (one 64-byte line of the row).  The row is
-// cut into one contiguous span of chunks per wavefront, and inside its span each
-// wavefront computes, with wave-level scans only (no workgroup barrier):
-//   CM[c]  = max MF[8c .. 8c+7]
-//   PMC[c] = max of CM over the chunks of the span up to and including c
-//   SMC[c] = max of CM over the chunks of the span from c on
-// plus the maximum of the whole span, left in LDS.  A query combines a table
-// entry with the span maxima of the other wavefronts and finishes inside its own
-// chunk by reading that one line of the row:
-//   max MF[0..o]  = max( PMC[(o>>3)-1], spans before that chunk's, MF[8(o>>3) .. o] )
-//   max MF[q..T)  = max( SMC[(q>>3)+1], spans after that chunk's,  MF[q .. 8(q>>3)+7] )
-// The tables live in a scratch area owned by the workgroup (3*T bytes), which
-// stays in L2 / the memory-side cache for the configurations at hand.
+// given the earliest swap-out / latest swap-in the host link's speed allows:
+//   score = P - max( max MF[0..o], max MF[q..T), P - size ).
 //
 // Which tensors can be candidates at a peak step t* does not depend on the plan:
 // they are the gaps (p, q) of the TAS with a feasible earliest swap-out step o
 // (a property of the gap alone: it follows from p, q, the transfer time and the
-// cumulative latency) and o < t* < q.  tensile_tas_load files every such gap,
-// as {p, q, o, tensor}, under each bucket of 2^shift steps that (o, q) overlaps,
-// so a plan looks at the one bucket of its t* instead of all gaps.
+// cumulative latency) and o < t* < q.  tensile_tas_load files every such gap
+// under each bucket of 2^shift steps that (o, q) overlaps, so a plan looks at the
+// one bucket of its t* (see CandIndex in common.h).  Everything a plan needs
+// beyond its own footprint row and interval list is static, shared by all plans
+// with the same bucket, and read in order; the row is read exactly once, in
+// order, and nothing per plan is kept in global memory.
 //
 // One workgroup walks a plan at a time (persistent workgroups, plans dealt
-// round-robin):
-//   1. the plan's output rows are cleared (score 0, windows -1);
-//   2. chunk tables as above;
-//   3. every entry of the bucket with o < t* < q puts its index into map[tensor]
-//      (a per-workgroup array over tensors, -1 elsewhere);
-//   4. the plan's own intervals look their tensor up in the map; an interval
-//      inside the candidate gap of its tensor cancels the candidate (map = -2):
-//      "tensor has not been swapped out" in the paper's Alg. 2;
-//   5. the bucket is walked again: surviving candidates get their score, and every
-//      touched map entry is reset to -1 for the next plan.
-// No search is needed anywhere: a tensor has at most one gap around t*.
+// round-robin).  Per plan, with acc[] one word per bucket entry in LDS:
+//   1. the plan's output rows are cleared (score 0, windows -1); acc = -inf;
+//   2. the plan's own intervals cancel candidates: an interval inside the gap of
+//      an entry of its tensor sets acc = +inf ("tensor has not been swapped out"
+//      in the paper's Alg. 2).  A per-bucket bit filter over tensors, kept in LDS,
+//      turns most intervals away; the others probe the bucket's hash table;
+//   3. every wavefront streams its own contiguous span of the row, 256 steps at a
+//      time, four consecutive steps per lane.  With two wave-level scans it forms,
+//      per lane, the running maximum from the span's start up to the lane's steps
+//      and the maximum from after them to the end of the 256, and puts both, with
+//      the values themselves, in a small LDS buffer of its own; the entries whose
+//      o (resp. q) falls inside these 256 steps complete their value from the
+//      buffer and fold it into acc (atomic max).  Entries are met in order because
+//      the bucket is sorted by o, and a second list is sorted by q; the wavefront
+//      takes them up 64 at a time.  The maxima of the 256-step pieces go to a table
+//      (LDS), suffix-scanned within the span at the end.  The waves of a workgroup
+//      meet at one barrier after this step; nothing inside it needs one;
+//   4. an entry with o < t* < q and acc != +inf scores
+//      P - max( acc, pieces after q's in its span, spans before o's, spans after q's, P - size ).
+// Buckets with more entries than acc holds are processed in slices, one full
+// pass per slice.
 #include "common.h"
 #include "wave_ops.h"
 
@@ -45,43 +42,47 @@ namespace tensile {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / 64;
-constexpr int kChunk = 8;       // steps per chunk = one 64-byte line
-constexpr int kFwdU = 4;        // chunks per lane and round of the forward pass
-constexpr int kBwdU = 8;        // chunk maxima per lane and round of the backward pass
-constexpr int kIvU = 4;         // intervals per thread and round
+constexpr int kThreads = kScoreThreads;
+constexpr int kWaves = kScoreWaves;
+constexpr int kMini = kScoreMini;
+constexpr int kMaxLocal = 4096;     // bucket entries per slice (acc: 32 KB)
+constexpr int kTabLds = 512;        // pieces of kMini steps whose maxima fit in LDS (T <= 131072)
+constexpr int kFilterWords = 1024;  // largest per-bucket filter (32768 bits)
+constexpr int kIvU = 4;             // intervals per thread and round
 
 typedef long long ll2 __attribute__((ext_vector_type(2)));
 
 struct ScoreArgs {
     int32_t T, N, B;
-    int32_t n_chunks;            // ceil(T / kChunk)
-    int32_t chunks_per_wave;     // span of one wavefront, a multiple of 64
+    int32_t span;                // steps per wavefront (a multiple of kMini)
+    int32_t n_tab;               // ceil(T / kMini)
+    int32_t vec16;               // rows are 16-byte aligned (T even, aligned base)
     int64_t n_intervals;
     const int64_t *plan_offsets;
     const int32_t *iv_tensor, *iv_out, *iv_in;
-    const int64_t *size;
-    const int4 *cand;            // bucketed candidate gaps {p, q, o, tensor}
-    const int64_t *cand_size;    // size of each entry's tensor
-    const int32_t *bucket_off;   // [n_buckets + 1] into cand
-    int32_t bucket_shift;
+    int32_t bucket_shift, filter_words;
+    const int32_t *bucket_off;
+    const int4 *cand;
+    const int64_t *cand_size;
+    const int32_t *cand_o;
+    const int2 *qord;
+    const int32_t *wave_ptr;
+    const int2 *hash_dir;
+    const int4 *hash_slots;
+    const uint32_t *filter;
     const int64_t *resident;
     const int64_t *peak;
     const int32_t *argmax;
     int64_t *score;
     int32_t *win_out, *win_in;
-    int64_t *tables;             // [gridDim.x][3][n_chunks]: CM, PMC, SMC of the plan in progress
-    int32_t *map;                // [gridDim.x][N]: candidate entry of each tensor for the plan in progress
-    int32_t vec16;               // rows are 16-byte aligned (T even, aligned base)
+    int64_t *tab_scratch;        // [gridDim.x][n_tab] when n_tab > kTabLds, else null
 };
 
 // row[0..n) = v with 16-byte stores where the row allows them
 template <typename E>
-__device__ __forceinline__ void fill_row(E *row, int32_t n, E v) {
+__device__ __forceinline__ void fill_row(E *row, int32_t n, E v, int tid) {
     constexpr int kPer = 16 / sizeof(E);
     typedef E vec_t __attribute__((ext_vector_type(kPer)));
-    const int tid = threadIdx.x;
     const uintptr_t addr = reinterpret_cast<uintptr_t>(row);
     int32_t head = static_cast<int32_t>(((16 - (addr & 15)) & 15) / sizeof(E));
     if (head > n) head = n;
@@ -96,103 +97,147 @@ __device__ __forceinline__ void fill_row(E *row, int32_t n, E v) {
     if (done + tid < n) row[done + tid] = v;
 }
 
-// Two consecutive steps of the row starting at the even step t (one 16-byte load when the row
-// allows it); steps outside [0, T) and masked-off lanes give INT64_MIN.  The load itself is
-// always issued, at a clamped address, so that a batch of them can be in flight together.
+// Four consecutive steps of the row starting at step t (a multiple of 4; two 16-byte loads when
+// the row allows them).  The loads are always issued, at clamped addresses; steps outside
+// [0, T) come back as INT64_MIN.
 template <bool kVec>
-__device__ __forceinline__ void load_pair(const int64_t *MF, int32_t t, int32_t T, int64_t &x0, int64_t &x1) {
-    if (kVec) {   // T is even here, so t < T implies t + 1 < T
-        const ll2 x = *reinterpret_cast<const ll2 *>(MF + (t < T ? t : T - 2));
-        x0 = x[0];
-        x1 = x[1];
+__device__ __forceinline__ void load_quad(const int64_t *MF, int32_t t, int32_t T, int64_t (&x)[4]) {
+    if (kVec) {   // T is even here, so an even step t' < T implies t' + 1 < T
+        const ll2 lo = *reinterpret_cast<const ll2 *>(MF + (t < T ? t : T - 2));
+        const ll2 hi = *reinterpret_cast<const ll2 *>(MF + (t + 2 < T ? t + 2 : T - 2));
+        x[0] = lo[0]; x[1] = lo[1]; x[2] = hi[0]; x[3] = hi[1];
     } else {
-        x0 = MF[t < T ? t : T - 1];
-        x1 = MF[t + 1 < T ? t + 1 : T - 1];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[j] = MF[t + j < T ? t + j : T - 1];
     }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (t + j >= T) x[j] = INT64_MIN;
 }
 
-// max over the four lanes of each quad, left in all four
-__device__ __forceinline__ int64_t quad_max(int64_t x) {
-    x = max64(x, dpp_move<0xB1, 0xf>(x, x));   // quad_perm:[1,0,3,2]
-    x = max64(x, dpp_move<0x4E, 0xf>(x, x));   // quad_perm:[2,3,0,1]
-    return x;
+// Inclusive max-scan over the 64 lanes from the high end: lane l receives the maximum of lanes
+// l .. 63.  Shifts towards lower lanes inside rows of 16, then the totals of the later rows.
+__device__ __forceinline__ int64_t wave_rscan_max(int64_t x, int lane) {
+    x = max64(x, dpp_move<0x101, 0xf>(x, INT64_MIN));
+    x = max64(x, dpp_move<0x102, 0xf>(x, INT64_MIN));
+    x = max64(x, dpp_move<0x104, 0xf>(x, INT64_MIN));
+    x = max64(x, dpp_move<0x108, 0xf>(x, INT64_MIN));
+    const int64_t r3 = lane_value(x, 48);
+    const int64_t r2 = max64(lane_value(x, 32), r3);
+    const int64_t r1 = max64(lane_value(x, 16), r2);
+    const int64_t later = lane < 16 ? r1 : (lane < 32 ? r2 : (lane < 48 ? r3 : INT64_MIN));
+    return max64(x, later);
 }
 
-__device__ __forceinline__ int64_t permute64(int64_t x, int src_lane) {
-    const int lo = __builtin_amdgcn_ds_bpermute(src_lane << 2, static_cast<int>(x));
-    const int hi = __builtin_amdgcn_ds_bpermute(src_lane << 2, static_cast<int>(x >> 32));
-    return (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
-}
+// value of the previous / next lane; the first / last lane receives `edge`
+__device__ __forceinline__ int64_t from_prev_lane(int64_t x, int64_t edge) { return dpp_move<0x138, 0xf>(x, edge); }   // wave_shr:1
+__device__ __forceinline__ int64_t from_next_lane(int64_t x, int64_t edge) { return dpp_move<0x130, 0xf>(x, edge); }   // wave_shl:1
 
-// The chunk tables of one wavefront's span [lo, hi) of the row MF; returns the span's maximum.
-// A load instruction covers 128 consecutive steps (lane l: steps 2l, 2l+1), i.e. 16 chunks with
-// one chunk per quad of lanes; four of them give 64 chunk maxima, which a lane permutation puts
-// into chunk order for one wave-level scan and full-width stores.
+// Step 3 for one wavefront: its span [span_lo, span_hi) of the row.  Returns the span's maximum.
+//   lo_k .. lo_end   the wavefront's entries in o order (positions local to the bucket)
+//   hi_k .. hi_end   its items of the q order
+//   slice_lo, n_slice   the slice of the bucket acc covers
+// The span is taken up kMini = 256 steps at a time, four consecutive steps per lane.  Per lane
+// the wavefront's buffer in LDS receives the four values, the maximum from the span's start up
+// to just before them (before[]) and the maximum from just after them to the end of the 256
+// (after[]); an entry completes its value from these:
+//   max MF[span_lo .. o]     = max( before[l], the lane's values up to o )     l = (o - t0) / 4
+//   max MF[q .. t0 + 255]    = max( after[l],  the lane's values from q on )
+// Both lists are met in order.  The wavefront holds a window of 64 consecutive items of each,
+// one per lane, and the window after it, requested when the current one was taken up; `pos`
+// counts the lanes of the window already served.
+struct SpanBuf {
+    int64_t raw[kMini];
+    int64_t before[64], after[64];
+};
+
 template <bool kVec>
-__device__ __forceinline__ int64_t span_tables(const ScoreArgs &a, const int64_t *MF, int64_t *CM, int64_t *PMC,
-                                               int32_t lo, int32_t hi) {
-    const int lane = threadIdx.x & 63;
-    const int in_order = ((lane & 15) << 2) | (lane >> 4);   // lane holding the maximum of chunk base + lane
+__device__ __forceinline__ int64_t stream_span(const ScoreArgs &a, const int64_t *MF, int32_t span_lo, int32_t span_hi,
+                                               const int32_t *cand_o, const int2 *qord, int32_t lo_k, int32_t lo_end,
+                                               int32_t hi_k, int32_t hi_end, int32_t slice_lo, int32_t n_slice,
+                                               int64_t *acc, SpanBuf *buf, int64_t *tab, int lane) {
+    const int32_t n_ms = (span_hi - span_lo + kMini - 1) / kMini;
+    auto load_lo = [&](int32_t k) { return k + lane < lo_end ? cand_o[k + lane] : INT32_MAX; };
+    auto load_hi = [&](int32_t k) { return k + lane < hi_end ? qord[k + lane] : make_int2(INT32_MAX, 0); };
+    int32_t lo_o = load_lo(lo_k), lo_next = load_lo(lo_k + 64), lo_pos = 0;
+    int2 hi_it = load_hi(hi_k), hi_next = load_hi(hi_k + 64);
+    int32_t hi_pos = 0;
+    int64_t x[4], x_next[4];
+    load_quad<kVec>(MF, span_lo + 4 * lane, a.T, x_next);
     int64_t carry = INT64_MIN;
-    for (int32_t base = lo; base < hi; base += 64 * kFwdU) {
-        int64_t x[kFwdU][4][2];
+    for (int32_t ms = 0; ms < n_ms; ++ms) {
+        const int32_t t0 = span_lo + ms * kMini;
 #pragma unroll
-        for (int u = 0; u < kFwdU; ++u) {
-            if (base + u * 64 >= hi) break;     // (wave-uniform)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                load_pair<kVec>(MF, (base + u * 64 + j * 16) * kChunk + 2 * lane, a.T, x[u][j][0], x[u][j][1]);
+        for (int j = 0; j < 4; ++j) x[j] = x_next[j];
+        load_quad<kVec>(MF, t0 + kMini + 4 * lane, a.T, x_next);
+        const int64_t m = max64(max64(x[0], x[1]), max64(x[2], x[3]));
+        const int64_t incl = max64(wave_scan_max(m), carry);
+        const int64_t excl = from_prev_lane(incl, carry);         // max MF[span_lo .. t0 + 4 lane - 1]
+        const int64_t rs = wave_rscan_max(m, lane);                     // max MF[t0 + 4 lane .. t0 + 255]
+        const int64_t rs_next = from_next_lane(rs, INT64_MIN);    // max MF[t0 + 4 lane + 4 .. t0 + 255]
+        carry = last_lane(incl);
+        const int64_t piece = lane_value(rs, 0);
+        // (the lanes of a wavefront execute in step and LDS serves a wavefront's accesses in
+        // order, so the buffer needs no barrier: the fences only pin the compiler's order)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        reinterpret_cast<ll2 *>(buf->raw)[2 * lane] = ll2{x[0], x[1]};
+        reinterpret_cast<ll2 *>(buf->raw)[2 * lane + 1] = ll2{x[2], x[3]};
+        buf->before[lane] = excl;
+        buf->after[lane] = rs_next;
+        if (lane == 0) tab[t0 / kMini] = piece;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (;;) {                                      // (wave-uniform)
+            const bool take = lane >= lo_pos && lo_o < t0 + kMini;
+            if (take) {
+                const int32_t r = lo_o - t0, l = r >> 2, j = r & 3;
+                int64_t v = max64(buf->before[l], buf->raw[4 * l]);
+                if (j >= 1) v = max64(v, buf->raw[4 * l + 1]);
+                if (j >= 2) v = max64(v, buf->raw[4 * l + 2]);
+                if (j >= 3) v = max64(v, buf->raw[4 * l + 3]);
+                atomicMax(reinterpret_cast<long long *>(acc + (lo_k + lane - slice_lo)), static_cast<long long>(v));
+            }
+            lo_pos += __builtin_popcountll(__builtin_amdgcn_ballot_w64(take));
+            if (lo_pos < 64) break;
+            lo_k += 64;
+            lo_pos = 0;
+            lo_o = lo_next;
+            lo_next = load_lo(lo_k + 64);
         }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int u = 0; u < kFwdU; ++u) {
-            if (base + u * 64 >= hi) break;
-            int64_t keep = INT64_MIN;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int32_t t = (base + u * 64 + j * 16) * kChunk + 2 * lane;
-                int64_t m = INT64_MIN;
-                if (t < a.T) m = x[u][j][0];
-                if (t + 1 < a.T) m = max64(m, x[u][j][1]);
-                m = quad_max(m);
-                if ((lane & 3) == j) keep = m;      // chunk base + 64u + 16j + (lane >> 2)
+        for (;;) {
+            const bool take = lane >= hi_pos && hi_it.x < t0 + kMini;
+            const uint32_t el = static_cast<uint32_t>(hi_it.y - slice_lo);
+            if (take && el < static_cast<uint32_t>(n_slice)) {
+                const int32_t r = hi_it.x - t0, l = r >> 2, j = r & 3;
+                int64_t v = max64(buf->after[l], buf->raw[4 * l + 3]);
+                if (j <= 2) v = max64(v, buf->raw[4 * l + 2]);
+                if (j <= 1) v = max64(v, buf->raw[4 * l + 1]);
+                if (j <= 0) v = max64(v, buf->raw[4 * l]);
+                atomicMax(reinterpret_cast<long long *>(acc + el), static_cast<long long>(v));
             }
-            const int32_t c = base + u * 64 + lane;
-            const int64_t ordered = permute64(keep, in_order);
-            const int64_t m = c < hi ? ordered : INT64_MIN;
-            const int64_t incl = max64(wave_scan_max(m), carry);
-            carry = last_lane(incl);
-            if (c < hi) {
-                CM[c] = m;
-                PMC[c] = incl;
-            }
+            hi_pos += __builtin_popcountll(__builtin_amdgcn_ballot_w64(take));
+            if (hi_pos < 64) break;
+            hi_k += 64;
+            hi_pos = 0;
+            hi_it = hi_next;
+            hi_next = load_hi(hi_k + 64);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    // tab[k] = max of the pieces k .. end of this span
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    {
+        const int32_t k_lo = span_lo / kMini;
+        int64_t run = INT64_MIN;
+        for (int32_t top = k_lo + n_ms; top > k_lo; top -= 64) {
+            const int32_t k = top - 1 - lane;
+            const int64_t v = k >= k_lo ? tab[k] : INT64_MIN;
+            const int64_t incl = max64(wave_scan_max(v), run);
+            run = last_lane(incl);
+            if (k >= k_lo) tab[k] = incl;
         }
     }
     return carry;
-}
-
-// SMC over the span [lo, hi) from the chunk maxima CM
-__device__ __forceinline__ void span_suffix(const int64_t *CM, int64_t *SMC, int32_t lo, int32_t hi) {
-    const int lane = threadIdx.x & 63;
-    int64_t carry = INT64_MIN;
-    for (int32_t top = hi; top > lo; top -= 64 * kBwdU) {
-        int64_t m[kBwdU];
-#pragma unroll
-        for (int u = 0; u < kBwdU; ++u) {
-            if (top - u * 64 <= lo) break;          // (wave-uniform)
-            const int32_t c = top - 1 - (u * 64 + lane);
-            m[u] = CM[c >= lo ? c : lo];
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int u = 0; u < kBwdU; ++u) {
-            if (top - u * 64 <= lo) break;
-            const int32_t c = top - 1 - (u * 64 + lane);
-            const int64_t incl = max64(wave_scan_max(c >= lo ? m[u] : INT64_MIN), carry);
-            carry = last_lane(incl);
-            if (c >= lo) SMC[c] = incl;
-        }
-    }
 }
 
 // Phase timing for tuning, compiled in with -DTENSILE_SCORE_PROF only: thread 0 of every
@@ -212,20 +257,24 @@ __device__ unsigned long long g_score_prof[8];
 #endif
 
 __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
+    __shared__ int64_t acc[kMaxLocal];
+    __shared__ __attribute__((aligned(16))) SpanBuf span_buf[kWaves];
+    __shared__ int64_t tab_lds[kTabLds];
+    __shared__ uint32_t filter[kFilterWords];
     __shared__ int64_t span_max[kWaves];
-    const int tid = threadIdx.x, wave = tid >> 6;
-    int64_t *CM = a.tables + static_cast<int64_t>(blockIdx.x) * 3 * a.n_chunks;
-    int64_t *PMC = CM + a.n_chunks, *SMC = PMC + a.n_chunks;
-    int32_t *map = a.map + static_cast<int64_t>(blockIdx.x) * a.N;
-    const int32_t span_lo = min(wave * a.chunks_per_wave, a.n_chunks);
-    const int32_t span_hi = min(span_lo + a.chunks_per_wave, a.n_chunks);
-
-    fill_row<int32_t>(map, a.N, -1);
+    int64_t *tab = a.tab_scratch ? a.tab_scratch + static_cast<int64_t>(blockIdx.x) * a.n_tab : tab_lds;
+    int32_t filter_of = -1;      // bucket whose filter is in LDS
 #ifdef TENSILE_SCORE_PROF
     unsigned long long prof_t = wall_clock64();
 #endif
 
     for (int32_t b = blockIdx.x; b < a.B; b += gridDim.x) {
+        // (the thread index is made opaque once per plan: everything derived from it is then
+        // recomputed where it is used instead of being held in registers across the whole loop)
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int32_t span_lo = min(wave * a.span, a.T), span_hi = min(span_lo + a.span, a.T);
         const int32_t tstar = a.argmax[b];
         const int64_t P = a.peak[b];
         const int64_t *MF = a.resident + static_cast<int64_t>(b) * a.T;
@@ -233,154 +282,124 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         int32_t *wout = a.win_out ? a.win_out + static_cast<int64_t>(b) * a.N : nullptr;
         int32_t *win = a.win_in ? a.win_in + static_cast<int64_t>(b) * a.N : nullptr;
 
-        // ---- 1: clear the output rows (independent of everything else)
-        fill_row<int64_t>(score, a.N, 0);
-        if (wout) fill_row<int32_t>(wout, a.N, -1);
-        if (win) fill_row<int32_t>(win, a.N, -1);
-        __syncthreads();   // the previous plan has finished with the tables, the map and span_max
-        PROF_MARK(0);
+        // ---- 1: clear the output rows
+        fill_row<int64_t>(score, a.N, 0, tid);
+        if (wout) fill_row<int32_t>(wout, a.N, -1, tid);
+        if (win) fill_row<int32_t>(win, a.N, -1, tid);
         if (tstar < 0 || tstar >= a.T) continue;   // not produced by the evaluator: no candidate
         const int32_t bk = tstar >> a.bucket_shift;
-        const int32_t e0 = a.bucket_off[bk], e1 = a.bucket_off[bk + 1];
-        if (e0 == e1) continue;                    // no gap around t* can be swapped in time
-
-        // ---- 2: chunk tables of this wavefront's span
-        {
-            const int64_t m = a.vec16 ? span_tables<true>(a, MF, CM, PMC, span_lo, span_hi)
-                                      : span_tables<false>(a, MF, CM, PMC, span_lo, span_hi);
-            if ((tid & 63) == 0) span_max[wave] = m;
-        }
-        PROF_MARK(1);
-        // ---- 3: candidate entries -> map[tensor]
-        for (int32_t e = e0 + tid; e < e1; e += kThreads) {
-            const int4 c = a.cand[e];
-            if (c.z < tstar && tstar < c.y) map[c.w] = e;
-        }
-        __syncthreads();   // CM, the map and span_max are complete
-        PROF_MARK(2);
-        span_suffix(CM, SMC, span_lo, span_hi);
-        PROF_MARK(3);
-
-        // ---- 4: the plan's own intervals cancel candidates
+        const int32_t e0 = a.bucket_off[bk], n_e = a.bucket_off[bk + 1] - e0;
+        if (n_e == 0) continue;                    // no gap around t* can be swapped in time
+        const int32_t *wp = a.wave_ptr + static_cast<int64_t>(bk) * 2 * (kWaves + 1);
+        const int2 hd = a.hash_dir[bk];
         int64_t k0 = a.plan_offsets[b], k1 = a.plan_offsets[b + 1];
         if (k0 < 0) k0 = 0;
         if (k1 > a.n_intervals) k1 = a.n_intervals;
-        for (int64_t kb = k0 + tid; kb < k1; kb += kIvU * kThreads) {
-            int32_t i[kIvU], o[kIvU], r[kIvU], e[kIvU];
-            int4 c[kIvU];
-#pragma unroll
-            for (int u = 0; u < kIvU; ++u) {
-                const int64_t k = kb + u * kThreads;
-                const int64_t kc = k < k1 ? k : k1 - 1;
-                i[u] = a.iv_tensor[kc];
-                o[u] = a.iv_out[kc];
-                r[u] = a.iv_in[kc];
-                if (k >= k1) i[u] = -1;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < kIvU; ++u) {
-                const bool ok = static_cast<uint32_t>(i[u]) < static_cast<uint32_t>(a.N) && o[u] >= 0 && r[u] <= a.T && r[u] > o[u];
-                e[u] = map[ok ? i[u] : 0];
-                if (!ok) e[u] = -1;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < kIvU; ++u) {
-                if (e[u] < e0 || e[u] >= e1) e[u] = -1;     // nothing, cancelled, or left by an earlier plan
-                c[u] = a.cand[e[u] >= 0 ? e[u] : e0];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < kIvU; ++u)
-                if (e[u] >= 0 && c[u].x <= o[u] && r[u] <= c[u].y) map[i[u]] = -2;   // all writers write the same value
-        }
-        __syncthreads();   // the map and SMC are complete
-        PROF_MARK(4);
+        PROF_MARK(0);
 
-        // ---- 5: scores of the surviving candidates.  A wavefront takes 64 entries at a time:
-        // one entry per lane for the table lookups, then, 16 entries at a time, one entry per
-        // quad of lanes for the two 64-byte lines of the row around o and q.
-        {
-            // maxima of the spans before / after each wavefront's
-            int64_t before[kWaves], after[kWaves];
-            int64_t run = INT64_MIN;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                before[w] = run;
-                run = max64(run, span_max[w]);
+        for (int32_t slice_lo = 0; slice_lo < n_e; slice_lo += kMaxLocal) {
+            const int32_t n_slice = min(kMaxLocal, n_e - slice_lo);
+            __syncthreads();   // the previous plan or slice has finished with acc, tab, span_max and the filter
+            for (int32_t k = tid; k < n_slice; k += kThreads) acc[k] = INT64_MIN;
+            if (filter_of != bk) {
+                const uint32_t *src = a.filter + static_cast<int64_t>(bk) * a.filter_words;
+                for (int32_t k = tid; k < a.filter_words; k += kThreads) filter[k] = src[k];
+                filter_of = bk;
             }
-            run = INT64_MIN;
+            __syncthreads();
+            PROF_MARK(1);
+
+            // ---- 2: the plan's own intervals cancel candidates
+            {
+                const uint32_t fmask = static_cast<uint32_t>(a.filter_words) * 32 - 1;
+                const int hshift = 32 - hd.y;
+                const uint32_t hmask = (1u << hd.y) - 1;
+                const int4 *slots = a.hash_slots + hd.x;
+                for (int64_t kb = k0 + tid; kb < k1; kb += kIvU * kThreads) {
+                    int32_t i[kIvU], o[kIvU], r[kIvU];
+                    uint32_t h[kIvU];
+                    int4 s[kIvU];
+                    bool go[kIvU];
 #pragma unroll
-            for (int w = kWaves - 1; w >= 0; --w) {
-                after[w] = run;
-                run = max64(run, span_max[w]);
-            }
-            const int lane = tid & 63;
-            for (int32_t eb = e0 + wave * 64; eb < e1; eb += kThreads) {   // (wave-uniform)
-                const int32_t e = eb + lane;
-                const int32_t ec = e < e1 ? e : e1 - 1;
-                const int4 c = a.cand[ec];
-                const int32_t q = c.y, o = c.z, i = c.w;
-                const int32_t co = o >> 3, cq = q >> 3;
-                const int32_t cp = co > 0 ? co - 1 : 0, cs = cq + 1 < a.n_chunks ? cq + 1 : a.n_chunks - 1;
-                // every operand is requested before the first is used
-                const int32_t owner = map[i];
-                const int64_t sz = a.cand_size[ec];
-                const int64_t pm = PMC[cp], sm = SMC[cs];
-                const bool alive = e < e1 && o < tstar && tstar < q && owner == e;
-                const int32_t o_or_none = alive ? o : -1;
-                int64_t lines = INT64_MIN;        // max( MF[8co .. o], MF[q .. 8cq+7] ) of this lane's entry
+                    for (int u = 0; u < kIvU; ++u) {
+                        const int64_t k = kb + u * kThreads;
+                        const int64_t kc = k < k1 ? k : k1 - 1;
+                        i[u] = a.iv_tensor[kc];
+                        o[u] = a.iv_out[kc];
+                        r[u] = a.iv_in[kc];
+                        if (k >= k1) i[u] = -1;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int src = 16 * r + (lane >> 2);
-                    const int32_t o_s = __builtin_amdgcn_ds_bpermute(src << 2, o_or_none);
-                    const int32_t q_s = __builtin_amdgcn_ds_bpermute(src << 2, q);
-                    int64_t m = INT64_MIN;
-                    if (o_s >= 0) {
-                        const int32_t t0 = (o_s >> 3) * kChunk + 2 * (lane & 3), t1 = (q_s >> 3) * kChunk + 2 * (lane & 3);
-                        int64_t x0, x1, y0, y1;
-                        if (a.vec16) {
-                            load_pair<true>(MF, t0, a.T, x0, x1);
-                            load_pair<true>(MF, t1, a.T, y0, y1);
-                        } else {
-                            load_pair<false>(MF, t0, a.T, x0, x1);
-                            load_pair<false>(MF, t1, a.T, y0, y1);
+                    for (int u = 0; u < kIvU; ++u) {
+                        go[u] = static_cast<uint32_t>(i[u]) < static_cast<uint32_t>(a.N) && o[u] >= 0 && r[u] <= a.T && r[u] > o[u];
+                        const uint32_t fb = static_cast<uint32_t>(i[u]) & fmask;
+                        go[u] = go[u] && ((filter[fb >> 5] >> (fb & 31)) & 1u);
+                        h[u] = go[u] ? (static_cast<uint32_t>(i[u]) * 2654435769u) >> hshift : 0u;
+                        s[u] = slots[h[u]];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < kIvU; ++u) {
+                        while (go[u] && s[u].x >= 0) {      // probe until the tensor's last entry or an empty slot
+                            if (s[u].x == i[u]) {
+                                if (s[u].y <= o[u] && r[u] <= s[u].z) {
+                                    const uint32_t el = static_cast<uint32_t>((s[u].w & INT32_MAX) - slice_lo);
+                                    if (el < static_cast<uint32_t>(n_slice)) acc[el] = INT64_MAX;
+                                }
+                                if (s[u].w < 0) break;
+                            }
+                            h[u] = (h[u] + 1) & hmask;
+                            s[u] = slots[h[u]];
                         }
-                        if (t0 <= o_s) m = max64(m, x0);                     // t0 <= o < T
-                        if (t0 + 1 <= o_s) m = max64(m, x1);
-                        if (t1 >= q_s && t1 < a.T) m = max64(m, y0);
-                        if (t1 + 1 >= q_s && t1 + 1 < a.T) m = max64(m, y1);
                     }
-                    m = quad_max(m);
-                    const int64_t back = permute64(m, (lane & 15) << 2);   // quad (lane & 15) of round lane >> 4
-                    if ((lane >> 4) == r) lines = back;
-                }
-                if (alive) {
-                    int64_t m = max64(P - sz, lines);
-                    if (co > 0) {      // whole chunks before o's chunk: this span's, then the earlier spans
-                        int64_t x = pm;
-                        const int32_t w = cp / a.chunks_per_wave;
-#pragma unroll
-                        for (int k = 0; k < kWaves; ++k)
-                            if (k == w) x = max64(x, before[k]);
-                        m = max64(m, x);
-                    }
-                    if (cq + 1 < a.n_chunks) {
-                        int64_t x = sm;
-                        const int32_t w = cs / a.chunks_per_wave;
-#pragma unroll
-                        for (int k = 0; k < kWaves; ++k)
-                            if (k == w) x = max64(x, after[k]);
-                        m = max64(m, x);
-                    }
-                    score[i] = P - m;
-                    if (wout) wout[i] = o;
-                    if (win) win[i] = q;
                 }
             }
+            PROF_MARK(2);
+
+            // ---- 3: stream the row (no barrier needed after step 2: +inf survives every max)
+            {
+                const int32_t lo_begin = max(wp[wave], slice_lo), lo_end = min(wp[wave + 1], slice_lo + n_slice);
+                const int32_t hi_begin = wp[kWaves + 1 + wave], hi_end = wp[kWaves + 1 + wave + 1];
+                const int64_t m =
+                    a.vec16 ? stream_span<true>(a, MF, span_lo, span_hi, a.cand_o + e0, a.qord + e0, lo_begin, lo_end, hi_begin,
+                                                hi_end, slice_lo, n_slice, acc, &span_buf[wave], tab, lane)
+                            : stream_span<false>(a, MF, span_lo, span_hi, a.cand_o + e0, a.qord + e0, lo_begin, lo_end, hi_begin,
+                                                 hi_end, slice_lo, n_slice, acc, &span_buf[wave], tab, lane);
+                if (lane == 0) span_max[wave] = m;
+            }
+            PROF_MARK(3);
+            __syncthreads();
+            PROF_MARK(4);
+
+            // ---- 4: scores of the surviving candidates
+            for (int32_t k = tid; k < n_slice; k += kThreads) {
+                const int32_t e = e0 + slice_lo + k;
+                const int4 c = a.cand[e];
+                const int64_t sz = a.cand_size[e];
+                const int64_t v = acc[k];
+                const int32_t q = c.y, o = c.z, i = c.w;
+                if (!(o < tstar && tstar < q) || v == INT64_MAX) continue;
+                int32_t w_o = 0, w_q = 0;
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w) {
+                    w_o += o >= w * a.span;
+                    w_q += q >= w * a.span;
+                }
+                int64_t m = max64(v, P - sz);
+                const int32_t piece = q / kMini + 1;                          // pieces after q's, inside q's span
+                if (piece * kMini < min((w_q + 1) * a.span, a.T)) m = max64(m, tab[piece]);
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    const int64_t sm = span_max[w];
+                    if (w < w_o || w > w_q) m = max64(m, sm);
+                }
+                score[i] = P - m;
+                if (wout) wout[i] = o;
+                if (win) win[i] = q;
+            }
+            PROF_MARK(5);
         }
-        PROF_MARK(5);
     }
 }
 
@@ -389,6 +408,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
 int launch_score(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident, const int64_t *peak,
                  const int32_t *argmax, int64_t *score, int32_t *win_out, int32_t *win_in, hipStream_t stream) {
     if (plans->B == 0 || tas->N == 0) return TENSILE_OK;
+    const CandIndex &ix = tas->index;
     // as many workgroups as the device keeps resident, the plans dealt evenly among them
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -399,29 +419,30 @@ int launch_score(const tensile_tas *tas, const tensile_plans *plans, const int64
     const int64_t resident_blocks = static_cast<int64_t>(tas->num_cus) * per_cu;
     const int64_t rounds = (plans->B + resident_blocks - 1) / resident_blocks;
     const int32_t blocks = static_cast<int32_t>((plans->B + rounds - 1) / rounds);
-    const int32_t n_chunks = (tas->T + kChunk - 1) / kChunk;
-    Scratch &sc = tas->scratch;
-    const size_t need = static_cast<size_t>(blocks) * 3 * static_cast<size_t>(n_chunks);
-    const size_t need_map = static_cast<size_t>(blocks) * static_cast<size_t>(tas->N);
-    if (sc.rowmax.n < need || sc.cand_map.n < need_map) {
-        TS_HIP(hipDeviceSynchronize());
-        TS_HIP(sc.rowmax.reserve(need));
-        TS_HIP(sc.cand_map.reserve(need_map));
-    }
     ScoreArgs a;
     a.T = tas->T; a.N = tas->N; a.B = plans->B;
-    a.n_chunks = n_chunks;
-    a.chunks_per_wave = (n_chunks + kWaves * 64 - 1) / (kWaves * 64) * 64;
+    a.span = ix.span;
+    a.n_tab = (tas->T + kMini - 1) / kMini;
+    a.vec16 = (tas->T % 2 == 0) && (reinterpret_cast<uintptr_t>(resident) % 16 == 0);
     a.n_intervals = plans->n_intervals;
     a.plan_offsets = plans->plan_offsets;
     a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;
-    a.size = tas->d_size.p;
-    a.cand = tas->d_cand.p; a.cand_size = tas->d_cand_size.p; a.bucket_off = tas->d_bucket_off.p; a.bucket_shift = tas->bucket_shift;
+    a.bucket_shift = ix.shift; a.filter_words = ix.filter_words;
+    a.bucket_off = ix.bucket_off.p;
+    a.cand = ix.cand.p; a.cand_size = ix.cand_size.p; a.cand_o = ix.cand_o.p; a.qord = ix.qord.p;
+    a.wave_ptr = ix.wave_ptr.p; a.hash_dir = ix.hash_dir.p; a.hash_slots = ix.hash_slots.p; a.filter = ix.filter.p;
     a.resident = resident; a.peak = peak; a.argmax = argmax;
     a.score = score; a.win_out = win_out; a.win_in = win_in;
-    a.tables = sc.rowmax.p;
-    a.map = sc.cand_map.p;
-    a.vec16 = (tas->T % 2 == 0) && (reinterpret_cast<uintptr_t>(resident) % 16 == 0);
+    a.tab_scratch = nullptr;
+    if (a.n_tab > kTabLds) {
+        Scratch &sc = tas->scratch;
+        const size_t need = static_cast<size_t>(blocks) * static_cast<size_t>(a.n_tab);
+        if (sc.score_tab.n < need) {
+            TS_HIP(hipDeviceSynchronize());
+            TS_HIP(sc.score_tab.reserve(need));
+        }
+        a.tab_scratch = sc.score_tab.p;
+    }
     hipLaunchKernelGGL(score_kernel, dim3(blocks), dim3(kThreads), 0, stream, a);
     TS_HIP(hipGetLastError());
     return TENSILE_OK;

@@ -121,7 +121,7 @@ __global__ void lifetime_intervals_kernel(int32_t N, const int64_t *size, const 
 int validate_desc(const tensile_tas_desc *d) {
     if (!d) { set_error("tas_load: desc is NULL"); return TENSILE_E_INVAL; }
     if (d->T <= 0) { set_error("tas_load: T = %d must be positive", d->T); return TENSILE_E_INVAL; }
-    if (d->T == INT32_MAX) { set_error("tas_load: T too large"); return TENSILE_E_INVAL; }
+    if (d->T > INT32_MAX - (1 << 20)) { set_error("tas_load: T too large"); return TENSILE_E_INVAL; }
     if (d->N < 0) { set_error("tas_load: N = %d is negative", d->N); return TENSILE_E_INVAL; }
     if (d->J < 1) { set_error("tas_load: J = %d must be at least 1", d->J); return TENSILE_E_INVAL; }
     if (d->N > 0 && (!d->size_bytes || !d->alloc_step || !d->free_step || !d->access_offsets)) {
@@ -178,38 +178,109 @@ int validate_desc(const tensile_tas_desc *d) {
 // A gap (p, q) with earliest swap-out step o >= 0 is a scoring candidate at the peak steps
 // t* with o < t* < q.  File it under every bucket of 2^shift steps that o+1 .. q-1 overlaps;
 // the bucket width starts at 256 steps and doubles while the index would hold more than
-// about 16 entries per gap.
+// about 16 entries per gap (or its filters more than 256 MiB).  CandIndex (common.h) lists
+// what is kept per bucket.
 int build_candidate_index(tensile_tas *h, const std::vector<int32_t> &gp, const std::vector<int32_t> &gq,
                           const std::vector<int32_t> &gt, const std::vector<int32_t> &gwin) {
+    CandIndex &ix = h->index;
     const size_t G = gp.size();
     const int32_t T = h->T;
+    auto usable = [&](size_t g) { return gwin[g] >= 0 && gwin[g] + 1 <= gq[g] - 1; };
+    uint32_t filter_bits = 1024;
+    while (filter_bits < 32768 && filter_bits < static_cast<uint32_t>(h->N)) filter_bits <<= 1;
+    ix.filter_words = static_cast<int32_t>(filter_bits / 32);
     int32_t shift = 8;
     uint64_t entries;
     for (;; ++shift) {
         entries = 0;
         for (size_t g = 0; g < G; ++g)
-            if (gwin[g] >= 0 && gwin[g] + 1 <= gq[g] - 1) entries += ((gq[g] - 1) >> shift) - ((gwin[g] + 1) >> shift) + 1;
-        if (entries <= 16 * static_cast<uint64_t>(G) + 4096 || (int64_t{1} << shift) >= T) break;
+            if (usable(g)) entries += ((gq[g] - 1) >> shift) - ((gwin[g] + 1) >> shift) + 1;
+        const uint64_t filter_bytes = (static_cast<uint64_t>((T - 1) >> shift) + 1) * (filter_bits / 8);
+        if ((entries <= 16 * static_cast<uint64_t>(G) + 4096 && filter_bytes <= (256u << 20)) || (int64_t{1} << shift) >= T) break;
     }
-    if (entries > static_cast<uint64_t>(INT32_MAX)) { set_error("tas_load: candidate index too large"); return TENSILE_E_RANGE; }
-    const int32_t n_buckets = ((T - 1) >> shift) + 1;
-    std::vector<int32_t> off(static_cast<size_t>(n_buckets) + 1, 0);
+    if (entries > static_cast<uint64_t>(INT32_MAX) / 4) { set_error("tas_load: candidate index too large"); return TENSILE_E_RANGE; }
+    const int32_t nb = ((T - 1) >> shift) + 1;
+    ix.shift = shift;
+    ix.n_buckets = nb;
+    ix.span = ((T + kScoreWaves - 1) / kScoreWaves + kScoreMini - 1) / kScoreMini * kScoreMini;
+
+    std::vector<int32_t> off(static_cast<size_t>(nb) + 1, 0);
     for (size_t g = 0; g < G; ++g)
-        if (gwin[g] >= 0 && gwin[g] + 1 <= gq[g] - 1)
+        if (usable(g))
             for (int32_t b = (gwin[g] + 1) >> shift; b <= (gq[g] - 1) >> shift; ++b) ++off[b + 1];
-    for (int32_t b = 0; b < n_buckets; ++b) off[b + 1] += off[b];
-    std::vector<int4> cand(static_cast<size_t>(off[n_buckets]));
-    std::vector<int32_t> fill(off.begin(), off.end() - 1);
-    for (size_t g = 0; g < G; ++g)
-        if (gwin[g] >= 0 && gwin[g] + 1 <= gq[g] - 1)
-            for (int32_t b = (gwin[g] + 1) >> shift; b <= (gq[g] - 1) >> shift; ++b)
-                cand[fill[b]++] = make_int4(gp[g], gq[g], gwin[g], gt[g]);
-    std::vector<int64_t> cand_size(cand.size());
-    for (size_t e = 0; e < cand.size(); ++e) cand_size[e] = h->h_size[cand[e].w];
-    h->bucket_shift = shift;
-    TS_HIP(h->d_cand.upload(cand.data(), cand.size()));
-    TS_HIP(h->d_cand_size.upload(cand_size.data(), cand_size.size()));
-    TS_HIP(h->d_bucket_off.upload(off.data(), off.size()));
+    for (int32_t b = 0; b < nb; ++b) off[b + 1] += off[b];
+    const size_t E = static_cast<size_t>(off[nb]);
+    std::vector<int4> cand(E);
+    {
+        std::vector<int32_t> fill(off.begin(), off.end() - 1);
+        for (size_t g = 0; g < G; ++g)
+            if (usable(g))
+                for (int32_t b = (gwin[g] + 1) >> shift; b <= (gq[g] - 1) >> shift; ++b)
+                    cand[fill[b]++] = make_int4(gp[g], gq[g], gwin[g], gt[g]);
+    }
+    std::vector<int64_t> cand_size(E);
+    std::vector<int32_t> cand_o(E);
+    std::vector<int2> qord(E);
+    std::vector<int32_t> wave_ptr(static_cast<size_t>(nb) * 2 * (kScoreWaves + 1));
+    std::vector<int2> hash_dir(static_cast<size_t>(nb));
+    std::vector<int4> hash_slots;
+    std::vector<uint32_t> filter(static_cast<size_t>(nb) * ix.filter_words, 0u);
+    std::vector<int32_t> order;
+    ix.max_bucket = 0;
+    for (int32_t b = 0; b < nb; ++b) {
+        const int32_t e0 = off[b], n = off[b + 1] - off[b];
+        ix.max_bucket = std::max(ix.max_bucket, n);
+        int4 *c = cand.data() + e0;
+        std::sort(c, c + n, [](const int4 &x, const int4 &y) {
+            return x.z != y.z ? x.z < y.z : (x.w != y.w ? x.w < y.w : x.x < y.x);
+        });
+        order.resize(n);
+        for (int32_t k = 0; k < n; ++k) {
+            cand_size[e0 + k] = h->h_size[c[k].w];
+            cand_o[e0 + k] = c[k].z;
+            order[k] = k;
+        }
+        std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return c[x].y != c[y].y ? c[x].y < c[y].y : x < y; });
+        for (int32_t k = 0; k < n; ++k) qord[e0 + k] = make_int2(c[order[k]].y, order[k]);
+        int32_t *wp = wave_ptr.data() + static_cast<size_t>(b) * 2 * (kScoreWaves + 1);
+        int32_t ko = 0, kq = 0;
+        for (int w = 0; w <= kScoreWaves; ++w) {
+            const int64_t bound = static_cast<int64_t>(w) * ix.span;
+            while (ko < n && c[ko].z < bound) ++ko;
+            while (kq < n && qord[e0 + kq].x < bound) ++kq;
+            wp[w] = w == kScoreWaves ? n : ko;
+            wp[kScoreWaves + 1 + w] = w == kScoreWaves ? n : kq;
+        }
+        // hash table: the entries of one tensor are inserted one after the other, the last flagged
+        int bits = 1;
+        while ((int64_t{1} << bits) < 2 * static_cast<int64_t>(n)) ++bits;
+        const size_t base = hash_slots.size();
+        hash_dir[b] = make_int2(static_cast<int32_t>(base), n > 0 ? bits : 0);
+        if (n == 0) continue;
+        if (base + (size_t{1} << bits) > static_cast<size_t>(INT32_MAX)) { set_error("tas_load: candidate index too large"); return TENSILE_E_RANGE; }
+        hash_slots.resize(base + (size_t{1} << bits), make_int4(-1, 0, 0, 0));
+        for (int32_t k = 0; k < n; ++k) order[k] = k;
+        std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return c[x].w != c[y].w ? c[x].w < c[y].w : x < y; });
+        const uint32_t mask = (1u << bits) - 1;
+        for (int32_t k = 0; k < n; ++k) {
+            const int4 &en = c[order[k]];
+            const bool last = k + 1 == n || c[order[k + 1]].w != en.w;
+            uint32_t s = (static_cast<uint32_t>(en.w) * 2654435769u) >> (32 - bits);
+            while (hash_slots[base + s].x >= 0) s = (s + 1) & mask;
+            hash_slots[base + s] = make_int4(en.w, en.x, en.y, order[k] | (last ? INT32_MIN : 0));
+            const uint32_t fb = static_cast<uint32_t>(en.w) & (filter_bits - 1);
+            filter[static_cast<size_t>(b) * ix.filter_words + (fb >> 5)] |= 1u << (fb & 31);
+        }
+    }
+    TS_HIP(ix.bucket_off.upload(off.data(), off.size()));
+    TS_HIP(ix.cand.upload(cand.data(), E));
+    TS_HIP(ix.cand_size.upload(cand_size.data(), E));
+    TS_HIP(ix.cand_o.upload(cand_o.data(), E));
+    TS_HIP(ix.qord.upload(qord.data(), E));
+    TS_HIP(ix.wave_ptr.upload(wave_ptr.data(), wave_ptr.size()));
+    TS_HIP(ix.hash_dir.upload(hash_dir.data(), hash_dir.size()));
+    TS_HIP(ix.hash_slots.upload(hash_slots.data(), hash_slots.size()));
+    TS_HIP(ix.filter.upload(filter.data(), filter.size()));
     return TENSILE_OK;
 }
 
