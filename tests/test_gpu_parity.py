@@ -18,6 +18,7 @@ import paper_2105_13336_amd as P  # noqa: E402
 from oracle import oracle as O  # noqa: E402
 from workloads import (CONFIGS, make_config_plans, make_plans, make_tas, plans_from_lists, small_random_tas,  # noqa: E402
                        tas_from_lists)
+from workloads import prng  # noqa: E402
 from workloads.plans import Plans  # noqa: E402
 
 
@@ -205,6 +206,23 @@ def test_score_random(seed, timed, T):
     pl = make_plans(tas, 24, seed, p_swap=0.25)
     say(f"score random seed={seed} T={T}")
     assert check_score(tas, pl) > 0
+
+
+@pytest.mark.parametrize("timed", [False, True])
+def test_score_crowded_bucket(timed):
+    """More candidate gaps around the peak than one pass of the scoring kernel holds, many of
+    them with the same swap-out step: every tensor is generated early and read late."""
+    T, N = 600, 9000
+    i = np.arange(N)
+    alloc = prng.randint(77, 1, i, 0, 249)
+    first = prng.randint(77, 2, i, 350, 598)
+    sizes = prng.randint(77, 3, i, 1, 1 << 16)
+    accs = [[int(first[k])] + ([int(first[k]) + 1] if k % 3 == 0 else []) for k in range(N)]
+    sn = prng.randint(77, 4, np.arange(T), 1, 1000).astype(np.int64) if timed else None
+    tas = tas_from_lists(T, [int(x) for x in sizes], [int(x) for x in alloc], accs, None, sn, 0, 4000 if timed else 0)
+    pl = make_plans(tas, 6, 5, p_swap=0.2)
+    say(f"score crowded bucket timed={timed}")
+    assert check_score(tas, pl) > 4096
 
 
 def test_score_optional_windows_and_blocking():
