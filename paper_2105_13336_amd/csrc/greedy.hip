@@ -69,6 +69,53 @@ struct Link {
 struct Cand {
     int32_t tensor;
     int64_t score, size;
+    int32_t wo, wi;
+};
+
+// What one iteration brings back from the device: the peak, its step and the tensors with a window.
+struct Header {
+    int64_t P;
+    int32_t tstar, count;
+};
+struct CandOut {
+    int64_t score;
+    int32_t tensor, wo, wi, pad;
+};
+constexpr int32_t kFirstCopy = 4096;   // candidates fetched together with the header
+
+// The tensors with a window, in no particular order (the host sorts them by a total order).
+__global__ __launch_bounds__(1024) void compact_candidates_kernel(int32_t N, const int64_t *score, const int32_t *wo,
+                                                                  const int32_t *wi, const int64_t *peak,
+                                                                  const int32_t *arg, Header *hdr, CandOut *out) {
+    __shared__ int32_t n;
+    if (threadIdx.x == 0) n = 0;
+    __syncthreads();
+    for (int32_t i = threadIdx.x; i < N; i += blockDim.x) {
+        const int32_t o = wo[i];
+        if (o < 0) continue;
+        const int32_t slot = atomicAdd(&n, 1);
+        out[slot] = CandOut{score[i], i, o, wi[i], 0};
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) *hdr = Header{*peak, *arg, n};
+}
+
+__global__ void peak_only_kernel(const int64_t *peak, const int32_t *arg, Header *hdr) { *hdr = Header{*peak, *arg, 0}; }
+
+// Appends one interval to the device copy of the plan (B = 1) and moves its end offset.
+__global__ void append_interval_kernel(int32_t *t, int32_t *o, int32_t *r, int64_t *offs, int32_t n, int32_t tensor,
+                                       int32_t out, int32_t in) {
+    t[n] = tensor;
+    o[n] = out;
+    r[n] = in;
+    offs[1] = n + 1;
+}
+
+// Pinned host memory that frees itself.
+struct PinnedBuf {
+    void *p = nullptr;
+    ~PinnedBuf() { if (p) (void)hipHostFree(p); }
+    hipError_t reserve(size_t bytes) { return hipHostMalloc(&p, bytes, hipHostMallocDefault); }
 };
 
 }  // namespace
@@ -95,20 +142,31 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
     const int32_t max_new = opt.max_iters > 0 ? opt.max_iters : INT32_MAX;
 
     try {
-        // device state: the growing plan (B = 1) and one row of every output
+        // device state: the growing plan (B = 1), one row of every output, the compacted candidates
         DevBuf<int64_t> d_offs, d_res, d_peak, d_min, d_score;
         DevBuf<int32_t> d_t, d_o, d_r, d_arg, d_wo, d_wi;
+        DevBuf<Header> d_hdr;           // header followed by the candidates, one allocation
         TS_HIP(d_offs.reserve(2));
         TS_HIP(d_t.reserve(capacity)); TS_HIP(d_o.reserve(capacity)); TS_HIP(d_r.reserve(capacity));
         TS_HIP(d_res.reserve(T)); TS_HIP(d_peak.reserve(1)); TS_HIP(d_min.reserve(1)); TS_HIP(d_arg.reserve(1));
         TS_HIP(d_score.reserve(N)); TS_HIP(d_wo.reserve(N)); TS_HIP(d_wi.reserve(N));
+        static_assert(sizeof(Header) == 16 && sizeof(CandOut) == 24, "layout of the iteration record");
+        const size_t rec_bytes = sizeof(Header) + static_cast<size_t>(N) * sizeof(CandOut);
+        TS_HIP(d_hdr.reserve((rec_bytes + sizeof(Header) - 1) / sizeof(Header)));
+        CandOut *d_cands = reinterpret_cast<CandOut *>(d_hdr.p + 1);
+        PinnedBuf h_rec;
+        TS_HIP(h_rec.reserve(rec_bytes));
+        const Header *hdr = static_cast<const Header *>(h_rec.p);
+        const CandOut *h_cands = reinterpret_cast<const CandOut *>(hdr + 1);
         if (n_initial > 0) {
             TS_HIP(hipMemcpy(d_t.p, iv_tensor, n_initial * 4, hipMemcpyHostToDevice));
             TS_HIP(hipMemcpy(d_o.p, iv_out, n_initial * 4, hipMemcpyHostToDevice));
             TS_HIP(hipMemcpy(d_r.p, iv_in, n_initial * 4, hipMemcpyHostToDevice));
         }
-        std::vector<int64_t> score(N);
-        std::vector<int32_t> wo(N), wi(N);
+        {
+            const int64_t h_offs[2] = {0, n_initial};
+            TS_HIP(hipMemcpy(d_offs.p, h_offs, sizeof h_offs, hipMemcpyHostToDevice));
+        }
         std::vector<Cand> cand;
         cand.reserve(N);
         std::vector<int64_t> hist;
@@ -119,48 +177,65 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
         int32_t n = n_initial;
         int64_t P = 0;
         for (;;) {
+            // One round trip per iteration: evaluate, score and compact on the device (the scores
+            // of the last iteration are computed in vain), then fetch the header and the first
+            // candidates together.
             const int32_t it = n - n_initial;
-            const int64_t h_offs[2] = {0, n};
-            TS_HIP(hipMemcpy(d_offs.p, h_offs, sizeof h_offs, hipMemcpyHostToDevice));
+            const bool last = it >= max_new || n >= capacity || N == 0;
             tensile_plans pl{1, n, d_offs.p, d_t.p, d_o.p, d_r.p, nullptr};
             int rc = tensile_eval_plans(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr);
             if (rc != TENSILE_OK) return rc;
-            int32_t tstar = 0;
-            TS_HIP(hipMemcpy(&P, d_peak.p, 8, hipMemcpyDeviceToHost));
-            TS_HIP(hipMemcpy(&tstar, d_arg.p, 4, hipMemcpyDeviceToHost));
+            size_t first_bytes = sizeof(Header);
+            if (last) {
+                hipLaunchKernelGGL(peak_only_kernel, dim3(1), dim3(1), 0, nullptr, d_peak.p, d_arg.p, d_hdr.p);
+            } else {
+                rc = tensile_score_candidates(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_score.p, d_wo.p, d_wi.p, nullptr);
+                if (rc != TENSILE_OK) return rc;
+                hipLaunchKernelGGL(compact_candidates_kernel, dim3(1), dim3(1024), 0, nullptr, N, d_score.p, d_wo.p, d_wi.p,
+                                   d_peak.p, d_arg.p, d_hdr.p, d_cands);
+                first_bytes += static_cast<size_t>(std::min(N, kFirstCopy)) * sizeof(CandOut);
+            }
+            TS_HIP(hipGetLastError());
+            TS_HIP(hipMemcpyAsync(h_rec.p, d_hdr.p, first_bytes, hipMemcpyDeviceToHost, nullptr));
+            TS_HIP(hipStreamSynchronize(nullptr));
+            P = hdr->P;
+            const int32_t tstar = hdr->tstar;
             hist.push_back(P);
             if (peak_trace) peak_trace[it] = P;
-            if (it >= max_new || n >= capacity) break;
+            if (last) break;
             if (opt.stop_at_budget && P <= budget_bytes) break;
             if (it > opt.min_iters && it >= 3 && (hist[it - 3] - P) * 10000 < 5 * hist[it - 3]) break;
-            if (N == 0) break;
-
-            rc = tensile_score_candidates(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_score.p, d_wo.p, d_wi.p, nullptr);
-            if (rc != TENSILE_OK) return rc;
-            TS_HIP(hipMemcpy(score.data(), d_score.p, static_cast<size_t>(N) * 8, hipMemcpyDeviceToHost));
-            TS_HIP(hipMemcpy(wo.data(), d_wo.p, static_cast<size_t>(N) * 4, hipMemcpyDeviceToHost));
-            TS_HIP(hipMemcpy(wi.data(), d_wi.p, static_cast<size_t>(N) * 4, hipMemcpyDeviceToHost));
+            if (hdr->count > kFirstCopy) {
+                TS_HIP(hipMemcpyAsync(static_cast<char *>(h_rec.p) + first_bytes, reinterpret_cast<const char *>(d_hdr.p) + first_bytes,
+                                      static_cast<size_t>(hdr->count - kFirstCopy) * sizeof(CandOut), hipMemcpyDeviceToHost, nullptr));
+                TS_HIP(hipStreamSynchronize(nullptr));
+            }
 
             cand.clear();
             const int64_t tot = std::max<int64_t>(1, swapped_total);
-            for (int32_t i = 0; i < N; ++i) {
-                if (wo[i] < 0) continue;
+            for (int32_t k = 0; k < hdr->count; ++k) {
+                const CandOut &c = h_cands[k];
                 if (opt.msr_num) {
-                    const int32_t j = tas->h_job[i];
+                    const int32_t j = tas->h_job[c.tensor];
                     if (!(swapped[j] * opt.msr_den <= opt.msr_num[j] * tot)) continue;
                 }
-                cand.push_back(Cand{i, score[i], tas->h_size[i]});
+                cand.push_back(Cand{c.tensor, c.score, tas->h_size[c.tensor], c.wo, c.wi});
             }
-            std::sort(cand.begin(), cand.end(), [](const Cand &a, const Cand &b) {
-                if (a.score != b.score) return a.score > b.score;
-                if (a.size != b.size) return a.size > b.size;
-                return a.tensor < b.tensor;
-            });
+            // candidates are tried in the order (score desc, size desc, tensor asc); usually one of the
+            // first few is accepted, so a heap is popped instead of sorting them all
+            auto later = [](const Cand &a, const Cand &b) {      // a comes after b
+                if (a.score != b.score) return a.score < b.score;
+                if (a.size != b.size) return a.size < b.size;
+                return a.tensor > b.tensor;
+            };
+            std::make_heap(cand.begin(), cand.end(), later);
 
             bool accepted = false;
-            for (const Cand &c : cand) {
+            for (auto end = cand.end(); end != cand.begin(); --end) {
+                std::pop_heap(cand.begin(), end, later);
+                const Cand &c = *(end - 1);
                 const int32_t i = c.tensor;
-                const int32_t q = wi[i];                         // p_{g+1}
+                const int32_t q = c.wi;                          // p_{g+1}
                 // p_g: the touch point just before q in the tensor's list
                 const int32_t *tb = tas->h_touch.data() + tas->h_touch_off[i];
                 const int32_t *te = tas->h_touch.data() + tas->h_touch_off[i + 1];
@@ -182,10 +257,9 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
                 iv_out[n] = o_placed;
                 iv_in[n] = r_placed;
                 iv_kind[n] = 0;
-                const int32_t triple[3] = {i, o_placed, r_placed};
-                TS_HIP(hipMemcpy(d_t.p + n, &triple[0], 4, hipMemcpyHostToDevice));
-                TS_HIP(hipMemcpy(d_o.p + n, &triple[1], 4, hipMemcpyHostToDevice));
-                TS_HIP(hipMemcpy(d_r.p + n, &triple[2], 4, hipMemcpyHostToDevice));
+                hipLaunchKernelGGL(append_interval_kernel, dim3(1), dim3(1), 0, nullptr, d_t.p, d_o.p, d_r.p, d_offs.p, n, i,
+                                   o_placed, r_placed);
+                TS_HIP(hipGetLastError());
                 ++swapped[tas->h_job[i]];
                 ++swapped_total;
                 ++n;
@@ -194,6 +268,7 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
             }
             if (!accepted) break;
         }
+        TS_HIP(hipDeviceSynchronize());
         *n_intervals = n;
         *final_peak = P;
     } catch (const std::bad_alloc &) {
