@@ -90,13 +90,32 @@ def score_plans(tas, plans, resident: np.ndarray, peak: np.ndarray, argmax: np.n
     return score, wo, wi
 
 
+def score_recompute_plans(tas, plans, resident: np.ndarray, peak: np.ndarray, argmax: np.ndarray,
+                          rows: Optional[Sequence[int]] = None):
+    """Recomputation savings of the plans in ``rows`` (default all): -> score [R,N], win_out [R,N], win_in [R,N]"""
+    rows = list(range(plans.B)) if rows is None else list(rows)
+    R, N = len(rows), tas.N
+    score = np.zeros((R, N), dtype=np.int64); wo = np.zeros((R, N), dtype=np.int32); wi = np.zeros((R, N), dtype=np.int32)
+    lib = _lib()
+    for n, b in enumerate(rows):
+        a, e = int(plans.plan_offsets[b]), int(plans.plan_offsets[b + 1])
+        t, o, r = (np.ascontiguousarray(v[a:e]) for v in (plans.iv_tensor, plans.iv_out, plans.iv_in))
+        MF = np.ascontiguousarray(resident[b])
+        _chk(lib.oracle_score_recompute_plan(i32(tas.T), i32(N), _p(tas.size_bytes), _p(tas.alloc_step),
+                                             _p(tas.access_offsets), _p(tas.access_steps), i64(e - a), _p(t), _p(o), _p(r),
+                                             _p(MF), i64(int(peak[b])), i32(int(argmax[b])), _p(score[n]), _p(wo[n]),
+                                             _p(wi[n])), "score_recompute")
+    return score, wo, wi
+
+
 class _GreedyOpts(ctypes.Structure):
     _fields_ = [("max_iters", i32), ("min_iters", i32), ("stop_at_budget", i32), ("J", i32),
-                ("job_id", ctypes.c_void_p), ("msr_num", ctypes.c_void_p), ("msr_den", i64)]
+                ("job_id", ctypes.c_void_p), ("msr_num", ctypes.c_void_p), ("msr_den", i64), ("recompute", i32)]
 
 
 def greedy(tas, budget: int, max_iters: int = 1 << 30, min_iters: int = 100, stop_at_budget: bool = False,
-           msr_num: Optional[np.ndarray] = None, msr_den: int = 1, capacity: Optional[int] = None, initial=None):
+           msr_num: Optional[np.ndarray] = None, msr_den: int = 1, capacity: Optional[int] = None, initial=None,
+           recompute: bool = False):
     """-> dict(iv_tensor, iv_out, iv_in, iv_kind, peak_trace, final_peak, xfer_out_start, xfer_in_start);
     ``initial`` = (iv_tensor, iv_out, iv_in, iv_kind) of a plan to extend."""
     n0 = 0 if initial is None else len(initial[0])
@@ -112,7 +131,7 @@ def greedy(tas, budget: int, max_iters: int = 1 << 30, min_iters: int = 100, sto
     job = np.ascontiguousarray(tas.job_id, dtype=np.int32)
     num = None if msr_num is None else np.ascontiguousarray(msr_num, dtype=np.int64)
     opts = _GreedyOpts(min(max_iters, 1 << 30), min_iters, int(stop_at_budget), tas.J if num is not None else 0,
-                       job.ctypes.data, None if num is None else num.ctypes.data, msr_den)
+                       job.ctypes.data, None if num is None else num.ctypes.data, msr_den, int(recompute))
     _chk(_lib().oracle_greedy(i32(tas.T), i32(tas.N), _p(tas.size_bytes), _p(tas.alloc_step), _p(tas.free_step),
                               _p(tas.access_offsets), _p(tas.access_steps), _p(tas.step_ns), i64(tas.base_bytes),
                               i64(tas.link_bytes_per_us), i64(budget), ctypes.byref(opts), i32(capacity), i32(n0),

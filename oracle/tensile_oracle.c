@@ -234,6 +234,53 @@ int oracle_score_plan(int32_t T, int32_t N, const int64_t *size, const int32_t *
     return OR_OK;
 }
 
+/* Recomputation candidates of ONE plan (section IV-D, "Recomputation
+ * Scheduling"): a tensor may be released after an access and regenerated right
+ * before its next access, but only if it "has never been released", read here as:
+ * the plan holds no interval of this tensor at all, in any gap (a tensor already
+ * swapped or recomputed somewhere stays out, so that the plan built so far is
+ * not disturbed).
+ *   1. gap g of tensor i with p_g < tstar < p_{g+1}, as for swapping.
+ *   2. zero if the plan holds any applicable interval of tensor i.
+ *   3. the window is the whole gap: o = p_g, r = p_{g+1} (no transfer, no link).
+ *   4. memory saving = P - max(PM[p_g], SM[p_{g+1}], P - size_i).
+ * win_out/win_in receive (p_g, p_{g+1}), or -1 when the tensor is no candidate. */
+int oracle_score_recompute_plan(int32_t T, int32_t N, const int64_t *size, const int32_t *alloc,
+                                const int64_t *access_offsets, const int32_t *access_steps, int64_t K,
+                                const int32_t *iv_tensor, const int32_t *iv_out, const int32_t *iv_in, const int64_t *MF,
+                                int64_t P, int32_t tstar, int64_t *score, int32_t *win_out, int32_t *win_in) {
+    if (T <= 0 || N < 0) return OR_E_INVAL;
+    for (int32_t i = 0; i < N; ++i) {
+        score[i] = 0;
+        if (win_out) win_out[i] = -1;
+        if (win_in) win_in[i] = -1;
+        int64_t a0 = access_offsets[i], a1 = access_offsets[i + 1];
+        int32_t pg = -1, pg1 = -1, prev = alloc[i];
+        for (int64_t k = a0; k < a1; ++k) {
+            if (prev < tstar && tstar < access_steps[k]) {
+                pg = prev;
+                pg1 = access_steps[k];
+            }
+            prev = access_steps[k];
+        }
+        if (pg < 0) continue;
+        int released = 0;
+        for (int64_t k = 0; k < K; ++k)
+            if (iv_tensor[k] == i && interval_applies(N, T, iv_tensor[k], iv_out[k], iv_in[k])) released = 1;
+        if (released) continue;
+        /* maxima outside the window, by direct search */
+        int64_t m = P - size[i];
+        for (int32_t t = 0; t <= pg; ++t)
+            if (MF[t] > m) m = MF[t];
+        for (int32_t t = pg1; t < T; ++t)
+            if (MF[t] > m) m = MF[t];
+        score[i] = P - m;
+        if (win_out) win_out[i] = pg;
+        if (win_in) win_in[i] = pg1;
+    }
+    return OR_OK;
+}
+
 /* Options of the greedy planner (Alg. 3's hyper-parameters). */
 typedef struct {
     int32_t max_iters;        /* hard cap on accepted intervals */
@@ -243,11 +290,13 @@ typedef struct {
     const int32_t *job_id;    /* [N] */
     const int64_t *msr_num;   /* [J] max swapping rate of job j = msr_num[j]/msr_den */
     int64_t msr_den;
+    int32_t recompute;        /* run the recomputation phase while the peak exceeds the budget */
 } oracle_greedy_opts;
 
 typedef struct {
     int32_t tensor;
     int64_t score, size;
+    int64_t time;             /* recomputation phase only: latency of the generating operator */
 } cand_t;
 
 static int cand_cmp(const void *pa, const void *pb) {
@@ -257,6 +306,16 @@ static int cand_cmp(const void *pa, const void *pb) {
     return a->tensor < b->tensor ? -1 : (a->tensor > b->tensor ? 1 : 0);
 }
 
+/* Recomputation candidates in the order of their value MSPS = memory saving /
+ * recomputation time (section IV-D), largest first; the quotients are compared
+ * exactly by cross-multiplication.  Ties: larger saving, larger tensor, lower id. */
+static int msps_cmp(const void *pa, const void *pb) {
+    const cand_t *a = (const cand_t *)pa, *b = (const cand_t *)pb;
+    __int128 l = (__int128)a->score * b->time, r = (__int128)b->score * a->time;
+    if (l != r) return l > r ? -1 : 1;
+    return cand_cmp(pa, pb);
+}
+
 /* Swap phase of Alg. 3 with Alg. 2's placement, one interval per iteration:
  * analyse the peak (Alg. 1), order the candidates by (score desc, size desc,
  * tensor id asc), place the swap-out as early and the swap-in as late as the
@@ -264,6 +323,10 @@ static int cand_cmp(const void *pa, const void *pb) {
  * whose placed window still contains the peak step; stop when nothing is
  * accepted, at max_iters, at the budget if asked, or when the last three
  * iterations lowered the peak by less than 0.05% after min_iters iterations.
+ * With opt->recompute, once no swap is accepted and while the peak is above the
+ * budget, recomputation intervals (kind 1) are added one per iteration, the
+ * candidate with the largest MSPS first (oracle_score_recompute_plan, msps_cmp),
+ * under the same stop rules.
  * The first n_initial entries of the interval arrays are a plan to extend (kept
  * as they are; their transfers are not entered into the link timeline).
  * peak_trace[k] is the peak before the k-th newly accepted interval
@@ -294,6 +357,7 @@ int oracle_greedy(int32_t T, int32_t N, const int64_t *size, const int32_t *allo
 
     int32_t iter = n_initial;
     int64_t P = 0, son_total = 0;
+    int swap_phase = 1;
     for (;;) {
         int32_t tstar;
         int64_t mn;
@@ -305,90 +369,119 @@ int oracle_greedy(int32_t T, int32_t N, const int64_t *size, const int32_t *allo
         if (opt->stop_at_budget && P <= budget) break;
         if (it > opt->min_iters && it >= 3 && (hist[it - 3] - P) * 10000 < 5 * hist[it - 3]) break;
 
-        rc = oracle_score_plan(T, N, size, alloc, access_offsets, access_steps, C, x, iter, iv_tensor, iv_out, iv_in,
-                               MF, P, tstar, score, wo, wi);
-        if (rc != OR_OK) goto done;
+        int accepted = 0;
         int32_t nc = 0;
-        for (int32_t i = 0; i < N; ++i) {
-            if (wo[i] < 0) continue;
-            if (opt->J > 0 && opt->msr_num) {   /* per-job max swapping rate (section IV-C) */
-                int32_t j = opt->job_id[i];
-                int64_t tot = son_total > 1 ? son_total : 1;
-                if (!(SON[j] * opt->msr_den <= opt->msr_num[j] * tot)) continue;
+        if (swap_phase) {
+            rc = oracle_score_plan(T, N, size, alloc, access_offsets, access_steps, C, x, iter, iv_tensor, iv_out, iv_in,
+                                   MF, P, tstar, score, wo, wi);
+            if (rc != OR_OK) goto done;
+            for (int32_t i = 0; i < N; ++i) {
+                if (wo[i] < 0) continue;
+                if (opt->J > 0 && opt->msr_num) {   /* per-job max swapping rate (section IV-C) */
+                    int32_t j = opt->job_id[i];
+                    int64_t tot = son_total > 1 ? son_total : 1;
+                    if (!(SON[j] * opt->msr_den <= opt->msr_num[j] * tot)) continue;
+                }
+                cand[nc].tensor = i;
+                cand[nc].score = score[i];
+                cand[nc].size = size[i];
+                cand[nc].time = 1;
+                ++nc;
             }
+            qsort(cand, (size_t)nc, sizeof(cand_t), cand_cmp);
+            for (int32_t c = 0; c < nc && !accepted; ++c) {
+                int32_t i = cand[c].tensor;
+                /* the gap around tstar: p_g is the last touch point before it, p_{g+1} = wi[i] */
+                int32_t pg1 = wi[i], pg = alloc[i];
+                for (int64_t k = access_offsets[i]; k < access_offsets[i + 1]; ++k)
+                    if (access_steps[k] < tstar) pg = access_steps[k];
+                int32_t o_placed, r_placed, a = -1, cc = -1, d = -1;
+                if (x[i] == 0) {
+                    o_placed = pg;
+                    r_placed = pg1;
+                } else {
+                    /* swap-out: earliest run of free steps [a..o'] from p_g+1 on with C[o'+1]-C[a] >= x */
+                    o_placed = -1;
+                    int32_t s = pg + 1;
+                    while (s <= pg1 - 1 && o_placed < 0) {
+                        if (link_busy[s]) {
+                            ++s;
+                            continue;
+                        }
+                        int32_t e = s;
+                        while (e <= pg1 - 1 && !link_busy[e] && C[e + 1] - C[s] < x[i]) ++e;
+                        if (e <= pg1 - 1 && !link_busy[e]) {
+                            a = s;
+                            o_placed = e;
+                        } else
+                            s = e + 1;      /* ran into a busy step or the end of the gap */
+                    }
+                    if (o_placed < 0) continue;
+                    /* swap-in: latest run of free steps [c..d], d <= p_{g+1}-1, c > o' */
+                    r_placed = -1;
+                    int32_t e2 = pg1 - 1;
+                    while (e2 > o_placed && r_placed < 0) {
+                        if (link_busy[e2]) {
+                            --e2;
+                            continue;
+                        }
+                        int32_t s2 = e2;
+                        while (s2 > o_placed && !link_busy[s2] && C[e2 + 1] - C[s2] < x[i]) --s2;
+                        if (s2 > o_placed && !link_busy[s2]) {
+                            cc = s2;
+                            d = e2;
+                            r_placed = e2 + 1;
+                        } else
+                            e2 = s2 - 1;
+                    }
+                    if (r_placed < 0) continue;
+                }
+                if (!(o_placed < tstar && tstar < r_placed)) continue;
+                if (x[i] != 0) {
+                    for (int32_t t = a; t <= o_placed; ++t) link_busy[t] = 1;
+                    for (int32_t t = cc; t <= d; ++t) link_busy[t] = 1;
+                }
+                iv_tensor[iter] = i;
+                iv_out[iter] = o_placed;
+                iv_in[iter] = r_placed;
+                iv_kind[iter] = 0;
+                if (xfer_out_start) xfer_out_start[iter] = x[i] != 0 ? a : -1;
+                if (xfer_in_start) xfer_in_start[iter] = x[i] != 0 ? cc : -1;
+                if (opt->J > 0 && opt->job_id) {
+                    ++SON[opt->job_id[i]];
+                    ++son_total;
+                }
+                ++iter;
+                accepted = 1;
+            }
+            if (accepted) continue;
+            swap_phase = 0;      /* "no swap events generated": swapping is not tried again (Alg. 3) */
+        }
+
+        /* Recomputation phase (Alg. 3: only while the peak does not fit; section IV-D): release the
+         * candidate with the largest MSPS over its whole gap.  Candidates that save nothing are left out. */
+        if (!(opt->recompute && P > budget)) break;
+        rc = oracle_score_recompute_plan(T, N, size, alloc, access_offsets, access_steps, iter, iv_tensor, iv_out, iv_in,
+                                         MF, P, tstar, score, wo, wi);
+        if (rc != OR_OK) goto done;
+        nc = 0;
+        for (int32_t i = 0; i < N; ++i) {
+            if (wo[i] < 0 || score[i] <= 0) continue;
             cand[nc].tensor = i;
             cand[nc].score = score[i];
             cand[nc].size = size[i];
+            cand[nc].time = step_ns ? step_ns[alloc[i]] : 1;
             ++nc;
         }
-        qsort(cand, (size_t)nc, sizeof(cand_t), cand_cmp);
-        int accepted = 0;
-        for (int32_t c = 0; c < nc && !accepted; ++c) {
-            int32_t i = cand[c].tensor;
-            /* the gap around tstar: p_g is the last touch point before it, p_{g+1} = wi[i] */
-            int32_t pg1 = wi[i], pg = alloc[i];
-            for (int64_t k = access_offsets[i]; k < access_offsets[i + 1]; ++k)
-                if (access_steps[k] < tstar) pg = access_steps[k];
-            int32_t o_placed, r_placed, a = -1, cc = -1, d = -1;
-            if (x[i] == 0) {
-                o_placed = pg;
-                r_placed = pg1;
-            } else {
-                /* swap-out: earliest run of free steps [a..o'] from p_g+1 on with C[o'+1]-C[a] >= x */
-                o_placed = -1;
-                int32_t s = pg + 1;
-                while (s <= pg1 - 1 && o_placed < 0) {
-                    if (link_busy[s]) {
-                        ++s;
-                        continue;
-                    }
-                    int32_t e = s;
-                    while (e <= pg1 - 1 && !link_busy[e] && C[e + 1] - C[s] < x[i]) ++e;
-                    if (e <= pg1 - 1 && !link_busy[e]) {
-                        a = s;
-                        o_placed = e;
-                    } else
-                        s = e + 1;      /* ran into a busy step or the end of the gap */
-                }
-                if (o_placed < 0) continue;
-                /* swap-in: latest run of free steps [c..d], d <= p_{g+1}-1, c > o' */
-                r_placed = -1;
-                int32_t e2 = pg1 - 1;
-                while (e2 > o_placed && r_placed < 0) {
-                    if (link_busy[e2]) {
-                        --e2;
-                        continue;
-                    }
-                    int32_t s2 = e2;
-                    while (s2 > o_placed && !link_busy[s2] && C[e2 + 1] - C[s2] < x[i]) --s2;
-                    if (s2 > o_placed && !link_busy[s2]) {
-                        cc = s2;
-                        d = e2;
-                        r_placed = e2 + 1;
-                    } else
-                        e2 = s2 - 1;
-                }
-                if (r_placed < 0) continue;
-            }
-            if (!(o_placed < tstar && tstar < r_placed)) continue;
-            if (x[i] != 0) {
-                for (int32_t t = a; t <= o_placed; ++t) link_busy[t] = 1;
-                for (int32_t t = cc; t <= d; ++t) link_busy[t] = 1;
-            }
-            iv_tensor[iter] = i;
-            iv_out[iter] = o_placed;
-            iv_in[iter] = r_placed;
-            iv_kind[iter] = 0;
-            if (xfer_out_start) xfer_out_start[iter] = x[i] != 0 ? a : -1;
-            if (xfer_in_start) xfer_in_start[iter] = x[i] != 0 ? cc : -1;
-            if (opt->J > 0 && opt->job_id) {
-                ++SON[opt->job_id[i]];
-                ++son_total;
-            }
-            ++iter;
-            accepted = 1;
-        }
-        if (!accepted) break;
+        if (nc == 0) break;
+        qsort(cand, (size_t)nc, sizeof(cand_t), msps_cmp);
+        iv_tensor[iter] = cand[0].tensor;
+        iv_out[iter] = wo[cand[0].tensor];
+        iv_in[iter] = wi[cand[0].tensor];
+        iv_kind[iter] = 1;
+        if (xfer_out_start) xfer_out_start[iter] = -1;
+        if (xfer_in_start) xfer_in_start[iter] = -1;
+        ++iter;
     }
     *n_out = iter;
     *final_peak = P;
