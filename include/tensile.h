@@ -149,6 +149,22 @@ int tensile_score_candidates(const tensile_tas *tas, const tensile_plans *plans,
                              const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
                              int32_t *win_in, void *hip_stream);
 
+/* Recomputation savings for every plan (section IV-D, "Recomputation
+ * Scheduling": recomputation is applied only to tensors that have never been
+ * released, and valued by the memory it saves).  Tensor i may be dropped after
+ * an access and regenerated right before the next one; no transfer is involved,
+ * so the window is the whole gap.  For plan b with t* = argmax[b], P = peak[b]:
+ *   1. gap g with p_g < t* < p_{g+1}; none -> 0
+ *   2. plan b holds any applicable interval of tensor i (any gap, any kind) -> 0
+ *   3. score = P - max( max_{t<=p_g} MF_b[t], max_{t>=p_{g+1}} MF_b[t], P - size_i )
+ *            = P - peak(plan b + (i, p_g, p_{g+1}))
+ * Arguments as for tensile_score_candidates; win_out/win_in receive p_g and
+ * p_{g+1}, or -1.  The first call on a handle builds a second candidate index
+ * (synchronous, allocates); later calls are asynchronous on hip_stream. */
+int tensile_score_recompute(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident,
+                            const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
+                            int32_t *win_in, void *hip_stream);
+
 /* Slow semantic check of a batch (synchronous; copies the plans to the host).
  * Valid means: applicable (see top), p_g <= o and r <= p_{g+1} for one gap g of
  * the tensor (section IV-C: a swap may not overlap the tensor's own accesses;
@@ -169,6 +185,8 @@ typedef struct {
                              * IV-C); a tensor of job j is a candidate while                         *
                              * swapped[j]*msr_den <= msr_num[j]*max(1, total swapped). NULL = off.   */
     int64_t msr_den;
+    int32_t recompute;      /* non-zero: once no swap is accepted and while peak > budget_bytes, add *
+                             * recomputation intervals (kind 1), see tensile_greedy_plan             */
 } tensile_greedy_opts;
 
 /* Swap phase of Alg. 3 with the placement of Alg. 2, one interval per
@@ -181,6 +199,14 @@ typedef struct {
  * (o', d+1) still has o' < t* < d+1.  Stops when no candidate is accepted, at
  * max_iters, at capacity, at the budget if asked, or when, after min_iters
  * iterations, the last three lowered the peak by less than 0.05 %.
+ * Recomputation branch of Alg. 3 (opts->recompute): when an iteration accepts no
+ * swap, swapping is over; from then on, while peak > budget_bytes, each iteration
+ * scores the tensors with tensile_score_recompute, leaves out those that save
+ * nothing, and appends (i, p_g, p_{g+1}, kind 1) for the one with the largest
+ * MSPS = saving / recomputation time (section IV-D), the time being the latency
+ * step_ns[alloc_i] of the operator that generates the tensor (1 without
+ * latencies); quotients are compared exactly by cross-multiplication, ties by
+ * (saving desc, size desc, tensor asc).  The same stop rules apply.
  * Synchronous; uses the default stream.
  *   capacity    length of the four HOST interval arrays
  *   n_initial   the first n_initial entries are an existing plan to extend (kept; their

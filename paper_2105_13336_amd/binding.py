@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_PKG, "libtensile.so")
 TENSILE_OK, TENSILE_E_INVAL, TENSILE_E_RANGE, TENSILE_E_NOMEM, TENSILE_E_HIP, TENSILE_E_CAPACITY = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["tensile_last_error", "tensile_version", "tensile_tas_load", "tensile_tas_free", "tensile_tas_info",
-           "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_score_candidates", "tensile_validate_plans",
+           "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_score_candidates", "tensile_score_recompute",
+           "tensile_validate_plans",
            "tensile_greedy_plan"]
 
 
@@ -45,7 +46,7 @@ class _Plans(ctypes.Structure):
 
 class _GreedyOpts(ctypes.Structure):
     _fields_ = [("max_iters", ctypes.c_int32), ("min_iters", ctypes.c_int32), ("stop_at_budget", ctypes.c_int32),
-                ("msr_num", ctypes.c_void_p), ("msr_den", ctypes.c_int64)]
+                ("msr_num", ctypes.c_void_p), ("msr_den", ctypes.c_int64), ("recompute", ctypes.c_int32)]
 
 
 def _load():
@@ -195,6 +196,17 @@ def tensile_score_candidates(h: TasHandle, plans: DevicePlans, resident: torch.T
                                          _dp(win_in, torch.int32, B * N, "win_in"), _stream(stream)))
 
 
+def tensile_score_recompute(h: TasHandle, plans: DevicePlans, resident: torch.Tensor, peak: torch.Tensor,
+                             argmax: torch.Tensor, score: torch.Tensor, win_out: Optional[torch.Tensor] = None,
+                             win_in: Optional[torch.Tensor] = None, stream=None) -> None:
+    B, N = plans.B, h.N
+    st = plans.struct()
+    _check(_lib.tensile_score_recompute(h.ptr, ctypes.byref(st), _dp(resident, torch.int64, B * h.T, "resident"),
+                                         _dp(peak, torch.int64, B, "peak"), _dp(argmax, torch.int32, B, "argmax"),
+                                         _dp(score, torch.int64, B * N, "score"), _dp(win_out, torch.int32, B * N, "win_out"),
+                                         _dp(win_in, torch.int32, B * N, "win_in"), _stream(stream)))
+
+
 def tensile_validate_plans(h: TasHandle, plans: DevicePlans):
     """-> (index of the first invalid interval or -1, reason code)"""
     bad, why = ctypes.c_int64(), ctypes.c_int32()
@@ -205,7 +217,7 @@ def tensile_validate_plans(h: TasHandle, plans: DevicePlans):
 
 def tensile_greedy_plan(h: TasHandle, budget_bytes: int = 0, max_iters: int = 0, min_iters: int = 100,
                         stop_at_budget: bool = False, msr_num=None, msr_den: int = 1, capacity: Optional[int] = None,
-                        initial=None) -> dict:
+                        initial=None, recompute: bool = False) -> dict:
     """-> dict(iv_tensor, iv_out, iv_in, iv_kind, peak_trace, final_peak, n_initial)"""
     n0 = 0 if initial is None else len(initial[0])
     cap = int(capacity) if capacity is not None else n0 + (max_iters if max_iters > 0 else 1 << 20)
@@ -215,7 +227,7 @@ def tensile_greedy_plan(h: TasHandle, budget_bytes: int = 0, max_iters: int = 0,
         t[:n0], o[:n0], r[:n0], k[:n0] = initial
     trace = np.zeros(cap - n0 + 1, dtype=np.int64)
     num = _np(msr_num, np.int64)
-    opts = _GreedyOpts(int(max_iters), int(min_iters), int(bool(stop_at_budget)), _hp(num), int(msr_den))
+    opts = _GreedyOpts(int(max_iters), int(min_iters), int(bool(stop_at_budget)), _hp(num), int(msr_den), int(bool(recompute)))
     n, fp = ctypes.c_int32(), ctypes.c_int64()
     _check(_lib.tensile_greedy_plan(h.ptr, ctypes.c_int64(int(budget_bytes)), ctypes.byref(opts), ctypes.c_int32(cap),
                                     ctypes.c_int32(n0), _hp(t), _hp(o), _hp(r), _hp(k), ctypes.byref(n), _hp(trace),

@@ -130,7 +130,11 @@ struct tensile_tas {
     tensile::DevBuf<uint32_t> d_size_units;   // empty when the sizes do not fit (see EvalArgs)
     int32_t size_shift = 0;
     tensile::DevBuf<int32_t> d_touch;
-    tensile::CandIndex index;
+    tensile::CandIndex index;                 // swap candidates: o = earliest feasible swap-out step
+    // recomputation candidates (every gap, o = p), built by the first tensile_score_recompute
+    mutable tensile::CandIndex recompute_index;
+    mutable bool recompute_index_built = false;
+    std::vector<int32_t> h_gp, h_gq, h_gt;    // gaps of length >= 2 in tensor order (host)
     // host copies used by the greedy driver and the validator
     std::vector<int64_t> h_size, h_C, h_x, h_touch_off;
     std::vector<int32_t> h_touch, h_job;
@@ -143,9 +147,12 @@ namespace tensile {
 int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, int32_t *argmax, int64_t *min_resident,
                 hipStream_t stream);
 // score.hip
-int launch_score(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident, const int64_t *peak,
-                 const int32_t *argmax, int64_t *score, int32_t *win_out, int32_t *win_in, hipStream_t stream);
+// (any_interval: an interval of the entry's tensor cancels the entry wherever it lies, not only inside the gap)
+int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
+                 const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
+                 int32_t *win_in, hipStream_t stream);
 // tas.hip
 int build_times(tensile_tas *tas, const int64_t *d_step_ns);
+int ensure_recompute_index(const tensile_tas *tas);
 
 }  // namespace tensile

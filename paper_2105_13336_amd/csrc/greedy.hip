@@ -176,41 +176,43 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
 
         int32_t n = n_initial;
         int64_t P = 0;
-        for (;;) {
-            // One round trip per iteration: evaluate, score and compact on the device (the scores
-            // of the last iteration are computed in vain), then fetch the header and the first
-            // candidates together.
-            const int32_t it = n - n_initial;
-            const bool last = it >= max_new || n >= capacity || N == 0;
-            tensile_plans pl{1, n, d_offs.p, d_t.p, d_o.p, d_r.p, nullptr};
-            int rc = tensile_eval_plans(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr);
+        // Scores of the current plan (swap or recomputation candidates), compacted and fetched:
+        // header plus the first candidates in one copy, the rest only when there are more.
+        tensile_plans pl{1, 0, d_offs.p, d_t.p, d_o.p, d_r.p, nullptr};
+        auto score_and_fetch = [&](bool recompute_scores) -> int {
+            int rc = recompute_scores
+                         ? tensile_score_recompute(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_score.p, d_wo.p, d_wi.p, nullptr)
+                         : tensile_score_candidates(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_score.p, d_wo.p, d_wi.p, nullptr);
             if (rc != TENSILE_OK) return rc;
-            size_t first_bytes = sizeof(Header);
-            if (last) {
-                hipLaunchKernelGGL(peak_only_kernel, dim3(1), dim3(1), 0, nullptr, d_peak.p, d_arg.p, d_hdr.p);
-            } else {
-                rc = tensile_score_candidates(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_score.p, d_wo.p, d_wi.p, nullptr);
-                if (rc != TENSILE_OK) return rc;
-                hipLaunchKernelGGL(compact_candidates_kernel, dim3(1), dim3(1024), 0, nullptr, N, d_score.p, d_wo.p, d_wi.p,
-                                   d_peak.p, d_arg.p, d_hdr.p, d_cands);
-                first_bytes += static_cast<size_t>(std::min(N, kFirstCopy)) * sizeof(CandOut);
-            }
+            hipLaunchKernelGGL(compact_candidates_kernel, dim3(1), dim3(1024), 0, nullptr, N, d_score.p, d_wo.p, d_wi.p,
+                               d_peak.p, d_arg.p, d_hdr.p, d_cands);
             TS_HIP(hipGetLastError());
+            const size_t first_bytes = sizeof(Header) + static_cast<size_t>(std::min(N, kFirstCopy)) * sizeof(CandOut);
             TS_HIP(hipMemcpyAsync(h_rec.p, d_hdr.p, first_bytes, hipMemcpyDeviceToHost, nullptr));
             TS_HIP(hipStreamSynchronize(nullptr));
-            P = hdr->P;
-            const int32_t tstar = hdr->tstar;
-            hist.push_back(P);
-            if (peak_trace) peak_trace[it] = P;
-            if (last) break;
-            if (opt.stop_at_budget && P <= budget_bytes) break;
-            if (it > opt.min_iters && it >= 3 && (hist[it - 3] - P) * 10000 < 5 * hist[it - 3]) break;
             if (hdr->count > kFirstCopy) {
                 TS_HIP(hipMemcpyAsync(static_cast<char *>(h_rec.p) + first_bytes, reinterpret_cast<const char *>(d_hdr.p) + first_bytes,
                                       static_cast<size_t>(hdr->count - kFirstCopy) * sizeof(CandOut), hipMemcpyDeviceToHost, nullptr));
                 TS_HIP(hipStreamSynchronize(nullptr));
             }
+            return TENSILE_OK;
+        };
+        auto append = [&](int32_t i, int32_t o, int32_t r, uint8_t kind) -> int {
+            iv_tensor[n] = i;
+            iv_out[n] = o;
+            iv_in[n] = r;
+            iv_kind[n] = kind;
+            hipLaunchKernelGGL(append_interval_kernel, dim3(1), dim3(1), 0, nullptr, d_t.p, d_o.p, d_r.p, d_offs.p, n, i, o, r);
+            TS_HIP(hipGetLastError());
+            ++n;
+            return TENSILE_OK;
+        };
 
+        // One swap iteration on the candidates just fetched (Alg. 2's placement); false when none is accepted.
+        int swap_error = TENSILE_OK;
+        int32_t tstar_now = 0;
+        auto try_swap = [&]() -> bool {
+            const int32_t tstar = tstar_now;
             cand.clear();
             const int64_t tot = std::max<int64_t>(1, swapped_total);
             for (int32_t k = 0; k < hdr->count; ++k) {
@@ -253,20 +255,79 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
                     link.occupy(a, e);
                     link.occupy(cs, d);
                 }
-                iv_tensor[n] = i;
-                iv_out[n] = o_placed;
-                iv_in[n] = r_placed;
-                iv_kind[n] = 0;
-                hipLaunchKernelGGL(append_interval_kernel, dim3(1), dim3(1), 0, nullptr, d_t.p, d_o.p, d_r.p, d_offs.p, n, i,
-                                   o_placed, r_placed);
-                TS_HIP(hipGetLastError());
+                const int rc_append = append(i, o_placed, r_placed, 0);
+                if (rc_append != TENSILE_OK) { swap_error = rc_append; return false; }
                 ++swapped[tas->h_job[i]];
                 ++swapped_total;
-                ++n;
                 accepted = true;
                 break;
             }
-            if (!accepted) break;
+                        return accepted;
+        };
+
+        bool swap_phase = true;
+        for (;;) {
+            // One round trip per iteration: evaluate, score and compact on the device (the scores
+            // of the last iteration are computed in vain), then fetch.
+            const int32_t it = n - n_initial;
+            const bool last = it >= max_new || n >= capacity || N == 0;
+            pl.n_intervals = n;
+            int rc = tensile_eval_plans(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr);
+            if (rc != TENSILE_OK) return rc;
+            if (last) {
+                hipLaunchKernelGGL(peak_only_kernel, dim3(1), dim3(1), 0, nullptr, d_peak.p, d_arg.p, d_hdr.p);
+                TS_HIP(hipGetLastError());
+                TS_HIP(hipMemcpyAsync(h_rec.p, d_hdr.p, sizeof(Header), hipMemcpyDeviceToHost, nullptr));
+                TS_HIP(hipStreamSynchronize(nullptr));
+            } else {
+                rc = score_and_fetch(!swap_phase);
+                if (rc != TENSILE_OK) return rc;
+            }
+            P = hdr->P;
+            tstar_now = hdr->tstar;
+            hist.push_back(P);
+            if (peak_trace) peak_trace[it] = P;
+            if (last) break;
+            if (opt.stop_at_budget && P <= budget_bytes) break;
+            if (it > opt.min_iters && it >= 3 && (hist[it - 3] - P) * 10000 < 5 * hist[it - 3]) break;
+
+            const bool swapped_one = swap_phase && try_swap();
+            if (swap_error != TENSILE_OK) return swap_error;
+            if (!swapped_one) {
+                // Recomputation branch of Alg. 3: swapping is over for good; while the peak does not fit,
+                // release the never-released tensor with the largest MSPS over its whole gap.
+                if (swap_phase) {
+                    swap_phase = false;
+                    if (!(opt.recompute && P > budget_bytes)) break;
+                    rc = score_and_fetch(true);        // same plan, same footprint: only the scores differ
+                    if (rc != TENSILE_OK) return rc;
+                } else if (!(P > budget_bytes)) {
+                    break;
+                }
+                const CandOut *best = nullptr;
+                int64_t best_time = 1;
+                for (int32_t k = 0; k < hdr->count; ++k) {
+                    const CandOut &c = h_cands[k];
+                    if (c.score <= 0) continue;
+                    const int32_t born = tas->h_touch[tas->h_touch_off[c.tensor]];
+                    const int64_t time = tas->timed ? tas->h_C[born + 1] - tas->h_C[born] : 1;
+                    bool better = best == nullptr;
+                    if (!better) {
+                        const __int128 l = static_cast<__int128>(c.score) * best_time, r = static_cast<__int128>(best->score) * time;
+                        if (l != r) better = l > r;
+                        else if (c.score != best->score) better = c.score > best->score;
+                        else if (tas->h_size[c.tensor] != tas->h_size[best->tensor]) better = tas->h_size[c.tensor] > tas->h_size[best->tensor];
+                        else better = c.tensor < best->tensor;
+                    }
+                    if (better) {
+                        best = &c;
+                        best_time = time;
+                    }
+                }
+                if (!best) break;
+                rc = append(best->tensor, best->wo, best->wi, 1);
+                if (rc != TENSILE_OK) return rc;
+            }
         }
         TS_HIP(hipDeviceSynchronize());
         *n_intervals = n;

@@ -57,6 +57,7 @@ struct ScoreArgs {
     int32_t span;                // steps per wavefront (a multiple of kMini)
     int32_t n_tab;               // ceil(T / kMini)
     int32_t vec16;               // rows are 16-byte aligned (T even, aligned base)
+    int32_t any_interval;        // an interval of the entry's tensor cancels it wherever it lies
     int64_t n_intervals;
     const int64_t *plan_offsets;
     const int32_t *iv_tensor, *iv_out, *iv_in;
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                     for (int u = 0; u < kIvU; ++u) {
                         while (go[u] && s[u].x >= 0) {      // probe until the tensor's last entry or an empty slot
                             if (s[u].x == i[u]) {
-                                if (s[u].y <= o[u] && r[u] <= s[u].z) {
+                                if (a.any_interval || (s[u].y <= o[u] && r[u] <= s[u].z)) {
                                     const uint32_t el = static_cast<uint32_t>((s[u].w & INT32_MAX) - slice_lo);
                                     if (el < static_cast<uint32_t>(n_slice)) acc[el] = INT64_MAX;
                                 }
@@ -405,10 +406,10 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
 
 }  // namespace
 
-int launch_score(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident, const int64_t *peak,
-                 const int32_t *argmax, int64_t *score, int32_t *win_out, int32_t *win_in, hipStream_t stream) {
+int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
+                 const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
+                 int32_t *win_in, hipStream_t stream) {
     if (plans->B == 0 || tas->N == 0) return TENSILE_OK;
-    const CandIndex &ix = tas->index;
     // as many workgroups as the device keeps resident, the plans dealt evenly among them
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -424,6 +425,7 @@ int launch_score(const tensile_tas *tas, const tensile_plans *plans, const int64
     a.span = ix.span;
     a.n_tab = (tas->T + kMini - 1) / kMini;
     a.vec16 = (tas->T % 2 == 0) && (reinterpret_cast<uintptr_t>(resident) % 16 == 0);
+    a.any_interval = any_interval ? 1 : 0;
     a.n_intervals = plans->n_intervals;
     a.plan_offsets = plans->plan_offsets;
     a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;

@@ -180,9 +180,8 @@ int validate_desc(const tensile_tas_desc *d) {
 // the bucket width starts at 256 steps and doubles while the index would hold more than
 // about 16 entries per gap (or its filters more than 256 MiB).  CandIndex (common.h) lists
 // what is kept per bucket.
-int build_candidate_index(tensile_tas *h, const std::vector<int32_t> &gp, const std::vector<int32_t> &gq,
-                          const std::vector<int32_t> &gt, const std::vector<int32_t> &gwin) {
-    CandIndex &ix = h->index;
+int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector<int32_t> &gp,
+                          const std::vector<int32_t> &gq, const std::vector<int32_t> &gt, const std::vector<int32_t> &gwin) {
     const size_t G = gp.size();
     const int32_t T = h->T;
     auto usable = [&](size_t g) { return gwin[g] >= 0 && gwin[g] + 1 <= gq[g] - 1; };
@@ -400,8 +399,11 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
         TS_HIP(hipDeviceSynchronize());
         std::vector<int32_t> gwin(gp.size());
         if (h->G > 0) TS_HIP(hipMemcpy(gwin.data(), d_gwin.p, gwin.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
-        int rc = build_candidate_index(h, gp, gq, gt, gwin);
+        int rc = build_candidate_index(h, h->index, gp, gq, gt, gwin);
         if (rc != TENSILE_OK) return rc;
+        h->h_gp = std::move(gp);
+        h->h_gq = std::move(gq);
+        h->h_gt = std::move(gt);
     }
     h->h_C.resize(static_cast<size_t>(T) + 1);
     h->h_x.resize(static_cast<size_t>(N));
@@ -409,6 +411,26 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
     if (N > 0) TS_HIP(hipMemcpy(h->h_x.data(), h->d_x.p, static_cast<size_t>(N) * sizeof(int64_t), hipMemcpyDeviceToHost));
     return TENSILE_OK;
 }
+
+}  // namespace
+
+// The index of the recomputation candidates: every gap, released right after the access that
+// opens it (o = p).  Built on first use; the handle is otherwise immutable, so concurrent first
+// calls on one handle are the caller's to avoid.
+int ensure_recompute_index(const tensile_tas *tas) {
+    if (tas->recompute_index_built) return TENSILE_OK;
+    try {
+        int rc = build_candidate_index(tas, tas->recompute_index, tas->h_gp, tas->h_gq, tas->h_gt, tas->h_gp);
+        if (rc != TENSILE_OK) return rc;
+    } catch (const std::bad_alloc &) {
+        set_error("score_recompute: out of host memory");
+        return TENSILE_E_NOMEM;
+    }
+    tas->recompute_index_built = true;
+    return TENSILE_OK;
+}
+
+namespace {
 
 int check_plans(const tensile_tas *tas, const tensile_plans *plans, const char *who) {
     if (!tas || !plans) { set_error("%s: NULL handle or plans", who); return TENSILE_E_INVAL; }
@@ -497,7 +519,24 @@ int tensile_score_candidates(const tensile_tas *tas, const tensile_plans *plans,
         set_error("score_candidates: resident, peak, argmax and score are required");
         return TENSILE_E_INVAL;
     }
-    return launch_score(tas, plans, resident, peak, argmax, score, win_out, win_in, static_cast<hipStream_t>(hip_stream));
+    return launch_score(tas, tas->index, false, plans, resident, peak, argmax, score, win_out, win_in,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int tensile_score_recompute(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident,
+                            const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
+                            int32_t *win_in, void *hip_stream) {
+    int rc = check_plans(tas, plans, "score_recompute");
+    if (rc != TENSILE_OK) return rc;
+    if (plans->B == 0) return TENSILE_OK;
+    if (!resident || !peak || !argmax || !score) {
+        set_error("score_recompute: resident, peak, argmax and score are required");
+        return TENSILE_E_INVAL;
+    }
+    rc = ensure_recompute_index(tas);
+    if (rc != TENSILE_OK) return rc;
+    return launch_score(tas, tas->recompute_index, true, plans, resident, peak, argmax, score, win_out, win_in,
+                        static_cast<hipStream_t>(hip_stream));
 }
 
 int tensile_validate_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *first_bad, int32_t *reason) {

@@ -240,6 +240,61 @@ def test_score_optional_windows_and_blocking():
     h.close()
 
 
+# -------------------------------------------------------------------- recomputation scores
+
+def gpu_score_recompute(h, dp, res, peak, arg):
+    B, N = dp.B, h.N
+    sc = torch.empty((B, N), dtype=torch.int64, device="cuda")
+    wo = torch.empty((B, N), dtype=torch.int32, device="cuda")
+    wi = torch.empty((B, N), dtype=torch.int32, device="cuda")
+    P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)
+    torch.cuda.synchronize()
+    return sc, wo, wi
+
+
+def check_score_recompute(tas, pl, rows=None, label=""):
+    h = P.tas_load(tas)
+    dp = upload(pl)
+    res, peak, arg, mn = gpu_eval(h, dp)
+    sc, wo, wi = gpu_score_recompute(h, dp, res, peak, arg)
+    # the swap scores of the same handle are untouched by the second index
+    s1, o1, i1 = gpu_score(h, dp, res, peak, arg)
+    rows = list(range(pl.B)) if rows is None else list(rows)
+    r0, p0, a0, m0 = O.eval_plans(tas, pl.select(rows))
+    s0, o0, i0 = O.score_recompute_plans(tas, pl.select(rows), r0, p0, a0)
+    idx = torch.as_tensor(np.asarray(rows), device="cuda")
+    assert np.array_equal(sc[idx].cpu().numpy(), s0), label + " saving"
+    assert np.array_equal(wo[idx].cpu().numpy(), o0), label + " win_out"
+    assert np.array_equal(wi[idx].cpu().numpy(), i0), label + " win_in"
+    s2, o2, i2 = O.score_plans(tas, pl.select(rows), r0, p0, a0)
+    assert np.array_equal(s1[idx].cpu().numpy(), s2) and np.array_equal(o1[idx].cpu().numpy(), o2)
+    h.close()
+    return int((o0 >= 0).sum())
+
+
+@pytest.mark.parametrize("idx,B,rows", [(0, None, None), (1, 300, range(0, 300, 7)), (2, 40, range(0, 40, 5))])
+def test_score_recompute_configs(idx, B, rows, configs_small):
+    tas = configs_small[idx]
+    pl = make_config_plans(idx, tas, B=B)
+    say(f"score recompute config {idx} B={pl.B}")
+    assert check_score_recompute(tas, pl, rows, label=f"c{idx}") > 10
+
+
+@pytest.mark.parametrize("seed,timed,T", [(1, True, 60), (2, False, 60), (3, True, 3000), (4, True, 9001)])
+def test_score_recompute_random(seed, timed, T):
+    tas = small_random_tas(500 + seed, N=min(500, T // 2), T=T, max_acc=5, timed=timed, link_bytes_per_us=400_000)
+    pl = make_plans(tas, 24, seed, p_swap=0.1)
+    say(f"score recompute random seed={seed} T={T}")
+    assert check_score_recompute(tas, pl) > 0
+
+
+def test_score_recompute_any_interval_excludes():
+    tas = tas_from_lists(10, [10, 3], [0, 6], [[4, 9], [7]])
+    pl = plans_from_lists([[], [(0, 1, 3)], [(0, 7, 9)], [(5, 1, 2), (0, -3, 2)]])
+    say("score recompute exclusion")
+    check_score_recompute(tas, pl)
+
+
 # -------------------------------------------------------------------- greedy
 
 def same_greedy(g, o):
@@ -279,6 +334,41 @@ def test_greedy_options(configs_small):
     init = (first["iv_tensor"], first["iv_out"], first["iv_in"], first["iv_kind"])
     same_greedy(P.tensile_greedy_plan(h, 0, max_iters=6, capacity=64, initial=init),
                 O.greedy(tas, 0, max_iters=6, initial=init))
+    h.close()
+
+
+@pytest.mark.parametrize("seed,link", [(11, 200_000), (12, 60_000), (13, 2)])
+def test_greedy_recompute_phase(seed, link):
+    tas = small_random_tas(400 + seed, N=150, T=240, max_acc=4, timed=True, link_bytes_per_us=link)
+    say(f"greedy recompute seed={seed}")
+    h = P.tas_load(tas)
+    o = O.greedy(tas, 0, recompute=True, min_iters=1 << 30)
+    assert (o["iv_kind"] == 1).sum() >= 2
+    g = P.tensile_greedy_plan(h, 0, recompute=True, min_iters=1 << 30, capacity=len(o["iv_tensor"]) + 8)
+    same_greedy(g, o)
+    # a budget in the middle of the recomputation phase, and one the swap phase already meets
+    n_swap = int((o["iv_kind"] == 0).sum())
+    for budget in (int(o["peak_trace"][n_swap + 1]), int(o["peak_trace"][n_swap])):
+        same_greedy(P.tensile_greedy_plan(h, budget, recompute=True, min_iters=1 << 30, capacity=512),
+                    O.greedy(tas, budget, recompute=True, min_iters=1 << 30))
+    # the paper's stall rule and a cap on the iterations cut through both phases alike
+    same_greedy(P.tensile_greedy_plan(h, 0, recompute=True, min_iters=2, capacity=512),
+                O.greedy(tas, 0, recompute=True, min_iters=2))
+    same_greedy(P.tensile_greedy_plan(h, 0, recompute=True, min_iters=1 << 30, max_iters=n_swap + 1, capacity=512),
+                O.greedy(tas, 0, recompute=True, min_iters=1 << 30, max_iters=n_swap + 1))
+    h.close()
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_greedy_recompute_config(idx, configs_small):
+    tas = configs_small[idx]        # (config 0 has no latencies: recomputation time 1 for every tensor)
+    say(f"greedy recompute config {idx}")
+    h = P.tas_load(tas)
+    o = O.greedy(tas, 0, recompute=True, min_iters=1 << 30)
+    g = P.tensile_greedy_plan(h, 0, recompute=True, min_iters=1 << 30, capacity=len(o["iv_tensor"]) + 8)
+    same_greedy(g, o)
+    if idx == 1:
+        assert (g["iv_kind"] == 1).sum() > 100 and (g["iv_kind"] == 0).sum() > 100
     h.close()
 
 
@@ -387,5 +477,12 @@ def test_full_size_config(idx, n_rows, n_score):
     assert np.array_equal(sc[sidx].cpu().numpy(), s0) and np.array_equal(wo[sidx].cpu().numpy(), o0)
     assert np.array_equal(wi[sidx].cpu().numpy(), i0)
     size = torch.from_numpy(tas.size_bytes).cuda()
+    assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
+    say("  recomputation savings of the whole batch")
+    P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)
+    torch.cuda.synchronize()
+    s0, o0, i0 = O.score_recompute_plans(tas, sel, r0, p0, a0, rows=pos[:2])
+    assert np.array_equal(sc[sidx[:2]].cpu().numpy(), s0) and np.array_equal(wo[sidx[:2]].cpu().numpy(), o0)
+    assert np.array_equal(wi[sidx[:2]].cpu().numpy(), i0)
     assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
     h.close()
