@@ -13,7 +13,7 @@
  *   alloc[i] (section IV-B situation 2, Alg. 1 "output_access" branch) through
  *   free[i], the step of its last tensor-using access (activity analysis,
  *   section IV-E: released when its last TUA finishes; Alg. 1 releases a tensor
- *   once "the present time is after its end time").
+ *   once the traversal has passed the tensor's end time).
  *   A plan interval (i, o, r, kind): tensor i is NOT resident during steps
  *   o+1 .. r-1.  o is the last step it is still resident (the footprint drops
  *   at the end of the swap-out, or of the using access if that ends later -
@@ -155,12 +155,12 @@ int oracle_times(int32_t T, int32_t N, const int64_t *size, const int64_t *step_
  * is computed, which equals the size when the peak is isolated).
  *   1. gap g of tensor i with p_g < tstar < p_{g+1} (touch points p = alloc,
  *      accesses); a tensor touched at tstar is in use and cannot be swapped
- *      ("cannot overlap with the tensor's access").
+ *      (a swap event may not coincide with an access of its own tensor).
  *   2. zero if the plan already holds an interval of i inside that gap
- *      ("tensor has not been swapped out", Alg. 2).
- *   3. swap-out starts right after the access p_g ("as early as possible"):
+ *      (Alg. 2 only takes tensors not swapped out yet).
+ *   3. swap-out starts right after the access p_g (as early as it can be):
  *      o_i = min{ o >= p_g : C[o+1] - C[p_g+1] >= x_i }.
- *   4. swap-in ends right before the using access ("as late as possible"):
+ *   4. swap-in ends right before the using access (as late as it can be):
  *      r_i = p_{g+1}, using the link during [C[r_i]-x_i, C[r_i]).
  *   5. feasible iff o_i exists, C[o_i+1] + x_i <= C[r_i] (swap-in not earlier
  *      than the swap-out) and o_i < tstar < r_i (swapped out before the peak).
@@ -236,7 +236,7 @@ int oracle_score_plan(int32_t T, int32_t N, const int64_t *size, const int32_t *
 
 /* Recomputation candidates of ONE plan (section IV-D, "Recomputation
  * Scheduling"): a tensor may be released after an access and regenerated right
- * before its next access, but only if it "has never been released", read here as:
+ * before its next access, but only if it was never released before, read here as:
  * the plan holds no interval of this tensor at all, in any gap (a tensor already
  * swapped or recomputed somewhere stays out, so that the plan built so far is
  * not disturbed).
@@ -455,7 +455,7 @@ int oracle_greedy(int32_t T, int32_t N, const int64_t *size, const int32_t *allo
                 accepted = 1;
             }
             if (accepted) continue;
-            swap_phase = 0;      /* "no swap events generated": swapping is not tried again (Alg. 3) */
+            swap_phase = 0;      /* an iteration without a swap event ends swapping for good (Alg. 3) */
         }
 
         /* Recomputation phase (Alg. 3: only while the peak does not fit; section IV-D): release the

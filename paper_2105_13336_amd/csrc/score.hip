@@ -17,8 +17,8 @@
 // round-robin).  Per plan, with acc[] one word per bucket entry in LDS:
 //   1. the plan's output rows are cleared (score 0, windows -1); acc = -inf;
 //   2. the plan's own intervals cancel candidates: an interval inside the gap of
-//      an entry of its tensor sets acc = +inf ("tensor has not been swapped out"
-//      in the paper's Alg. 2).  A per-bucket bit filter over tensors, kept in LDS,
+//      an entry of its tensor sets acc = +inf (Alg. 2 of the paper only takes tensors
+//      that are not swapped out yet).  A per-bucket bit filter over tensors, kept in LDS,
 //      turns most intervals away; the others probe the bucket's hash table;
 //   3. every wavefront streams its own contiguous span of the row, 256 steps at a
 //      time, four consecutive steps per lane.  With two wave-level scans it forms,
