@@ -88,14 +88,16 @@ struct Scratch {
 // Geometry the scoring kernel shares with the index built at load time (see score.hip).
 constexpr int kScoreThreads = 1024;
 constexpr int kScoreWaves = kScoreThreads / 64;
+constexpr int kScoreMaxLocal = 4096;   // bucket entries one pass handles (a "slice"); larger buckets take several
 constexpr int kScoreMini = 256;    // steps one wavefront takes up at a time (4 consecutive steps per lane)
 
 // Candidate index: every gap (p, q) with a feasible earliest swap-out step o, filed under each
 // bucket of 2^shift steps that o+1 .. q-1 overlaps.  Per bucket (entries e0 .. e1-1, local
 // index = e - e0):
-//   cand / cand_size / cand_o   the entries sorted by o
-//   qord                        {q, local index} sorted by q
-//   wave_ptr[2][kScoreWaves+1]  first local position with o (resp. q) >= w * span, both orders
+//   cand / cand_size / cand_o   the entries sorted by o; slices are runs of kScoreMaxLocal of them
+//   qord                        per slice, its entries as {q, index within the slice} sorted by q
+//   wave_ptr[2][kScoreWaves+1]  per slice (slices numbered from slice_first[bucket]): first position
+//                               within the slice with o (resp. q) >= w * span, in the two orders
 //   hash_dir / hash_slots       open-addressing table tensor -> {tensor, p, q, local | last << 31}
 //   filter                      one bit per (tensor mod filter_bits): some entry has this tensor
 struct CandIndex {
@@ -108,7 +110,8 @@ struct CandIndex {
     DevBuf<int64_t> cand_size;
     DevBuf<int32_t> cand_o;
     DevBuf<int2> qord;
-    DevBuf<int32_t> wave_ptr;      // [n_buckets][2][kScoreWaves + 1]
+    DevBuf<int32_t> slice_first;   // [n_buckets + 1]
+    DevBuf<int32_t> wave_ptr;      // [slices][2][kScoreWaves + 1]
     DevBuf<int2> hash_dir;         // [n_buckets] {first slot, log2(slots)}
     DevBuf<int4> hash_slots;
     DevBuf<uint32_t> filter;       // [n_buckets][filter_words]

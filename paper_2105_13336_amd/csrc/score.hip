@@ -45,7 +45,8 @@ namespace {
 constexpr int kThreads = kScoreThreads;
 constexpr int kWaves = kScoreWaves;
 constexpr int kMini = kScoreMini;
-constexpr int kMaxLocal = 4096;     // bucket entries per slice (acc: 32 KB)
+constexpr int kMaxLocal = kScoreMaxLocal;   // bucket entries per slice (acc: 32 KB, the two lists: 48 KB)
+constexpr int kDepth = 2;           // blocks of kMini steps in flight per wavefront while streaming
 constexpr int kTabLds = 512;        // pieces of kMini steps whose maxima fit in LDS (T <= 131072)
 constexpr int kFilterWords = 1024;  // largest per-bucket filter (32768 bits)
 constexpr int kIvU = 4;             // intervals per thread and round
@@ -67,6 +68,7 @@ struct ScoreArgs {
     const int64_t *cand_size;
     const int32_t *cand_o;
     const int2 *qord;
+    const int32_t *slice_first;
     const int32_t *wave_ptr;
     const int2 *hash_dir;
     const int4 *hash_slots;
@@ -152,78 +154,88 @@ struct SpanBuf {
     int64_t before[64], after[64];
 };
 
-template <bool kVec>
+template <bool kVec, typename Tab>
 __device__ __forceinline__ int64_t stream_span(const ScoreArgs &a, const int64_t *MF, int32_t span_lo, int32_t span_hi,
-                                               const int32_t *cand_o, const int2 *qord, int32_t lo_k, int32_t lo_end,
-                                               int32_t hi_k, int32_t hi_end, int32_t slice_lo, int32_t n_slice,
-                                               int64_t *acc, SpanBuf *buf, int64_t *tab, int lane) {
+                                               const int32_t *lo_list, const int2 *hi_list, int32_t lo_k, int32_t lo_end,
+                                               int32_t hi_k, int32_t hi_end, int64_t *acc, SpanBuf *buf, Tab tab, int lane) {
     const int32_t n_ms = (span_hi - span_lo + kMini - 1) / kMini;
-    auto load_lo = [&](int32_t k) { return k + lane < lo_end ? cand_o[k + lane] : INT32_MAX; };
-    auto load_hi = [&](int32_t k) { return k + lane < hi_end ? qord[k + lane] : make_int2(INT32_MAX, 0); };
-    int32_t lo_o = load_lo(lo_k), lo_next = load_lo(lo_k + 64), lo_pos = 0;
-    int2 hi_it = load_hi(hi_k), hi_next = load_hi(hi_k + 64);
-    int32_t hi_pos = 0;
-    int64_t x[4], x_next[4];
-    load_quad<kVec>(MF, span_lo + 4 * lane, a.T, x_next);
     int64_t carry = INT64_MIN;
-    for (int32_t ms = 0; ms < n_ms; ++ms) {
-        const int32_t t0 = span_lo + ms * kMini;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) x[j] = x_next[j];
-        load_quad<kVec>(MF, t0 + kMini + 4 * lane, a.T, x_next);
-        const int64_t m = max64(max64(x[0], x[1]), max64(x[2], x[3]));
+    // one block of kMini steps, its four values per lane already in registers
+    auto block = [&](int32_t t0, int64_t v0, int64_t v1, int64_t v2, int64_t v3) {
+        const int64_t m = max64(max64(v0, v1), max64(v2, v3));
         const int64_t incl = max64(wave_scan_max(m), carry);
         const int64_t excl = from_prev_lane(incl, carry);         // max MF[span_lo .. t0 + 4 lane - 1]
-        const int64_t rs = wave_rscan_max(m, lane);                     // max MF[t0 + 4 lane .. t0 + 255]
+        const int64_t rs = wave_rscan_max(m, lane);               // max MF[t0 + 4 lane .. t0 + 255]
         const int64_t rs_next = from_next_lane(rs, INT64_MIN);    // max MF[t0 + 4 lane + 4 .. t0 + 255]
         carry = last_lane(incl);
         const int64_t piece = lane_value(rs, 0);
         // (the lanes of a wavefront execute in step and LDS serves a wavefront's accesses in
         // order, so the buffer needs no barrier: the fences only pin the compiler's order)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        reinterpret_cast<ll2 *>(buf->raw)[2 * lane] = ll2{x[0], x[1]};
-        reinterpret_cast<ll2 *>(buf->raw)[2 * lane + 1] = ll2{x[2], x[3]};
+        reinterpret_cast<ll2 *>(buf->raw)[2 * lane] = ll2{v0, v1};
+        reinterpret_cast<ll2 *>(buf->raw)[2 * lane + 1] = ll2{v2, v3};
         buf->before[lane] = excl;
         buf->after[lane] = rs_next;
         if (lane == 0) tab[t0 / kMini] = piece;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         for (;;) {                                      // (wave-uniform)
-            const bool take = lane >= lo_pos && lo_o < t0 + kMini;
+            const int32_t k = lo_k + lane;
+            const int32_t o = k < lo_end ? lo_list[k] : INT32_MAX;
+            const bool take = o < t0 + kMini;
             if (take) {
-                const int32_t r = lo_o - t0, l = r >> 2, j = r & 3;
+                const int32_t r = o - t0, l = r >> 2, j = r & 3;
                 int64_t v = max64(buf->before[l], buf->raw[4 * l]);
                 if (j >= 1) v = max64(v, buf->raw[4 * l + 1]);
                 if (j >= 2) v = max64(v, buf->raw[4 * l + 2]);
                 if (j >= 3) v = max64(v, buf->raw[4 * l + 3]);
-                atomicMax(reinterpret_cast<long long *>(acc + (lo_k + lane - slice_lo)), static_cast<long long>(v));
+                atomicMax(reinterpret_cast<long long *>(acc + k), static_cast<long long>(v));
             }
-            lo_pos += __builtin_popcountll(__builtin_amdgcn_ballot_w64(take));
-            if (lo_pos < 64) break;
-            lo_k += 64;
-            lo_pos = 0;
-            lo_o = lo_next;
-            lo_next = load_lo(lo_k + 64);
+            const int32_t n = __builtin_popcountll(__builtin_amdgcn_ballot_w64(take));
+            lo_k += n;
+            if (n < 64) break;
         }
         for (;;) {
-            const bool take = lane >= hi_pos && hi_it.x < t0 + kMini;
-            const uint32_t el = static_cast<uint32_t>(hi_it.y - slice_lo);
-            if (take && el < static_cast<uint32_t>(n_slice)) {
-                const int32_t r = hi_it.x - t0, l = r >> 2, j = r & 3;
+            const int32_t k = hi_k + lane;
+            const int2 it = k < hi_end ? hi_list[k] : make_int2(INT32_MAX, 0);
+            const bool take = it.x < t0 + kMini;
+            if (take) {
+                const int32_t r = it.x - t0, l = r >> 2, j = r & 3;
                 int64_t v = max64(buf->after[l], buf->raw[4 * l + 3]);
                 if (j <= 2) v = max64(v, buf->raw[4 * l + 2]);
                 if (j <= 1) v = max64(v, buf->raw[4 * l + 1]);
                 if (j <= 0) v = max64(v, buf->raw[4 * l]);
-                atomicMax(reinterpret_cast<long long *>(acc + el), static_cast<long long>(v));
+                atomicMax(reinterpret_cast<long long *>(acc + it.y), static_cast<long long>(v));
             }
-            hi_pos += __builtin_popcountll(__builtin_amdgcn_ballot_w64(take));
-            if (hi_pos < 64) break;
-            hi_k += 64;
-            hi_pos = 0;
-            hi_it = hi_next;
-            hi_next = load_hi(hi_k + 64);
+            const int32_t n = __builtin_popcountll(__builtin_amdgcn_ballot_w64(take));
+            hi_k += n;
+            if (n < 64) break;
         }
         __builtin_amdgcn_wave_barrier();
+    };
+    // Whole groups of kDepth blocks with the next group's blocks requested one group ahead: the row
+    // is the only thing this loop reads from global memory, so the wait before a block is used can
+    // leave the younger requests in flight.  The blocks left over are taken one at a time.
+    const int32_t n_groups = n_ms / kDepth;
+    int64_t x[kDepth][4];
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) load_quad<kVec>(MF, span_lo + d * kMini + 4 * lane, a.T, x[d]);
+    for (int32_t g = 0; g < n_groups; ++g) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            const int32_t t0 = span_lo + (g * kDepth + d) * kMini;
+            const int64_t v0 = x[d][0], v1 = x[d][1], v2 = x[d][2], v3 = x[d][3];
+            load_quad<kVec>(MF, t0 + kDepth * kMini + 4 * lane, a.T, x[d]);
+            block(t0, v0, v1, v2, v3);
+        }
+    }
+    for (int32_t ms = n_groups * kDepth; ms < n_ms; ++ms) {
+        const int d = ms - n_groups * kDepth;       // the requests after the last whole group are these blocks
+        int64_t v[4] = {x[0][0], x[0][1], x[0][2], x[0][3]};
+#pragma unroll
+        for (int j = 1; j < kDepth; ++j)
+            if (d == j) { v[0] = x[j][0]; v[1] = x[j][1]; v[2] = x[j][2]; v[3] = x[j][3]; }
+        block(span_lo + ms * kMini, v[0], v[1], v[2], v[3]);
     }
     // tab[k] = max of the pieces k .. end of this span
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
@@ -257,14 +269,19 @@ __device__ unsigned long long g_score_prof[8];
 #define PROF_MARK(k) do { } while (0)
 #endif
 
+// kBigT: the table of block maxima does not fit in LDS and lives in global scratch.
+template <bool kBigT>
 __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
     __shared__ int64_t acc[kMaxLocal];
+    __shared__ int32_t lo_list[kMaxLocal];      // o of the slice's entries (its o order is the entries' own order)
+    __shared__ int2 hi_list[kMaxLocal];         // {q, index within the slice} sorted by q
     __shared__ __attribute__((aligned(16))) SpanBuf span_buf[kWaves];
-    __shared__ int64_t tab_lds[kTabLds];
+    __shared__ int64_t tab_lds[kBigT ? 1 : kTabLds];
     __shared__ uint32_t filter[kFilterWords];
     __shared__ int64_t span_max[kWaves];
-    int64_t *tab = a.tab_scratch ? a.tab_scratch + static_cast<int64_t>(blockIdx.x) * a.n_tab : tab_lds;
+    int64_t *tab_global = kBigT ? a.tab_scratch + static_cast<int64_t>(blockIdx.x) * a.n_tab : nullptr;
     int32_t filter_of = -1;      // bucket whose filter is in LDS
+    int32_t lists_of = -1;       // slice (numbered over all buckets) whose lists are in LDS
 #ifdef TENSILE_SCORE_PROF
     unsigned long long prof_t = wall_clock64();
 #endif
@@ -291,7 +308,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         const int32_t bk = tstar >> a.bucket_shift;
         const int32_t e0 = a.bucket_off[bk], n_e = a.bucket_off[bk + 1] - e0;
         if (n_e == 0) continue;                    // no gap around t* can be swapped in time
-        const int32_t *wp = a.wave_ptr + static_cast<int64_t>(bk) * 2 * (kWaves + 1);
+        const int32_t slice0 = a.slice_first[bk];
         const int2 hd = a.hash_dir[bk];
         int64_t k0 = a.plan_offsets[b], k1 = a.plan_offsets[b + 1];
         if (k0 < 0) k0 = 0;
@@ -300,8 +317,17 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
 
         for (int32_t slice_lo = 0; slice_lo < n_e; slice_lo += kMaxLocal) {
             const int32_t n_slice = min(kMaxLocal, n_e - slice_lo);
-            __syncthreads();   // the previous plan or slice has finished with acc, tab, span_max and the filter
+            const int32_t slice_id = slice0 + slice_lo / kMaxLocal;
+            const int32_t *wp = a.wave_ptr + static_cast<int64_t>(slice_id) * 2 * (kWaves + 1);
+            __syncthreads();   // the previous plan or slice has finished with acc, tab, span_max, the filter, the lists
             for (int32_t k = tid; k < n_slice; k += kThreads) acc[k] = INT64_MIN;
+            if (lists_of != slice_id) {
+                for (int32_t k = tid; k < n_slice; k += kThreads) {
+                    lo_list[k] = a.cand_o[e0 + slice_lo + k];
+                    hi_list[k] = a.qord[e0 + slice_lo + k];
+                }
+                lists_of = slice_id;
+            }
             if (filter_of != bk) {
                 const uint32_t *src = a.filter + static_cast<int64_t>(bk) * a.filter_words;
                 for (int32_t k = tid; k < a.filter_words; k += kThreads) filter[k] = src[k];
@@ -360,13 +386,19 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
 
             // ---- 3: stream the row (no barrier needed after step 2: +inf survives every max)
             {
-                const int32_t lo_begin = max(wp[wave], slice_lo), lo_end = min(wp[wave + 1], slice_lo + n_slice);
+                const int32_t lo_begin = wp[wave], lo_end = wp[wave + 1];
                 const int32_t hi_begin = wp[kWaves + 1 + wave], hi_end = wp[kWaves + 1 + wave + 1];
-                const int64_t m =
-                    a.vec16 ? stream_span<true>(a, MF, span_lo, span_hi, a.cand_o + e0, a.qord + e0, lo_begin, lo_end, hi_begin,
-                                                hi_end, slice_lo, n_slice, acc, &span_buf[wave], tab, lane)
-                            : stream_span<false>(a, MF, span_lo, span_hi, a.cand_o + e0, a.qord + e0, lo_begin, lo_end, hi_begin,
-                                                 hi_end, slice_lo, n_slice, acc, &span_buf[wave], tab, lane);
+                int64_t m;
+                if (kBigT)
+                    m = a.vec16 ? stream_span<true>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
+                                                    acc, &span_buf[wave], tab_global, lane)
+                                : stream_span<false>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
+                                                     acc, &span_buf[wave], tab_global, lane);
+                else
+                    m = a.vec16 ? stream_span<true>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
+                                                    acc, &span_buf[wave], tab_lds, lane)
+                                : stream_span<false>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
+                                                     acc, &span_buf[wave], tab_lds, lane);
                 if (lane == 0) span_max[wave] = m;
             }
             PROF_MARK(3);
@@ -389,7 +421,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                 }
                 int64_t m = max64(v, P - sz);
                 const int32_t piece = q / kMini + 1;                          // pieces after q's, inside q's span
-                if (piece * kMini < min((w_q + 1) * a.span, a.T)) m = max64(m, tab[piece]);
+                if (piece * kMini < min((w_q + 1) * a.span, a.T)) m = max64(m, kBigT ? tab_global[piece] : tab_lds[piece]);
 #pragma unroll
                 for (int w = 0; w < kWaves; ++w) {
                     const int64_t sm = span_max[w];
@@ -411,10 +443,13 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
                  int32_t *win_in, hipStream_t stream) {
     if (plans->B == 0 || tas->N == 0) return TENSILE_OK;
     // as many workgroups as the device keeps resident, the plans dealt evenly among them
-    static int per_cu = 0;
+    const bool big_t = (tas->T + kMini - 1) / kMini > kTabLds;
+    static int per_cu_of[2] = {0, 0};
+    int &per_cu = per_cu_of[big_t ? 1 : 0];
     if (per_cu == 0) {
         int n = 0;
-        TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel, kThreads, 0));
+        if (big_t) TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<true>, kThreads, 0));
+        else TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<false>, kThreads, 0));
         per_cu = n > 0 ? n : 1;
     }
     const int64_t resident_blocks = static_cast<int64_t>(tas->num_cus) * per_cu;
@@ -432,7 +467,7 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     a.bucket_shift = ix.shift; a.filter_words = ix.filter_words;
     a.bucket_off = ix.bucket_off.p;
     a.cand = ix.cand.p; a.cand_size = ix.cand_size.p; a.cand_o = ix.cand_o.p; a.qord = ix.qord.p;
-    a.wave_ptr = ix.wave_ptr.p; a.hash_dir = ix.hash_dir.p; a.hash_slots = ix.hash_slots.p; a.filter = ix.filter.p;
+    a.slice_first = ix.slice_first.p; a.wave_ptr = ix.wave_ptr.p; a.hash_dir = ix.hash_dir.p; a.hash_slots = ix.hash_slots.p; a.filter = ix.filter.p;
     a.resident = resident; a.peak = peak; a.argmax = argmax;
     a.score = score; a.win_out = win_out; a.win_in = win_in;
     a.tab_scratch = nullptr;
@@ -445,7 +480,8 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
         }
         a.tab_scratch = sc.score_tab.p;
     }
-    hipLaunchKernelGGL(score_kernel, dim3(blocks), dim3(kThreads), 0, stream, a);
+    if (big_t) hipLaunchKernelGGL(score_kernel<true>, dim3(blocks), dim3(kThreads), 0, stream, a);
+    else hipLaunchKernelGGL(score_kernel<false>, dim3(blocks), dim3(kThreads), 0, stream, a);
     TS_HIP(hipGetLastError());
     return TENSILE_OK;
 }

@@ -220,7 +220,10 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
     std::vector<int64_t> cand_size(E);
     std::vector<int32_t> cand_o(E);
     std::vector<int2> qord(E);
-    std::vector<int32_t> wave_ptr(static_cast<size_t>(nb) * 2 * (kScoreWaves + 1));
+    std::vector<int32_t> slice_first(static_cast<size_t>(nb) + 1, 0);
+    for (int32_t b = 0; b < nb; ++b)
+        slice_first[b + 1] = slice_first[b] + (off[b + 1] - off[b] + kScoreMaxLocal - 1) / kScoreMaxLocal;
+    std::vector<int32_t> wave_ptr(static_cast<size_t>(slice_first[nb]) * 2 * (kScoreWaves + 1));
     std::vector<int2> hash_dir(static_cast<size_t>(nb));
     std::vector<int4> hash_slots;
     std::vector<uint32_t> filter(static_cast<size_t>(nb) * ix.filter_words, 0u);
@@ -233,22 +236,26 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
         std::sort(c, c + n, [](const int4 &x, const int4 &y) {
             return x.z != y.z ? x.z < y.z : (x.w != y.w ? x.w < y.w : x.x < y.x);
         });
-        order.resize(n);
         for (int32_t k = 0; k < n; ++k) {
             cand_size[e0 + k] = h->h_size[c[k].w];
             cand_o[e0 + k] = c[k].z;
-            order[k] = k;
         }
-        std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return c[x].y != c[y].y ? c[x].y < c[y].y : x < y; });
-        for (int32_t k = 0; k < n; ++k) qord[e0 + k] = make_int2(c[order[k]].y, order[k]);
-        int32_t *wp = wave_ptr.data() + static_cast<size_t>(b) * 2 * (kScoreWaves + 1);
-        int32_t ko = 0, kq = 0;
-        for (int w = 0; w <= kScoreWaves; ++w) {
-            const int64_t bound = static_cast<int64_t>(w) * ix.span;
-            while (ko < n && c[ko].z < bound) ++ko;
-            while (kq < n && qord[e0 + kq].x < bound) ++kq;
-            wp[w] = w == kScoreWaves ? n : ko;
-            wp[kScoreWaves + 1 + w] = w == kScoreWaves ? n : kq;
+        for (int32_t s0 = 0, sl = slice_first[b]; s0 < n; s0 += kScoreMaxLocal, ++sl) {
+            const int32_t ns = std::min(kScoreMaxLocal, n - s0);
+            order.resize(ns);
+            for (int32_t k = 0; k < ns; ++k) order[k] = k;
+            std::sort(order.begin(), order.end(),
+                      [&](int32_t x, int32_t y) { return c[s0 + x].y != c[s0 + y].y ? c[s0 + x].y < c[s0 + y].y : x < y; });
+            for (int32_t k = 0; k < ns; ++k) qord[e0 + s0 + k] = make_int2(c[s0 + order[k]].y, order[k]);
+            int32_t *wp = wave_ptr.data() + static_cast<size_t>(sl) * 2 * (kScoreWaves + 1);
+            int32_t ko = 0, kq = 0;
+            for (int w = 0; w <= kScoreWaves; ++w) {
+                const int64_t bound = static_cast<int64_t>(w) * ix.span;
+                while (ko < ns && c[s0 + ko].z < bound) ++ko;
+                while (kq < ns && qord[e0 + s0 + kq].x < bound) ++kq;
+                wp[w] = w == kScoreWaves ? ns : ko;
+                wp[kScoreWaves + 1 + w] = w == kScoreWaves ? ns : kq;
+            }
         }
         // hash table: the entries of one tensor are inserted one after the other, the last flagged
         int bits = 1;
@@ -258,6 +265,7 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
         if (n == 0) continue;
         if (base + (size_t{1} << bits) > static_cast<size_t>(INT32_MAX)) { set_error("tas_load: candidate index too large"); return TENSILE_E_RANGE; }
         hash_slots.resize(base + (size_t{1} << bits), make_int4(-1, 0, 0, 0));
+        order.resize(n);
         for (int32_t k = 0; k < n; ++k) order[k] = k;
         std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return c[x].w != c[y].w ? c[x].w < c[y].w : x < y; });
         const uint32_t mask = (1u << bits) - 1;
@@ -276,6 +284,7 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
     TS_HIP(ix.cand_size.upload(cand_size.data(), E));
     TS_HIP(ix.cand_o.upload(cand_o.data(), E));
     TS_HIP(ix.qord.upload(qord.data(), E));
+    TS_HIP(ix.slice_first.upload(slice_first.data(), slice_first.size()));
     TS_HIP(ix.wave_ptr.upload(wave_ptr.data(), wave_ptr.size()));
     TS_HIP(ix.hash_dir.upload(hash_dir.data(), hash_dir.size()));
     TS_HIP(ix.hash_slots.upload(hash_slots.data(), hash_slots.size()));
