@@ -53,7 +53,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
-    ap.add_argument("--cpu-plans", type=int, default=1536, help="plans in the oracle's sample (about 10-20 s of CPU work)")
+    ap.add_argument("--cpu-plans", type=int, default=4096, help="plans in the oracle's sample (about 10-20 s of CPU work)")
     ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-planner leg")
     ap.add_argument("--eval-only", action="store_true", help="steps run tensile_eval_plans alone (profiling aid)")
     args = ap.parse_args()
