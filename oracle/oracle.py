@@ -65,6 +65,17 @@ def eval_plans(tas, plans, want_resident: bool = True, MF0: Optional[np.ndarray]
     return resident, peak, arg, mn
 
 
+def eval_per_job(tas, plans):
+    """-> (job_peak [J,B], job_argmax [J,B], sum_peak [B] = base_bytes + sum over jobs of their peaks)"""
+    B, J = plans.B, int(tas.J)
+    jp = np.empty((J, B), dtype=np.int64); ja = np.empty((J, B), dtype=np.int32)
+    job = np.ascontiguousarray(tas.job_id, dtype=np.int32)
+    _chk(_lib().oracle_eval_per_job(i32(tas.T), i32(tas.N), i32(J), _p(tas.size_bytes), _p(tas.alloc_step),
+                                    _p(tas.free_step), _p(job), i64(B), _p(plans.plan_offsets), i64(plans.n_intervals),
+                                    _p(plans.iv_tensor), _p(plans.iv_out), _p(plans.iv_in), _p(jp), _p(ja)), "eval_per_job")
+    return jp, ja, jp.sum(axis=0) + int(tas.base_bytes)
+
+
 def times(tas):
     """-> (C [T+1], x [N]) cumulative step time and per-tensor transfer time, ns"""
     C = np.empty(tas.T + 1, dtype=np.int64); x = np.empty(tas.N, dtype=np.int64)

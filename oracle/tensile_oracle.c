@@ -129,6 +129,54 @@ int oracle_eval(int32_t T, int32_t N, const int64_t *size, const int64_t *MF0, i
     return OR_OK;
 }
 
+/* Per-workload peaks (section III-A): the footprint MF_j of workload W_j sums
+ * Mem over the accesses and schedule events of that workload only, MP_j is its
+ * maximum, and for workloads that run asynchronously the global peak is taken as
+ * the sum of the MP_j.  Here: job j owns the tensors with job_id[i] == j; its
+ * timeline counts those tensors (generated at alloc, released after free) and the
+ * plan's intervals on them; the job-independent base_bytes belongs to no job and
+ * is left to the caller.  job_peak[j*B + b], job_arg[j*B + b] (earliest step of
+ * the maximum, strict comparison as in Alg. 1). */
+int oracle_eval_per_job(int32_t T, int32_t N, int32_t J, const int64_t *size, const int32_t *alloc,
+                        const int32_t *free_step, const int32_t *job_id, int64_t B, const int64_t *plan_offsets,
+                        int64_t n_intervals, const int32_t *iv_tensor, const int32_t *iv_out, const int32_t *iv_in,
+                        int64_t *job_peak, int32_t *job_arg) {
+    if (T <= 0 || N < 0 || J <= 0 || B < 0) return OR_E_INVAL;
+    int64_t *D = (int64_t *)malloc(((size_t)T + 1) * sizeof(int64_t));
+    if (!D) return OR_E_NOMEM;
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t k0, k1;
+        plan_range(plan_offsets, b, n_intervals, &k0, &k1);
+        for (int32_t j = 0; j < J; ++j) {
+            memset(D, 0, ((size_t)T + 1) * sizeof(int64_t));
+            for (int32_t i = 0; i < N; ++i) {
+                if ((job_id ? job_id[i] : 0) != j) continue;
+                D[alloc[i]] += size[i];
+                D[free_step[i] + 1] -= size[i];
+            }
+            for (int64_t k = k0; k < k1; ++k) {
+                int32_t i = iv_tensor[k], o = iv_out[k], r = iv_in[k];
+                if (!interval_applies(N, T, i, o, r) || (job_id ? job_id[i] : 0) != j) continue;
+                D[o + 1] -= size[i];
+                if (r < T) D[r] += size[i];
+            }
+            int64_t run = D[0], peak = D[0];
+            int32_t arg = 0;
+            for (int32_t t = 1; t < T; ++t) {
+                run += D[t];
+                if (run > peak) {
+                    peak = run;
+                    arg = t;
+                }
+            }
+            job_peak[(int64_t)j * B + b] = peak;
+            if (job_arg) job_arg[(int64_t)j * B + b] = arg;
+        }
+    }
+    free(D);
+    return OR_OK;
+}
+
 /* Cumulative operator latency C[0..T] (C[0] = 0) and transfer time
  * x_i = ceil(size_i * 1000 / link_bytes_per_us) in ns.  step_ns == NULL means
  * no timing information: C == 0 and x == 0 (every window is the whole gap). */
