@@ -141,6 +141,21 @@ def main() -> int:
         },
     }
 
+    if not args.eval_only and tas.J > 1:
+        # per-job peaks and their sum (one pass of the evaluation kernel per job, no rows written)
+        jp = torch.empty((int(tas.J), B), dtype=torch.int64, device="cuda")
+        tot = torch.empty(B, dtype=torch.int64, device="cuda")
+        P.tensile_eval_plans_per_job(h, dp, jp, None, tot)                 # first call builds the per-job tables
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            P.tensile_eval_plans_per_job(h, dp, jp, None, tot)
+        e1.record()
+        torch.cuda.synchronize()
+        out["rows"]["eval_plans_per_job"] = {"ms": e0.elapsed_time(e1) / 3, "jobs": int(tas.J)}
+        del jp, tot
+
     if not args.eval_only:
         # the recomputation savings of the same batch (second scoring mode; not part of the step)
         P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)       # first call builds its index

@@ -127,6 +127,22 @@ typedef struct {
 int tensile_eval_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *resident, int64_t *peak,
                        int32_t *argmax, int64_t *min_resident, void *hip_stream);
 
+/* Per-workload peaks (section III-A: the footprint MF_j of workload W_j counts
+ * the accesses and schedule events of that workload alone, MP_j is its maximum,
+ * and the global peak of workloads that run asynchronously is the sum of the
+ * MP_j).  Job j owns the tensors with job_id[i] == j; base_bytes belongs to no
+ * job.  For every plan b and job j:
+ *   MF_{b,j}[t] = sum of size_i over job j's tensors resident at t under plan b
+ *   job_peak[j*B + b]   = max_t MF_{b,j}[t]           (job-major layout)
+ *   job_argmax[j*B + b] = earliest step attaining it  (may be NULL)
+ *   sum_peak[b]         = base_bytes + sum_j job_peak[j*B + b]   (may be NULL)
+ * With one job, sum_peak equals tensile_eval_plans' peak.  sum_peak >= peak
+ * always.  DEVICE outputs.  Runs the evaluation kernel once per job without
+ * writing footprint rows; the first call on a handle builds per-job tables
+ * (synchronous, allocates), later calls are asynchronous on hip_stream. */
+int tensile_eval_plans_per_job(const tensile_tas *tas, const tensile_plans *plans, int64_t *job_peak,
+                               int32_t *job_argmax, int64_t *sum_peak, void *hip_stream);
+
 /* Per-tensor candidate scores for every plan (section IV-C: the candidates are
  * the tensors resident and idle at the peak; the paper orders them by size,
  * this returns the exact peak reduction, which is the size when the peak is

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libtensile.so")
 TENSILE_OK, TENSILE_E_INVAL, TENSILE_E_RANGE, TENSILE_E_NOMEM, TENSILE_E_HIP, TENSILE_E_CAPACITY = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["tensile_last_error", "tensile_version", "tensile_tas_load", "tensile_tas_free", "tensile_tas_info",
-           "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_score_candidates", "tensile_score_recompute",
+           "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_score_candidates", "tensile_score_recompute",
            "tensile_validate_plans",
            "tensile_greedy_plan"]
 
@@ -183,6 +183,17 @@ def tensile_eval_plans(h: TasHandle, plans: DevicePlans, resident: Optional[torc
     _check(_lib.tensile_eval_plans(h.ptr, ctypes.byref(st), _dp(resident, torch.int64, B * h.T, "resident"),
                                    _dp(peak, torch.int64, B, "peak"), _dp(argmax, torch.int32, B, "argmax"),
                                    _dp(min_resident, torch.int64, B, "min_resident"), _stream(stream)))
+
+
+def tensile_eval_plans_per_job(h: TasHandle, plans: DevicePlans, job_peak: torch.Tensor,
+                               job_argmax: Optional[torch.Tensor] = None, sum_peak: Optional[torch.Tensor] = None,
+                               stream=None) -> None:
+    """job_peak / job_argmax: [J, B] (job-major), sum_peak: [B]"""
+    B, J = plans.B, h.J
+    st = plans.struct()
+    _check(_lib.tensile_eval_plans_per_job(h.ptr, ctypes.byref(st), _dp(job_peak, torch.int64, J * B, "job_peak"),
+                                           _dp(job_argmax, torch.int32, J * B, "job_argmax"),
+                                           _dp(sum_peak, torch.int64, B, "sum_peak"), _stream(stream)))
 
 
 def tensile_score_candidates(h: TasHandle, plans: DevicePlans, resident: torch.Tensor, peak: torch.Tensor,

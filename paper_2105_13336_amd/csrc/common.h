@@ -83,6 +83,15 @@ struct Scratch {
     DevBuf<unsigned long long> tail_flag;   // eval: see EvalArgs::tail_flag
     unsigned long long epoch = 0;
     DevBuf<int64_t> score_tab;     // score: per-workgroup sub-span maxima when they do not fit in LDS
+    DevBuf<int32_t> job_arg;       // per-job evaluation: peak steps when the caller does not want them
+};
+
+// Per-job tables of tensile_eval_plans_per_job (see tas.hip), job-major.
+struct JobTables {
+    bool built = false;
+    size_t T_pad = 0;
+    DevBuf<int64_t> size, MF0, dMF0;   // [J][N], [J][T], [J][T_pad]
+    DevBuf<uint32_t> units;            // [J][N] when the handle has 32-bit size units
 };
 
 // Geometry the scoring kernel shares with the index built at load time (see score.hip).
@@ -138,6 +147,7 @@ struct tensile_tas {
     mutable tensile::CandIndex recompute_index;
     mutable bool recompute_index_built = false;
     std::vector<int32_t> h_gp, h_gq, h_gt;    // gaps of length >= 2 in tensor order (host)
+    mutable tensile::JobTables job_tables;    // built by the first tensile_eval_plans_per_job
     // host copies used by the greedy driver and the validator
     std::vector<int64_t> h_size, h_C, h_x, h_touch_off;
     std::vector<int32_t> h_touch, h_job;

@@ -175,6 +175,43 @@ int validate_desc(const tensile_tas_desc *d) {
     return TENSILE_OK;
 }
 
+// The unscheduled timeline of the tensors with the given sizes on top of a constant `base`, with the
+// evaluation kernel: start from the constant and "evict" every tensor with a negated size over its
+// lifetime [alloc, free].  MF_out [T]; dMF_out [T rounded up to tiles + 1 tile], zeroed by the caller.
+int build_timeline(const tensile_tas *h, const int64_t *d_size, int64_t base_value, const int32_t *d_alloc,
+                   const int32_t *d_free, int64_t *MF_out, int64_t *dMF_out, int64_t *peak_host, int32_t *arg_host) {
+    const int32_t T = h->T, N = h->N;
+    const size_t T_pad = ((static_cast<size_t>(T) + kEvalTile - 1) / kEvalTile + 1) * kEvalTile;
+    DevBuf<int64_t> base, dbase, neg, offs, peak, mn;
+    DevBuf<int32_t> it, io, ir, arg;
+    TS_HIP(base.reserve(T));
+    TS_HIP(dbase.reserve(T_pad));     // differences of the constant timeline: base, 0, 0, ...
+    TS_HIP(hipMemset(dbase.p, 0, T_pad * sizeof(int64_t)));
+    TS_HIP(hipMemcpy(dbase.p, &base_value, sizeof(int64_t), hipMemcpyHostToDevice));
+    TS_HIP(neg.reserve(N));
+    TS_HIP(it.reserve(N)); TS_HIP(io.reserve(N)); TS_HIP(ir.reserve(N));
+    const int64_t h_offs[2] = {0, N};
+    TS_HIP(offs.upload(h_offs, 2));
+    TS_HIP(peak.reserve(1)); TS_HIP(mn.reserve(1)); TS_HIP(arg.reserve(1));
+    hipLaunchKernelGGL(fill_kernel, dim3((T + 255) / 256), dim3(256), 0, 0, static_cast<int64_t>(T), base_value, base.p);
+    if (N > 0)
+        hipLaunchKernelGGL(lifetime_intervals_kernel, dim3((N + 255) / 256), dim3(256), 0, 0, N, d_size, d_alloc, d_free,
+                           neg.p, it.p, io.p, ir.p);
+    TS_HIP(hipGetLastError());
+    EvalArgs a{};
+    a.T = T; a.N = N; a.B = 1; a.o_min = -1; a.n_intervals = N;
+    a.plan_offsets = offs.p; a.iv_tensor = it.p; a.iv_out = io.p; a.iv_in = ir.p;
+    a.size = neg.p; a.size_units = nullptr; a.MF0 = base.p; a.dMF0 = dbase.p; a.resident = MF_out;
+    int rc = launch_eval(h, a, peak.p, arg.p, mn.p, nullptr);
+    if (rc != TENSILE_OK) return rc;
+    if (peak_host) TS_HIP(hipMemcpy(peak_host, peak.p, sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (arg_host) TS_HIP(hipMemcpy(arg_host, arg.p, sizeof(int32_t), hipMemcpyDeviceToHost));
+    hipLaunchKernelGGL(difference_kernel, dim3((T + 255) / 256), dim3(256), 0, 0, T, MF_out, dMF_out);
+    TS_HIP(hipGetLastError());
+    TS_HIP(hipDeviceSynchronize());     // the temporaries above are freed on return
+    return TENSILE_OK;
+}
+
 // A gap (p, q) with earliest swap-out step o >= 0 is a scoring candidate at the peak steps
 // t* with o < t* < q.  File it under every bucket of 2^shift steps that o+1 .. q-1 overlaps;
 // the bucket width starts at 256 steps and doubles while the index would hold more than
@@ -355,37 +392,14 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
     TS_HIP(h->d_C.reserve(static_cast<size_t>(T) + 1));
     TS_HIP(h->d_x.reserve(N));
 
-    // ---- MF0 with the evaluation kernel: start from the constant base_bytes and
-    // "evict" every tensor with a negated size over its lifetime [alloc, free].
+    // ---- MF0 and its differences
     {
-        DevBuf<int64_t> base, dbase, neg, offs, peak, mn;
-        DevBuf<int32_t> alloc, fr, it, io, ir, arg;
-        TS_HIP(base.reserve(T));
-        TS_HIP(dbase.reserve(T_pad));     // differences of the constant timeline: base_bytes, 0, 0, ...
-        TS_HIP(hipMemset(dbase.p, 0, T_pad * sizeof(int64_t)));
-        TS_HIP(hipMemcpy(dbase.p, &d->base_bytes, sizeof(int64_t), hipMemcpyHostToDevice));
-        TS_HIP(neg.reserve(N));
+        DevBuf<int32_t> alloc, fr;
         TS_HIP(alloc.upload(d->alloc_step, N));
         TS_HIP(fr.upload(d->free_step, N));
-        TS_HIP(it.reserve(N)); TS_HIP(io.reserve(N)); TS_HIP(ir.reserve(N));
-        const int64_t h_offs[2] = {0, N};
-        TS_HIP(offs.upload(h_offs, 2));
-        TS_HIP(peak.reserve(1)); TS_HIP(mn.reserve(1)); TS_HIP(arg.reserve(1));
-        hipLaunchKernelGGL(fill_kernel, dim3((T + 255) / 256), dim3(256), 0, 0, static_cast<int64_t>(T), d->base_bytes, base.p);
-        if (N > 0)
-            hipLaunchKernelGGL(lifetime_intervals_kernel, dim3((N + 255) / 256), dim3(256), 0, 0, N, h->d_size.p, alloc.p,
-                               fr.p, neg.p, it.p, io.p, ir.p);
-        TS_HIP(hipGetLastError());
-        EvalArgs a{};
-        a.T = T; a.N = N; a.B = 1; a.o_min = -1; a.n_intervals = N;
-        a.plan_offsets = offs.p; a.iv_tensor = it.p; a.iv_out = io.p; a.iv_in = ir.p;
-        a.size = neg.p; a.size_units = nullptr; a.MF0 = base.p; a.dMF0 = dbase.p; a.resident = h->d_MF0.p;
-        int rc = launch_eval(h, a, peak.p, arg.p, mn.p, nullptr);
+        int rc = build_timeline(h, h->d_size.p, d->base_bytes, alloc.p, fr.p, h->d_MF0.p, h->d_dMF0.p, &h->unscheduled_peak,
+                                &h->unscheduled_argmax);
         if (rc != TENSILE_OK) return rc;
-        TS_HIP(hipMemcpy(&h->unscheduled_peak, peak.p, sizeof(int64_t), hipMemcpyDeviceToHost));
-        TS_HIP(hipMemcpy(&h->unscheduled_argmax, arg.p, sizeof(int32_t), hipMemcpyDeviceToHost));
-        hipLaunchKernelGGL(difference_kernel, dim3((T + 255) / 256), dim3(256), 0, 0, T, h->d_MF0.p, h->d_dMF0.p);
-        TS_HIP(hipGetLastError());
     }
 
     // ---- C, x, per-gap windows
@@ -439,7 +453,59 @@ int ensure_recompute_index(const tensile_tas *tas) {
     return TENSILE_OK;
 }
 
+// Per-job copies of the tables the evaluation kernel reads: sizes with the other jobs' tensors set to
+// zero (an interval on such a tensor then changes nothing), and each job's own unscheduled timeline
+// without the base bytes.  Built on first use (see ensure_recompute_index about concurrency).
+int ensure_job_tables(const tensile_tas *tas) {
+    JobTables &jt = tas->job_tables;
+    if (jt.built) return TENSILE_OK;
+    const int32_t T = tas->T, N = tas->N, J = tas->J;
+    jt.T_pad = ((static_cast<size_t>(T) + kEvalTile - 1) / kEvalTile + 1) * kEvalTile;
+    try {
+        std::vector<int64_t> sizes(static_cast<size_t>(J) * N, 0);
+        std::vector<uint32_t> units;
+        const bool narrow = tas->d_size_units.p != nullptr;
+        if (narrow) units.assign(static_cast<size_t>(J) * N, 0u);
+        std::vector<int32_t> alloc(static_cast<size_t>(N)), fr(static_cast<size_t>(N));
+        for (int32_t i = 0; i < N; ++i) {
+            const int32_t j = tas->h_job.empty() ? 0 : tas->h_job[i];
+            sizes[static_cast<size_t>(j) * N + i] = tas->h_size[i];
+            if (narrow) units[static_cast<size_t>(j) * N + i] = static_cast<uint32_t>(static_cast<uint64_t>(tas->h_size[i]) >> tas->size_shift);
+            alloc[i] = tas->h_touch[tas->h_touch_off[i]];
+            fr[i] = tas->h_touch[tas->h_touch_off[i + 1] - 1];
+        }
+        TS_HIP(jt.size.upload(sizes.data(), sizes.size()));
+        if (narrow) TS_HIP(jt.units.upload(units.data(), units.size()));
+        TS_HIP(jt.MF0.reserve(static_cast<size_t>(J) * T));
+        TS_HIP(jt.dMF0.reserve(static_cast<size_t>(J) * jt.T_pad));
+        TS_HIP(hipMemset(jt.dMF0.p, 0, static_cast<size_t>(J) * jt.T_pad * sizeof(int64_t)));
+        DevBuf<int32_t> d_alloc, d_free;
+        TS_HIP(d_alloc.upload(alloc.data(), alloc.size()));
+        TS_HIP(d_free.upload(fr.data(), fr.size()));
+        for (int32_t j = 0; j < J; ++j) {
+            int rc = build_timeline(tas, jt.size.p + static_cast<size_t>(j) * N, 0, d_alloc.p, d_free.p,
+                                    jt.MF0.p + static_cast<size_t>(j) * T, jt.dMF0.p + static_cast<size_t>(j) * jt.T_pad, nullptr,
+                                    nullptr);
+            if (rc != TENSILE_OK) return rc;
+        }
+    } catch (const std::bad_alloc &) {
+        set_error("eval_plans_per_job: out of host memory");
+        return TENSILE_E_NOMEM;
+    }
+    jt.built = true;
+    return TENSILE_OK;
+}
+
 namespace {
+
+// sum_peak[b] = base + sum over jobs of job_peak[j*B + b]
+__global__ void sum_job_peaks_kernel(int32_t B, int32_t J, int64_t base, const int64_t *job_peak, int64_t *sum_peak) {
+    const int32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int64_t s = base;
+    for (int32_t j = 0; j < J; ++j) s += job_peak[static_cast<int64_t>(j) * B + b];
+    sum_peak[b] = s;
+}
 
 int check_plans(const tensile_tas *tas, const tensile_plans *plans, const char *who) {
     if (!tas || !plans) { set_error("%s: NULL handle or plans", who); return TENSILE_E_INVAL; }
@@ -516,6 +582,48 @@ int tensile_eval_plans(const tensile_tas *tas, const tensile_plans *plans, int64
     a.size = tas->d_size.p; a.size_units = tas->d_size_units.p; a.size_shift = tas->size_shift;
     a.MF0 = tas->d_MF0.p; a.dMF0 = tas->d_dMF0.p; a.resident = resident;
     return launch_eval(tas, a, peak, argmax, min_resident, static_cast<hipStream_t>(hip_stream));
+}
+
+int tensile_eval_plans_per_job(const tensile_tas *tas, const tensile_plans *plans, int64_t *job_peak, int32_t *job_argmax,
+                               int64_t *sum_peak, void *hip_stream) {
+    int rc = check_plans(tas, plans, "eval_plans_per_job");
+    if (rc != TENSILE_OK) return rc;
+    if (plans->B == 0) return TENSILE_OK;
+    if (!job_peak) { set_error("eval_plans_per_job: job_peak is required"); return TENSILE_E_INVAL; }
+    rc = ensure_job_tables(tas);
+    if (rc != TENSILE_OK) return rc;
+    const JobTables &jt = tas->job_tables;
+    const int32_t B = plans->B, J = tas->J;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!job_argmax) {
+        Scratch &sc = tas->scratch;
+        const size_t need = static_cast<size_t>(J) * B;
+        if (sc.job_arg.n < need) {
+            TS_HIP(hipDeviceSynchronize());
+            TS_HIP(sc.job_arg.reserve(need));
+        }
+        job_argmax = sc.job_arg.p;
+    }
+    for (int32_t j = 0; j < J; ++j) {      // one pass of the evaluation kernel per job, footprint rows not written
+        EvalArgs a{};
+        a.T = tas->T; a.N = tas->N; a.B = B; a.o_min = 0; a.n_intervals = plans->n_intervals;
+        a.plan_offsets = plans->plan_offsets;
+        a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;
+        a.size = jt.size.p + static_cast<size_t>(j) * tas->N;
+        a.size_units = jt.units.p ? jt.units.p + static_cast<size_t>(j) * tas->N : nullptr;
+        a.size_shift = tas->size_shift;
+        a.MF0 = jt.MF0.p + static_cast<size_t>(j) * tas->T;
+        a.dMF0 = jt.dMF0.p + static_cast<size_t>(j) * jt.T_pad;
+        a.resident = nullptr;
+        rc = launch_eval(tas, a, job_peak + static_cast<size_t>(j) * B, job_argmax + static_cast<size_t>(j) * B, nullptr, stream);
+        if (rc != TENSILE_OK) return rc;
+    }
+    if (sum_peak) {
+        hipLaunchKernelGGL(sum_job_peaks_kernel, dim3((B + 255) / 256), dim3(256), 0, stream, B, J, tas->base_bytes, job_peak,
+                           sum_peak);
+        TS_HIP(hipGetLastError());
+    }
+    return TENSILE_OK;
 }
 
 int tensile_score_candidates(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident,

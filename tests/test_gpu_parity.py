@@ -240,6 +240,49 @@ def test_score_optional_windows_and_blocking():
     h.close()
 
 
+# -------------------------------------------------------------------- per-job peaks
+
+def check_per_job(tas, pl, label=""):
+    h = P.tas_load(tas)
+    dp = upload(pl)
+    J, B = int(tas.J), pl.B
+    jp = torch.empty((J, B), dtype=torch.int64, device="cuda")
+    ja = torch.empty((J, B), dtype=torch.int32, device="cuda")
+    tot = torch.empty(B, dtype=torch.int64, device="cuda")
+    P.tensile_eval_plans_per_job(h, dp, jp, ja, tot)
+    torch.cuda.synchronize()
+    p0, a0, t0 = O.eval_per_job(tas, pl)
+    assert np.array_equal(jp.cpu().numpy(), p0), label + " job_peak"
+    assert np.array_equal(ja.cpu().numpy(), a0), label + " job_argmax"
+    assert np.array_equal(tot.cpu().numpy(), t0), label + " sum_peak"
+    # optional outputs left out; the merged evaluation of the same handle is unaffected
+    jp2 = torch.empty((J, B), dtype=torch.int64, device="cuda")
+    P.tensile_eval_plans_per_job(h, dp, jp2)
+    res, peak, arg, mn = gpu_eval(h, dp)
+    assert torch.equal(jp2, jp) and bool((tot >= peak).all())
+    _, p1, a1, _ = O.eval_plans(tas, pl, want_resident=False)
+    assert np.array_equal(peak.cpu().numpy(), p1) and np.array_equal(arg.cpu().numpy(), a1)
+    h.close()
+
+
+@pytest.mark.parametrize("seed,J,T", [(1, 2, 90), (2, 3, 5000), (3, 7, 20001)])
+def test_per_job_random(seed, J, T):
+    tas = small_random_tas(600 + seed, N=min(400, T // 2), T=T, max_acc=4, timed=False, base_bytes=1000 * seed)
+    tas.job_id = prng.randint(seed, 9, np.arange(tas.N), 0, J - 1).astype(np.int32)
+    tas.J = J
+    pl = make_plans(tas, 20, seed, p_swap=0.3)
+    say(f"per-job random seed={seed} J={J} T={T}")
+    check_per_job(tas, pl)
+
+
+def test_per_job_configs(configs_small):
+    say("per-job config 0 (one job) and hand example")
+    tas = configs_small[0]
+    check_per_job(tas, make_config_plans(0, tas, B=16), "c0")
+    tas = tas_from_lists(8, [4, 2, 5, 3], [0, 1, 4, 5], [[3], [2], [7], [6]], jobs=[0, 0, 1, 1], base_bytes=10)
+    check_per_job(tas, plans_from_lists([[], [(2, 4, 7)], [(0, 0, 3), (2, 4, 7)], [(9, 1, 2), (0, -1, 2)]]), "hand")
+
+
 # -------------------------------------------------------------------- recomputation scores
 
 def gpu_score_recompute(h, dp, res, peak, arg):
@@ -478,6 +521,16 @@ def test_full_size_config(idx, n_rows, n_score):
     assert np.array_equal(wi[sidx].cpu().numpy(), i0)
     size = torch.from_numpy(tas.size_bytes).cuda()
     assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
+    if tas.J > 1 and tas.J <= 8:
+        say(f"  per-job peaks of the whole batch ({tas.J} jobs)")
+        jp = torch.empty((int(tas.J), cfg.B), dtype=torch.int64, device="cuda")
+        ja = torch.empty((int(tas.J), cfg.B), dtype=torch.int32, device="cuda")
+        tot = torch.empty(cfg.B, dtype=torch.int64, device="cuda")
+        P.tensile_eval_plans_per_job(h, dp, jp, ja, tot)
+        torch.cuda.synchronize()
+        jp0, ja0, t0 = O.eval_per_job(tas, pl.select(srows))
+        assert np.array_equal(jp[:, sidx].cpu().numpy(), jp0) and np.array_equal(ja[:, sidx].cpu().numpy(), ja0)
+        assert np.array_equal(tot[sidx].cpu().numpy(), t0) and bool((tot >= peak).all())
     say("  recomputation savings of the whole batch")
     P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)
     torch.cuda.synchronize()
