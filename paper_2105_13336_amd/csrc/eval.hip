@@ -3,8 +3,10 @@
 // LDS tile, prefix scan over the steps, store the footprint row, and reduce
 // (max, earliest argmax, min) on the way.
 //
-// Work decomposition.  A workgroup (512 threads) owns one (plan, segment):
-// `tiles_per_seg` consecutive tiles of kEvalTile steps.  The running sum that
+// Work decomposition.  A workgroup owns one (plan, segment): `tiles_per_seg`
+// consecutive tiles of 8 steps per thread.  Two geometries are compiled: 1024 threads
+// with 8192-step tiles (one workgroup per CU: long rows) and 512 threads with 4096-step
+// tiles (two workgroups per CU, so that one can load while the other scans: short rows).  The running sum that
 // enters a segment is MF0 just before it plus the plan's deltas before it, which
 // the workgroup takes straight from the plan's intervals (an interval
 // contributes -size if its out+1 lies before the segment and +size if its in
@@ -54,14 +56,19 @@ namespace tensile {
 
 namespace {
 
-constexpr int kWaves = kEvalThreads / 64;
-constexpr int kVpt = kEvalTile / kEvalThreads;   // steps per lane per tile
-static_assert(kWaves <= 16 && kVpt == 8, "the scan below is written for 8 steps per lane");
+constexpr int kVpt = 8;   // steps per lane per tile: the scan below is written for 8
 // LDS layouts are skewed: 16-byte granule g lives at granule g + (g >> 4), i.e. cell u at
 // u + 2 * (u >> 5).  A lane's four granules stay contiguous (they never straddle a multiple of 16).
-constexpr int kTileCells = kEvalTile + 2 * (kEvalTile >> 5);          // 4352
 constexpr int kStageCells = 64 * kVpt + 2 * ((64 * kVpt) >> 5) + 2;    // 546 per wave, rounded up below
 constexpr int kStageStride = (kStageCells + 7) / 8 * 8;               // 552
+// Geometry of a workgroup with kThr threads
+template <int kThr>
+struct Geom {
+    static constexpr int kWaves = kThr / 64;
+    static constexpr int kTile = kThr * kVpt;                          // steps per LDS difference tile
+    static constexpr int kTileCells = kTile + 2 * (kTile >> 5);
+    static_assert(kWaves <= 16 && kTile <= kEvalTile, "wave totals are scanned by 16 lanes; dMF0 is padded for kEvalTile");
+};
 __device__ __forceinline__ uint32_t skew(uint32_t u) { return u + ((u >> 5) << 1); }
 
 struct Best {
@@ -123,9 +130,10 @@ __device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o,
 // kOut: 0 = no footprint rows are written (peaks only), 1 = rows written with 8-byte stores
 // (odd T or unaligned buffer), 2 = with 16-byte stores.  A compile-time property so that
 // every path through the tile loop issues the same memory operations.
-template <int R, bool kTail, bool kNarrow, int kOut>
+template <int kThr, int R, bool kTail, bool kNarrow, int kOut>
 __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     constexpr bool kStore = kOut != 0, kVec16 = kOut == 2;
+    constexpr int kWaves = Geom<kThr>::kWaves, kTile = Geom<kThr>::kTile, kTileCells = Geom<kThr>::kTileCells;
     // the tile, followed by 64 "trash" cells: a lane whose endpoint lies outside the tile adds to
     // trash[lane] instead (never read), which keeps the scatter free of branches and of
     // execution-mask changes
@@ -156,7 +164,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
         return;
     }
 
-    const int64_t seg_len = static_cast<int64_t>(a.tiles_per_seg) * kEvalTile;
+    const int64_t seg_len = static_cast<int64_t>(a.tiles_per_seg) * kTile;
     const int64_t seg_lo64 = seg * seg_len;
     if (seg_lo64 >= a.T) return;   // cannot happen with the host's choice of S; keeps indexing safe
     const int32_t seg_lo = static_cast<int32_t>(seg_lo64);
@@ -183,7 +191,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
         // all loads are unconditional (indices clamped into the plan's list, tensor index
         // clamped to 0) and issued back to back, then waited for once
         const int32_t *pt = a.iv_tensor + k0, *po = a.iv_out + k0, *pr = a.iv_in + k0;
-        const uint32_t len = k1 - k0 < R * kEvalThreads ? static_cast<uint32_t>(k1 - k0) : R * kEvalThreads;
+        const uint32_t len = k1 - k0 < R * kThr ? static_cast<uint32_t>(k1 - k0) : R * kThr;
         int32_t ti[R], vo[R], vr[R];
 #pragma unroll
         for (int j = 0; j < R; ++j) {
@@ -223,7 +231,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
             sz[j] = 0;
         }
     }
-    const int64_t k_over = k0 + static_cast<int64_t>(R) * kEvalThreads;   // the rest is re-read per tile
+    const int64_t k_over = k0 + static_cast<int64_t>(R) * kThr;   // the rest is re-read per tile
 
 #pragma unroll
     for (int j = 0; j < kVpt / 2; ++j) reinterpret_cast<ll2 *>(&delta[my_cell])[j] = fill[j];
@@ -240,7 +248,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
             c += (e1[j] < skew(seg_lo) ? s : 0) - (e0[j] < skew(seg_lo) ? s : 0);
         }
         if constexpr (kTail) {
-            for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
+            for (int64_t k = k_over + tid; k < k1; k += kThr) {
                 const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
                 if (!applies(a, i, o, r)) continue;
                 const int64_t s = a.size[i];
@@ -265,7 +273,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     auto store_part = [&](int32_t t_lo, int32_t t_hi, int j) {
         const int32_t wave_t0 = t_lo + wave_u * (64 * kVpt);
         const ll2 x = (reinterpret_cast<const ll2 *>(stage) + lane + (lane >> 4))[68 * j];
-        if (kVec16 && t_hi - t_lo == kEvalTile) {
+        if (kVec16 && t_hi - t_lo == kTile) {
             (reinterpret_cast<ll2 *>(row + wave_t0) + lane)[64 * j] = x;   // plain store: nontemporal ones measured slower
         } else {
             const int32_t t = wave_t0 + 2 * (j * 64 + lane);
@@ -288,18 +296,18 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     // separate instantiation so that the same operations are issued on every path.
     auto do_tile = [&](int32_t tile_lo, auto first_tag) {
         constexpr bool kFirst = decltype(first_tag)::value;
-        const int32_t tile_hi = tile_lo + kEvalTile < seg_hi ? tile_lo + kEvalTile : seg_hi;
+        const int32_t tile_hi = tile_lo + kTile < seg_hi ? tile_lo + kTile : seg_hi;
         const uint32_t tile_n = static_cast<uint32_t>(tile_hi - tile_lo);
         // delta holds dMF0 of this tile: written before the loop, or by the scan of the previous
         // tile ahead of its barrier.  dMF0 has one whole tile of padding past the end, so the load
         // of the "next" tile is unconditional (what it brings is never scanned in that case).
 #pragma unroll
         for (int j = 0; j < kVpt / 2; ++j)
-            fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kEvalTile + my)[j];
+            fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kTile + my)[j];
         constexpr bool kPrev = !kFirst && kStore;
         if constexpr (kPrev) {
             __builtin_amdgcn_wave_barrier();
-            store_part(tile_lo - kEvalTile, tile_lo, 0);
+            store_part(tile_lo - kTile, tile_lo, 0);
         }
 
         // ---- scatter: endpoints of this plan that fall into [tile_lo, tile_hi); a wavefront none
@@ -321,7 +329,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
             }
         }
         if constexpr (kTail) {
-            for (int64_t k = k_over + tid; k < k1; k += kEvalThreads) {
+            for (int64_t k = k_over + tid; k < k1; k += kThr) {
                 const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
                 if (!applies(a, i, o, r)) continue;
                 const uint32_t u0 = static_cast<uint32_t>(o + 1 - tile_lo), u1 = static_cast<uint32_t>(r - tile_lo);
@@ -332,7 +340,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
                 }
             }
         }
-        if constexpr (kPrev) store_part(tile_lo - kEvalTile, tile_lo, 1);
+        if constexpr (kPrev) store_part(tile_lo - kTile, tile_lo, 1);
         __syncthreads();
 
         // ---- local scan of this lane's 8 cells; the cells receive the next tile's dMF0.  In the
@@ -355,10 +363,10 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
             incl = wave_scan_add(v[kVpt - 1]);
         }
         if (lane == 63) wave_tot[wave] = incl;
-        if constexpr (kPrev) store_part(tile_lo - kEvalTile, tile_lo, 2);
+        if constexpr (kPrev) store_part(tile_lo - kTile, tile_lo, 2);
         __syncthreads();
         if (!wave_live) {   // (the ragged tile is the last one of its row: no later tile needs carry)
-            if constexpr (kPrev) store_part(tile_lo - kEvalTile, tile_lo, 3);
+            if constexpr (kPrev) store_part(tile_lo - kTile, tile_lo, 3);
             return;
         }
         // prefix over the wave totals: the first lanes scan them, then every lane picks the
@@ -426,7 +434,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
         // ---- park the results in the wave's staging area (lane-contiguous, skewed); they are
         // stored during the next iteration, or after the loop
         if constexpr (kPrev) {
-            store_part(tile_lo - kEvalTile, tile_lo, 3);
+            store_part(tile_lo - kTile, tile_lo, 3);
             __builtin_amdgcn_wave_barrier();
         }
         if constexpr (kStore) {
@@ -438,7 +446,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
 
     do_tile(seg_lo, std::true_type{});
     int32_t last_lo = seg_lo;
-    for (int32_t tile_lo = seg_lo + kEvalTile; tile_lo < seg_hi; tile_lo += kEvalTile) {
+    for (int32_t tile_lo = seg_lo + kTile; tile_lo < seg_hi; tile_lo += kTile) {
         do_tile(tile_lo, std::false_type{});
         last_lo = tile_lo;
     }
@@ -471,24 +479,22 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     }
 }
 
-// Two workgroups per CU (four waves per SIMD) need at most 128 VGPRs; up to 12 intervals per
-// thread fit without spilling.  The tail kernel keeps 16 and is left to the register allocator.
-template <int R, bool kNarrow, int kOut>
-__global__ __launch_bounds__(kEvalThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void eval_kernel(const EvalArgs a) {
-    eval_body<R, false, kNarrow, kOut>(a, blockIdx.x);
+// Four waves per SIMD (one workgroup of 1024 threads or two of 512 per CU) need at most 128 VGPRs;
+// up to 12 intervals per thread fit without spilling.  The tail kernel is left to the register allocator.
+template <int kThr, int R, bool kNarrow, int kOut>
+__global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) void eval_kernel(const EvalArgs a) {
+    eval_body<kThr, R, false, kNarrow, kOut>(a, blockIdx.x);
 }
-// intervals per thread held in registers: three sizes for the common kernel (2048, 4096 and
-// 6144 intervals per plan), 8192 for the tail kernel
-constexpr int kRSmall = 2048 / kEvalThreads, kRMid = 4096 / kEvalThreads, kRBig = 6144 / kEvalThreads;
-constexpr int kTailR = 8192 / kEvalThreads;
+// intervals per plan held in registers: three sizes for the common kernel, 8192 for the tail kernel
+constexpr int kCapSmall = 2048, kCapMid = 4096, kCapBig = 6144, kCapTail = 8192;
 // The tail kernel runs after the common one on the same stream with a small persistent grid.
 // It does nothing unless the common kernel met a plan it had to leave (flag == this launch's
 // epoch); then its workgroups walk all (plan, segment) pairs and take the long plans.
-template <bool kNarrow, int kOut>
-__global__ __launch_bounds__(kEvalThreads) void eval_tail_kernel(const EvalArgs a, const int64_t n_logical) {
+template <int kThr, bool kNarrow, int kOut>
+__global__ __launch_bounds__(kThr) void eval_tail_kernel(const EvalArgs a, const int64_t n_logical) {
     if (*a.tail_flag != a.epoch) return;
     for (int64_t w = blockIdx.x; w < n_logical; w += gridDim.x) {
-        eval_body<kTailR, true, kNarrow, kOut>(a, w);
+        eval_body<kThr, kCapTail / kThr, true, kNarrow, kOut>(a, w);
         __syncthreads();   // LDS is reused by the next logical workgroup
     }
 }
@@ -516,10 +522,51 @@ __global__ void eval_finalize_kernel(int32_t B, int32_t S, const int64_t *part_m
     if (min_resident) min_resident[b] = mn;
 }
 
+constexpr int kSmallGeometryMaxT = 16384;   // rows up to this length use the 512-thread geometry
+
 int env_int(const char *name, int fallback) {
     const char *s = std::getenv(name);
     if (!s || !*s) return fallback;
     return std::atoi(s);
+}
+
+// The launches of one geometry: common kernel (three register capacities), tail kernel.
+template <int kThr>
+int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, int cap, int out, bool narrow,
+                    hipStream_t stream) {
+    const dim3 grid(static_cast<uint32_t>(blocks)), block(kThr);
+#define TS_LAUNCH_OUT(KERNEL, ...)                                                                   \
+    do {                                                                                             \
+        if (out == 2) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 2>), grid, block, 0, stream, a);       \
+        else if (out == 1) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 1>), grid, block, 0, stream, a);  \
+        else hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 0>), grid, block, 0, stream, a);                \
+    } while (0)
+#define TS_LAUNCH_EVAL(R)                                         \
+    do {                                                          \
+        if (narrow) TS_LAUNCH_OUT(eval_kernel, kThr, R, true);    \
+        else TS_LAUNCH_OUT(eval_kernel, kThr, R, false);          \
+    } while (0)
+    if (cap == kCapSmall) TS_LAUNCH_EVAL(kCapSmall / kThr);
+    else if (cap == kCapMid) TS_LAUNCH_EVAL(kCapMid / kThr);
+    else TS_LAUNCH_EVAL(kCapBig / kThr);
+    TS_HIP(hipGetLastError());
+#undef TS_LAUNCH_EVAL
+#undef TS_LAUNCH_OUT
+    {
+        const int64_t resident = static_cast<int64_t>(tas->num_cus) * (1024 / kThr);
+        const dim3 tgrid(static_cast<uint32_t>(blocks < resident ? blocks : resident));
+#define TS_LAUNCH_TAIL(NARROW)                                                                                            \
+    do {                                                                                                                  \
+        if (out == 2) hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 2>), tgrid, block, 0, stream, a, blocks);        \
+        else if (out == 1) hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 1>), tgrid, block, 0, stream, a, blocks);   \
+        else hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 0>), tgrid, block, 0, stream, a, blocks);                 \
+    } while (0)
+        if (narrow) TS_LAUNCH_TAIL(true);
+        else TS_LAUNCH_TAIL(false);
+#undef TS_LAUNCH_TAIL
+    }
+    TS_HIP(hipGetLastError());
+    return TENSILE_OK;
 }
 
 }  // namespace
@@ -528,7 +575,12 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
                 hipStream_t stream) {
     EvalArgs a = proto;
     if (a.B == 0) return TENSILE_OK;
-    const int64_t n_tiles = (static_cast<int64_t>(a.T) + kEvalTile - 1) / kEvalTile;
+    // geometry: short rows get the small workgroups (see the top of the file)
+    int threads = a.T <= kSmallGeometryMaxT ? 512 : 1024;
+    const int threads_forced = env_int("TENSILE_EVAL_THREADS", 0);   // tuning knob
+    if (threads_forced == 512 || threads_forced == 1024) threads = threads_forced;
+    const int tile = threads * kVpt;
+    const int64_t n_tiles = (static_cast<int64_t>(a.T) + tile - 1) / tile;
     // enough workgroups to fill the chip several times over; otherwise one segment per plan
     const int64_t want_blocks = static_cast<int64_t>(tas->num_cus) * 16;
     int64_t S = (want_blocks + a.B - 1) / a.B;
@@ -567,14 +619,14 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     const int out = !a.resident ? 0
                     : ((a.T % 2 == 0) && (reinterpret_cast<uintptr_t>(a.resident) % 16 == 0)) ? 2 : 1;
     const bool narrow = a.size_units != nullptr;
-    // intervals per thread kept in registers by the common kernel: sized for the average plan
-    // with some slack; longer plans are left to the tail kernel
+    // intervals kept in registers by the common kernel: sized for the average plan with some
+    // slack; longer plans are left to the tail kernel
     const int64_t avg_k = (a.n_intervals + a.B - 1) / a.B;
-    int64_t r_need = (avg_k + avg_k / 8 + kEvalThreads - 1) / kEvalThreads;
-    const int r_forced = env_int("TENSILE_EVAL_R", 0);   // tuning knob
-    if (r_forced > 0) r_need = r_forced;
-    const int r_fast = r_need <= kRSmall ? kRSmall : r_need <= kRMid ? kRMid : kRBig;
-    a.tail_threshold = static_cast<int64_t>(r_fast) * kEvalThreads;
+    int64_t need = avg_k + avg_k / 8;
+    const int r_forced = env_int("TENSILE_EVAL_R", 0);   // tuning knob: registers per thread at 1024 threads
+    if (r_forced > 0) need = static_cast<int64_t>(r_forced) * 1024;
+    const int cap = need <= kCapSmall ? kCapSmall : need <= kCapMid ? kCapMid : kCapBig;
+    a.tail_threshold = cap;
     {
         Scratch &sc = tas->scratch;
         if (!sc.tail_flag.p) {
@@ -584,40 +636,12 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
         a.tail_flag = sc.tail_flag.p;
         a.epoch = ++sc.epoch;
     }
-    const dim3 grid(static_cast<uint32_t>(blocks)), block(kEvalThreads);
-#define TS_LAUNCH_OUT(KERNEL, ...)                                                                   \
-    do {                                                                                             \
-        if (out == 2) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 2>), grid, block, 0, stream, a);       \
-        else if (out == 1) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 1>), grid, block, 0, stream, a);  \
-        else hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 0>), grid, block, 0, stream, a);                \
-    } while (0)
-#define TS_LAUNCH_EVAL(R)                                   \
-    do {                                                    \
-        if (narrow) TS_LAUNCH_OUT(eval_kernel, R, true);    \
-        else TS_LAUNCH_OUT(eval_kernel, R, false);          \
-    } while (0)
-    if (r_fast == kRSmall) TS_LAUNCH_EVAL(kRSmall);
-    else if (r_fast == kRMid) TS_LAUNCH_EVAL(kRMid);
-    else TS_LAUNCH_EVAL(kRBig);
-    TS_HIP(hipGetLastError());
-#undef TS_LAUNCH_EVAL
-#undef TS_LAUNCH_OUT
-    {
-        const dim3 tgrid(static_cast<uint32_t>(blocks < tas->num_cus ? blocks : tas->num_cus));
-#define TS_LAUNCH_TAIL(NARROW)                                                                                      \
-    do {                                                                                                            \
-        if (out == 2) hipLaunchKernelGGL((eval_tail_kernel<NARROW, 2>), tgrid, block, 0, stream, a, blocks);        \
-        else if (out == 1) hipLaunchKernelGGL((eval_tail_kernel<NARROW, 1>), tgrid, block, 0, stream, a, blocks);   \
-        else hipLaunchKernelGGL((eval_tail_kernel<NARROW, 0>), tgrid, block, 0, stream, a, blocks);                 \
-    } while (0)
-        if (narrow) TS_LAUNCH_TAIL(true);
-        else TS_LAUNCH_TAIL(false);
-#undef TS_LAUNCH_TAIL
-    }
-    TS_HIP(hipGetLastError());
+    const int rc = threads == 512 ? launch_geometry<512>(tas, a, blocks, cap, out, narrow, stream)
+                                  : launch_geometry<1024>(tas, a, blocks, cap, out, narrow, stream);
+    if (rc != TENSILE_OK) return rc;
     if (S > 1) {
-        const int threads = 256;
-        hipLaunchKernelGGL(eval_finalize_kernel, dim3((a.B + threads - 1) / threads), dim3(threads), 0, stream, a.B,
+        const int fthreads = 256;
+        hipLaunchKernelGGL(eval_finalize_kernel, dim3((a.B + fthreads - 1) / fthreads), dim3(fthreads), 0, stream, a.B,
                            a.S, a.out_max, a.out_arg, a.out_min, peak, argmax, min_resident);
         TS_HIP(hipGetLastError());
     }
