@@ -75,6 +75,11 @@ struct EvalArgs {
     int64_t *out_max;              // S == 1: peak[B]; else partials [B*S]
     int32_t *out_arg;
     int64_t *out_min;              // may be null when S == 1
+    // binned mode (batches of long plans, see eval.hip): the plans' endpoints sorted by tile
+    const int2 *recs;              // [2 * n_intervals] {cell in the skewed tile | sign << 31, size units}; plan b's at 2 * offset
+    const int32_t *tile_off;       // [B][n_tiles + 1] first record of each tile, relative to the plan's records
+    const int64_t *tile_sum;       // [B][n_tiles] sum of the deltas that fall into each tile
+    int32_t n_tiles;
 };
 
 struct Scratch {
@@ -84,6 +89,9 @@ struct Scratch {
     unsigned long long epoch = 0;
     DevBuf<int64_t> score_tab;     // score: per-workgroup sub-span maxima when they do not fit in LDS
     DevBuf<int32_t> job_arg;       // per-job evaluation: peak steps when the caller does not want them
+    DevBuf<int2> bin_recs;         // eval, binned mode: see EvalArgs
+    DevBuf<int32_t> bin_off;
+    DevBuf<int64_t> bin_sum;
 };
 
 // Per-job tables of tensile_eval_plans_per_job (see tas.hip), job-major.

@@ -130,7 +130,9 @@ __device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o,
 // kOut: 0 = no footprint rows are written (peaks only), 1 = rows written with 8-byte stores
 // (odd T or unaligned buffer), 2 = with 16-byte stores.  A compile-time property so that
 // every path through the tile loop issues the same memory operations.
-template <int kThr, int R, bool kTail, bool kNarrow, int kOut>
+// kBinned: the batch went through bin_kernel first; nothing is kept in registers (R is 1 and unused),
+// every tile reads its own records.  Every plan of the batch is taken.
+template <int kThr, int R, bool kTail, bool kNarrow, int kOut, bool kBinned = false>
 __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     constexpr bool kStore = kOut != 0, kVec16 = kOut == 2;
     constexpr int kWaves = Geom<kThr>::kWaves, kTile = Geom<kThr>::kTile, kTileCells = Geom<kThr>::kTileCells;
@@ -159,9 +161,11 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     if (k0 < 0) k0 = 0;
     if (k1 > a.n_intervals) k1 = a.n_intervals;
     if (k1 < k0) k1 = k0;
-    if ((k1 - k0 > a.tail_threshold) != kTail) {   // block-uniform: the other kernel's plan
-        if (!kTail && tid == 0) atomicMax(a.tail_flag, a.epoch);   // tell the tail kernel it has work
-        return;
+    if constexpr (!kBinned) {
+        if ((k1 - k0 > a.tail_threshold) != kTail) {   // block-uniform: the other kernel's plan
+            if (!kTail && tid == 0) atomicMax(a.tail_flag, a.epoch);   // tell the tail kernel it has work
+            return;
+        }
     }
 
     const int64_t seg_len = static_cast<int64_t>(a.tiles_per_seg) * kTile;
@@ -187,7 +191,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     uint32_t e0[R], e1[R];
     typename SR::type sz[R];
     int32_t lo_t = INT32_MAX, hi_t = -1;
-    if (k1 > k0) {   // block-uniform
+    if (!kBinned && k1 > k0) {   // block-uniform
         // all loads are unconditional (indices clamped into the plan's list, tensor index
         // clamped to 0) and issued back to back, then waited for once
         const int32_t *pt = a.iv_tensor + k0, *po = a.iv_out + k0, *pr = a.iv_in + k0;
@@ -254,6 +258,10 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
                 const int64_t s = a.size[i];
                 c += (r < seg_lo ? s : 0) - (o + 1 < seg_lo ? s : 0);
             }
+        }
+        if constexpr (kBinned) {   // the tiles before the segment, already summed by bin_kernel
+            const int64_t *ts = a.tile_sum + static_cast<int64_t>(plan) * a.n_tiles;
+            for (int32_t tl = tid; tl < seg_lo / kTile; tl += kThr) c += ts[tl];
         }
         c = last_lane(wave_scan_add(c));
         if (lane == 0) carry_part[wave] = c;
@@ -338,6 +346,16 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
                     if (u0 < tile_n) lds_add(&delta[skew(u0)], -s);
                     if (u1 < tile_n) lds_add(&delta[skew(u1)], s);
                 }
+            }
+        }
+        if constexpr (kBinned) {
+            const int32_t *off = a.tile_off + static_cast<int64_t>(plan) * (a.n_tiles + 1) + tile_lo / kTile;
+            const int2 *recs = a.recs + 2 * k0;
+            for (int32_t k = off[0] + tid; k < off[1]; k += kThr) {
+                const int2 rec = recs[k];
+                const int64_t bytes = static_cast<int64_t>(static_cast<uint64_t>(static_cast<uint32_t>(rec.y)) << a.size_shift);
+                if (rec.x < 0) lds_sub(&delta[rec.x & 0x7fffffff], bytes);
+                else lds_add(&delta[rec.x], bytes);
             }
         }
         if constexpr (kPrev) store_part(tile_lo - kTile, tile_lo, 1);
@@ -499,6 +517,91 @@ __global__ __launch_bounds__(kThr) void eval_tail_kernel(const EvalArgs a, const
     }
 }
 
+// ---- batches of long plans -------------------------------------------------------------
+// When the average plan is longer than the registers hold, the whole batch is binned first:
+// one workgroup per plan sorts the plan's endpoints by tile (counting sort with LDS counters;
+// two passes over the plan) into records {cell | sign, size units} and sums each tile's deltas.
+// The evaluation kernel then reads, per tile, only that tile's records, and takes the running
+// sum entering a segment from the tile sums.  Records of a tile are in no particular order
+// (integer additions commute).
+constexpr int kMaxBinTiles = 4096;
+
+template <int kThr>
+__global__ __launch_bounds__(1024) void bin_kernel(const EvalArgs a, int2 *recs_all, int32_t *tile_off, int64_t *tile_sum) {
+    constexpr int kTile = Geom<kThr>::kTile;
+    __shared__ int32_t cnt[kMaxBinTiles + 1];
+    __shared__ int64_t sum[kMaxBinTiles];
+    __shared__ int32_t wave_cnt[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t plan = blockIdx.x, nt = a.n_tiles;
+    int64_t k0 = a.plan_offsets[plan], k1 = a.plan_offsets[plan + 1];
+    if (k0 < 0) k0 = 0;
+    if (k1 > a.n_intervals) k1 = a.n_intervals;
+    if (k1 < k0) k1 = k0;
+    for (int32_t t = tid; t <= nt; t += 1024) cnt[t] = 0;
+    for (int32_t t = tid; t < nt; t += 1024) sum[t] = 0;
+    __syncthreads();
+    for (int64_t k = k0 + tid; k < k1; k += 1024) {
+        const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
+        if (!applies(a, i, o, r)) continue;
+        const int64_t bytes = static_cast<int64_t>(static_cast<uint64_t>(a.size_units[i]) << a.size_shift);
+        if (o + 1 < a.T) {
+            atomicAdd(&cnt[(o + 1) / kTile], 1);
+            lds_sub(&sum[(o + 1) / kTile], bytes);
+        }
+        if (r < a.T) {
+            atomicAdd(&cnt[r / kTile], 1);
+            lds_add(&sum[r / kTile], bytes);
+        }
+    }
+    __syncthreads();
+    // exclusive prefix of the counts, 4 consecutive tiles per thread (nt <= 4096)
+    {
+        int32_t c[4], run = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            c[j] = 4 * tid + j < nt ? cnt[4 * tid + j] : 0;
+            run += c[j];
+        }
+        const int32_t incl = static_cast<int32_t>(wave_scan_add(run));
+        if (lane == 63) wave_cnt[wave] = incl;
+        __syncthreads();
+        int32_t before = incl - run;
+        for (int v = 0; v < wave; ++v) before += wave_cnt[v];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (4 * tid + j <= nt) cnt[4 * tid + j] = before;      // (entry nt receives the total)
+            before += c[j];
+        }
+    }
+    __syncthreads();
+    int32_t *off_out = tile_off + static_cast<int64_t>(plan) * (nt + 1);
+    int64_t *sum_out = tile_sum + static_cast<int64_t>(plan) * nt;
+    for (int32_t t = tid; t <= nt; t += 1024) off_out[t] = cnt[t];
+    for (int32_t t = tid; t < nt; t += 1024) sum_out[t] = sum[t];
+    __syncthreads();
+    // second pass: cnt[] now serves as the tiles' write cursors
+    int2 *recs = recs_all + 2 * k0;
+    for (int64_t k = k0 + tid; k < k1; k += 1024) {
+        const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
+        if (!applies(a, i, o, r)) continue;
+        const int32_t units = static_cast<int32_t>(a.size_units[i]);
+        if (o + 1 < a.T) {
+            const int32_t tl = (o + 1) / kTile;
+            recs[atomicAdd(&cnt[tl], 1)] = make_int2(static_cast<int32_t>(skew(o + 1 - tl * kTile) | 0x80000000u), units);
+        }
+        if (r < a.T) {
+            const int32_t tl = r / kTile;
+            recs[atomicAdd(&cnt[tl], 1)] = make_int2(static_cast<int32_t>(skew(r - tl * kTile)), units);
+        }
+    }
+}
+
+template <int kThr, int kOut>
+__global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) void eval_binned_kernel(const EvalArgs a) {
+    eval_body<kThr, 1, false, true, kOut, true>(a, blockIdx.x);
+}
+
 // Combine the per-segment partials of each plan; segments are in time order, so
 // a strict '>' keeps the earliest step.
 __global__ void eval_finalize_kernel(int32_t B, int32_t S, const int64_t *part_max, const int32_t *part_arg,
@@ -532,9 +635,19 @@ int env_int(const char *name, int fallback) {
 
 // The launches of one geometry: common kernel (three register capacities), tail kernel.
 template <int kThr>
-int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, int cap, int out, bool narrow,
+int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, int cap, int out, bool narrow, bool binned,
                     hipStream_t stream) {
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kThr);
+    if (binned) {
+        Scratch &sc = tas->scratch;
+        hipLaunchKernelGGL(bin_kernel<kThr>, dim3(a.B), dim3(1024), 0, stream, a, sc.bin_recs.p, sc.bin_off.p, sc.bin_sum.p);
+        TS_HIP(hipGetLastError());
+        if (out == 2) hipLaunchKernelGGL((eval_binned_kernel<kThr, 2>), grid, block, 0, stream, a);
+        else if (out == 1) hipLaunchKernelGGL((eval_binned_kernel<kThr, 1>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((eval_binned_kernel<kThr, 0>), grid, block, 0, stream, a);
+        TS_HIP(hipGetLastError());
+        return TENSILE_OK;
+    }
 #define TS_LAUNCH_OUT(KERNEL, ...)                                                                   \
     do {                                                                                             \
         if (out == 2) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 2>), grid, block, 0, stream, a);       \
@@ -636,8 +749,28 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
         a.tail_flag = sc.tail_flag.p;
         a.epoch = ++sc.epoch;
     }
-    const int rc = threads == 512 ? launch_geometry<512>(tas, a, blocks, cap, out, narrow, stream)
-                                  : launch_geometry<1024>(tas, a, blocks, cap, out, narrow, stream);
+    // a batch whose average plan does not fit the registers is binned by tile first
+    bool binned = narrow && need > kCapBig && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2);
+    const int bin_forced = env_int("TENSILE_EVAL_BINNED", -1);   // tuning knob: 0 = never, 1 = whenever possible
+    if (bin_forced == 0) binned = false;
+    if (bin_forced == 1) binned = narrow && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2);
+    if (binned) {
+        Scratch &sc = tas->scratch;
+        const size_t n_recs = 2 * static_cast<size_t>(a.n_intervals), n_off = static_cast<size_t>(a.B) * (n_tiles + 1),
+                     n_sum = static_cast<size_t>(a.B) * n_tiles;
+        if (sc.bin_recs.n < n_recs || sc.bin_off.n < n_off || sc.bin_sum.n < n_sum) {
+            TS_HIP(hipDeviceSynchronize());
+            TS_HIP(sc.bin_recs.reserve(n_recs));
+            TS_HIP(sc.bin_off.reserve(n_off));
+            TS_HIP(sc.bin_sum.reserve(n_sum));
+        }
+        a.recs = sc.bin_recs.p;
+        a.tile_off = sc.bin_off.p;
+        a.tile_sum = sc.bin_sum.p;
+        a.n_tiles = static_cast<int32_t>(n_tiles);
+    }
+    const int rc = threads == 512 ? launch_geometry<512>(tas, a, blocks, cap, out, narrow, binned, stream)
+                                  : launch_geometry<1024>(tas, a, blocks, cap, out, narrow, binned, stream);
     if (rc != TENSILE_OK) return rc;
     if (S > 1) {
         const int fthreads = 256;
