@@ -114,6 +114,30 @@ def test_eval_shapes_and_segments(T, B, segs, monkeypatch):
     check_eval(tas, pl, label=f"T={T}")
 
 
+@pytest.mark.parametrize("threads,binned,T,segs", [(512, 0, 20011, 0), (1024, 0, 4097, 0), (512, 1, 12291, 0),
+                                                    (1024, 1, 20011, 2), (512, 1, 7, 0), (1024, 1, 50001, 3)])
+def test_eval_geometries_and_binning(threads, binned, T, segs, monkeypatch):
+    """Both workgroup geometries on rows they would not get by default, and the binned path (endpoints
+    sorted by tile first) on short and ragged rows, with and without several segments per plan."""
+    monkeypatch.setenv("TENSILE_EVAL_THREADS", str(threads))
+    monkeypatch.setenv("TENSILE_EVAL_BINNED", str(binned))
+    if segs:
+        monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", str(segs))
+    N = max(1, min(400, T // 2))
+    tas = small_random_tas(2000 + T, N=N, T=T, max_acc=4 if T > 8 else 1, base_bytes=11)
+    pl = make_plans(tas, 6, 7, p_swap=0.7)
+    say(f"eval threads={threads} binned={binned} T={T} segs={segs}")
+    check_eval(tas, pl, label=f"threads={threads} binned={binned}")
+
+
+def test_eval_binned_config(configs_small, monkeypatch):
+    monkeypatch.setenv("TENSILE_EVAL_BINNED", "1")
+    tas = configs_small[2]
+    pl = make_config_plans(2, tas, B=64)
+    say("eval binned config 2")
+    check_eval(tas, pl, rows=range(0, 64, 9), label="c2 binned")
+
+
 def test_eval_optional_outputs_and_empty_batches(configs_small):
     tas = configs_small[1]
     h = P.tas_load(tas)
