@@ -98,6 +98,17 @@ void tensile_tas_free(tensile_tas *tas);
 /* Peak and earliest peak step of the unscheduled timeline MF0 (either output may be NULL). */
 int tensile_tas_info(const tensile_tas *tas, int64_t *unscheduled_peak, int32_t *argmax);
 
+/* New operator latencies for a loaded sequence (section IV-E, "Scheduling Plan
+ * Updating": when the measured latencies have drifted, the plan is regenerated
+ * from the corrected sequence).  Latencies do not enter the footprint, so only
+ * what depends on them is rebuilt: cumulative latency, transfer times, every
+ * gap's earliest swap-out step and the swap-candidate index; footprints that were
+ * evaluated before stay valid and can be scored again.  step_ns: HOST [T], all
+ * > 0, or NULL for "no latencies"; link_bytes_per_us > 0 when step_ns is given.
+ * Synchronous (waits for the device first).  The caller must not run any other
+ * call on this handle at the same time. */
+int tensile_tas_update_latencies(tensile_tas *tas, const int64_t *step_ns, int64_t link_bytes_per_us);
+
 /* Copies MF0 into a HOST buffer of T words (synchronous). */
 int tensile_tas_base_timeline(const tensile_tas *tas, int64_t *mf0_host);
 

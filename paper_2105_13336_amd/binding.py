@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libtensile.so")
 TENSILE_OK, TENSILE_E_INVAL, TENSILE_E_RANGE, TENSILE_E_NOMEM, TENSILE_E_HIP, TENSILE_E_CAPACITY = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["tensile_last_error", "tensile_version", "tensile_tas_load", "tensile_tas_free", "tensile_tas_info",
+           "tensile_tas_update_latencies",
            "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_score_candidates", "tensile_score_recompute",
            "tensile_validate_plans",
            "tensile_greedy_plan"]
@@ -140,6 +141,14 @@ def tas_load(tas) -> TasHandle:
 
 def tensile_tas_free(h: TasHandle) -> None:
     h.close()
+
+
+def tensile_tas_update_latencies(h: TasHandle, step_ns, link_bytes_per_us: int = 0) -> None:
+    """New operator latencies (HOST array of T values, or None) and link speed for a loaded sequence."""
+    sn = None if step_ns is None else np.ascontiguousarray(step_ns, dtype=np.int64)
+    if sn is not None and sn.shape[0] != h.T:
+        raise TensileError(TENSILE_E_INVAL, "step_ns must have T entries")
+    _check(_lib.tensile_tas_update_latencies(h.ptr, _hp(sn), ctypes.c_int64(int(link_bytes_per_us))))
 
 
 def tensile_tas_info(h: TasHandle):

@@ -173,7 +173,7 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
                  int32_t *win_in, hipStream_t stream);
 // tas.hip
-int build_times(tensile_tas *tas, const int64_t *d_step_ns);
+int build_times_and_index(tensile_tas *tas, const int64_t *step_ns_host);
 int ensure_recompute_index(const tensile_tas *tas);
 
 }  // namespace tensile

@@ -118,6 +118,21 @@ __global__ void lifetime_intervals_kernel(int32_t N, const int64_t *size, const 
     iv_in[i] = free_step[i] + 1;
 }
 
+int check_latencies(const char *who, int32_t T, int32_t N, const int64_t *step_ns, int64_t link_bytes_per_us) {
+    if (!step_ns) return TENSILE_OK;
+    if (link_bytes_per_us <= 0) {
+        set_error("%s: link_bytes_per_us must be positive when step_ns is given", who);
+        return TENSILE_E_INVAL;
+    }
+    int64_t sum = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        if (step_ns[t] <= 0) { set_error("%s: step_ns[%d] <= 0", who, t); return TENSILE_E_INVAL; }
+        if (__builtin_add_overflow(sum, step_ns[t], &sum)) { set_error("%s: step_ns sums past int64", who); return TENSILE_E_RANGE; }
+    }
+    if (N > 0 && sum > INT64_MAX / 4) { set_error("%s: total latency too large", who); return TENSILE_E_RANGE; }
+    return TENSILE_OK;
+}
+
 int validate_desc(const tensile_tas_desc *d) {
     if (!d) { set_error("tas_load: desc is NULL"); return TENSILE_E_INVAL; }
     if (d->T <= 0) { set_error("tas_load: T = %d must be positive", d->T); return TENSILE_E_INVAL; }
@@ -129,10 +144,6 @@ int validate_desc(const tensile_tas_desc *d) {
         return TENSILE_E_INVAL;
     }
     if (d->base_bytes < 0) { set_error("tas_load: base_bytes is negative"); return TENSILE_E_INVAL; }
-    if (d->step_ns && d->link_bytes_per_us <= 0) {
-        set_error("tas_load: link_bytes_per_us must be positive when step_ns is given");
-        return TENSILE_E_INVAL;
-    }
     if (d->N > 0 && d->access_offsets[0] != 0) { set_error("tas_load: access_offsets[0] != 0"); return TENSILE_E_INVAL; }
     int64_t total = 0;    // the sum of all sizes bounds every footprint: keep it inside int64
     for (int32_t i = 0; i < d->N; ++i) {
@@ -164,15 +175,7 @@ int validate_desc(const tensile_tas_desc *d) {
             return TENSILE_E_RANGE;
         }
     }
-    if (d->step_ns) {
-        int64_t sum = 0;
-        for (int32_t t = 0; t < d->T; ++t) {
-            if (d->step_ns[t] <= 0) { set_error("tas_load: step_ns[%d] <= 0", t); return TENSILE_E_INVAL; }
-            if (__builtin_add_overflow(sum, d->step_ns[t], &sum)) { set_error("tas_load: step_ns sums past int64"); return TENSILE_E_RANGE; }
-        }
-        if (d->N > 0 && sum > INT64_MAX / 4) { set_error("tas_load: total latency too large"); return TENSILE_E_RANGE; }
-    }
-    return TENSILE_OK;
+    return check_latencies("tas_load", d->T, d->N, d->step_ns, d->link_bytes_per_us);
 }
 
 // The unscheduled timeline of the tensors with the given sizes on top of a constant `base`, with the
@@ -402,10 +405,23 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
         if (rc != TENSILE_OK) return rc;
     }
 
-    // ---- C, x, per-gap windows
+    h->h_gp = std::move(gp);
+    h->h_gq = std::move(gq);
+    h->h_gt = std::move(gt);
+    return build_times_and_index(h, d->step_ns);
+}
+
+}  // namespace
+
+// Everything that depends on the operator latencies and the link speed: cumulative latency C,
+// transfer times x, every gap's earliest swap-out step, and the swap-candidate index built from
+// them.  step_ns is a HOST array or null (no latencies: all transfer times 0).
+int build_times_and_index(tensile_tas *h, const int64_t *step_ns) {
+    const int32_t T = h->T, N = h->N;
+    const std::vector<int32_t> &gp = h->h_gp, &gq = h->h_gq, &gt = h->h_gt;
     {
         DevBuf<int64_t> step;
-        if (h->timed) TS_HIP(step.upload(d->step_ns, T));
+        if (h->timed) TS_HIP(step.upload(step_ns, T));
         hipLaunchKernelGGL(cumulative_latency_kernel, dim3(1), dim3(256), 0, 0, T, h->timed ? step.p : nullptr, h->d_C.p);
         if (N > 0)
             hipLaunchKernelGGL(transfer_time_kernel, dim3((N + 255) / 256), dim3(256), 0, 0, N, h->d_size.p,
@@ -424,9 +440,6 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
         if (h->G > 0) TS_HIP(hipMemcpy(gwin.data(), d_gwin.p, gwin.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
         int rc = build_candidate_index(h, h->index, gp, gq, gt, gwin);
         if (rc != TENSILE_OK) return rc;
-        h->h_gp = std::move(gp);
-        h->h_gq = std::move(gq);
-        h->h_gt = std::move(gt);
     }
     h->h_C.resize(static_cast<size_t>(T) + 1);
     h->h_x.resize(static_cast<size_t>(N));
@@ -434,8 +447,6 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
     if (N > 0) TS_HIP(hipMemcpy(h->h_x.data(), h->d_x.p, static_cast<size_t>(N) * sizeof(int64_t), hipMemcpyDeviceToHost));
     return TENSILE_OK;
 }
-
-}  // namespace
 
 // The index of the recomputation candidates: every gap, released right after the access that
 // opens it (o = p).  Built on first use; the handle is otherwise immutable, so concurrent first
@@ -554,6 +565,21 @@ void tensile_tas_free(tensile_tas *tas) {
     if (!tas) return;
     (void)hipDeviceSynchronize();
     delete tas;
+}
+
+int tensile_tas_update_latencies(tensile_tas *tas, const int64_t *step_ns, int64_t link_bytes_per_us) {
+    if (!tas) { set_error("tas_update_latencies: NULL handle"); return TENSILE_E_INVAL; }
+    int rc = check_latencies("tas_update_latencies", tas->T, tas->N, step_ns, link_bytes_per_us);
+    if (rc != TENSILE_OK) return rc;
+    TS_HIP(hipDeviceSynchronize());     // earlier launches may still read the tables replaced below
+    tas->timed = step_ns != nullptr;
+    tas->link_bytes_per_us = tas->timed ? link_bytes_per_us : 0;
+    try {
+        return build_times_and_index(tas, step_ns);
+    } catch (const std::bad_alloc &) {
+        set_error("tas_update_latencies: out of host memory");
+        return TENSILE_E_NOMEM;
+    }
 }
 
 int tensile_tas_info(const tensile_tas *tas, int64_t *unscheduled_peak, int32_t *argmax) {

@@ -264,6 +264,44 @@ def test_score_optional_windows_and_blocking():
     h.close()
 
 
+# -------------------------------------------------------------------- latency updates
+
+def test_update_latencies_rescoring_and_greedy():
+    """After new latencies only the scores, windows and the greedy's choices change; footprints
+    evaluated before stay valid.  Everything must equal what a freshly loaded sequence gives."""
+    import copy
+    tas = small_random_tas(901, N=300, T=3000, max_acc=4, timed=True, link_bytes_per_us=300_000)
+    pl = make_plans(tas, 16, 3, p_swap=0.25)
+    h = P.tas_load(tas)
+    dp = upload(pl)
+    res, peak, arg, mn = gpu_eval(h, dp)
+    say("update latencies")
+    r0, p0, a0, m0 = O.eval_plans(tas, pl)
+    variants = [
+        (prng.randint(5, 1, np.arange(tas.T), 1, 5000).astype(np.int64), 300_000),     # drifted latencies
+        (tas.step_ns, 40_000),                                                           # slower link
+        (None, 0),                                                                        # no latencies at all
+        (tas.step_ns, 300_000),                                                          # back to the start
+    ]
+    for step_ns, link in variants:
+        t2 = copy.copy(tas)
+        t2.step_ns, t2.link_bytes_per_us = step_ns, link
+        P.tensile_tas_update_latencies(h, step_ns, link)
+        sc, wo, wi = gpu_score(h, dp, res, peak, arg)            # footprints from before the update
+        s0, o0, i0 = O.score_plans(t2, pl, r0, p0, a0)
+        assert np.array_equal(sc.cpu().numpy(), s0) and np.array_equal(wo.cpu().numpy(), o0)
+        assert np.array_equal(wi.cpu().numpy(), i0)
+        same_greedy(P.tensile_greedy_plan(h, 0, max_iters=25, capacity=64, recompute=True),
+                    O.greedy(t2, 0, max_iters=25, recompute=True))
+        res2, peak2, arg2, mn2 = gpu_eval(h, dp)
+        assert torch.equal(res2, res) and torch.equal(peak2, peak) and torch.equal(arg2, arg)
+    with pytest.raises(P.TensileError):
+        P.tensile_tas_update_latencies(h, np.zeros(tas.T, dtype=np.int64), 1000)       # latencies must be positive
+    with pytest.raises(P.TensileError):
+        P.tensile_tas_update_latencies(h, tas.step_ns, 0)
+    h.close()
+
+
 # -------------------------------------------------------------------- per-job peaks
 
 def check_per_job(tas, pl, label=""):
