@@ -11,7 +11,10 @@
 // one bucket of its t* (see CandIndex in common.h).  Everything a plan needs
 // beyond its own footprint row and interval list is static, shared by all plans
 // with the same bucket, and read in order; the row is read exactly once, in
-// order, and nothing per plan is kept in global memory.
+// order, and nothing per plan is kept in global memory (except, for rows longer
+// than 131,072 steps, one word per 256 steps).  The recomputation savings
+// (section IV-D) use the same kernel on a second index in which every gap is
+// filed with o = p, and any interval of a tensor cancels its entries.
 //
 // One workgroup walks a plan at a time (persistent workgroups, plans dealt
 // round-robin).  Per plan, with acc[] one word per bucket entry in LDS:
@@ -27,14 +30,16 @@
 //      the values themselves, in a small LDS buffer of its own; the entries whose
 //      o (resp. q) falls inside these 256 steps complete their value from the
 //      buffer and fold it into acc (atomic max).  Entries are met in order because
-//      the bucket is sorted by o, and a second list is sorted by q; the wavefront
-//      takes them up 64 at a time.  The maxima of the 256-step pieces go to a table
+//      the bucket is sorted by o, and a second list is sorted by q; both lists sit
+//      in LDS (reloaded only when the bucket changes) and the wavefront takes them
+//      up 64 at a time.  The maxima of the 256-step pieces go to a table
 //      (LDS), suffix-scanned within the span at the end.  The waves of a workgroup
 //      meet at one barrier after this step; nothing inside it needs one;
 //   4. an entry with o < t* < q and acc != +inf scores
 //      P - max( acc, pieces after q's in its span, spans before o's, spans after q's, P - size ).
-// Buckets with more entries than acc holds are processed in slices, one full
-// pass per slice.
+// Buckets with more entries than acc holds are processed in slices of kMaxLocal
+// entries, one full pass per slice; the index keeps the q order and the
+// wavefronts' start positions per slice.
 #include "common.h"
 #include "wave_ops.h"
 
