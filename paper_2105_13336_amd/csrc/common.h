@@ -105,7 +105,8 @@ struct JobTables {
 // Geometry the scoring kernel shares with the index built at load time (see score.hip).
 constexpr int kScoreThreads = 1024;
 constexpr int kScoreWaves = kScoreThreads / 64;
-constexpr int kScoreMaxLocal = 4096;   // bucket entries one pass handles (a "slice"); larger buckets take several
+constexpr int kScoreMaxLocal = 3072;   // bucket entries one pass handles (a "slice"); larger buckets take several
+constexpr int kScoreStage = 192;       // tensors whose output (16 bytes each) one wavefront composes in LDS at a time
 constexpr int kScoreMini = 256;    // steps one wavefront takes up at a time (4 consecutive steps per lane)
 
 // Candidate index: every gap (p, q) with a feasible earliest swap-out step o, filed under each
@@ -113,22 +114,24 @@ constexpr int kScoreMini = 256;    // steps one wavefront takes up at a time (4 
 // index = e - e0):
 //   cand / cand_size / cand_o   the entries sorted by o; slices are runs of kScoreMaxLocal of them
 //   qord                        per slice, its entries as {q, index within the slice} sorted by q
-//   wave_ptr[2][kScoreWaves+1]  per slice (slices numbered from slice_first[bucket]): first position
-//                               within the slice with o (resp. q) >= w * span, in the two orders
+//   tord                        per slice, its entries as {tensor, index within the slice} sorted by tensor
+//   wave_ptr[3][kScoreWaves+1]  per slice (slices numbered from slice_first[bucket]): first position
+//                               within the slice with o (resp. q, tensor) >= w * span (w * tspan), per order
 //   hash_dir / hash_slots       open-addressing table tensor -> {tensor, p, q, local | last << 31}
 //   filter                      one bit per (tensor mod filter_bits): some entry has this tensor
 struct CandIndex {
     int32_t shift = 0, n_buckets = 0;
     int32_t span = kScoreMini;     // steps per wavefront: ceil(T / kScoreWaves) rounded up to kScoreMini
+    int32_t tspan = kScoreStage;   // tensors per wavefront: ceil(N / kScoreWaves) rounded up to kScoreStage
     int32_t filter_words = 0;      // words per bucket, a power of two
     int32_t max_bucket = 0;        // entries in the largest bucket
     DevBuf<int32_t> bucket_off;    // [n_buckets + 1]
     DevBuf<int4> cand;
     DevBuf<int64_t> cand_size;
     DevBuf<int32_t> cand_o;
-    DevBuf<int2> qord;
+    DevBuf<int2> qord, tord;
     DevBuf<int32_t> slice_first;   // [n_buckets + 1]
-    DevBuf<int32_t> wave_ptr;      // [slices][2][kScoreWaves + 1]
+    DevBuf<int32_t> wave_ptr;      // [slices][3][kScoreWaves + 1]
     DevBuf<int2> hash_dir;         // [n_buckets] {first slot, log2(slots)}
     DevBuf<int4> hash_slots;
     DevBuf<uint32_t> filter;       // [n_buckets][filter_words]

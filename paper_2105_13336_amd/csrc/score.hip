@@ -50,7 +50,7 @@ namespace {
 constexpr int kThreads = kScoreThreads;
 constexpr int kWaves = kScoreWaves;
 constexpr int kMini = kScoreMini;
-constexpr int kMaxLocal = kScoreMaxLocal;   // bucket entries per slice (acc: 32 KB, the two lists: 48 KB)
+constexpr int kMaxLocal = kScoreMaxLocal;   // bucket entries per slice (acc 24 KB, o and q lists 36 KB, tensor order 30 KB)
 constexpr int kDepth = 2;           // blocks of kMini steps in flight per wavefront while streaming
 constexpr int kTabLds = 512;        // pieces of kMini steps whose maxima fit in LDS (T <= 131072)
 constexpr int kFilterWords = 1024;  // largest per-bucket filter (32768 bits)
@@ -61,6 +61,7 @@ typedef long long ll2 __attribute__((ext_vector_type(2)));
 struct ScoreArgs {
     int32_t T, N, B;
     int32_t span;                // steps per wavefront (a multiple of kMini)
+    int32_t tspan;               // tensors per wavefront (a multiple of kScoreStage)
     int32_t n_tab;               // ceil(T / kMini)
     int32_t vec16;               // rows are 16-byte aligned (T even, aligned base)
     int32_t any_interval;        // an interval of the entry's tensor cancels it wherever it lies
@@ -72,7 +73,7 @@ struct ScoreArgs {
     const int4 *cand;
     const int64_t *cand_size;
     const int32_t *cand_o;
-    const int2 *qord;
+    const int2 *qord, *tord;
     const int32_t *slice_first;
     const int32_t *wave_ptr;
     const int2 *hash_dir;
@@ -280,6 +281,9 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
     __shared__ int64_t acc[kMaxLocal];
     __shared__ int32_t lo_list[kMaxLocal];      // o of the slice's entries (its o order is the entries' own order)
     __shared__ int2 hi_list[kMaxLocal];         // {q, index within the slice} sorted by q
+    __shared__ int32_t t_tensor[kMaxLocal];     // tensors of the slice's entries in ascending order ...
+    __shared__ uint16_t t_el[kMaxLocal];        // ... and the entries' indices within the slice
+    __shared__ int32_t q_of[kMaxLocal];         // q of entry el (written per plan, read when the rows are composed)
     __shared__ __attribute__((aligned(16))) SpanBuf span_buf[kWaves];
     __shared__ int64_t tab_lds[kBigT ? 1 : kTabLds];
     __shared__ uint32_t filter[kFilterWords];
@@ -305,13 +309,17 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         int32_t *wout = a.win_out ? a.win_out + static_cast<int64_t>(b) * a.N : nullptr;
         int32_t *win = a.win_in ? a.win_in + static_cast<int64_t>(b) * a.N : nullptr;
 
-        // ---- 1: clear the output rows
-        fill_row<int64_t>(score, a.N, 0, tid);
-        if (wout) fill_row<int32_t>(wout, a.N, -1, tid);
-        if (win) fill_row<int32_t>(win, a.N, -1, tid);
-        if (tstar < 0 || tstar >= a.T) continue;   // not produced by the evaluator: no candidate
-        const int32_t bk = tstar >> a.bucket_shift;
-        const int32_t e0 = a.bucket_off[bk], n_e = a.bucket_off[bk + 1] - e0;
+        // ---- 1: output rows.  A bucket that fits one slice gets its rows composed in LDS and written
+        // once, in step 4; otherwise they are cleared here and the candidates written over them.
+        const bool has_peak = tstar >= 0 && tstar < a.T;     // else not produced by the evaluator: no candidate
+        const int32_t bk = has_peak ? tstar >> a.bucket_shift : 0;
+        const int32_t e0 = a.bucket_off[bk], n_e = has_peak ? a.bucket_off[bk + 1] - e0 : 0;
+        const bool staged = n_e <= kMaxLocal;
+        if (n_e == 0 || !staged) {
+            fill_row<int64_t>(score, a.N, 0, tid);
+            if (wout) fill_row<int32_t>(wout, a.N, -1, tid);
+            if (win) fill_row<int32_t>(win, a.N, -1, tid);
+        }
         if (n_e == 0) continue;                    // no gap around t* can be swapped in time
         const int32_t slice0 = a.slice_first[bk];
         const int2 hd = a.hash_dir[bk];
@@ -323,13 +331,16 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         for (int32_t slice_lo = 0; slice_lo < n_e; slice_lo += kMaxLocal) {
             const int32_t n_slice = min(kMaxLocal, n_e - slice_lo);
             const int32_t slice_id = slice0 + slice_lo / kMaxLocal;
-            const int32_t *wp = a.wave_ptr + static_cast<int64_t>(slice_id) * 2 * (kWaves + 1);
+            const int32_t *wp = a.wave_ptr + static_cast<int64_t>(slice_id) * 3 * (kWaves + 1);
             __syncthreads();   // the previous plan or slice has finished with acc, tab, span_max, the filter, the lists
             for (int32_t k = tid; k < n_slice; k += kThreads) acc[k] = INT64_MIN;
             if (lists_of != slice_id) {
                 for (int32_t k = tid; k < n_slice; k += kThreads) {
                     lo_list[k] = a.cand_o[e0 + slice_lo + k];
                     hi_list[k] = a.qord[e0 + slice_lo + k];
+                    const int2 t = a.tord[e0 + slice_lo + k];
+                    t_tensor[k] = t.x;
+                    t_el[k] = static_cast<uint16_t>(t.y);
                 }
                 lists_of = slice_id;
             }
@@ -411,13 +422,8 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
             PROF_MARK(4);
 
             // ---- 4: scores of the surviving candidates
-            for (int32_t k = tid; k < n_slice; k += kThreads) {
-                const int32_t e = e0 + slice_lo + k;
-                const int4 c = a.cand[e];
-                const int64_t sz = a.cand_size[e];
-                const int64_t v = acc[k];
-                const int32_t q = c.y, o = c.z, i = c.w;
-                if (!(o < tstar && tstar < q) || v == INT64_MAX) continue;
+            auto final_score = [&](const int4 &c, int64_t sz, int64_t v) -> int64_t {
+                const int32_t q = c.y, o = c.z;
                 int32_t w_o = 0, w_q = 0;
 #pragma unroll
                 for (int w = 1; w < kWaves; ++w) {
@@ -432,9 +438,100 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                     const int64_t sm = span_max[w];
                     if (w < w_o || w > w_q) m = max64(m, sm);
                 }
-                score[i] = P - m;
-                if (wout) wout[i] = o;
-                if (win) win[i] = q;
+                return P - m;
+            };
+            if (!staged) {
+                for (int32_t k = tid; k < n_slice; k += kThreads) {
+                    const int32_t e = e0 + slice_lo + k;
+                    const int4 c = a.cand[e];
+                    const int64_t sz = a.cand_size[e];
+                    const int64_t v = acc[k];
+                    if (!(c.z < tstar && tstar < c.y) || v == INT64_MAX) continue;
+                    score[c.w] = final_score(c, sz, v);
+                    if (wout) wout[c.w] = c.z;
+                    if (win) win[c.w] = c.y;
+                }
+            } else {
+                // The scores first, entry by entry (in place: acc becomes the score, or -inf for an entry
+                // without output).  Then every wavefront composes the output of its own range of tensors,
+                // kScoreStage at a time, in its LDS buffer (scores, then the two windows) and writes whole
+                // pieces of the rows, so that each output line goes to memory once.  The entries in tensor
+                // order, their o and q are all in LDS: this part reads nothing from global memory, and no
+                // wait for a load ever holds back the stores queued before it.
+                for (int32_t k = tid; k < n_e; k += kThreads) {
+                    const int4 c = a.cand[e0 + k];
+                    const int64_t sz = a.cand_size[e0 + k];
+                    const int64_t v = acc[k];
+                    acc[k] = (c.z < tstar && tstar < c.y && v != INT64_MAX) ? final_score(c, sz, v) : INT64_MIN;
+                    q_of[k] = c.y;
+                }
+                __syncthreads();
+                int64_t *st_score = reinterpret_cast<int64_t *>(&span_buf[wave]);
+                int32_t *st_wo = reinterpret_cast<int32_t *>(st_score + kScoreStage), *st_wi = st_wo + kScoreStage;
+                int32_t tk = wp[2 * (kWaves + 1) + wave];
+                const bool wide = ((reinterpret_cast<uintptr_t>(score) | reinterpret_cast<uintptr_t>(wout) |
+                                    reinterpret_cast<uintptr_t>(win)) & 15) == 0;
+                const int32_t t_end = min((wave + 1) * a.tspan, a.N);
+                for (int32_t t0 = wave * a.tspan; t0 < t_end; t0 += kScoreStage) {
+                    const int32_t n_t = min(kScoreStage, a.N - t0);
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+#pragma unroll
+                    for (int j = 0; j < 3; ++j) {       // 192 vectors of 16 bytes: 96 of scores (0), 96 of windows (-1)
+                        const int v = j * 64 + lane;
+                        reinterpret_cast<ll2 *>(st_score)[v] = v < kScoreStage / 2 ? ll2{0, 0} : ll2{-1, -1};
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    for (;;) {                                  // (wave-uniform)
+                        const int32_t k = tk + lane;
+                        const int32_t tensor = k < n_e ? t_tensor[k] : INT32_MAX;
+                        const bool take = tensor < t0 + kScoreStage;
+                        if (take) {
+                            const int32_t el = t_el[k];
+                            const int64_t v = acc[el];
+                            if (v != INT64_MIN) {
+                                st_score[tensor - t0] = v;
+                                st_wo[tensor - t0] = lo_list[el];
+                                st_wi[tensor - t0] = q_of[el];
+                            }
+                        }
+                        const int32_t n = __builtin_popcountll(__builtin_amdgcn_ballot_w64(take));
+                        tk += n;
+                        if (n < 64) break;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    if (wide) {
+                        typedef int i4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const int v = j * 64 + lane;            // two scores per vector
+                            if (2 * v + 1 < n_t) reinterpret_cast<ll2 *>(score + t0)[v] = reinterpret_cast<const ll2 *>(st_score)[v];
+                            else if (2 * v < n_t) score[t0 + 2 * v] = st_score[2 * v];
+                        }
+                        if (lane < kScoreStage / 4) {               // four window values per vector
+                            if (4 * lane + 3 < n_t) {
+                                if (wout) reinterpret_cast<i4 *>(wout + t0)[lane] = reinterpret_cast<const i4 *>(st_wo)[lane];
+                                if (win) reinterpret_cast<i4 *>(win + t0)[lane] = reinterpret_cast<const i4 *>(st_wi)[lane];
+                            } else {
+                                for (int32_t k = 4 * lane; k < n_t; ++k) {
+                                    if (wout) wout[t0 + k] = st_wo[k];
+                                    if (win) win[t0 + k] = st_wi[k];
+                                }
+                            }
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < kScoreStage / 64; ++j) {
+                            const int32_t k = j * 64 + lane;
+                            if (k < n_t) {
+                                score[t0 + k] = st_score[k];
+                                if (wout) wout[t0 + k] = st_wo[k];
+                                if (win) win[t0 + k] = st_wi[k];
+                            }
+                        }
+                    }
+                }
             }
             PROF_MARK(5);
         }
@@ -463,6 +560,7 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     ScoreArgs a;
     a.T = tas->T; a.N = tas->N; a.B = plans->B;
     a.span = ix.span;
+    a.tspan = ix.tspan;
     a.n_tab = (tas->T + kMini - 1) / kMini;
     a.vec16 = (tas->T % 2 == 0) && (reinterpret_cast<uintptr_t>(resident) % 16 == 0);
     a.any_interval = any_interval ? 1 : 0;
@@ -471,7 +569,7 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;
     a.bucket_shift = ix.shift; a.filter_words = ix.filter_words;
     a.bucket_off = ix.bucket_off.p;
-    a.cand = ix.cand.p; a.cand_size = ix.cand_size.p; a.cand_o = ix.cand_o.p; a.qord = ix.qord.p;
+    a.cand = ix.cand.p; a.cand_size = ix.cand_size.p; a.cand_o = ix.cand_o.p; a.qord = ix.qord.p; a.tord = ix.tord.p;
     a.slice_first = ix.slice_first.p; a.wave_ptr = ix.wave_ptr.p; a.hash_dir = ix.hash_dir.p; a.hash_slots = ix.hash_slots.p; a.filter = ix.filter.p;
     a.resident = resident; a.peak = peak; a.argmax = argmax;
     a.score = score; a.win_out = win_out; a.win_in = win_in;

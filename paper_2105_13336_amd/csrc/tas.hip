@@ -242,6 +242,7 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
     ix.shift = shift;
     ix.n_buckets = nb;
     ix.span = ((T + kScoreWaves - 1) / kScoreWaves + kScoreMini - 1) / kScoreMini * kScoreMini;
+    ix.tspan = ((h->N + kScoreWaves - 1) / kScoreWaves + kScoreStage - 1) / kScoreStage * kScoreStage;
 
     std::vector<int32_t> off(static_cast<size_t>(nb) + 1, 0);
     for (size_t g = 0; g < G; ++g)
@@ -259,11 +260,11 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
     }
     std::vector<int64_t> cand_size(E);
     std::vector<int32_t> cand_o(E);
-    std::vector<int2> qord(E);
+    std::vector<int2> qord(E), tord(E);
     std::vector<int32_t> slice_first(static_cast<size_t>(nb) + 1, 0);
     for (int32_t b = 0; b < nb; ++b)
         slice_first[b + 1] = slice_first[b] + (off[b + 1] - off[b] + kScoreMaxLocal - 1) / kScoreMaxLocal;
-    std::vector<int32_t> wave_ptr(static_cast<size_t>(slice_first[nb]) * 2 * (kScoreWaves + 1));
+    std::vector<int32_t> wave_ptr(static_cast<size_t>(slice_first[nb]) * 3 * (kScoreWaves + 1));
     std::vector<int2> hash_dir(static_cast<size_t>(nb));
     std::vector<int4> hash_slots;
     std::vector<uint32_t> filter(static_cast<size_t>(nb) * ix.filter_words, 0u);
@@ -287,14 +288,19 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
             std::sort(order.begin(), order.end(),
                       [&](int32_t x, int32_t y) { return c[s0 + x].y != c[s0 + y].y ? c[s0 + x].y < c[s0 + y].y : x < y; });
             for (int32_t k = 0; k < ns; ++k) qord[e0 + s0 + k] = make_int2(c[s0 + order[k]].y, order[k]);
-            int32_t *wp = wave_ptr.data() + static_cast<size_t>(sl) * 2 * (kScoreWaves + 1);
-            int32_t ko = 0, kq = 0;
+            std::sort(order.begin(), order.end(),
+                      [&](int32_t x, int32_t y) { return c[s0 + x].w != c[s0 + y].w ? c[s0 + x].w < c[s0 + y].w : x < y; });
+            for (int32_t k = 0; k < ns; ++k) tord[e0 + s0 + k] = make_int2(c[s0 + order[k]].w, order[k]);
+            int32_t *wp = wave_ptr.data() + static_cast<size_t>(sl) * 3 * (kScoreWaves + 1);
+            int32_t ko = 0, kq = 0, kt = 0;
             for (int w = 0; w <= kScoreWaves; ++w) {
-                const int64_t bound = static_cast<int64_t>(w) * ix.span;
+                const int64_t bound = static_cast<int64_t>(w) * ix.span, tbound = static_cast<int64_t>(w) * ix.tspan;
                 while (ko < ns && c[s0 + ko].z < bound) ++ko;
                 while (kq < ns && qord[e0 + s0 + kq].x < bound) ++kq;
+                while (kt < ns && tord[e0 + s0 + kt].x < tbound) ++kt;
                 wp[w] = w == kScoreWaves ? ns : ko;
                 wp[kScoreWaves + 1 + w] = w == kScoreWaves ? ns : kq;
+                wp[2 * (kScoreWaves + 1) + w] = w == kScoreWaves ? ns : kt;
             }
         }
         // hash table: the entries of one tensor are inserted one after the other, the last flagged
@@ -324,6 +330,7 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
     TS_HIP(ix.cand_size.upload(cand_size.data(), E));
     TS_HIP(ix.cand_o.upload(cand_o.data(), E));
     TS_HIP(ix.qord.upload(qord.data(), E));
+    TS_HIP(ix.tord.upload(tord.data(), E));
     TS_HIP(ix.slice_first.upload(slice_first.data(), slice_first.size()));
     TS_HIP(ix.wave_ptr.upload(wave_ptr.data(), wave_ptr.size()));
     TS_HIP(ix.hash_dir.upload(hash_dir.data(), hash_dir.size()));
