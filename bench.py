@@ -8,7 +8,7 @@ batch, inputs already resident in HBM.  The workload is configuration 3 (four
 jobs merged on one timeline, 16,384 plans), the one the bandwidth target is
 stated for.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu] [--no-greedy] [--no-extras]
 """
 from __future__ import annotations
 
@@ -56,6 +56,7 @@ def main() -> int:
     ap.add_argument("--cpu-plans", type=int, default=4096, help="plans in the oracle's sample (about 10-20 s of CPU work)")
     ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-planner leg")
     ap.add_argument("--eval-only", action="store_true", help="steps run tensile_eval_plans alone (profiling aid)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-job and recomputation rows (profiling aid)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build evaluates plans on ONE GPU (plans are independent; no multi-GPU path is built); "
@@ -141,7 +142,7 @@ def main() -> int:
         },
     }
 
-    if not args.eval_only and tas.J > 1:
+    if not args.eval_only and not args.no_extras and tas.J > 1:
         # per-job peaks and their sum (one pass of the evaluation kernel per job, no rows written)
         jp = torch.empty((int(tas.J), B), dtype=torch.int64, device="cuda")
         tot = torch.empty(B, dtype=torch.int64, device="cuda")
@@ -156,7 +157,7 @@ def main() -> int:
         out["rows"]["eval_plans_per_job"] = {"ms": e0.elapsed_time(e1) / 3, "jobs": int(tas.J)}
         del jp, tot
 
-    if not args.eval_only:
+    if not args.eval_only and not args.no_extras:
         # the recomputation savings of the same batch (second scoring mode; not part of the step)
         P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)       # first call builds its index
         torch.cuda.synchronize()
