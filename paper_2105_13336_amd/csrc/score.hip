@@ -276,7 +276,8 @@ __device__ unsigned long long g_score_prof[8];
 #endif
 
 // kBigT: the table of block maxima does not fit in LDS and lives in global scratch.
-template <bool kBigT>
+// kVec: the footprint rows are 16-byte aligned and T is even (two steps per load).
+template <bool kBigT, bool kVec>
 __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
     __shared__ int64_t acc[kMaxLocal];
     __shared__ int32_t lo_list[kMaxLocal];      // o of the slice's entries (its o order is the entries' own order)
@@ -406,15 +407,11 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                 const int32_t hi_begin = wp[kWaves + 1 + wave], hi_end = wp[kWaves + 1 + wave + 1];
                 int64_t m;
                 if (kBigT)
-                    m = a.vec16 ? stream_span<true>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
-                                                    acc, &span_buf[wave], tab_global, lane)
-                                : stream_span<false>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
-                                                     acc, &span_buf[wave], tab_global, lane);
+                    m = stream_span<kVec>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
+                                          acc, &span_buf[wave], tab_global, lane);
                 else
-                    m = a.vec16 ? stream_span<true>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
-                                                    acc, &span_buf[wave], tab_lds, lane)
-                                : stream_span<false>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
-                                                     acc, &span_buf[wave], tab_lds, lane);
+                    m = stream_span<kVec>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
+                                          acc, &span_buf[wave], tab_lds, lane);
                 if (lane == 0) span_max[wave] = m;
             }
             PROF_MARK(3);
@@ -550,8 +547,8 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     int &per_cu = per_cu_of[big_t ? 1 : 0];
     if (per_cu == 0) {
         int n = 0;
-        if (big_t) TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<true>, kThreads, 0));
-        else TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<false>, kThreads, 0));
+        if (big_t) TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<true, true>, kThreads, 0));
+        else TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<false, true>, kThreads, 0));
         per_cu = n > 0 ? n : 1;
     }
     const int64_t resident_blocks = static_cast<int64_t>(tas->num_cus) * per_cu;
@@ -583,8 +580,13 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
         }
         a.tab_scratch = sc.score_tab.p;
     }
-    if (big_t) hipLaunchKernelGGL(score_kernel<true>, dim3(blocks), dim3(kThreads), 0, stream, a);
-    else hipLaunchKernelGGL(score_kernel<false>, dim3(blocks), dim3(kThreads), 0, stream, a);
+    if (big_t) {
+        if (a.vec16) hipLaunchKernelGGL((score_kernel<true, true>), dim3(blocks), dim3(kThreads), 0, stream, a);
+        else hipLaunchKernelGGL((score_kernel<true, false>), dim3(blocks), dim3(kThreads), 0, stream, a);
+    } else {
+        if (a.vec16) hipLaunchKernelGGL((score_kernel<false, true>), dim3(blocks), dim3(kThreads), 0, stream, a);
+        else hipLaunchKernelGGL((score_kernel<false, false>), dim3(blocks), dim3(kThreads), 0, stream, a);
+    }
     TS_HIP(hipGetLastError());
     return TENSILE_OK;
 }
