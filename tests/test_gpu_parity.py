@@ -130,6 +130,34 @@ def test_eval_geometries_and_binning(threads, binned, T, segs, monkeypatch):
     check_eval(tas, pl, label=f"threads={threads} binned={binned}")
 
 
+@pytest.mark.parametrize("threads,T,B,slots,tail", [(1024, 20011, 23, 3, False), (512, 12291, 40, 7, False), (1024, 4097, 9, 2, False),
+                                                     (512, 7, 33, 4, False), (1024, 8192, 12, 5, False), (512, 20012, 21, 2, True),
+                                                     (1024, 50001, 11, 3, True), (512, 4096, 5, 8, False)])
+def test_eval_persistent_grid(threads, T, B, slots, tail, monkeypatch):
+    """The persistent kernel (several plans per workgroup, the next plan's intervals loaded during the
+    current plan's last tile) with a grid forced small: ragged and whole last tiles, one tile per row,
+    plans without intervals in the middle and at the end of a workgroup's walk, more workgroups than
+    plans, and (tail) plans too long for the registers, which it must leave to the tail kernel."""
+    monkeypatch.setenv("TENSILE_EVAL_THREADS", str(threads))
+    monkeypatch.setenv("TENSILE_EVAL_PERSISTENT", "1")
+    monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", "1")
+    monkeypatch.setenv("TENSILE_EVAL_SLOTS", str(slots))
+    N = max(1, min(400, T // 2))
+    tas = small_random_tas(3000 + T, N=N, T=T, max_acc=4 if T > 8 else 1, base_bytes=13)
+    base = make_plans(tas, B, 9, p_swap=0.7)
+    lists = [[(int(base.iv_tensor[k]), int(base.iv_out[k]), int(base.iv_in[k]), int(base.iv_kind[k]))
+              for k in range(int(base.plan_offsets[b]), int(base.plan_offsets[b + 1]))] for b in range(B)]
+    for b in (1, B // 2, B - 1):
+        lists[b] = []
+    if tail:   # repeat a plan's intervals until they exceed the smallest register capacity (2048)
+        for b in (0, B // 3, B - 2):
+            if lists[b]:
+                lists[b] = (lists[b] * (2100 // len(lists[b]) + 1))[:2100 + b]
+    pl = plans_from_lists(lists)
+    say(f"eval persistent threads={threads} T={T} B={B} slots={slots} tail={tail} K={pl.n_intervals}")
+    check_eval(tas, pl, label=f"persistent threads={threads} T={T}")
+
+
 def test_eval_binned_config(configs_small, monkeypatch):
     monkeypatch.setenv("TENSILE_EVAL_BINNED", "1")
     tas = configs_small[2]
