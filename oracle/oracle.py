@@ -76,6 +76,20 @@ def eval_per_job(tas, plans):
     return jp, ja, jp.sum(axis=0) + int(tas.base_bytes)
 
 
+def link_occupancy(tas, plans, reuse: bool = False, want_rows: bool = True):
+    """-> (link [B,T] int32 or None, peak [B], argmax [B], overbooked [B]): steps of the host link that the
+    plans' transfers occupy (canonical placement, see oracle_link_occupancy)"""
+    B, T = plans.B, tas.T
+    rows = np.empty((B, T), dtype=np.int32) if want_rows else None
+    pk = np.empty(B, dtype=np.int32); arg = np.empty(B, dtype=np.int32); over = np.empty(B, dtype=np.int32)
+    kind = np.ascontiguousarray(plans.iv_kind, dtype=np.uint8)
+    _chk(_lib().oracle_link_occupancy(i32(T), i32(tas.N), _p(tas.size_bytes), _p(tas.step_ns), i64(tas.link_bytes_per_us),
+                                      i64(B), _p(plans.plan_offsets), i64(plans.n_intervals), _p(plans.iv_tensor),
+                                      _p(plans.iv_out), _p(plans.iv_in), _p(kind), i32(1 if reuse else 0),
+                                      _p(rows), _p(pk), _p(arg), _p(over)), "link_occupancy")
+    return rows, pk, arg, over
+
+
 def times(tas):
     """-> (C [T+1], x [N]) cumulative step time and per-tensor transfer time, ns"""
     C = np.empty(tas.T + 1, dtype=np.int64); x = np.empty(tas.N, dtype=np.int64)

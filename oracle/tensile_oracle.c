@@ -196,6 +196,77 @@ int oracle_times(int32_t T, int32_t N, const int64_t *size, const int64_t *step_
     return OR_OK;
 }
 
+/* Occupancy of the host link by the transfers of each plan, step by step (section
+ * IV-C, "Swap Event Scheduling": transfers use the PCIe channel exclusively, so
+ * only one tensor is in flight at a time; a plan respects that iff no step is
+ * occupied twice).  The plan format stores, for a swap (kind 0) of tensor i, only
+ * o (last resident step) and r (step the bytes are back); the transfers are read
+ * in their canonical, shortest form:
+ *   - the swap-out finishes with step o: it occupies the steps s..o for the
+ *     LATEST s with C[o+1] - C[s] >= x_i (step 0 if even that is too short);
+ *   - the swap-in finishes right before step r (section IV-B situation 3): it
+ *     occupies s'..r-1 for the latest s' with C[r] - C[s'] >= x_i (likewise).
+ * Any real placement that ends at the same steps occupies at least these steps.
+ * Recomputation intervals (kind != 0) use no link; without latencies (x == 0)
+ * nothing is occupied.  Inapplicable intervals are skipped as everywhere.
+ * reuse != 0: the copy in host memory stays until the tensor's last access
+ * (section III-C, "Swap Event"), so of several swap-outs of one tensor in a plan
+ * only the earliest (smallest o) transfers anything; every swap-in transfers.
+ * Out, per plan: link[b*T + t] (may be NULL), peak[b] = max_t, argmax[b] = earliest
+ * step of the maximum, overbooked[b] = number of steps occupied more than once. */
+int oracle_link_occupancy(int32_t T, int32_t N, const int64_t *size, const int64_t *step_ns, int64_t link_bytes_per_us,
+                          int64_t B, const int64_t *plan_offsets, int64_t n_intervals, const int32_t *iv_tensor,
+                          const int32_t *iv_out, const int32_t *iv_in, const uint8_t *iv_kind, int32_t reuse,
+                          int32_t *link, int32_t *peak, int32_t *argmax, int32_t *overbooked) {
+    if (T <= 0 || N < 0 || B < 0) return OR_E_INVAL;
+    int64_t *C = (int64_t *)malloc(((size_t)T + 1) * sizeof(int64_t));
+    int64_t *x = (int64_t *)malloc(((size_t)N + 1) * sizeof(int64_t));
+    int32_t *L = (int32_t *)malloc((size_t)T * sizeof(int32_t));
+    int32_t *first_o = (int32_t *)malloc(((size_t)N + 1) * sizeof(int32_t));
+    int rc = OR_E_NOMEM;
+    if (!C || !x || !L || !first_o) goto done;
+    if ((rc = oracle_times(T, N, size, step_ns, link_bytes_per_us, C, x)) != OR_OK) goto done;
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t k0, k1;
+        plan_range(plan_offsets, b, n_intervals, &k0, &k1);
+        for (int32_t t = 0; t < T; ++t) L[t] = 0;
+        for (int32_t i = 0; i < N; ++i) first_o[i] = INT32_MAX;
+        for (int64_t k = k0; k < k1; ++k) {
+            int32_t i = iv_tensor[k], o = iv_out[k], r = iv_in[k];
+            if (!interval_applies(N, T, i, o, r) || iv_kind[k] != 0) continue;
+            if (o < first_o[i]) first_o[i] = o;
+        }
+        for (int64_t k = k0; k < k1; ++k) {
+            int32_t i = iv_tensor[k], o = iv_out[k], r = iv_in[k];
+            if (!interval_applies(N, T, i, o, r) || iv_kind[k] != 0 || x[i] == 0) continue;
+            if (!reuse || o == first_o[i]) {
+                int32_t s = o;                                   /* walk back until the run is long enough */
+                while (s > 0 && C[o + 1] - C[s] < x[i]) --s;
+                for (int32_t t = s; t <= o; ++t) ++L[t];
+            }
+            int32_t s = r - 1;
+            while (s > 0 && C[r] - C[s] < x[i]) --s;
+            for (int32_t t = s; t <= r - 1; ++t) ++L[t];
+        }
+        int32_t mx = L[0], arg = 0, over = 0;
+        for (int32_t t = 0; t < T; ++t) {
+            if (L[t] > mx) {
+                mx = L[t];
+                arg = t;
+            }
+            if (L[t] >= 2) ++over;
+            if (link) link[b * (int64_t)T + t] = L[t];
+        }
+        peak[b] = mx;
+        if (argmax) argmax[b] = arg;
+        if (overbooked) overbooked[b] = over;
+    }
+    rc = OR_OK;
+done:
+    free(C); free(x); free(L); free(first_o);
+    return rc;
+}
+
 /* Candidate score of every tensor for ONE plan whose footprint MF, peak P and
  * peak time tstar are given (section IV-C: the candidates are the tensors that
  * are in GPU memory at the peak, MPTensor of Alg. 1; the paper ranks them by
