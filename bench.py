@@ -171,6 +171,27 @@ def main() -> int:
         P.tensile_score_candidates(h, dp, res, peak, arg, sc, wo, wi)      # the outputs the checks below expect
         torch.cuda.synchronize()
 
+    if not args.eval_only and not args.no_extras and tas.step_ns is not None:
+        # occupancy of the host link by the same batch's transfers (second evaluated channel; not part of the step)
+        lrows = torch.empty((B, T), dtype=torch.int32, device="cuda")
+        lpk = torch.empty(B, dtype=torch.int32, device="cuda")
+        larg = torch.empty(B, dtype=torch.int32, device="cuda")
+        lover = torch.empty(B, dtype=torch.int32, device="cuda")
+        link_ms = {}
+        for name, rows_out in (("rows", lrows), ("peaks_only", None)):
+            P.tensile_eval_link(h, dp, lpk, rows_out, larg, lover)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                P.tensile_eval_link(h, dp, lpk, rows_out, larg, lover)
+            e1.record()
+            torch.cuda.synchronize()
+            link_ms[name] = e0.elapsed_time(e1) / 3
+        out["rows"]["eval_link"] = {"ms": link_ms["rows"], "ms_peaks_only": link_ms["peaks_only"],
+                                    "max_link_peak": int(lpk.max()), "plans_within_one": int((lpk <= 1).sum())}
+        del lrows, lpk, larg, lover
+
     if not args.no_greedy:
         iters = 48
         torch.cuda.synchronize()

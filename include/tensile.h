@@ -201,6 +201,30 @@ int tensile_score_recompute(const tensile_tas *tas, const tensile_plans *plans, 
  * 2 = not inside one gap, 3 = second interval in a gap, 4 = bad plan_offsets. */
 int tensile_validate_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *first_bad, int32_t *reason);
 
+/* Occupancy of the host link by the transfers of each plan (section IV-C, "Swap
+ * Event Scheduling": a transfer occupies the PCIe channel exclusively, only one
+ * tensor can be on its way at a time).  A swap interval (i, o, r) of a timed
+ * sequence is read as two transfers of x_i ns in their shortest form: the
+ * swap-out ends with step o and occupies s..o for the latest s with
+ * C[o+1] - C[s] >= x_i, the swap-in ends right before step r and occupies
+ * s'..r-1 for the latest s' with C[r] - C[s'] >= x_i (C = cumulative step
+ * latency; from step 0 if the past is too short).  Any real placement that ends
+ * at the same steps occupies at least these steps, so link_peak[b] <= 1 is
+ * necessary for plan b to respect the exclusive channel, and sufficient for the
+ * placement of tensile_greedy_plan, whose plans always satisfy it.
+ * Recomputation intervals (kind 1) and sequences without latencies occupy nothing.
+ *   reuse_host_copies  non-zero: the copy in host memory stays until the tensor's
+ *                last access (section III-C, "Swap Event"), so of several swap-outs
+ *                of one tensor in a plan only the earliest (smallest o) transfers
+ *   link         DEVICE [B*T] int32 row-major: transfers on the link at step t; may be NULL
+ *   link_peak    DEVICE [B]   max_t link_b[t]
+ *   link_argmax  DEVICE [B]   earliest step of the maximum; may be NULL
+ *   overbooked   DEVICE [B]   number of steps with link_b[t] >= 2; may be NULL
+ * Inapplicable intervals are skipped as in tensile_eval_plans.
+ * Asynchronous on hip_stream.  B == 0 is a no-op. */
+int tensile_eval_link(const tensile_tas *tas, const tensile_plans *plans, int32_t reuse_host_copies, int32_t *link,
+                      int32_t *link_peak, int32_t *link_argmax, int32_t *overbooked, void *hip_stream);
+
 /* --------------------------------------------------------------- greedy */
 
 /* Hyper-parameters of the complete scheduling algorithm (Alg. 3). */

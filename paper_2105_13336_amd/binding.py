@@ -21,7 +21,7 @@ TENSILE_OK, TENSILE_E_INVAL, TENSILE_E_RANGE, TENSILE_E_NOMEM, TENSILE_E_HIP, TE
 
 EXPORTS = ["tensile_last_error", "tensile_version", "tensile_tas_load", "tensile_tas_free", "tensile_tas_info",
            "tensile_tas_update_latencies",
-           "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_score_candidates", "tensile_score_recompute",
+           "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_eval_link", "tensile_score_candidates", "tensile_score_recompute",
            "tensile_validate_plans",
            "tensile_greedy_plan"]
 
@@ -203,6 +203,18 @@ def tensile_eval_plans_per_job(h: TasHandle, plans: DevicePlans, job_peak: torch
     _check(_lib.tensile_eval_plans_per_job(h.ptr, ctypes.byref(st), _dp(job_peak, torch.int64, J * B, "job_peak"),
                                            _dp(job_argmax, torch.int32, J * B, "job_argmax"),
                                            _dp(sum_peak, torch.int64, B, "sum_peak"), _stream(stream)))
+
+
+def tensile_eval_link(h: TasHandle, plans: DevicePlans, link_peak: torch.Tensor, link: Optional[torch.Tensor] = None,
+                      link_argmax: Optional[torch.Tensor] = None, overbooked: Optional[torch.Tensor] = None,
+                      reuse_host_copies: bool = False, stream=None) -> None:
+    """link: [B, T] int32, link_peak / link_argmax / overbooked: [B] int32"""
+    B = plans.B
+    st = plans.struct()
+    _check(_lib.tensile_eval_link(h.ptr, ctypes.byref(st), ctypes.c_int32(1 if reuse_host_copies else 0),
+                                  _dp(link, torch.int32, B * h.T, "link"), _dp(link_peak, torch.int32, B, "link_peak"),
+                                  _dp(link_argmax, torch.int32, B, "link_argmax"), _dp(overbooked, torch.int32, B, "overbooked"),
+                                  _stream(stream)))
 
 
 def tensile_score_candidates(h: TasHandle, plans: DevicePlans, resident: torch.Tensor, peak: torch.Tensor,

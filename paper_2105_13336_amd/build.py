@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libtensile.so")
-SOURCES = ["tas.hip", "eval.hip", "score.hip", "greedy.hip"]
+SOURCES = ["tas.hip", "eval.hip", "score.hip", "greedy.hip", "link.hip"]
 
 
 def build_library(verbose: bool = False) -> str:

@@ -92,6 +92,8 @@ struct Scratch {
     DevBuf<int2> bin_recs;         // eval, binned mode: see EvalArgs
     DevBuf<int32_t> bin_off;
     DevBuf<int64_t> bin_sum;
+    DevBuf<int32_t> link_first;    // link: earliest swap-out step per tensor, one row per workgroup (INT32_MAX between plans)
+    DevBuf<int32_t> link_acc;      // link: one row per workgroup where the passes of a long plan add up
 };
 
 // Per-job tables of tensile_eval_plans_per_job (see tas.hip), job-major.
@@ -175,6 +177,9 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
 int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
                  int32_t *win_in, hipStream_t stream);
+// link.hip
+int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak, int32_t *argmax,
+                int32_t *overbooked, hipStream_t stream);
 // tas.hip
 int build_times_and_index(tensile_tas *tas, const int64_t *step_ns_host);
 int ensure_recompute_index(const tensile_tas *tas);

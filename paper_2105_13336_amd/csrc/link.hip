@@ -1,0 +1,372 @@
+// Occupancy of the host link by the transfers of each plan (section IV-C of the paper, "Swap Event
+// Scheduling": data transfers use the PCIe channel exclusively, so only one tensor can be on its way
+// at a time; a plan respects that iff no step of its occupancy timeline exceeds one).
+//
+// A plan stores, for a swap of tensor i, the last resident step o and the step r at which the bytes
+// are back.  The transfers are taken in their shortest form: the swap-out ends with step o and
+// occupies s..o for the latest s with C[o+1] - C[s] >= x_i, the swap-in ends right before step r and
+// occupies s'..r-1 for the latest s' with C[r] - C[s'] >= x_i (C = cumulative operator latency, x_i =
+// transfer time; step 0 if the past is too short).  Recomputation intervals use no link.  With host
+// copy reuse (section III-C: the copy in host memory stays until the tensor's last access) only the
+// earliest swap-out of a tensor within a plan transfers anything.
+//
+// One persistent workgroup of 1024 threads per CU walks the plans slot, slot + grid, ...:
+//  * the start step of a transfer is a search in C: first in a table of every stride-th value kept in
+//    LDS for the whole launch (at most 2048 entries), then a few probes of C itself (L2 resident);
+//  * the four endpoints of an interval (+1 at s, -1 at o+1, +1 at s', -1 at r) stay in registers, six
+//    intervals per thread; a longer plan takes several passes of 6144 intervals, each over all tiles,
+//    and the passes add up in the output row (or in a scratch row per workgroup when no rows are
+//    wanted): occupancy is additive over the intervals;
+//  * per tile of 8192 steps: scatter into an int32 difference tile in LDS, barrier, each lane scans its
+//    8 cells (and zeroes them for the next tile), DPP wave scan, wave totals through LDS, barrier,
+//    reduce (max, earliest argmax, steps occupied twice), and the row leaves through a per-wavefront
+//    staging area as 16 contiguous bytes per lane;
+//  * reuse: a table of the earliest swap-out step per tensor (one row of N entries per workgroup in
+//    global memory, L2 atomics) is filled before a plan's first pass and cleaned after its last.
+#include "common.h"
+#include "wave_ops.h"
+
+namespace tensile {
+
+namespace {
+
+constexpr int kThr = 1024, kWaves = kThr / 64;
+constexpr int kVpt = 8;                              // steps per lane per tile
+constexpr int kTile = kThr * kVpt;                   // 8192
+constexpr int kR = 6;                                // intervals per thread and pass
+constexpr int kPass = kR * kThr;                     // 6144
+constexpr int kTabMax = 2048;                        // entries of the coarse table of C
+// LDS layouts are skewed by one 16-byte granule per 16 granules (cell u lives at u + 4 * (u >> 6)): both
+// the lane-contiguous pattern (8 cells per lane) and the striped one (one granule per lane) are then
+// free of bank conflicts.  A lane's two granules never straddle a multiple of 16.
+constexpr int kTileCells = kTile + 4 * (kTile >> 6);
+constexpr int kStageCells = 64 * kVpt + 4 * ((64 * kVpt) >> 6);   // 544 per wavefront
+__device__ __forceinline__ uint32_t skew(uint32_t u) { return u + ((u >> 6) << 2); }
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+struct LinkArgs {
+    int32_t T, N, B;
+    int32_t reuse;
+    int64_t n_intervals;
+    const int64_t *plan_offsets;
+    const int32_t *iv_tensor, *iv_out, *iv_in;
+    const uint8_t *iv_kind;        // may be null: every interval is a swap
+    const int64_t *C;              // [T+1]
+    const int64_t *x;              // [N]
+    int32_t tab_stride, n_tab;     // coarse table: C[k * tab_stride], k < n_tab
+    int32_t *first_out;            // [grid][N], INT32_MAX everywhere between plans (reuse only)
+    int32_t *acc_rows;             // [grid][T] scratch rows for plans of several passes when link == null
+    int32_t *link;                 // [B*T] or null
+    int32_t *peak, *argmax, *overbooked;   // [B]; the last two may be null
+};
+
+// inclusive add-scan over the 64 lanes (32-bit)
+__device__ __forceinline__ int32_t wave_scan_add32(int32_t x) {
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, true);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, true);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, true);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, true);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, true);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, true);
+    return x;
+}
+
+__global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
+    __shared__ __attribute__((aligned(16))) int32_t delta[kTileCells + 64];   // the tile, then 64 "trash" cells
+    __shared__ __attribute__((aligned(16))) int32_t stage_all[kWaves * kStageCells];
+    __shared__ int64_t tab[kTabMax];
+    __shared__ int32_t wave_tot[kWaves];
+    __shared__ int32_t red_mx[kWaves], red_arg[kWaves], red_over[kWaves];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int my = tid * kVpt;
+    const int my_cell = static_cast<int>(skew(my));
+    int32_t *stage = stage_all + wave * kStageCells;
+
+    for (int k = tid; k < a.n_tab; k += kThr) tab[k] = a.C[static_cast<int64_t>(k) * a.tab_stride];
+    for (int u = tid; u < kTileCells + 64; u += kThr) delta[u] = 0;
+    __syncthreads();
+
+    // the latest step s in [0, hi) with C[hi] - C[s] >= x, or 0 if there is none (x > 0; C increases strictly)
+    auto start_step = [&](int32_t hi, int64_t x) -> int32_t {
+        const int64_t v = a.C[hi] - x;
+        if (v < 0) return 0;
+        // coarse: the last table entry <= v (entry 0 is C[0] = 0 <= v)
+        int32_t lo_k = 0, hi_k = a.n_tab;                 // invariant: tab[lo_k] <= v, tab[hi_k] > v (or hi_k == n_tab)
+        while (hi_k - lo_k > 1) {
+            const int32_t mid = (lo_k + hi_k) >> 1;
+            if (tab[mid] <= v) lo_k = mid;
+            else hi_k = mid;
+        }
+        int32_t lo_s = lo_k * a.tab_stride;               // C[lo_s] <= v
+        int32_t hi_s = lo_s + a.tab_stride;               // C[hi_s] > v, or hi_s beyond the table's reach
+        if (hi_s > hi) hi_s = hi;                         // C[hi] > v
+        while (hi_s - lo_s > 1) {
+            const int32_t mid = (lo_s + hi_s) >> 1;
+            if (a.C[mid] <= v) lo_s = mid;
+            else hi_s = mid;
+        }
+        return lo_s;
+    };
+
+    int32_t *first_out = a.reuse ? a.first_out + static_cast<int64_t>(blockIdx.x) * a.N : nullptr;
+
+    for (int64_t plan = blockIdx.x; plan < a.B; plan += gridDim.x) {
+        int64_t k0 = a.plan_offsets[plan], k1 = a.plan_offsets[plan + 1];
+        if (k0 < 0) k0 = 0;
+        if (k1 > a.n_intervals) k1 = a.n_intervals;
+        if (k1 < k0) k1 = k0;
+        auto swap_at = [&](int64_t k, int32_t &i, int32_t &o, int32_t &r) {   // an applicable swap interval?
+            i = a.iv_tensor[k];
+            o = a.iv_out[k];
+            r = a.iv_in[k];
+            const bool kind0 = a.iv_kind ? a.iv_kind[k] == 0 : true;
+            return kind0 && static_cast<uint32_t>(i) < static_cast<uint32_t>(a.N) && o >= 0 && r <= a.T && r > o;
+        };
+        if (a.reuse) {   // the earliest swap-out step of every tensor of the plan
+            for (int64_t k = k0 + tid; k < k1; k += kThr) {
+                int32_t i, o, r;
+                if (swap_at(k, i, o, r)) atomicMin(&first_out[i], o);
+            }
+            __threadfence();   // the minima are in L2 before anyone reads them
+            __syncthreads();
+        }
+        const int64_t n_pass = k1 > k0 ? (k1 - k0 + kPass - 1) / kPass : 1;
+        int32_t *row = a.link ? a.link + plan * a.T : nullptr;
+        // where the passes add up: the output row, else this workgroup's scratch row
+        int32_t *acc = row ? row : (n_pass > 1 ? a.acc_rows + static_cast<int64_t>(blockIdx.x) * a.T : nullptr);
+        int32_t best_mx = -1, best_arg = 0, over = 0;
+
+        for (int64_t pass = 0; pass < n_pass; ++pass) {
+            const bool first = pass == 0, last = pass == n_pass - 1;
+            // ---- this pass's intervals: endpoints in the skewed numbering, UINT32_MAX = none
+            uint32_t e[kR][4];
+            int32_t lo_t = INT32_MAX, hi_t = -1;
+            const int64_t kb = k0 + pass * kPass;
+#pragma unroll
+            for (int j = 0; j < kR; ++j) {
+                const int64_t k = kb + static_cast<int64_t>(tid) * kR + j;
+                e[j][0] = e[j][1] = e[j][2] = e[j][3] = UINT32_MAX;
+                int32_t i, o, r;
+                if (k < k1 && swap_at(k, i, o, r)) {
+                    const int64_t x = a.x[i];
+                    if (x > 0) {
+                        bool charged = true;
+                        if (a.reuse) charged = __hip_atomic_load(&first_out[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == o;
+                        if (charged) {
+                            const int32_t s = start_step(o + 1, x);
+                            e[j][0] = skew(static_cast<uint32_t>(s));
+                            e[j][1] = skew(static_cast<uint32_t>(o + 1));
+                            lo_t = s < lo_t ? s : lo_t;
+                        }
+                        const int32_t s2 = start_step(r, x);
+                        e[j][2] = skew(static_cast<uint32_t>(s2));
+                        e[j][3] = skew(static_cast<uint32_t>(r));
+                        lo_t = s2 < lo_t ? s2 : lo_t;
+                        hi_t = r > hi_t ? r : hi_t;
+                    }
+                }
+            }
+
+            int32_t carry = 0;
+            for (int32_t tile_lo = 0; tile_lo < a.T; tile_lo += kTile) {
+                const int32_t tile_hi = a.T - tile_lo < kTile ? a.T : tile_lo + kTile;
+                const uint32_t tile_n = static_cast<uint32_t>(tile_hi - tile_lo);
+                // ---- scatter (a wavefront none of whose lanes has an endpoint in range skips it)
+                const bool mine = hi_t >= tile_lo && lo_t < tile_hi;
+                if (__builtin_amdgcn_ballot_w64(mine) != 0) {
+                    const uint32_t base_cell = skew(static_cast<uint32_t>(tile_lo)), n_cell = skew(tile_n);
+                    const uint32_t trash = kTileCells + lane;
+#pragma unroll
+                    for (int j = 0; j < kR; ++j) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const uint32_t u = e[j][q] - base_cell;
+                            atomicAdd(&delta[u < n_cell ? u : trash], (q & 1) ? -1 : 1);
+                        }
+                    }
+                }
+                __syncthreads();
+                // ---- this lane's 8 cells: read, clear for the next tile, local scan, wave scan
+                int32_t v[kVpt];
+                {
+                    i32x4 *cell = reinterpret_cast<i32x4 *>(&delta[my_cell]);
+                    const i32x4 c0 = cell[0], c1 = cell[1];
+                    cell[0] = i32x4{0, 0, 0, 0};
+                    cell[1] = i32x4{0, 0, 0, 0};
+                    v[0] = c0[0]; v[1] = c0[1]; v[2] = c0[2]; v[3] = c0[3];
+                    v[4] = c1[0]; v[5] = c1[1]; v[6] = c1[2]; v[7] = c1[3];
+                }
+#pragma unroll
+                for (int j = 1; j < kVpt; ++j) v[j] += v[j - 1];
+                const int32_t incl = wave_scan_add32(v[kVpt - 1]);
+                if (lane == 63) wave_tot[wave] = incl;
+                __syncthreads();
+                int32_t before = 0, total = 0;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    const int32_t t = wave_tot[w];
+                    before += w < wave ? t : 0;
+                    total += t;
+                }
+                const int32_t base = carry + before + incl - v[kVpt - 1];
+                carry += total;
+#pragma unroll
+                for (int j = 0; j < kVpt; ++j) v[j] += base;
+                const int32_t t0 = tile_lo + my;
+                // ---- earlier passes of a long plan
+                if (!first) {
+#pragma unroll
+                    for (int j = 0; j < kVpt; ++j)
+                        if (t0 + j < tile_hi) v[j] += __hip_atomic_load(&acc[t0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (!last) {
+#pragma unroll
+                    for (int j = 0; j < kVpt; ++j)
+                        if (t0 + j < tile_hi) __hip_atomic_store(&acc[t0 + j], v[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    continue;   // (block-uniform; the next pass reads these sums back in the same lanes)
+                }
+                // ---- reduce
+#pragma unroll
+                for (int j = 0; j < kVpt; ++j) {
+                    if (t0 + j < tile_hi) {
+                        if (v[j] > best_mx) {
+                            best_mx = v[j];
+                            best_arg = t0 + j;
+                        }
+                        over += v[j] >= 2 ? 1 : 0;
+                    }
+                }
+                // ---- the row: through the wavefront's staging area, 16 contiguous bytes per lane
+                if (row) {
+                    __builtin_amdgcn_wave_barrier();
+                    i32x4 *mine_out = reinterpret_cast<i32x4 *>(stage + 8 * lane + 4 * (lane >> 3));
+                    mine_out[0] = i32x4{v[0], v[1], v[2], v[3]};
+                    mine_out[1] = i32x4{v[4], v[5], v[6], v[7]};
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    const int32_t wave_t0 = tile_lo + wave * (64 * kVpt);
+                    const bool wide = (reinterpret_cast<uintptr_t>(row + wave_t0) & 15) == 0 && wave_t0 + 64 * kVpt <= tile_hi;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const i32x4 xv = (reinterpret_cast<const i32x4 *>(stage) + lane + (lane >> 4))[68 * j];
+                        const int32_t t = wave_t0 + 4 * (j * 64 + lane);
+                        if (wide) {
+                            *reinterpret_cast<i32x4 *>(row + t) = xv;
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (t + q < tile_hi) row[t + q] = xv[q];
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+
+        // ---- the plan's result
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const int32_t omx = __shfl_xor(best_mx, d, 64), oarg = __shfl_xor(best_arg, d, 64);
+            over += __shfl_xor(over, d, 64);
+            if (omx > best_mx || (omx == best_mx && oarg < best_arg)) {
+                best_mx = omx;
+                best_arg = oarg;
+            }
+        }
+        if (lane == 0) {
+            red_mx[wave] = best_mx;
+            red_arg[wave] = best_arg;
+            red_over[wave] = over;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int32_t mx = red_mx[0], arg = red_arg[0], ov = red_over[0];
+            for (int w = 1; w < kWaves; ++w) {
+                if (red_mx[w] > mx || (red_mx[w] == mx && red_arg[w] < arg)) {
+                    mx = red_mx[w];
+                    arg = red_arg[w];
+                }
+                ov += red_over[w];
+            }
+            a.peak[plan] = mx;
+            if (a.argmax) a.argmax[plan] = arg;
+            if (a.overbooked) a.overbooked[plan] = ov;
+        }
+        if (a.reuse) {   // leave the table as it was found
+            for (int64_t k = k0 + tid; k < k1; k += kThr) {
+                int32_t i, o, r;
+                if (swap_at(k, i, o, r)) __hip_atomic_store(&first_out[i], INT32_MAX, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __threadfence();   // ... before the next plan's minima arrive
+        }
+        __syncthreads();   // red_* and the table are reused by the next plan
+    }
+}
+
+// Without latencies nothing is transferred in measurable time: every output is zero.
+__global__ void link_zero_kernel(int64_t n_rows, int32_t *link, int32_t B, int32_t *peak, int32_t *argmax, int32_t *overbooked) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t k = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; k < n_rows; k += stride) link[k] = 0;
+    for (int64_t k = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; k < B; k += stride) {
+        peak[k] = 0;
+        if (argmax) argmax[k] = 0;
+        if (overbooked) overbooked[k] = 0;
+    }
+}
+
+__global__ void link_fill_kernel(int32_t *p, int64_t n, int32_t v) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t k = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; k < n; k += stride) p[k] = v;
+}
+
+}  // namespace
+
+int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak, int32_t *argmax,
+                int32_t *overbooked, hipStream_t stream) {
+    const int32_t B = plans->B, T = tas->T;
+    if (B == 0) return TENSILE_OK;
+    if (!tas->timed || tas->N == 0) {
+        const int64_t n_rows = link ? static_cast<int64_t>(B) * T : 0;
+        hipLaunchKernelGGL(link_zero_kernel, dim3(tas->num_cus * 4), dim3(256), 0, stream, n_rows, link, B, peak, argmax, overbooked);
+        TS_HIP(hipGetLastError());
+        return TENSILE_OK;
+    }
+    LinkArgs a{};
+    a.T = T; a.N = tas->N; a.B = B; a.reuse = reuse ? 1 : 0;
+    a.n_intervals = plans->n_intervals;
+    a.plan_offsets = plans->plan_offsets;
+    a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in; a.iv_kind = plans->iv_kind;
+    a.C = tas->d_C.p; a.x = tas->d_x.p;
+    a.tab_stride = static_cast<int32_t>((static_cast<int64_t>(T) + kTabMax) / kTabMax);   // ceil((T + 1) / kTabMax)
+    a.n_tab = static_cast<int32_t>(static_cast<int64_t>(T) / a.tab_stride + 1);           // entries k with k * stride <= T
+    const int32_t grid = B < tas->num_cus ? B : tas->num_cus;
+    Scratch &sc = tas->scratch;
+    if (reuse) {
+        const size_t need = static_cast<size_t>(grid) * static_cast<size_t>(tas->N);
+        if (sc.link_first.n < need) {
+            TS_HIP(hipDeviceSynchronize());   // an earlier launch may still use the old table
+            TS_HIP(sc.link_first.reserve(need));
+            hipLaunchKernelGGL(link_fill_kernel, dim3(tas->num_cus * 4), dim3(256), 0, stream, sc.link_first.p,
+                               static_cast<int64_t>(sc.link_first.n), INT32_MAX);
+            TS_HIP(hipGetLastError());
+        }
+        a.first_out = sc.link_first.p;
+    }
+    if (!link && plans->n_intervals > kPass) {   // some plan may need several passes
+        const size_t need = static_cast<size_t>(grid) * static_cast<size_t>(T);
+        if (sc.link_acc.n < need) {
+            TS_HIP(hipDeviceSynchronize());
+            TS_HIP(sc.link_acc.reserve(need));
+        }
+        a.acc_rows = sc.link_acc.p;
+    }
+    a.link = link; a.peak = peak; a.argmax = argmax; a.overbooked = overbooked;
+    hipLaunchKernelGGL(link_kernel, dim3(grid), dim3(kThr), 0, stream, a);
+    TS_HIP(hipGetLastError());
+    return TENSILE_OK;
+}
+
+}  // namespace tensile

@@ -659,6 +659,16 @@ int tensile_eval_plans_per_job(const tensile_tas *tas, const tensile_plans *plan
     return TENSILE_OK;
 }
 
+int tensile_eval_link(const tensile_tas *tas, const tensile_plans *plans, int32_t reuse_host_copies, int32_t *link,
+                      int32_t *link_peak, int32_t *link_argmax, int32_t *overbooked, void *hip_stream) {
+    int rc = check_plans(tas, plans, "eval_link");
+    if (rc != TENSILE_OK) return rc;
+    if (plans->B == 0) return TENSILE_OK;
+    if (!link_peak) { set_error("eval_link: link_peak is required"); return TENSILE_E_INVAL; }
+    return launch_link(tas, plans, reuse_host_copies != 0, link, link_peak, link_argmax, overbooked,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
 int tensile_score_candidates(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident,
                              const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
                              int32_t *win_in, void *hip_stream) {

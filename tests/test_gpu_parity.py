@@ -158,6 +158,113 @@ def test_eval_persistent_grid(threads, T, B, slots, tail, monkeypatch):
     check_eval(tas, pl, label=f"persistent threads={threads} T={T}")
 
 
+# ---- link occupancy -----------------------------------------------------------------------
+
+def gpu_link(h, dp, reuse=False, want_rows=True, want_all=True):
+    B = dp.B
+    rows = torch.full((B, h.T), -7, dtype=torch.int32, device="cuda") if want_rows else None
+    pk = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    arg = torch.full((B,), -7, dtype=torch.int32, device="cuda") if want_all else None
+    over = torch.full((B,), -7, dtype=torch.int32, device="cuda") if want_all else None
+    P.tensile_eval_link(h, dp, pk, rows, arg, over, reuse_host_copies=reuse)
+    torch.cuda.synchronize()
+    return rows, pk, arg, over
+
+
+def check_link(tas, pl, reuse, h=None, label=""):
+    own = h is None
+    h = h or P.tas_load(tas)
+    dp = upload(pl)
+    rows, pk, arg, over = gpu_link(h, dp, reuse)
+    r0, p0, a0, o0 = O.link_occupancy(tas, pl, reuse=reuse)
+    assert np.array_equal(pk.cpu().numpy(), p0), label + " peak"
+    assert np.array_equal(arg.cpu().numpy(), a0), label + " argmax"
+    assert np.array_equal(over.cpu().numpy(), o0), label + " overbooked"
+    assert np.array_equal(rows.cpu().numpy(), r0), label + " rows"
+    # peaks only (no rows, no optional outputs)
+    _, pk2, _, _ = gpu_link(h, dp, reuse, want_rows=False, want_all=False)
+    assert np.array_equal(pk2.cpu().numpy(), p0), label + " peak without rows"
+    if own:
+        h.close()
+
+
+def merged_plans(tas, B, seed, p_swap=0.5):
+    """Two batches merged plan by plan: tensors repeat inside a plan (several swaps of one tensor)."""
+    a, b = make_plans(tas, B, seed, p_swap=p_swap), make_plans(tas, B, seed + 1000, p_swap=p_swap)
+    lists = []
+    for p in range(B):
+        cur = []
+        for src in (a, b):
+            t, o, r, k = src.plan(p)
+            cur += [(int(t[j]), int(o[j]), int(r[j]), int(k[j])) for j in range(len(t))]
+        lists.append(cur)
+    return plans_from_lists(lists)
+
+
+@pytest.mark.parametrize("T,B,reuse", [(1, 2, False), (7, 5, True), (8191, 3, False), (8192, 3, True), (8193, 4, False),
+                                        (20011, 6, True), (20012, 5, False), (300, 700, True)])
+def test_link_occupancy_shapes(T, B, reuse):
+    """One tile, tile edges, ragged last tiles, odd and even T (8- and 16-byte aligned rows), several
+    swaps of one tensor in a plan, recomputation intervals in between, and more plans than workgroups."""
+    N = max(1, min(300, T // 2))
+    tas = small_random_tas(4000 + T, N=N, T=T, max_acc=5 if T > 8 else 1, timed=True)
+    pl = merged_plans(tas, B, 11) if T > 1 else plans_from_lists([[], []])
+    say(f"link T={T} B={B} reuse={reuse} K={pl.n_intervals}")
+    check_link(tas, pl, reuse, label=f"link T={T}")
+
+
+def test_link_occupancy_long_plans_take_several_passes():
+    """Plans of more than 6144 intervals (the registers of one pass), with and without rows."""
+    tas = small_random_tas(4100, N=400, T=9000, max_acc=6, timed=True)
+    base = merged_plans(tas, 4, 21, p_swap=0.9)
+    lists = []
+    for b in range(4):
+        t, o, r, k = base.plan(b)
+        one = [(int(t[j]), int(o[j]), int(r[j]), int(k[j])) for j in range(len(t))]
+        lists.append((one * (14000 // max(1, len(one)) + 1))[:6144 * b + 5 + 6140 * (b % 2)])
+    pl = plans_from_lists(lists)
+    say(f"link long plans: {[len(x) for x in lists]}")
+    for reuse in (False, True):
+        check_link(tas, pl, reuse, label=f"link long reuse={reuse}")
+
+
+def test_link_occupancy_edge_cases(configs_small):
+    # no latencies: nothing is occupied
+    tas = small_random_tas(4200, N=50, T=100, max_acc=4, timed=False)
+    pl = make_plans(tas, 5, 3, p_swap=0.5)
+    check_link(tas, pl, False, label="link untimed")
+    # kinds omitted: every interval is a swap; inapplicable intervals are skipped; B == 0
+    tas = small_random_tas(4201, N=50, T=100, max_acc=4, timed=True)
+    pl = plans_from_lists([[(0, 3, 9, 0), (70, 1, 5, 0), (1, -1, 5, 0), (2, 5, 101, 0), (3, 9, 9, 0), (4, 20, 100, 0)], []])
+    h = P.tas_load(tas)
+    dp = P.DevicePlans.from_numpy(pl.plan_offsets, pl.iv_tensor, pl.iv_out, pl.iv_in, None)
+    rows, pk, arg, over = gpu_link(h, dp)
+    r0, p0, a0, o0 = O.link_occupancy(tas, pl)
+    assert np.array_equal(rows.cpu().numpy(), r0) and np.array_equal(pk.cpu().numpy(), p0)
+    assert np.array_equal(arg.cpu().numpy(), a0) and np.array_equal(over.cpu().numpy(), o0)
+    empty = upload(plans_from_lists([]))
+    P.tensile_eval_link(h, empty, pk, None)
+    h.close()
+    # a workload-shaped sequence
+    tas = configs_small[1]
+    pl = make_config_plans(1, tas, B=24)
+    check_link(tas, pl, True, label="link c1")
+
+
+def test_link_of_a_greedy_plan_is_exclusive(configs_small):
+    """The plan that tensile_greedy_plan builds never books the link twice."""
+    tas = configs_small[1]
+    h = P.tas_load(tas)
+    g = P.tensile_greedy_plan(h, budget_bytes=0, max_iters=150, min_iters=1 << 30)
+    n = len(g["iv_tensor"])
+    assert n > 20
+    offs = np.array([0, n], dtype=np.int64)
+    dp = P.DevicePlans.from_numpy(offs, g["iv_tensor"], g["iv_out"], g["iv_in"], g["iv_kind"])
+    rows, pk, arg, over = gpu_link(h, dp)
+    assert int(pk[0]) == 1 and int(over[0]) == 0 and int(rows.max()) == 1
+    h.close()
+
+
 def test_eval_binned_config(configs_small, monkeypatch):
     monkeypatch.setenv("TENSILE_EVAL_BINNED", "1")
     tas = configs_small[2]
@@ -621,6 +728,20 @@ def test_full_size_config(idx, n_rows, n_score):
         jp0, ja0, t0 = O.eval_per_job(tas, pl.select(srows))
         assert np.array_equal(jp[:, sidx].cpu().numpy(), jp0) and np.array_equal(ja[:, sidx].cpu().numpy(), ja0)
         assert np.array_equal(tot[sidx].cpu().numpy(), t0) and bool((tot >= peak).all())
+    if tas.step_ns is not None:
+        say("  link occupancy of the whole batch")
+        lrows = torch.empty((cfg.B, tas.T), dtype=torch.int32, device="cuda")
+        lpk = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
+        larg = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
+        lover = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
+        P.tensile_eval_link(h, dp, lpk, lrows, larg, lover, reuse_host_copies=True)
+        torch.cuda.synchronize()
+        l0, lp0, la0, lo0 = O.link_occupancy(tas, pl.select(srows), reuse=True)
+        assert np.array_equal(lrows[sidx].cpu().numpy(), l0) and np.array_equal(lpk[sidx].cpu().numpy(), lp0)
+        assert np.array_equal(larg[sidx].cpu().numpy(), la0) and np.array_equal(lover[sidx].cpu().numpy(), lo0)
+        assert torch.equal(lrows.max(dim=1).values, lpk) and bool((lrows >= 0).all())
+        assert torch.equal((lrows >= 2).sum(dim=1).to(torch.int32), lover)
+        del lrows
     say("  recomputation savings of the whole batch")
     P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)
     torch.cuda.synchronize()
