@@ -12,7 +12,8 @@
 //
 // One persistent workgroup of 1024 threads per CU walks the plans slot, slot + grid, ...:
 //  * the start step of a transfer is a search in C: first in a table of every stride-th value kept in
-//    LDS for the whole launch (at most 2048 entries), then a few probes of C itself (L2 resident);
+//    LDS for the whole launch (8192 entries), then log2(stride) probes of C itself (L2 resident); a
+//    thread's twelve searches run in lockstep, one probe each per round, so that their latencies overlap;
 //  * the four endpoints of an interval (+1 at s, -1 at o+1, +1 at s', -1 at r) stay in registers, six
 //    intervals per thread; a longer plan takes several passes of 6144 intervals, each over all tiles,
 //    and the passes add up in the output row (or in a scratch row per workgroup when no rows are
@@ -35,7 +36,7 @@ constexpr int kVpt = 8;                              // steps per lane per tile
 constexpr int kTile = kThr * kVpt;                   // 8192
 constexpr int kR = 6;                                // intervals per thread and pass
 constexpr int kPass = kR * kThr;                     // 6144
-constexpr int kTabMax = 2048;                        // entries of the coarse table of C
+constexpr int kTabBits = 13, kTabMax = 1 << kTabBits; // entries of the coarse table of C (64 KB of LDS)
 // LDS layouts are skewed by one 16-byte granule per 16 granules (cell u lives at u + 4 * (u >> 6)): both
 // the lane-contiguous pattern (8 cells per lane) and the striped one (one granule per lane) are then
 // free of bank conflicts.  A lane's two granules never straddle a multiple of 16.
@@ -55,6 +56,7 @@ struct LinkArgs {
     const int64_t *C;              // [T+1]
     const int64_t *x;              // [N]
     int32_t tab_stride, n_tab;     // coarse table: C[k * tab_stride], k < n_tab
+    int32_t fine_bits;             // ceil(log2(tab_stride))
     int32_t *first_out;            // [grid][N], INT32_MAX everywhere between plans (reuse only)
     int32_t *acc_rows;             // [grid][T] scratch rows for plans of several passes when link == null
     int32_t *link;                 // [B*T] or null
@@ -72,47 +74,51 @@ __device__ __forceinline__ int32_t wave_scan_add32(int32_t x) {
     return x;
 }
 
+// Phase timing for tuning, compiled in with -DTENSILE_LINK_PROF only: thread 0 of every workgroup adds the
+// 100 MHz ticks it spent in each phase to g_link_prof.
+#ifdef TENSILE_LINK_PROF
+__device__ unsigned long long g_link_prof[8];
+#define LINK_MARK(k)                                              \
+    do {                                                          \
+        if (threadIdx.x == 0) {                                   \
+            const unsigned long long now_ = wall_clock64();       \
+            atomicAdd(&g_link_prof[k], now_ - prof_t);            \
+            prof_t = now_;                                        \
+        }                                                         \
+    } while (0)
+#else
+#define LINK_MARK(k) do { } while (0)
+#endif
+
 __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
-    __shared__ __attribute__((aligned(16))) int32_t delta[kTileCells + 64];   // the tile, then 64 "trash" cells
+    __shared__ __attribute__((aligned(16))) int32_t delta[kTileCells];
     __shared__ __attribute__((aligned(16))) int32_t stage_all[kWaves * kStageCells];
     __shared__ int64_t tab[kTabMax];
     __shared__ int32_t wave_tot[kWaves];
     __shared__ int32_t red_mx[kWaves], red_arg[kWaves], red_over[kWaves];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int my = tid * kVpt;
-    const int my_cell = static_cast<int>(skew(my));
-    int32_t *stage = stage_all + wave * kStageCells;
-
-    for (int k = tid; k < a.n_tab; k += kThr) tab[k] = a.C[static_cast<int64_t>(k) * a.tab_stride];
-    for (int u = tid; u < kTileCells + 64; u += kThr) delta[u] = 0;
+    for (int k = threadIdx.x; k < kTabMax; k += kThr) tab[k] = k < a.n_tab ? a.C[static_cast<int64_t>(k) * a.tab_stride] : INT64_MAX;
+    for (int u = threadIdx.x; u < kTileCells; u += kThr) delta[u] = 0;
     __syncthreads();
 
-    // the latest step s in [0, hi) with C[hi] - C[s] >= x, or 0 if there is none (x > 0; C increases strictly)
-    auto start_step = [&](int32_t hi, int64_t x) -> int32_t {
-        const int64_t v = a.C[hi] - x;
-        if (v < 0) return 0;
-        // coarse: the last table entry <= v (entry 0 is C[0] = 0 <= v)
-        int32_t lo_k = 0, hi_k = a.n_tab;                 // invariant: tab[lo_k] <= v, tab[hi_k] > v (or hi_k == n_tab)
-        while (hi_k - lo_k > 1) {
-            const int32_t mid = (lo_k + hi_k) >> 1;
-            if (tab[mid] <= v) lo_k = mid;
-            else hi_k = mid;
-        }
-        int32_t lo_s = lo_k * a.tab_stride;               // C[lo_s] <= v
-        int32_t hi_s = lo_s + a.tab_stride;               // C[hi_s] > v, or hi_s beyond the table's reach
-        if (hi_s > hi) hi_s = hi;                         // C[hi] > v
-        while (hi_s - lo_s > 1) {
-            const int32_t mid = (lo_s + hi_s) >> 1;
-            if (a.C[mid] <= v) lo_s = mid;
-            else hi_s = mid;
-        }
-        return lo_s;
-    };
-
+    // C[k] through the uniform base and a 32-bit byte offset (the host keeps T below 2^28): no 64-bit
+    // address per probe
+    auto c_at = [&](uint32_t k) { return *reinterpret_cast<const int64_t *>(reinterpret_cast<const char *>(a.C) + k * 8u); };
     int32_t *first_out = a.reuse ? a.first_out + static_cast<int64_t>(blockIdx.x) * a.N : nullptr;
 
+#ifdef TENSILE_LINK_PROF
+    unsigned long long prof_t = wall_clock64();
+#endif
     for (int64_t plan = blockIdx.x; plan < a.B; plan += gridDim.x) {
+        LINK_MARK(0);
+        // the per-lane numbers, derived afresh for every plan from a copy of the thread id that the compiler
+        // cannot trace back: otherwise dozens of values computed from it are kept (and spilled) across the kernel
+        int tid_now = threadIdx.x;
+        asm volatile("" : "+v"(tid_now));
+        const int tid = tid_now, lane = tid & 63, wave = tid >> 6;
+        const int my = tid * kVpt;
+        const int my_cell = static_cast<int>(skew(my));
+        int32_t *stage = stage_all + wave * kStageCells;
         int64_t k0 = a.plan_offsets[plan], k1 = a.plan_offsets[plan + 1];
         if (k0 < 0) k0 = 0;
         if (k1 > a.n_intervals) k1 = a.n_intervals;
@@ -140,35 +146,112 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
 
         for (int64_t pass = 0; pass < n_pass; ++pass) {
             const bool first = pass == 0, last = pass == n_pass - 1;
-            // ---- this pass's intervals: endpoints in the skewed numbering, UINT32_MAX = none
+            // ---- this pass's intervals: endpoints in the skewed numbering, UINT32_MAX = none.
+            // Every load is issued for all kR intervals before the first is used, at clamped indices, and the
+            // 2 * kR searches (start of the swap-out, start of the swap-in) advance together, one probe
+            // each per round: a search alone is a chain of dependent memory latencies.
             uint32_t e[kR][4];
             int32_t lo_t = INT32_MAX, hi_t = -1;
             const int64_t kb = k0 + pass * kPass;
+            int32_t iv_i[kR], iv_o[kR], iv_r[kR];
+            bool ok[kR], charged[kR];
+            {
+                const uint32_t len = k1 - kb < kPass ? static_cast<uint32_t>(k1 - kb) : kPass;   // (>= 1 unless the plan is empty)
+                uint32_t kind[kR];
 #pragma unroll
-            for (int j = 0; j < kR; ++j) {
-                const int64_t k = kb + static_cast<int64_t>(tid) * kR + j;
-                e[j][0] = e[j][1] = e[j][2] = e[j][3] = UINT32_MAX;
-                int32_t i, o, r;
-                if (k < k1 && swap_at(k, i, o, r)) {
-                    const int64_t x = a.x[i];
-                    if (x > 0) {
-                        bool charged = true;
-                        if (a.reuse) charged = __hip_atomic_load(&first_out[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == o;
-                        if (charged) {
-                            const int32_t s = start_step(o + 1, x);
-                            e[j][0] = skew(static_cast<uint32_t>(s));
-                            e[j][1] = skew(static_cast<uint32_t>(o + 1));
-                            lo_t = s < lo_t ? s : lo_t;
-                        }
-                        const int32_t s2 = start_step(r, x);
-                        e[j][2] = skew(static_cast<uint32_t>(s2));
-                        e[j][3] = skew(static_cast<uint32_t>(r));
-                        lo_t = s2 < lo_t ? s2 : lo_t;
-                        hi_t = r > hi_t ? r : hi_t;
+                for (int j = 0; j < kR; ++j) {
+                    const uint32_t k = tid * kR + j;
+                    ok[j] = k < len;
+                    const int64_t kc = kb + (ok[j] ? k : 0);
+                    const bool any = len > 0;
+                    iv_i[j] = any ? a.iv_tensor[kc] : 0;
+                    iv_o[j] = any ? a.iv_out[kc] : 0;
+                    iv_r[j] = any ? a.iv_in[kc] : 0;
+                    kind[j] = (any && a.iv_kind) ? a.iv_kind[kc] : 0;
+                }
+#pragma unroll
+                for (int j = 0; j < kR; ++j) {
+                    ok[j] = ok[j] && kind[j] == 0 && static_cast<uint32_t>(iv_i[j]) < static_cast<uint32_t>(a.N) && iv_o[j] >= 0 &&
+                            iv_r[j] <= a.T && iv_r[j] > iv_o[j];
+                    if (!ok[j]) {   // harmless stand-ins for the loads below
+                        iv_i[j] = 0;
+                        iv_o[j] = 0;
+                        iv_r[j] = 1;
                     }
                 }
             }
+            LINK_MARK(1);
+            int64_t v[kR][2];     // C at the transfer's end minus its duration: the transfer starts inside the last step that begins at or before v
+#pragma unroll
+            for (int j = 0; j < kR; ++j) {
+                const int64_t x = a.x[iv_i[j]];
+                charged[j] = true;
+                if (a.reuse) charged[j] = __hip_atomic_load(&first_out[iv_i[j]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == iv_o[j];
+                v[j][0] = c_at(static_cast<uint32_t>(iv_o[j] + 1)) - x;
+                v[j][1] = c_at(static_cast<uint32_t>(iv_r[j])) - x;
+                ok[j] = ok[j] && x > 0;
+            }
+            LINK_MARK(2);
+            // coarse: the last table entry <= v (none when v < 0: position 0, and the fine rounds then stay at step 0)
+            uint32_t pos[kR][2];
+#pragma unroll
+            for (int j = 0; j < kR; ++j) pos[j][0] = pos[j][1] = 0;
+#pragma unroll
+            for (int bit = kTabBits - 1; bit >= 0; --bit) {
+#pragma unroll
+                for (int j = 0; j < kR; ++j) {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const uint32_t cand = pos[j][q] | (1u << bit);
+                        pos[j][q] = tab[cand] <= v[j][q] ? cand : pos[j][q];
+                    }
+                }
+            }
+            // fine: from the block's first step, forward by decreasing powers of two while C stays <= v.  C increases,
+            // so a probe beyond the block (or beyond the transfer's end) fails by itself; only the array's end needs a guard.
+            LINK_MARK(3);
+#pragma unroll
+            for (int j = 0; j < kR; ++j) {
+                pos[j][0] *= a.tab_stride;
+                pos[j][1] *= a.tab_stride;
+            }
+            for (int bit = a.fine_bits - 1; bit >= 0; --bit) {   // (uniform)
+                int64_t c[kR][2];
+#pragma unroll
+                for (int j = 0; j < kR; ++j) {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const uint32_t at = pos[j][q] + (1u << bit);
+                        c[j][q] = c_at(at <= static_cast<uint32_t>(a.T) ? at : static_cast<uint32_t>(a.T));
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < kR; ++j) {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const uint32_t at = pos[j][q] + (1u << bit);
+                        pos[j][q] = (at <= static_cast<uint32_t>(a.T) && c[j][q] <= v[j][q]) ? at : pos[j][q];
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kR; ++j) {
+                e[j][0] = e[j][1] = e[j][2] = e[j][3] = UINT32_MAX;
+                if (ok[j]) {
+                    const int32_t s = static_cast<int32_t>(pos[j][0]), s2 = static_cast<int32_t>(pos[j][1]);
+                    if (charged[j]) {
+                        e[j][0] = skew(static_cast<uint32_t>(s));
+                        e[j][1] = skew(static_cast<uint32_t>(iv_o[j] + 1));
+                        lo_t = s < lo_t ? s : lo_t;
+                    }
+                    e[j][2] = skew(static_cast<uint32_t>(s2));
+                    e[j][3] = skew(static_cast<uint32_t>(iv_r[j]));
+                    lo_t = s2 < lo_t ? s2 : lo_t;
+                    hi_t = iv_r[j] > hi_t ? iv_r[j] : hi_t;
+                }
+            }
 
+            LINK_MARK(4);
             int32_t carry = 0;
             for (int32_t tile_lo = 0; tile_lo < a.T; tile_lo += kTile) {
                 const int32_t tile_hi = a.T - tile_lo < kTile ? a.T : tile_lo + kTile;
@@ -177,17 +260,17 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
                 const bool mine = hi_t >= tile_lo && lo_t < tile_hi;
                 if (__builtin_amdgcn_ballot_w64(mine) != 0) {
                     const uint32_t base_cell = skew(static_cast<uint32_t>(tile_lo)), n_cell = skew(tile_n);
-                    const uint32_t trash = kTileCells + lane;
 #pragma unroll
                     for (int j = 0; j < kR; ++j) {
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
                             const uint32_t u = e[j][q] - base_cell;
-                            atomicAdd(&delta[u < n_cell ? u : trash], (q & 1) ? -1 : 1);
+                            if (u < n_cell) atomicAdd(&delta[u], (q & 1) ? -1 : 1);
                         }
                     }
                 }
                 __syncthreads();
+                LINK_MARK(5);
                 // ---- this lane's 8 cells: read, clear for the next tile, local scan, wave scan
                 int32_t v[kVpt];
                 {
@@ -263,9 +346,11 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
                     }
                     __builtin_amdgcn_wave_barrier();
                 }
+                LINK_MARK(6);
             }
         }
 
+        LINK_MARK(6);
         // ---- the plan's result
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) {
@@ -328,6 +413,7 @@ int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, 
                 int32_t *overbooked, hipStream_t stream) {
     const int32_t B = plans->B, T = tas->T;
     if (B == 0) return TENSILE_OK;
+    if (T > (1 << 28)) { set_error("eval_link: T = %d exceeds 2^28 steps", T); return TENSILE_E_RANGE; }
     if (!tas->timed || tas->N == 0) {
         const int64_t n_rows = link ? static_cast<int64_t>(B) * T : 0;
         hipLaunchKernelGGL(link_zero_kernel, dim3(tas->num_cus * 4), dim3(256), 0, stream, n_rows, link, B, peak, argmax, overbooked);
@@ -342,6 +428,8 @@ int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, 
     a.C = tas->d_C.p; a.x = tas->d_x.p;
     a.tab_stride = static_cast<int32_t>((static_cast<int64_t>(T) + kTabMax) / kTabMax);   // ceil((T + 1) / kTabMax)
     a.n_tab = static_cast<int32_t>(static_cast<int64_t>(T) / a.tab_stride + 1);           // entries k with k * stride <= T
+    a.fine_bits = 0;
+    while ((1 << a.fine_bits) < a.tab_stride) ++a.fine_bits;
     const int32_t grid = B < tas->num_cus ? B : tas->num_cus;
     Scratch &sc = tas->scratch;
     if (reuse) {
@@ -368,5 +456,16 @@ int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, 
     TS_HIP(hipGetLastError());
     return TENSILE_OK;
 }
+
+#ifdef TENSILE_LINK_PROF
+extern "C" int tensile_debug_link_prof(unsigned long long *out, int reset) {
+    if (out) (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_link_prof), sizeof(g_link_prof));
+    if (reset) {
+        unsigned long long z[8] = {};
+        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_link_prof), z, sizeof(z));
+    }
+    return 0;
+}
+#endif
 
 }  // namespace tensile
