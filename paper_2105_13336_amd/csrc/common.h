@@ -117,13 +117,15 @@ constexpr int kScoreMini = 256;    // steps one wavefront takes up at a time (4 
 //   cand / cand_size / cand_o   the entries sorted by o; slices are runs of kScoreMaxLocal of them
 //   qord                        per slice, its entries as {q, index within the slice} sorted by q
 //   tord                        per slice, its entries as {tensor, index within the slice} sorted by tensor
-//   wave_ptr[3][kScoreWaves+1]  per slice (slices numbered from slice_first[bucket]): first position
-//                               within the slice with o (resp. q, tensor) >= w * span (w * tspan), per order
+//   wave_ptr[4][kScoreWaves+1]  per slice (slices numbered from slice_first[bucket]): rows 0-2 = first position
+//                               within the slice with o (resp. q) >= the w-th span boundary, tensor >= w * tspan,
+//                               per order; row 3 = the span boundaries themselves: first step of wavefront w's
+//                               part of the row (multiples of kScoreMini, the last one T), placed so that
+//                               steps and entries together are spread evenly over the wavefronts
 //   hash_dir / hash_slots       open-addressing table tensor -> {tensor, p, q, local | last << 31}
 //   filter                      one bit per (tensor mod filter_bits): some entry has this tensor
 struct CandIndex {
     int32_t shift = 0, n_buckets = 0;
-    int32_t span = kScoreMini;     // steps per wavefront: ceil(T / kScoreWaves) rounded up to kScoreMini
     int32_t tspan = kScoreStage;   // tensors per wavefront: ceil(N / kScoreWaves) rounded up to kScoreStage
     int32_t filter_words = 0;      // words per bucket, a power of two
     int32_t max_bucket = 0;        // entries in the largest bucket
@@ -133,7 +135,7 @@ struct CandIndex {
     DevBuf<int32_t> cand_o;
     DevBuf<int2> qord, tord;
     DevBuf<int32_t> slice_first;   // [n_buckets + 1]
-    DevBuf<int32_t> wave_ptr;      // [slices][3][kScoreWaves + 1]
+    DevBuf<int32_t> wave_ptr;      // [slices][4][kScoreWaves + 1]
     DevBuf<int2> hash_dir;         // [n_buckets] {first slot, log2(slots)}
     DevBuf<int4> hash_slots;
     DevBuf<uint32_t> filter;       // [n_buckets][filter_words]

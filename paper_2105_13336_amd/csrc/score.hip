@@ -60,7 +60,6 @@ typedef long long ll2 __attribute__((ext_vector_type(2)));
 
 struct ScoreArgs {
     int32_t T, N, B;
-    int32_t span;                // steps per wavefront (a multiple of kMini)
     int32_t tspan;               // tensors per wavefront (a multiple of kScoreStage)
     int32_t n_tab;               // ceil(T / kMini)
     int32_t vec16;               // rows are 16-byte aligned (T even, aligned base)
@@ -289,6 +288,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
     __shared__ int64_t tab_lds[kBigT ? 1 : kTabLds];
     __shared__ uint32_t filter[kFilterWords];
     __shared__ int64_t span_max[kWaves];
+    __shared__ int32_t span_bound[kWaves + 1];  // first step of every wavefront's span in the slice at hand, then T
     int64_t *tab_global = kBigT ? a.tab_scratch + static_cast<int64_t>(blockIdx.x) * a.n_tab : nullptr;
     int32_t filter_of = -1;      // bucket whose filter is in LDS
     int32_t lists_of = -1;       // slice (numbered over all buckets) whose lists are in LDS
@@ -302,7 +302,6 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         int tid = threadIdx.x;
         asm volatile("" : "+v"(tid));
         const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-        const int32_t span_lo = min(wave * a.span, a.T), span_hi = min(span_lo + a.span, a.T);
         const int32_t tstar = a.argmax[b];
         const int64_t P = a.peak[b];
         const int64_t *MF = a.resident + static_cast<int64_t>(b) * a.T;
@@ -332,7 +331,10 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         for (int32_t slice_lo = 0; slice_lo < n_e; slice_lo += kMaxLocal) {
             const int32_t n_slice = min(kMaxLocal, n_e - slice_lo);
             const int32_t slice_id = slice0 + slice_lo / kMaxLocal;
-            const int32_t *wp = a.wave_ptr + static_cast<int64_t>(slice_id) * 3 * (kWaves + 1);
+            const int32_t *wp = a.wave_ptr + static_cast<int64_t>(slice_id) * 4 * (kWaves + 1);
+            // the wavefronts' spans of the row: the slice's own boundaries (multiples of kMini, the last one T),
+            // chosen when the index is built so that steps and entries together are spread evenly
+            const int32_t span_lo = wp[3 * (kWaves + 1) + wave], span_hi = wp[3 * (kWaves + 1) + wave + 1];
             __syncthreads();   // the previous plan or slice has finished with acc, tab, span_max, the filter, the lists
             for (int32_t k = tid; k < n_slice; k += kThreads) acc[k] = INT64_MIN;
             if (lists_of != slice_id) {
@@ -343,6 +345,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                     t_tensor[k] = t.x;
                     t_el[k] = static_cast<uint16_t>(t.y);
                 }
+                if (tid <= kWaves) span_bound[tid] = wp[3 * (kWaves + 1) + tid];
                 lists_of = slice_id;
             }
             if (filter_of != bk) {
@@ -424,12 +427,13 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                 int32_t w_o = 0, w_q = 0;
 #pragma unroll
                 for (int w = 1; w < kWaves; ++w) {
-                    w_o += o >= w * a.span;
-                    w_q += q >= w * a.span;
+                    const int32_t bound = span_bound[w];
+                    w_o += o >= bound;
+                    w_q += q >= bound;
                 }
                 int64_t m = max64(v, P - sz);
                 const int32_t piece = q / kMini + 1;                          // pieces after q's, inside q's span
-                if (piece * kMini < min((w_q + 1) * a.span, a.T)) m = max64(m, kBigT ? tab_global[piece] : tab_lds[piece]);
+                if (piece * kMini < span_bound[w_q + 1]) m = max64(m, kBigT ? tab_global[piece] : tab_lds[piece]);
 #pragma unroll
                 for (int w = 0; w < kWaves; ++w) {
                     const int64_t sm = span_max[w];
@@ -556,7 +560,6 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     const int32_t blocks = static_cast<int32_t>((plans->B + rounds - 1) / rounds);
     ScoreArgs a;
     a.T = tas->T; a.N = tas->N; a.B = plans->B;
-    a.span = ix.span;
     a.tspan = ix.tspan;
     a.n_tab = (tas->T + kMini - 1) / kMini;
     a.vec16 = (tas->T % 2 == 0) && (reinterpret_cast<uintptr_t>(resident) % 16 == 0);

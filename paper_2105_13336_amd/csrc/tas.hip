@@ -241,7 +241,6 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
     const int32_t nb = ((T - 1) >> shift) + 1;
     ix.shift = shift;
     ix.n_buckets = nb;
-    ix.span = ((T + kScoreWaves - 1) / kScoreWaves + kScoreMini - 1) / kScoreMini * kScoreMini;
     ix.tspan = ((h->N + kScoreWaves - 1) / kScoreWaves + kScoreStage - 1) / kScoreStage * kScoreStage;
 
     std::vector<int32_t> off(static_cast<size_t>(nb) + 1, 0);
@@ -264,7 +263,7 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
     std::vector<int32_t> slice_first(static_cast<size_t>(nb) + 1, 0);
     for (int32_t b = 0; b < nb; ++b)
         slice_first[b + 1] = slice_first[b] + (off[b + 1] - off[b] + kScoreMaxLocal - 1) / kScoreMaxLocal;
-    std::vector<int32_t> wave_ptr(static_cast<size_t>(slice_first[nb]) * 3 * (kScoreWaves + 1));
+    std::vector<int32_t> wave_ptr(static_cast<size_t>(slice_first[nb]) * 4 * (kScoreWaves + 1));
     std::vector<int2> hash_dir(static_cast<size_t>(nb));
     std::vector<int4> hash_slots;
     std::vector<uint32_t> filter(static_cast<size_t>(nb) * ix.filter_words, 0u);
@@ -291,10 +290,39 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
             std::sort(order.begin(), order.end(),
                       [&](int32_t x, int32_t y) { return c[s0 + x].w != c[s0 + y].w ? c[s0 + x].w < c[s0 + y].w : x < y; });
             for (int32_t k = 0; k < ns; ++k) tord[e0 + s0 + k] = make_int2(c[s0 + order[k]].w, order[k]);
-            int32_t *wp = wave_ptr.data() + static_cast<size_t>(sl) * 3 * (kScoreWaves + 1);
+            int32_t *wp = wave_ptr.data() + static_cast<size_t>(sl) * 4 * (kScoreWaves + 1);
+            // The wavefronts' spans of the row.  A wavefront's time in the streaming pass is about one unit per
+            // block of kScoreMini steps plus one per kEntriesPerBlock entries whose o or q it meets (measured:
+            // 1.05 us per block, 7 ns per entry), so the boundaries are put where the running cost
+            // blocks * kEntriesPerBlock + entries passes w/16 of the total (boundaries on whole blocks).
+            int32_t *sb = wp + 3 * (kScoreWaves + 1);
+            {
+                constexpr int64_t kEntriesPerBlock = 150;
+                const int64_t nblk = (static_cast<int64_t>(T) + kScoreMini - 1) / kScoreMini;
+                auto cost_before = [&](int64_t blk) {   // cost of the blocks [0, blk)
+                    const int64_t step = blk * kScoreMini;
+                    const int64_t n_o = std::lower_bound(c + s0, c + s0 + ns, step, [](const int4 &e, int64_t v) { return e.z < v; }) - (c + s0);
+                    const int2 *qo = qord.data() + e0 + s0;
+                    const int64_t n_q = std::lower_bound(qo, qo + ns, step, [](const int2 &e, int64_t v) { return e.x < v; }) - qo;
+                    return blk * kEntriesPerBlock + n_o + n_q;
+                };
+                const int64_t total = cost_before(nblk);
+                sb[0] = 0;
+                for (int w = 1; w < kScoreWaves; ++w) {
+                    const int64_t want = (total * w + kScoreWaves - 1) / kScoreWaves;
+                    int64_t lo_b = sb[w - 1] / kScoreMini, hi_b = nblk;       // smallest block count with cost >= want
+                    while (lo_b < hi_b) {
+                        const int64_t mid = (lo_b + hi_b) / 2;
+                        if (cost_before(mid) >= want) hi_b = mid;
+                        else lo_b = mid + 1;
+                    }
+                    sb[w] = static_cast<int32_t>(std::min<int64_t>(lo_b * kScoreMini, T));
+                }
+                sb[kScoreWaves] = T;
+            }
             int32_t ko = 0, kq = 0, kt = 0;
             for (int w = 0; w <= kScoreWaves; ++w) {
-                const int64_t bound = static_cast<int64_t>(w) * ix.span, tbound = static_cast<int64_t>(w) * ix.tspan;
+                const int64_t bound = sb[w], tbound = static_cast<int64_t>(w) * ix.tspan;
                 while (ko < ns && c[s0 + ko].z < bound) ++ko;
                 while (kq < ns && qord[e0 + s0 + kq].x < bound) ++kq;
                 while (kt < ns && tord[e0 + s0 + kt].x < tbound) ++kt;
