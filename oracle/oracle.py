@@ -76,6 +76,18 @@ def eval_per_job(tas, plans):
     return jp, ja, jp.sum(axis=0) + int(tas.base_bytes)
 
 
+def apply_intervals(tas, tensor, out, in_, resident: np.ndarray):
+    """One more interval per plan on existing rows (in place) -> (peak [B], argmax [B], min [B])"""
+    B = resident.shape[0]
+    assert resident.dtype == np.int64 and resident.flags.c_contiguous and resident.shape == (B, tas.T)
+    t = np.ascontiguousarray(tensor, dtype=np.int32); o = np.ascontiguousarray(out, dtype=np.int32)
+    r = np.ascontiguousarray(in_, dtype=np.int32)
+    pk = np.empty(B, dtype=np.int64); arg = np.empty(B, dtype=np.int32); mn = np.empty(B, dtype=np.int64)
+    _chk(_lib().oracle_apply_intervals(i32(tas.T), i32(tas.N), _p(tas.size_bytes), i64(B), _p(t), _p(o), _p(r),
+                                       _p(resident), _p(pk), _p(arg), _p(mn)), "apply_intervals")
+    return pk, arg, mn
+
+
 def link_occupancy(tas, plans, reuse: bool = False, want_rows: bool = True):
     """-> (link [B,T] int32 or None, peak [B], argmax [B], overbooked [B]): steps of the host link that the
     plans' transfers occupy (canonical placement, see oracle_link_occupancy)"""

@@ -129,6 +129,36 @@ int oracle_eval(int32_t T, int32_t N, const int64_t *size, const int64_t *MF0, i
     return OR_OK;
 }
 
+/* One more interval per plan, applied to footprint rows that already exist (Alg. 3
+ * analyses the peak again after every scheduled tensor, section IV-C; only the
+ * steps o+1 .. r-1 of the row change when (i, o, r) joins the plan).  Row b loses
+ * size[i_b] during those steps if the interval can be applied (otherwise it stays
+ * as it is); peak, earliest peak step (strict '>' as in Alg. 1) and minimum are
+ * taken over the whole row again. */
+int oracle_apply_intervals(int32_t T, int32_t N, const int64_t *size, int64_t B, const int32_t *tensor,
+                           const int32_t *out, const int32_t *in, int64_t *resident, int64_t *peak, int32_t *argmax,
+                           int64_t *min_resident) {
+    if (T <= 0 || N < 0 || B < 0) return OR_E_INVAL;
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t *row = resident + b * (int64_t)T;
+        if (interval_applies(N, T, tensor[b], out[b], in[b]))
+            for (int32_t t = out[b] + 1; t < in[b]; ++t) row[t] -= size[tensor[b]];
+        int64_t mx = row[0], mn = row[0];
+        int32_t arg = 0;
+        for (int32_t t = 1; t < T; ++t) {
+            if (row[t] > mx) {
+                mx = row[t];
+                arg = t;
+            }
+            if (row[t] < mn) mn = row[t];
+        }
+        peak[b] = mx;
+        argmax[b] = arg;
+        if (min_resident) min_resident[b] = mn;
+    }
+    return OR_OK;
+}
+
 /* Per-workload peaks (section III-A): the footprint MF_j of workload W_j sums
  * Mem over the accesses and schedule events of that workload only, MP_j is its
  * maximum, and for workloads that run asynchronously the global peak is taken as
