@@ -201,6 +201,23 @@ int tensile_score_recompute(const tensile_tas *tas, const tensile_plans *plans, 
  * 2 = not inside one gap, 3 = second interval in a gap, 4 = bad plan_offsets. */
 int tensile_validate_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *first_bad, int32_t *reason);
 
+/* Windowed re-evaluation: plan b gains ONE interval (tensor[b], out_step[b],
+ * in_step[b]) and its footprint row, which exists already, is brought up to
+ * date in place.  Alg. 3 analyses the peak again after every tensor it
+ * schedules (section IV-C); only the steps out_step+1 .. in_step-1 of the row
+ * change, so nothing but that window is written and the plan's other
+ * intervals are not read again.  The result is the one tensile_eval_plans
+ * gives for the extended plan.
+ *   tensor, out_step, in_step  DEVICE [B]; an interval that cannot be applied
+ *                (see tensile_eval_plans) leaves its row as it is
+ *   resident     DEVICE [B*T] in/out: rows as tensile_eval_plans wrote them
+ *   peak, argmax DEVICE [B] out: of the updated rows
+ *   min_resident DEVICE [B] out; may be NULL
+ * Asynchronous on hip_stream.  B == 0 is a no-op. */
+int tensile_apply_intervals(const tensile_tas *tas, int32_t B, const int32_t *tensor, const int32_t *out_step,
+                            const int32_t *in_step, int64_t *resident, int64_t *peak, int32_t *argmax,
+                            int64_t *min_resident, void *hip_stream);
+
 /* Occupancy of the host link by the transfers of each plan (section IV-C, "Swap
  * Event Scheduling": a transfer occupies the PCIe channel exclusively, only one
  * tensor can be on its way at a time).  A swap interval (i, o, r) of a timed

@@ -21,7 +21,7 @@ TENSILE_OK, TENSILE_E_INVAL, TENSILE_E_RANGE, TENSILE_E_NOMEM, TENSILE_E_HIP, TE
 
 EXPORTS = ["tensile_last_error", "tensile_version", "tensile_tas_load", "tensile_tas_free", "tensile_tas_info",
            "tensile_tas_update_latencies",
-           "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_eval_link", "tensile_score_candidates", "tensile_score_recompute",
+           "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_eval_link", "tensile_apply_intervals", "tensile_score_candidates", "tensile_score_recompute",
            "tensile_validate_plans",
            "tensile_greedy_plan"]
 
@@ -203,6 +203,18 @@ def tensile_eval_plans_per_job(h: TasHandle, plans: DevicePlans, job_peak: torch
     _check(_lib.tensile_eval_plans_per_job(h.ptr, ctypes.byref(st), _dp(job_peak, torch.int64, J * B, "job_peak"),
                                            _dp(job_argmax, torch.int32, J * B, "job_argmax"),
                                            _dp(sum_peak, torch.int64, B, "sum_peak"), _stream(stream)))
+
+
+def tensile_apply_intervals(h: TasHandle, tensor: torch.Tensor, out_step: torch.Tensor, in_step: torch.Tensor,
+                            resident: torch.Tensor, peak: torch.Tensor, argmax: torch.Tensor,
+                            min_resident: Optional[torch.Tensor] = None, stream=None) -> None:
+    """tensor / out_step / in_step: [B] int32 (one new interval per plan), resident: [B, T] int64 in/out"""
+    B = int(tensor.numel())
+    _check(_lib.tensile_apply_intervals(h.ptr, ctypes.c_int32(B), _dp(tensor, torch.int32, B, "tensor"),
+                                        _dp(out_step, torch.int32, B, "out_step"), _dp(in_step, torch.int32, B, "in_step"),
+                                        _dp(resident, torch.int64, B * h.T, "resident"), _dp(peak, torch.int64, B, "peak"),
+                                        _dp(argmax, torch.int32, B, "argmax"), _dp(min_resident, torch.int64, B, "min_resident"),
+                                        _stream(stream)))
 
 
 def tensile_eval_link(h: TasHandle, plans: DevicePlans, link_peak: torch.Tensor, link: Optional[torch.Tensor] = None,

@@ -174,6 +174,8 @@ namespace tensile {
 // eval.hip
 int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, int32_t *argmax, int64_t *min_resident,
                 hipStream_t stream);
+int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const int32_t *out, const int32_t *in,
+                 int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream);
 // score.hip
 // (any_interval: an interval of the entry's tensor cancels the entry wherever it lies, not only inside the gap)
 int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,

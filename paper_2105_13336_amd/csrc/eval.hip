@@ -1111,7 +1111,131 @@ int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, i
     return TENSILE_OK;
 }
 
+// ---- one more interval per plan: windowed update -----------------------------------------
+// The rows exist already; plan b gains the interval (tensor[b], out[b], in[b]).  A workgroup takes
+// 8192 steps of one row: 16 contiguous bytes per lane and load, the window's steps lose the tensor's
+// size and are the only ones written back, and the chunk's (max, earliest argmax, min) go to the
+// per-segment partials that eval_finalize_kernel combines (or straight to the outputs when the row
+// is one chunk).  Reads 8 bytes per step, writes 8 per step of the window.
+constexpr int kApplyThr = 1024, kApplyChunk = kApplyThr * 8;
+
+template <bool kVec16>
+__global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(int32_t T, int32_t N, int32_t S, const int64_t *size,
+                                                                   const int32_t *tensor, const int32_t *out, const int32_t *in,
+                                                                   int64_t *resident, int64_t *out_max, int32_t *out_arg,
+                                                                   int64_t *out_min) {
+    constexpr int kWaves = kApplyThr / 64;
+    __shared__ int64_t red_mx[kWaves], red_mn[kWaves];
+    __shared__ int32_t red_arg[kWaves];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t plan = blockIdx.x / S;
+    const int32_t chunk = static_cast<int32_t>(blockIdx.x % S);
+    const int32_t lo = chunk * kApplyChunk, hi = T - lo < kApplyChunk ? T : lo + kApplyChunk;
+    const int32_t i = tensor[plan], o = out[plan], r = in[plan];
+    const bool ok = static_cast<uint32_t>(i) < static_cast<uint32_t>(N) && o >= 0 && r <= T && r > o;
+    const int64_t sz = ok ? size[i] : 0;
+    const int32_t win_lo = ok ? o + 1 : 0, win_hi = ok ? r : 0;   // steps win_lo .. win_hi - 1 change
+    int64_t *row = resident + plan * T;
+    Best best{INT64_MIN, INT64_MAX, INT32_MAX};
+    auto take = [&](int32_t t, int64_t v) {   // (a thread meets its steps in ascending order)
+        if (v > best.mx) {
+            best.mx = v;
+            best.arg = t;
+        }
+        if (v < best.mn) best.mn = v;
+    };
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int32_t t = lo + 2 * (j * kApplyThr + tid);
+        const bool in0 = t >= win_lo && t < win_hi, in1 = t + 1 >= win_lo && t + 1 < win_hi;
+        if (kVec16 && t + 2 <= hi) {
+            ll2 x = *reinterpret_cast<const ll2 *>(row + t);
+            x[0] -= in0 ? sz : 0;
+            x[1] -= in1 ? sz : 0;
+            if (in0 && in1) *reinterpret_cast<ll2 *>(row + t) = x;
+            else if (in0) row[t] = x[0];
+            else if (in1) row[t + 1] = x[1];
+            take(t, x[0]);
+            take(t + 1, x[1]);
+        } else {
+            if (t < hi) {
+                const int64_t v = row[t] - (in0 ? sz : 0);
+                if (in0) row[t] = v;
+                take(t, v);
+            }
+            if (t + 1 < hi) {
+                const int64_t v = row[t + 1] - (in1 ? sz : 0);
+                if (in1) row[t + 1] = v;
+                take(t + 1, v);
+            }
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const int64_t omx = __shfl_xor(best.mx, d, 64), omn = __shfl_xor(best.mn, d, 64);
+        const int32_t oarg = __shfl_xor(best.arg, d, 64);
+        best_merge(best, omx, oarg, omn);
+    }
+    if (lane == 0) {
+        red_mx[wave] = best.mx;
+        red_mn[wave] = best.mn;
+        red_arg[wave] = best.arg;
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int u = 1; u < kWaves; ++u) best_merge(best, red_mx[u], red_arg[u], red_mn[u]);
+        const int64_t slot = plan * S + chunk;
+        out_max[slot] = best.mx;
+        out_arg[slot] = best.arg;
+        if (out_min) out_min[slot] = best.mn;
+    }
+}
+
 }  // namespace
+
+int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const int32_t *out, const int32_t *in,
+                 int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream) {
+    if (B == 0) return TENSILE_OK;
+    const int32_t T = tas->T;
+    const int64_t S = (static_cast<int64_t>(T) + kApplyChunk - 1) / kApplyChunk;
+    const int64_t blocks = static_cast<int64_t>(B) * S;
+    if (blocks > 0x7fffffffLL) {
+        set_error("apply_intervals: B*chunks = %lld workgroups exceeds the grid limit", static_cast<long long>(blocks));
+        return TENSILE_E_INVAL;
+    }
+    int64_t *out_max = peak, *out_min = min_resident;
+    int32_t *out_arg = argmax;
+    if (S > 1) {
+        Scratch &sc = tas->scratch;
+        const size_t n = static_cast<size_t>(blocks);
+        if (sc.part_max.n < n || sc.part_arg.n < n || sc.part_min.n < n) {
+            TS_HIP(hipDeviceSynchronize());   // an earlier launch may still read the old buffers
+            TS_HIP(sc.part_max.reserve(n));
+            TS_HIP(sc.part_arg.reserve(n));
+            TS_HIP(sc.part_min.reserve(n));
+        }
+        out_max = sc.part_max.p;
+        out_arg = sc.part_arg.p;
+        out_min = sc.part_min.p;
+    }
+    const bool vec16 = (T % 2 == 0) && (reinterpret_cast<uintptr_t>(resident) % 16 == 0);
+    const dim3 grid(static_cast<uint32_t>(blocks)), block(kApplyThr);
+    if (vec16)
+        hipLaunchKernelGGL(apply_interval_kernel<true>, grid, block, 0, stream, T, tas->N, static_cast<int32_t>(S), tas->d_size.p,
+                           tensor, out, in, resident, out_max, out_arg, out_min);
+    else
+        hipLaunchKernelGGL(apply_interval_kernel<false>, grid, block, 0, stream, T, tas->N, static_cast<int32_t>(S), tas->d_size.p,
+                           tensor, out, in, resident, out_max, out_arg, out_min);
+    TS_HIP(hipGetLastError());
+    if (S > 1) {
+        const int fthreads = 256;
+        hipLaunchKernelGGL(eval_finalize_kernel, dim3((B + fthreads - 1) / fthreads), dim3(fthreads), 0, stream, B,
+                           static_cast<int32_t>(S), out_max, out_arg, out_min, peak, argmax, min_resident);
+        TS_HIP(hipGetLastError());
+    }
+    return TENSILE_OK;
+}
 
 int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, int32_t *argmax, int64_t *min_resident,
                 hipStream_t stream) {

@@ -272,7 +272,11 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
             const int32_t it = n - n_initial;
             const bool last = it >= max_new || n >= capacity || N == 0;
             pl.n_intervals = n;
-            int rc = tensile_eval_plans(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr);
+            // the first footprint comes from the whole plan; afterwards exactly one interval has joined
+            // since the last analysis and only its window of the row is brought up to date
+            int rc = it == 0 ? tensile_eval_plans(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr)
+                             : tensile_apply_intervals(tas, 1, d_t.p + (n - 1), d_o.p + (n - 1), d_r.p + (n - 1), d_res.p,
+                                                       d_peak.p, d_arg.p, d_min.p, nullptr);
             if (rc != TENSILE_OK) return rc;
             if (last) {
                 hipLaunchKernelGGL(peak_only_kernel, dim3(1), dim3(1), 0, nullptr, d_peak.p, d_arg.p, d_hdr.p);

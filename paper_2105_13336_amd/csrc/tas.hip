@@ -687,6 +687,20 @@ int tensile_eval_plans_per_job(const tensile_tas *tas, const tensile_plans *plan
     return TENSILE_OK;
 }
 
+int tensile_apply_intervals(const tensile_tas *tas, int32_t B, const int32_t *tensor, const int32_t *out_step,
+                            const int32_t *in_step, int64_t *resident, int64_t *peak, int32_t *argmax,
+                            int64_t *min_resident, void *hip_stream) {
+    if (!tas) { set_error("apply_intervals: NULL handle"); return TENSILE_E_INVAL; }
+    if (B < 0) { set_error("apply_intervals: negative B"); return TENSILE_E_INVAL; }
+    if (B == 0) return TENSILE_OK;
+    if (!tensor || !out_step || !in_step || !resident || !peak || !argmax) {
+        set_error("apply_intervals: tensor, out_step, in_step, resident, peak and argmax are required");
+        return TENSILE_E_INVAL;
+    }
+    return launch_apply(tas, B, tensor, out_step, in_step, resident, peak, argmax, min_resident,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
 int tensile_eval_link(const tensile_tas *tas, const tensile_plans *plans, int32_t reuse_host_copies, int32_t *link,
                       int32_t *link_peak, int32_t *link_argmax, int32_t *overbooked, void *hip_stream) {
     int rc = check_plans(tas, plans, "eval_link");

@@ -40,7 +40,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_binding_lists_the_same_names():
     from paper_2105_13336_amd import binding
     assert sorted(binding.EXPORTS) == declared_functions()
-    for name in ("tensile_tas_load", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_eval_link", "tensile_score_candidates",
+    for name in ("tensile_tas_load", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_eval_link", "tensile_apply_intervals", "tensile_score_candidates",
                  "tensile_score_recompute",
                  "tensile_greedy_plan", "tensile_validate_plans", "tensile_tas_info", "tensile_tas_base_timeline", "tensile_tas_free",
                  "tensile_version"):
@@ -92,6 +92,7 @@ def test_null_arguments_are_errors_not_crashes(lib):
     assert lib.tensile_score_recompute(None, None, None, None, None, None, None, None, None) == -1
     assert lib.tensile_eval_plans_per_job(None, None, None, None, None, None) == -1
     assert lib.tensile_eval_link(None, None, 0, None, None, None, None, None) == -1
+    assert lib.tensile_apply_intervals(None, 0, None, None, None, None, None, None, None, None) == -1
     assert lib.tensile_validate_plans(None, None, None, None) == -1
     assert lib.tensile_greedy_plan(None, ctypes.c_int64(0), None, 0, 0, None, None, None, None, None, None, None) == -1
     assert b"NULL" in lib.tensile_last_error()

@@ -19,7 +19,7 @@ from oracle import oracle as O  # noqa: E402
 from workloads import (CONFIGS, make_config_plans, make_plans, make_tas, plans_from_lists, small_random_tas,  # noqa: E402
                        tas_from_lists)
 from workloads import prng  # noqa: E402
-from workloads.plans import Plans  # noqa: E402
+from workloads.plans import Plans, eligible_gaps  # noqa: E402
 
 
 def say(msg):
@@ -156,6 +156,58 @@ def test_eval_persistent_grid(threads, T, B, slots, tail, monkeypatch):
     pl = plans_from_lists(lists)
     say(f"eval persistent threads={threads} T={T} B={B} slots={slots} tail={tail} K={pl.n_intervals}")
     check_eval(tas, pl, label=f"persistent threads={threads} T={T}")
+
+
+# ---- windowed update ------------------------------------------------------------------------
+
+def extra_intervals(tas, B, seed):
+    """One new interval per plan inside a random gap; every fifth one cannot be applied."""
+    eoff, ep, eq = eligible_gaps(tas)
+    rng = np.random.default_rng(seed)
+    bad = [(tas.N + 3, 2, 9), (1, -1, 5), (2, 7, 7), (0, 5, tas.T + 1)]
+    t, o, r = [], [], []
+    for b in range(B):
+        if b % 5 == 4 or len(ep) == 0:
+            i, oo, rr = bad[(b // 5) % 4]
+        else:
+            g = int(rng.integers(0, len(ep)))
+            i = int(np.searchsorted(eoff, g, side="right") - 1)
+            oo = int(rng.integers(ep[g], eq[g] - 1))
+            rr = int(rng.integers(oo + 2, eq[g] + 1))
+        t.append(i); o.append(oo); r.append(rr)
+    return np.array(t, dtype=np.int32), np.array(o, dtype=np.int32), np.array(r, dtype=np.int32)
+
+
+@pytest.mark.parametrize("T,B", [(1, 2), (7, 6), (8191, 5), (8192, 5), (8193, 6), (20011, 7), (20012, 11), (300, 400)])
+def test_apply_intervals(T, B):
+    """One more interval per plan on rows that exist: odd and even T (8- and 16-byte accesses), one chunk,
+    chunk edges, several chunks (finalize kernel), windows across chunk borders, inapplicable intervals."""
+    N = max(1, min(300, T // 2))
+    tas = small_random_tas(5000 + T, N=N, T=T, max_acc=5 if T > 8 else 1, timed=False, base_bytes=9)
+    pl = make_plans(tas, B, 13, p_swap=0.4)
+    say(f"apply T={T} B={B}")
+    h = P.tas_load(tas)
+    res, peak, arg, mn = gpu_eval(h, upload(pl))
+    r0, _, _, _ = O.eval_plans(tas, pl)
+    t, o, r = extra_intervals(tas, B, 7 + T)
+    up = lambda a: torch.from_numpy(a).cuda()
+    P.tensile_apply_intervals(h, up(t), up(o), up(r), res, peak, arg, mn)
+    torch.cuda.synchronize()
+    p1, a1, m1 = O.apply_intervals(tas, t, o, r, r0)
+    assert np.array_equal(res.cpu().numpy(), r0) and np.array_equal(peak.cpu().numpy(), p1)
+    assert np.array_equal(arg.cpu().numpy(), a1) and np.array_equal(mn.cpu().numpy(), m1)
+    # the same as evaluating the extended plans from scratch
+    lists = []
+    for b in range(B):
+        pt, po, pr, pk = pl.plan(b)
+        lists.append([(int(pt[j]), int(po[j]), int(pr[j]), int(pk[j])) for j in range(len(pt))] + [(int(t[b]), int(o[b]), int(r[b]), 0)])
+    res2, peak2, arg2, mn2 = gpu_eval(h, upload(plans_from_lists(lists)))
+    assert torch.equal(res, res2) and torch.equal(peak, peak2) and torch.equal(arg, arg2) and torch.equal(mn, mn2)
+    # without the optional minimum
+    P.tensile_apply_intervals(h, up(np.full(B, -1, dtype=np.int32)), up(o), up(r), res, peak, arg, None)
+    torch.cuda.synchronize()
+    assert torch.equal(res, res2) and torch.equal(peak, peak2) and torch.equal(arg, arg2)
+    h.close()
 
 
 # ---- link occupancy -----------------------------------------------------------------------
@@ -749,4 +801,12 @@ def test_full_size_config(idx, n_rows, n_score):
     assert np.array_equal(sc[sidx[:2]].cpu().numpy(), s0) and np.array_equal(wo[sidx[:2]].cpu().numpy(), o0)
     assert np.array_equal(wi[sidx[:2]].cpu().numpy(), i0)
     assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
+    say("  one more interval per plan of the whole batch (windowed update)")
+    t1, o1, r1 = extra_intervals(tas, cfg.B, 99)
+    P.tensile_apply_intervals(h, torch.from_numpy(t1).cuda(), torch.from_numpy(o1).cuda(), torch.from_numpy(r1).cuda(), res, peak, arg, mn)
+    torch.cuda.synchronize()
+    pa, aa, ma = O.apply_intervals(tas, t1[rows], o1[rows], r1[rows], r0)
+    assert np.array_equal(res[idxs].cpu().numpy(), r0) and np.array_equal(peak[idxs].cpu().numpy(), pa)
+    assert np.array_equal(arg[idxs].cpu().numpy(), aa) and np.array_equal(mn[idxs].cpu().numpy(), ma)
+    assert torch.equal(res.max(dim=1).values, peak) and torch.equal(res.min(dim=1).values, mn)
     h.close()
