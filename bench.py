@@ -192,6 +192,29 @@ def main() -> int:
                                     "max_link_peak": int(lpk.max()), "plans_within_one": int((lpk <= 1).sum())}
         del lrows, lpk, larg, lover
 
+    if not args.eval_only and not args.no_extras:
+        # windowed update: one more interval per plan on the rows that exist (a random gap of a random tensor each)
+        from workloads.plans import eligible_gaps
+        eoff, ep, eq = eligible_gaps(tas)
+        rng = np.random.default_rng(2105_13336)
+        g = rng.integers(0, len(ep), size=B)
+        ti = (np.searchsorted(eoff, g, side="right") - 1).astype(np.int32)
+        oi = (ep[g] + rng.integers(0, 1 << 30, size=B) % (eq[g] - 1 - ep[g])).astype(np.int32)
+        ri = (oi + 2 + rng.integers(0, 1 << 30, size=B) % (eq[g] - oi - 1)).astype(np.int32)
+        d_ti, d_oi, d_ri = (torch.from_numpy(x).cuda() for x in (ti, oi, ri))
+        res2 = res.clone()
+        pk2, ar2, mn2 = torch.empty_like(peak), torch.empty_like(arg), torch.empty_like(mn)
+        P.tensile_apply_intervals(h, d_ti, d_oi, d_ri, res2, pk2, ar2, mn2)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):      # (each call takes the window out once more: the timing is what matters here)
+            P.tensile_apply_intervals(h, d_ti, d_oi, d_ri, res2, pk2, ar2, mn2)
+        e1.record()
+        torch.cuda.synchronize()
+        out["rows"]["apply_intervals"] = {"ms": e0.elapsed_time(e1) / 3, "mean_window_steps": float((ri - oi - 1).mean())}
+        del res2, pk2, ar2, mn2
+
     if not args.no_greedy:
         iters = 48
         torch.cuda.synchronize()

@@ -1112,25 +1112,26 @@ int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, i
 }
 
 // ---- one more interval per plan: windowed update -----------------------------------------
-// The rows exist already; plan b gains the interval (tensor[b], out[b], in[b]).  A workgroup takes
-// 8192 steps of one row: 16 contiguous bytes per lane and load, the window's steps lose the tensor's
-// size and are the only ones written back, and the chunk's (max, earliest argmax, min) go to the
-// per-segment partials that eval_finalize_kernel combines (or straight to the outputs when the row
-// is one chunk).  Reads 8 bytes per step, writes 8 per step of the window.
+// The rows exist already; plan b gains the interval (tensor[b], out[b], in[b]).  A workgroup takes a
+// run of 8192-step chunks of one row: 16 contiguous bytes per lane and load, one chunk ahead; the
+// window's steps lose the tensor's size and are the only ones written back; the run's (max, earliest
+// argmax, min) go to the per-segment partials that eval_finalize_kernel combines, or straight to the
+// outputs when a row is one run.  Reads 8 bytes per step, writes 8 per step of the window.
 constexpr int kApplyThr = 1024, kApplyChunk = kApplyThr * 8;
 
 template <bool kVec16>
-__global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(int32_t T, int32_t N, int32_t S, const int64_t *size,
-                                                                   const int32_t *tensor, const int32_t *out, const int32_t *in,
-                                                                   int64_t *resident, int64_t *out_max, int32_t *out_arg,
-                                                                   int64_t *out_min) {
+__global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(int32_t T, int32_t N, int32_t S, int32_t chunks_per_group,
+                                                                   const int64_t *size, const int32_t *tensor, const int32_t *out,
+                                                                   const int32_t *in, int64_t *resident, int64_t *out_max,
+                                                                   int32_t *out_arg, int64_t *out_min) {
     constexpr int kWaves = kApplyThr / 64;
     __shared__ int64_t red_mx[kWaves], red_mn[kWaves];
     __shared__ int32_t red_arg[kWaves];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t plan = blockIdx.x / S;
-    const int32_t chunk = static_cast<int32_t>(blockIdx.x % S);
-    const int32_t lo = chunk * kApplyChunk, hi = T - lo < kApplyChunk ? T : lo + kApplyChunk;
+    const int32_t group = static_cast<int32_t>(blockIdx.x % S);     // this workgroup's run of chunks of the row
+    const int32_t g_lo = group * chunks_per_group * kApplyChunk;    // (fits: the host keeps S * chunks_per_group * chunk near T)
+    const int32_t g_hi = T - g_lo < chunks_per_group * kApplyChunk ? T : g_lo + chunks_per_group * kApplyChunk;
     const int32_t i = tensor[plan], o = out[plan], r = in[plan];
     const bool ok = static_cast<uint32_t>(i) < static_cast<uint32_t>(N) && o >= 0 && r <= T && r > o;
     const int64_t sz = ok ? size[i] : 0;
@@ -1144,30 +1145,37 @@ __global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(int32_t T, in
         }
         if (v < best.mn) best.mn = v;
     };
+    // the loads of a chunk are issued one chunk ahead (at clamped addresses past the end of the run)
+    ll2 nxt[4];
+    auto load_chunk = [&](int32_t lo) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int32_t t = lo + 2 * (j * kApplyThr + tid);
-        const bool in0 = t >= win_lo && t < win_hi, in1 = t + 1 >= win_lo && t + 1 < win_hi;
-        if (kVec16 && t + 2 <= hi) {
-            ll2 x = *reinterpret_cast<const ll2 *>(row + t);
+        for (int j = 0; j < 4; ++j) {
+            const int32_t t = lo + 2 * (j * kApplyThr + tid);
+            if (kVec16) nxt[j] = *reinterpret_cast<const ll2 *>(row + (t + 2 <= T ? t : T - 2));
+            else nxt[j] = ll2{row[t < T ? t : T - 1], row[t + 1 < T ? t + 1 : T - 1]};
+        }
+    };
+    load_chunk(g_lo);
+    for (int32_t lo = g_lo; lo < g_hi; lo += kApplyChunk) {
+        ll2 cur[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cur[j] = nxt[j];
+        if (lo + kApplyChunk < g_hi) load_chunk(lo + kApplyChunk);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int32_t t = lo + 2 * (j * kApplyThr + tid);
+            const bool in0 = t >= win_lo && t < win_hi, in1 = t + 1 >= win_lo && t + 1 < win_hi;
+            ll2 x = cur[j];
             x[0] -= in0 ? sz : 0;
             x[1] -= in1 ? sz : 0;
-            if (in0 && in1) *reinterpret_cast<ll2 *>(row + t) = x;
-            else if (in0) row[t] = x[0];
-            else if (in1) row[t + 1] = x[1];
-            take(t, x[0]);
-            take(t + 1, x[1]);
-        } else {
-            if (t < hi) {
-                const int64_t v = row[t] - (in0 ? sz : 0);
-                if (in0) row[t] = v;
-                take(t, v);
+            if (kVec16 && in0 && in1) {
+                *reinterpret_cast<ll2 *>(row + t) = x;     // (t + 1 < win_hi <= T: both steps exist)
+            } else {
+                if (in0) row[t] = x[0];
+                if (in1) row[t + 1] = x[1];
             }
-            if (t + 1 < hi) {
-                const int64_t v = row[t + 1] - (in1 ? sz : 0);
-                if (in1) row[t + 1] = v;
-                take(t + 1, v);
-            }
+            if (t < g_hi) take(t, x[0]);
+            if (t + 1 < g_hi) take(t + 1, x[1]);
         }
     }
 #pragma unroll
@@ -1185,7 +1193,7 @@ __global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(int32_t T, in
     if (tid == 0) {
 #pragma unroll
         for (int u = 1; u < kWaves; ++u) best_merge(best, red_mx[u], red_arg[u], red_mn[u]);
-        const int64_t slot = plan * S + chunk;
+        const int64_t slot = plan * S + group;
         out_max[slot] = best.mx;
         out_arg[slot] = best.arg;
         if (out_min) out_min[slot] = best.mn;
@@ -1198,10 +1206,16 @@ int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const
                  int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream) {
     if (B == 0) return TENSILE_OK;
     const int32_t T = tas->T;
-    const int64_t S = (static_cast<int64_t>(T) + kApplyChunk - 1) / kApplyChunk;
+    // a row is cut into runs of chunks, one workgroup each: one run per row when the batch fills the chip by
+    // itself (no partials, no second kernel), otherwise enough runs for about four workgroups per CU
+    const int64_t n_chunks = (static_cast<int64_t>(T) + kApplyChunk - 1) / kApplyChunk;
+    const int64_t want = (4 * static_cast<int64_t>(tas->num_cus) + B - 1) / B;
+    int64_t S = want < 1 ? 1 : want > n_chunks ? n_chunks : want;
+    const int64_t per_group = (n_chunks + S - 1) / S;
+    S = (n_chunks + per_group - 1) / per_group;
     const int64_t blocks = static_cast<int64_t>(B) * S;
     if (blocks > 0x7fffffffLL) {
-        set_error("apply_intervals: B*chunks = %lld workgroups exceeds the grid limit", static_cast<long long>(blocks));
+        set_error("apply_intervals: B*runs = %lld workgroups exceeds the grid limit", static_cast<long long>(blocks));
         return TENSILE_E_INVAL;
     }
     int64_t *out_max = peak, *out_min = min_resident;
@@ -1222,11 +1236,11 @@ int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const
     const bool vec16 = (T % 2 == 0) && (reinterpret_cast<uintptr_t>(resident) % 16 == 0);
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kApplyThr);
     if (vec16)
-        hipLaunchKernelGGL(apply_interval_kernel<true>, grid, block, 0, stream, T, tas->N, static_cast<int32_t>(S), tas->d_size.p,
-                           tensor, out, in, resident, out_max, out_arg, out_min);
+        hipLaunchKernelGGL(apply_interval_kernel<true>, grid, block, 0, stream, T, tas->N, static_cast<int32_t>(S),
+                           static_cast<int32_t>(per_group), tas->d_size.p, tensor, out, in, resident, out_max, out_arg, out_min);
     else
-        hipLaunchKernelGGL(apply_interval_kernel<false>, grid, block, 0, stream, T, tas->N, static_cast<int32_t>(S), tas->d_size.p,
-                           tensor, out, in, resident, out_max, out_arg, out_min);
+        hipLaunchKernelGGL(apply_interval_kernel<false>, grid, block, 0, stream, T, tas->N, static_cast<int32_t>(S),
+                           static_cast<int32_t>(per_group), tas->d_size.p, tensor, out, in, resident, out_max, out_arg, out_min);
     TS_HIP(hipGetLastError());
     if (S > 1) {
         const int fthreads = 256;
