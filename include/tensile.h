@@ -237,7 +237,8 @@ int tensile_apply_intervals(const tensile_tas *tas, int32_t B, const int32_t *te
  *   link_peak    DEVICE [B]   max_t link_b[t]
  *   link_argmax  DEVICE [B]   earliest step of the maximum; may be NULL
  *   overbooked   DEVICE [B]   number of steps with link_b[t] >= 2; may be NULL
- * Inapplicable intervals are skipped as in tensile_eval_plans.
+ * Inapplicable intervals are skipped as in tensile_eval_plans.  Sequences of
+ * more than 2^28 steps are refused (TENSILE_E_RANGE).
  * Asynchronous on hip_stream.  B == 0 is a no-op. */
 int tensile_eval_link(const tensile_tas *tas, const tensile_plans *plans, int32_t reuse_host_copies, int32_t *link,
                       int32_t *link_peak, int32_t *link_argmax, int32_t *overbooked, void *hip_stream);
