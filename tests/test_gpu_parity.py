@@ -158,6 +158,64 @@ def test_eval_persistent_grid(threads, T, B, slots, tail, monkeypatch):
     check_eval(tas, pl, label=f"persistent threads={threads} T={T}")
 
 
+# ---- seeded sweep over shapes and launch variants ----------------------------------------------
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_shapes_and_variants(case, monkeypatch):
+    """Every entry point on a seeded random shape (row length, batch, density, odd/even T) under a random
+    choice of the evaluator's launch variants (geometry, segments, binning, persistent grid)."""
+    rng = np.random.default_rng(9000 + case)
+    T = int(rng.choice([3, 17, 255, 256, 1000, 4095, 4097, 8190, 9001, 16385, 23456, 33333]))
+    B = int(rng.integers(1, 24))
+    N = max(1, min(int(rng.integers(1, 500)), T // 2))
+    timed = bool(rng.integers(0, 2))
+    threads = int(rng.choice([0, 512, 1024]))
+    segs = int(rng.choice([0, 0, 1, 2, 3]))
+    binned = int(rng.choice([-1, -1, 0, 1]))
+    pers = int(rng.choice([-1, 0, 1]))
+    if threads:
+        monkeypatch.setenv("TENSILE_EVAL_THREADS", str(threads))
+    if segs:
+        monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", str(segs))
+    if binned >= 0:
+        monkeypatch.setenv("TENSILE_EVAL_BINNED", str(binned))
+    if pers >= 0:
+        monkeypatch.setenv("TENSILE_EVAL_PERSISTENT", str(pers))
+        monkeypatch.setenv("TENSILE_EVAL_SLOTS", str(int(rng.integers(1, 6))))
+    tas = small_random_tas(9100 + case, N=N, T=T, max_acc=int(rng.integers(1, 7)) if T > 8 else 1, timed=timed,
+                           base_bytes=int(rng.integers(0, 1000)))
+    pl = merged_plans(tas, B, 50 + case, p_swap=float(rng.uniform(0.05, 0.95))) if T > 2 else plans_from_lists([[]] * B)
+    say(f"sweep {case}: T={T} B={B} N={N} K={pl.n_intervals} timed={timed} threads={threads} segs={segs} binned={binned} persistent={pers}")
+    h = P.tas_load(tas)
+    dp = upload(pl)
+    res, peak, arg, mn = gpu_eval(h, dp)
+    r0, p0, a0, m0 = O.eval_plans(tas, pl)
+    assert np.array_equal(res.cpu().numpy(), r0) and np.array_equal(peak.cpu().numpy(), p0)
+    assert np.array_equal(arg.cpu().numpy(), a0) and np.array_equal(mn.cpu().numpy(), m0)
+    _, peak2, arg2, _ = gpu_eval(h, dp, want_resident=False, want_min=False)
+    assert torch.equal(peak, peak2) and torch.equal(arg, arg2)
+    sc, wo, wi = gpu_score(h, dp, res, peak, arg)
+    s0, o0, i0 = O.score_plans(tas, pl, r0, p0, a0)
+    assert np.array_equal(sc.cpu().numpy(), s0) and np.array_equal(wo.cpu().numpy(), o0) and np.array_equal(wi.cpu().numpy(), i0)
+    P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)
+    torch.cuda.synchronize()
+    s1, o1, i1 = O.score_recompute_plans(tas, pl, r0, p0, a0)
+    assert np.array_equal(sc.cpu().numpy(), s1) and np.array_equal(wo.cpu().numpy(), o1) and np.array_equal(wi.cpu().numpy(), i1)
+    reuse = bool(rng.integers(0, 2))
+    rows, lpk, larg, lover = gpu_link(h, dp, reuse)
+    l0, lp0, la0, lo0 = O.link_occupancy(tas, pl, reuse=reuse)
+    assert np.array_equal(rows.cpu().numpy(), l0) and np.array_equal(lpk.cpu().numpy(), lp0)
+    assert np.array_equal(larg.cpu().numpy(), la0) and np.array_equal(lover.cpu().numpy(), lo0)
+    if T > 2:
+        t, o, r = extra_intervals(tas, B, 70 + case)
+        P.tensile_apply_intervals(h, torch.from_numpy(t).cuda(), torch.from_numpy(o).cuda(), torch.from_numpy(r).cuda(), res, peak, arg, mn)
+        torch.cuda.synchronize()
+        p1, a1, m1 = O.apply_intervals(tas, t, o, r, r0)
+        assert np.array_equal(res.cpu().numpy(), r0) and np.array_equal(peak.cpu().numpy(), p1)
+        assert np.array_equal(arg.cpu().numpy(), a1) and np.array_equal(mn.cpu().numpy(), m1)
+    h.close()
+
+
 # ---- windowed update ------------------------------------------------------------------------
 
 def extra_intervals(tas, B, seed):
