@@ -177,10 +177,21 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
 int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const int32_t *out, const int32_t *in,
                  int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream);
 // score.hip
-// (any_interval: an interval of the entry's tensor cancels the entry wherever it lies, not only inside the gap)
+// What one greedy iteration brings back from the device: the peak, its step and the tensors with a window.
+struct ScoreHeader {
+    int64_t P;
+    int32_t tstar, count;
+};
+struct ScoreCand {
+    int64_t score;
+    int32_t tensor, wo, wi, pad;
+};
+// (any_interval: an interval of the entry's tensor cancels the entry wherever it lies, not only inside the gap.
+//  compact != null, B == 1 only: instead of the dense rows, one record per tensor with a window, in no
+//  particular order, behind *hdr = {peak, peak step, number of records}; score/win_out/win_in are not touched.)
 int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
-                 int32_t *win_in, hipStream_t stream);
+                 int32_t *win_in, hipStream_t stream, ScoreHeader *hdr = nullptr, ScoreCand *compact = nullptr);
 // link.hip
 int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak, int32_t *argmax,
                 int32_t *overbooked, hipStream_t stream);

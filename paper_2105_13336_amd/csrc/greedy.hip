@@ -72,33 +72,9 @@ struct Cand {
     int32_t wo, wi;
 };
 
-// What one iteration brings back from the device: the peak, its step and the tensors with a window.
-struct Header {
-    int64_t P;
-    int32_t tstar, count;
-};
-struct CandOut {
-    int64_t score;
-    int32_t tensor, wo, wi, pad;
-};
+typedef ScoreHeader Header;
+typedef ScoreCand CandOut;
 constexpr int32_t kFirstCopy = 4096;   // candidates fetched together with the header
-
-// The tensors with a window, in no particular order (the host sorts them by a total order).
-__global__ __launch_bounds__(1024) void compact_candidates_kernel(int32_t N, const int64_t *score, const int32_t *wo,
-                                                                  const int32_t *wi, const int64_t *peak,
-                                                                  const int32_t *arg, Header *hdr, CandOut *out) {
-    __shared__ int32_t n;
-    if (threadIdx.x == 0) n = 0;
-    __syncthreads();
-    for (int32_t i = threadIdx.x; i < N; i += blockDim.x) {
-        const int32_t o = wo[i];
-        if (o < 0) continue;
-        const int32_t slot = atomicAdd(&n, 1);
-        out[slot] = CandOut{score[i], i, o, wi[i], 0};
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) *hdr = Header{*peak, *arg, n};
-}
 
 __global__ void peak_only_kernel(const int64_t *peak, const int32_t *arg, Header *hdr) { *hdr = Header{*peak, *arg, 0}; }
 
@@ -143,13 +119,12 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
 
     try {
         // device state: the growing plan (B = 1), one row of every output, the compacted candidates
-        DevBuf<int64_t> d_offs, d_res, d_peak, d_min, d_score;
-        DevBuf<int32_t> d_t, d_o, d_r, d_arg, d_wo, d_wi;
+        DevBuf<int64_t> d_offs, d_res, d_peak, d_min;
+        DevBuf<int32_t> d_t, d_o, d_r, d_arg;
         DevBuf<Header> d_hdr;           // header followed by the candidates, one allocation
         TS_HIP(d_offs.reserve(2));
         TS_HIP(d_t.reserve(capacity)); TS_HIP(d_o.reserve(capacity)); TS_HIP(d_r.reserve(capacity));
         TS_HIP(d_res.reserve(T)); TS_HIP(d_peak.reserve(1)); TS_HIP(d_min.reserve(1)); TS_HIP(d_arg.reserve(1));
-        TS_HIP(d_score.reserve(N)); TS_HIP(d_wo.reserve(N)); TS_HIP(d_wi.reserve(N));
         static_assert(sizeof(Header) == 16 && sizeof(CandOut) == 24, "layout of the iteration record");
         const size_t rec_bytes = sizeof(Header) + static_cast<size_t>(N) * sizeof(CandOut);
         TS_HIP(d_hdr.reserve((rec_bytes + sizeof(Header) - 1) / sizeof(Header)));
@@ -180,13 +155,12 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
         // header plus the first candidates in one copy, the rest only when there are more.
         tensile_plans pl{1, 0, d_offs.p, d_t.p, d_o.p, d_r.p, nullptr};
         auto score_and_fetch = [&](bool recompute_scores) -> int {
-            int rc = recompute_scores
-                         ? tensile_score_recompute(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_score.p, d_wo.p, d_wi.p, nullptr)
-                         : tensile_score_candidates(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_score.p, d_wo.p, d_wi.p, nullptr);
+            // the scoring kernel writes the record itself: {peak, peak step, count}, then one entry per tensor with a window
+            int rc = recompute_scores ? ensure_recompute_index(tas) : TENSILE_OK;
             if (rc != TENSILE_OK) return rc;
-            hipLaunchKernelGGL(compact_candidates_kernel, dim3(1), dim3(1024), 0, nullptr, N, d_score.p, d_wo.p, d_wi.p,
-                               d_peak.p, d_arg.p, d_hdr.p, d_cands);
-            TS_HIP(hipGetLastError());
+            rc = launch_score(tas, recompute_scores ? tas->recompute_index : tas->index, recompute_scores, &pl, d_res.p, d_peak.p,
+                              d_arg.p, nullptr, nullptr, nullptr, nullptr, d_hdr.p, d_cands);
+            if (rc != TENSILE_OK) return rc;
             const size_t first_bytes = sizeof(Header) + static_cast<size_t>(std::min(N, kFirstCopy)) * sizeof(CandOut);
             TS_HIP(hipMemcpyAsync(h_rec.p, d_hdr.p, first_bytes, hipMemcpyDeviceToHost, nullptr));
             TS_HIP(hipStreamSynchronize(nullptr));

@@ -84,6 +84,8 @@ struct ScoreArgs {
     int64_t *score;
     int32_t *win_out, *win_in;
     int64_t *tab_scratch;        // [gridDim.x][n_tab] when n_tab > kTabLds, else null
+    ScoreHeader *hdr;            // compact mode (B == 1): records instead of rows, see launch_score
+    ScoreCand *compact;
 };
 
 // row[0..n) = v with 16-byte stores where the row allows them
@@ -289,6 +291,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
     __shared__ uint32_t filter[kFilterWords];
     __shared__ int64_t span_max[kWaves];
     __shared__ int32_t span_bound[kWaves + 1];  // first step of every wavefront's span in the slice at hand, then T
+    __shared__ int32_t n_compact;               // records written so far (compact mode)
     int64_t *tab_global = kBigT ? a.tab_scratch + static_cast<int64_t>(blockIdx.x) * a.n_tab : nullptr;
     int32_t filter_of = -1;      // bucket whose filter is in LDS
     int32_t lists_of = -1;       // slice (numbered over all buckets) whose lists are in LDS
@@ -315,7 +318,10 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         const int32_t bk = has_peak ? tstar >> a.bucket_shift : 0;
         const int32_t e0 = a.bucket_off[bk], n_e = has_peak ? a.bucket_off[bk + 1] - e0 : 0;
         const bool staged = n_e <= kMaxLocal;
-        if (n_e == 0 || !staged) {
+        if (a.compact) {                            // (B == 1: one plan per launch)
+            if (tid == 0) n_compact = 0;
+            if (n_e == 0 && tid == 0) *a.hdr = ScoreHeader{P, tstar, 0};
+        } else if (n_e == 0 || !staged) {
             fill_row<int64_t>(score, a.N, 0, tid);
             if (wout) fill_row<int32_t>(wout, a.N, -1, tid);
             if (win) fill_row<int32_t>(win, a.N, -1, tid);
@@ -448,6 +454,10 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                     const int64_t sz = a.cand_size[e];
                     const int64_t v = acc[k];
                     if (!(c.z < tstar && tstar < c.y) || v == INT64_MAX) continue;
+                    if (a.compact) {
+                        a.compact[atomicAdd(&n_compact, 1)] = ScoreCand{final_score(c, sz, v), c.w, c.z, c.y, 0};
+                        continue;
+                    }
                     score[c.w] = final_score(c, sz, v);
                     if (wout) wout[c.w] = c.z;
                     if (win) win[c.w] = c.y;
@@ -459,6 +469,16 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                 // pieces of the rows, so that each output line goes to memory once.  The entries in tensor
                 // order, their o and q are all in LDS: this part reads nothing from global memory, and no
                 // wait for a load ever holds back the stores queued before it.
+                if (a.compact) {
+                    for (int32_t k = tid; k < n_e; k += kThreads) {
+                        const int4 c = a.cand[e0 + k];
+                        const int64_t sz = a.cand_size[e0 + k];
+                        const int64_t v = acc[k];
+                        if (c.z < tstar && tstar < c.y && v != INT64_MAX)
+                            a.compact[atomicAdd(&n_compact, 1)] = ScoreCand{final_score(c, sz, v), c.w, c.z, c.y, 0};
+                    }
+                    continue;   // (block-uniform; a staged bucket is one slice: this ends the slice loop)
+                }
                 for (int32_t k = tid; k < n_e; k += kThreads) {
                     const int4 c = a.cand[e0 + k];
                     const int64_t sz = a.cand_size[e0 + k];
@@ -536,6 +556,10 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
             }
             PROF_MARK(5);
         }
+        if (a.compact) {
+            __syncthreads();
+            if (tid == 0) *a.hdr = ScoreHeader{P, tstar, n_compact};
+        }
     }
 }
 
@@ -543,8 +567,9 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
 
 int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
-                 int32_t *win_in, hipStream_t stream) {
+                 int32_t *win_in, hipStream_t stream, ScoreHeader *hdr, ScoreCand *compact) {
     if (plans->B == 0 || tas->N == 0) return TENSILE_OK;
+    if (compact && (plans->B != 1 || !hdr)) { set_error("score: the compact form takes one plan"); return TENSILE_E_INVAL; }
     // as many workgroups as the device keeps resident, the plans dealt evenly among them
     const bool big_t = (tas->T + kMini - 1) / kMini > kTabLds;
     static int per_cu_of[2] = {0, 0};
@@ -574,6 +599,7 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     a.resident = resident; a.peak = peak; a.argmax = argmax;
     a.score = score; a.win_out = win_out; a.win_in = win_in;
     a.tab_scratch = nullptr;
+    a.hdr = hdr; a.compact = compact;
     if (a.n_tab > kTabLds) {
         Scratch &sc = tas->scratch;
         const size_t need = static_cast<size_t>(blocks) * static_cast<size_t>(a.n_tab);
