@@ -92,6 +92,7 @@ struct Scratch {
     DevBuf<int2> bin_recs;         // eval, binned mode: see EvalArgs
     DevBuf<int32_t> bin_off;
     DevBuf<int64_t> bin_sum;
+    DevBuf<unsigned int> apply_tickets;   // windowed update: finished runs per row (zero between launches)
     DevBuf<int32_t> link_first;    // link: earliest swap-out step per tensor, one row per workgroup (INT32_MAX between plans)
     DevBuf<int32_t> link_acc;      // link: one row per workgroup where the passes of a long plan add up
 };
@@ -174,8 +175,14 @@ namespace tensile {
 // eval.hip
 int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, int32_t *argmax, int64_t *min_resident,
                 hipStream_t stream);
+struct ApplyAppend {   // see launch_apply
+    int32_t tensor, out, in, n;
+    int32_t *plan_t, *plan_o, *plan_r;
+    int64_t *plan_offs;
+};
 int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const int32_t *out, const int32_t *in,
-                 int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream);
+                 int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream,
+                 const ApplyAppend *append_to = nullptr);
 // score.hip
 // What one greedy iteration brings back from the device: the peak, its step and the tensors with a window.
 struct ScoreHeader {

@@ -1119,24 +1119,45 @@ int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, i
 // outputs when a row is one run.  Reads 8 bytes per step, writes 8 per step of the window.
 constexpr int kApplyThr = 1024, kApplyChunk = kApplyThr * 8;
 
+struct ApplyArgs {
+    int32_t T, N, S, chunks_per_group;
+    const int64_t *size;
+    const int32_t *tensor, *out, *in;      // [B] the new intervals (unless `append`)
+    int64_t *resident;
+    int64_t *part_max, *part_min;          // [B*S] per-run partials when S > 1
+    int32_t *part_arg;
+    unsigned int *tickets;                 // [B] zero between launches: runs of a row that have finished (S > 1)
+    int64_t *peak, *min_resident;          // [B] results (min may be null)
+    int32_t *argmax;
+    // one plan whose new interval comes by value and is appended to the plan's device arrays on the way
+    int32_t append, one_tensor, one_out, one_in, plan_n;
+    int32_t *plan_t, *plan_o, *plan_r;
+    int64_t *plan_offs;
+};
+
 template <bool kVec16>
-__global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(int32_t T, int32_t N, int32_t S, int32_t chunks_per_group,
-                                                                   const int64_t *size, const int32_t *tensor, const int32_t *out,
-                                                                   const int32_t *in, int64_t *resident, int64_t *out_max,
-                                                                   int32_t *out_arg, int64_t *out_min) {
+__global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(const ApplyArgs a) {
     constexpr int kWaves = kApplyThr / 64;
     __shared__ int64_t red_mx[kWaves], red_mn[kWaves];
     __shared__ int32_t red_arg[kWaves];
+    const int32_t T = a.T, S = a.S;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t plan = blockIdx.x / S;
     const int32_t group = static_cast<int32_t>(blockIdx.x % S);     // this workgroup's run of chunks of the row
-    const int32_t g_lo = group * chunks_per_group * kApplyChunk;    // (fits: the host keeps S * chunks_per_group * chunk near T)
-    const int32_t g_hi = T - g_lo < chunks_per_group * kApplyChunk ? T : g_lo + chunks_per_group * kApplyChunk;
-    const int32_t i = tensor[plan], o = out[plan], r = in[plan];
-    const bool ok = static_cast<uint32_t>(i) < static_cast<uint32_t>(N) && o >= 0 && r <= T && r > o;
-    const int64_t sz = ok ? size[i] : 0;
+    const int32_t g_lo = group * a.chunks_per_group * kApplyChunk;  // (fits: the host keeps S * chunks_per_group * chunk near T)
+    const int32_t g_hi = T - g_lo < a.chunks_per_group * kApplyChunk ? T : g_lo + a.chunks_per_group * kApplyChunk;
+    const int32_t i = a.append ? a.one_tensor : a.tensor[plan], o = a.append ? a.one_out : a.out[plan],
+                  r = a.append ? a.one_in : a.in[plan];
+    if (a.append && blockIdx.x == 0 && tid == 0) {   // the plan's own arrays learn of the interval here
+        a.plan_t[a.plan_n] = i;
+        a.plan_o[a.plan_n] = o;
+        a.plan_r[a.plan_n] = r;
+        a.plan_offs[1] = a.plan_n + 1;
+    }
+    const bool ok = static_cast<uint32_t>(i) < static_cast<uint32_t>(a.N) && o >= 0 && r <= T && r > o;
+    const int64_t sz = ok ? a.size[i] : 0;
     const int32_t win_lo = ok ? o + 1 : 0, win_hi = ok ? r : 0;   // steps win_lo .. win_hi - 1 change
-    int64_t *row = resident + plan * T;
+    int64_t *row = a.resident + plan * T;
     Best best{INT64_MIN, INT64_MAX, INT32_MAX};
     auto take = [&](int32_t t, int64_t v) {   // (a thread meets its steps in ascending order)
         if (v > best.mx) {
@@ -1190,24 +1211,48 @@ __global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(int32_t T, in
         red_arg[wave] = best.arg;
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tid != 0) return;
 #pragma unroll
-        for (int u = 1; u < kWaves; ++u) best_merge(best, red_mx[u], red_arg[u], red_mn[u]);
+    for (int u = 1; u < kWaves; ++u) best_merge(best, red_mx[u], red_arg[u], red_mn[u]);
+    if (S > 1) {
+        // the run that finishes last combines the row's partials (they are in time order: a strict '>' keeps
+        // the earliest step) and leaves the ticket counter at zero for the next launch
         const int64_t slot = plan * S + group;
-        out_max[slot] = best.mx;
-        out_arg[slot] = best.arg;
-        if (out_min) out_min[slot] = best.mn;
+        a.part_max[slot] = best.mx;
+        a.part_arg[slot] = best.arg;
+        a.part_min[slot] = best.mn;
+        __threadfence();
+        if (atomicAdd(&a.tickets[plan], 1u) != static_cast<unsigned int>(S - 1)) return;
+        __threadfence();
+        best = Best{INT64_MIN, INT64_MAX, INT32_MAX};
+        for (int32_t s = 0; s < S; ++s) {
+            const int64_t mx = __hip_atomic_load(&a.part_max[plan * S + s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int64_t mn = __hip_atomic_load(&a.part_min[plan * S + s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int32_t arg = __hip_atomic_load(&a.part_arg[plan * S + s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (mx > best.mx) {
+                best.mx = mx;
+                best.arg = arg;
+            }
+            if (mn < best.mn) best.mn = mn;
+        }
+        __hip_atomic_store(&a.tickets[plan], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    a.peak[plan] = best.mx;
+    a.argmax[plan] = best.arg;
+    if (a.min_resident) a.min_resident[plan] = best.mn;
 }
 
 }  // namespace
 
+// append_to: null, or the device arrays {tensor, out, in} and offsets of a one-plan batch that receive the
+// interval (one_tensor, one_out, one_in) at position plan_n (B must be 1; the device arrays of intervals are not read)
 int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const int32_t *out, const int32_t *in,
-                 int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream) {
+                 int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream,
+                 const ApplyAppend *append_to) {
     if (B == 0) return TENSILE_OK;
     const int32_t T = tas->T;
     // a row is cut into runs of chunks, one workgroup each: one run per row when the batch fills the chip by
-    // itself (no partials, no second kernel), otherwise enough runs for about four workgroups per CU
+    // itself (no partials), otherwise enough runs for about four workgroups per CU
     const int64_t n_chunks = (static_cast<int64_t>(T) + kApplyChunk - 1) / kApplyChunk;
     const int64_t want = (4 * static_cast<int64_t>(tas->num_cus) + B - 1) / B;
     int64_t S = want < 1 ? 1 : want > n_chunks ? n_chunks : want;
@@ -1218,8 +1263,10 @@ int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const
         set_error("apply_intervals: B*runs = %lld workgroups exceeds the grid limit", static_cast<long long>(blocks));
         return TENSILE_E_INVAL;
     }
-    int64_t *out_max = peak, *out_min = min_resident;
-    int32_t *out_arg = argmax;
+    ApplyArgs a{};
+    a.T = T; a.N = tas->N; a.S = static_cast<int32_t>(S); a.chunks_per_group = static_cast<int32_t>(per_group);
+    a.size = tas->d_size.p; a.tensor = tensor; a.out = out; a.in = in; a.resident = resident;
+    a.peak = peak; a.argmax = argmax; a.min_resident = min_resident;
     if (S > 1) {
         Scratch &sc = tas->scratch;
         const size_t n = static_cast<size_t>(blocks);
@@ -1229,25 +1276,25 @@ int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const
             TS_HIP(sc.part_arg.reserve(n));
             TS_HIP(sc.part_min.reserve(n));
         }
-        out_max = sc.part_max.p;
-        out_arg = sc.part_arg.p;
-        out_min = sc.part_min.p;
+        if (sc.apply_tickets.n < static_cast<size_t>(B)) {
+            TS_HIP(hipDeviceSynchronize());
+            TS_HIP(sc.apply_tickets.reserve(static_cast<size_t>(B)));
+            TS_HIP(hipMemset(sc.apply_tickets.p, 0, sc.apply_tickets.n * sizeof(unsigned int)));
+        }
+        a.part_max = sc.part_max.p; a.part_arg = sc.part_arg.p; a.part_min = sc.part_min.p;
+        a.tickets = sc.apply_tickets.p;
+    }
+    if (append_to) {
+        if (B != 1) { set_error("apply_intervals: appending takes one plan"); return TENSILE_E_INVAL; }
+        a.append = 1;
+        a.one_tensor = append_to->tensor; a.one_out = append_to->out; a.one_in = append_to->in; a.plan_n = append_to->n;
+        a.plan_t = append_to->plan_t; a.plan_o = append_to->plan_o; a.plan_r = append_to->plan_r; a.plan_offs = append_to->plan_offs;
     }
     const bool vec16 = (T % 2 == 0) && (reinterpret_cast<uintptr_t>(resident) % 16 == 0);
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kApplyThr);
-    if (vec16)
-        hipLaunchKernelGGL(apply_interval_kernel<true>, grid, block, 0, stream, T, tas->N, static_cast<int32_t>(S),
-                           static_cast<int32_t>(per_group), tas->d_size.p, tensor, out, in, resident, out_max, out_arg, out_min);
-    else
-        hipLaunchKernelGGL(apply_interval_kernel<false>, grid, block, 0, stream, T, tas->N, static_cast<int32_t>(S),
-                           static_cast<int32_t>(per_group), tas->d_size.p, tensor, out, in, resident, out_max, out_arg, out_min);
+    if (vec16) hipLaunchKernelGGL(apply_interval_kernel<true>, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(apply_interval_kernel<false>, grid, block, 0, stream, a);
     TS_HIP(hipGetLastError());
-    if (S > 1) {
-        const int fthreads = 256;
-        hipLaunchKernelGGL(eval_finalize_kernel, dim3((B + fthreads - 1) / fthreads), dim3(fthreads), 0, stream, B,
-                           static_cast<int32_t>(S), out_max, out_arg, out_min, peak, argmax, min_resident);
-        TS_HIP(hipGetLastError());
-    }
     return TENSILE_OK;
 }
 

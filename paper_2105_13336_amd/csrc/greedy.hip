@@ -78,15 +78,6 @@ constexpr int32_t kFirstCopy = 4096;   // candidates fetched together with the h
 
 __global__ void peak_only_kernel(const int64_t *peak, const int32_t *arg, Header *hdr) { *hdr = Header{*peak, *arg, 0}; }
 
-// Appends one interval to the device copy of the plan (B = 1) and moves its end offset.
-__global__ void append_interval_kernel(int32_t *t, int32_t *o, int32_t *r, int64_t *offs, int32_t n, int32_t tensor,
-                                       int32_t out, int32_t in) {
-    t[n] = tensor;
-    o[n] = out;
-    r[n] = in;
-    offs[1] = n + 1;
-}
-
 // Pinned host memory that frees itself.
 struct PinnedBuf {
     void *p = nullptr;
@@ -171,13 +162,12 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
             }
             return TENSILE_OK;
         };
+        // (the device copy of the plan receives the interval from the next iteration's update kernel)
         auto append = [&](int32_t i, int32_t o, int32_t r, uint8_t kind) -> int {
             iv_tensor[n] = i;
             iv_out[n] = o;
             iv_in[n] = r;
             iv_kind[n] = kind;
-            hipLaunchKernelGGL(append_interval_kernel, dim3(1), dim3(1), 0, nullptr, d_t.p, d_o.p, d_r.p, d_offs.p, n, i, o, r);
-            TS_HIP(hipGetLastError());
             ++n;
             return TENSILE_OK;
         };
@@ -187,29 +177,20 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
         int32_t tstar_now = 0;
         auto try_swap = [&]() -> bool {
             const int32_t tstar = tstar_now;
-            cand.clear();
             const int64_t tot = std::max<int64_t>(1, swapped_total);
-            for (int32_t k = 0; k < hdr->count; ++k) {
-                const CandOut &c = h_cands[k];
-                if (opt.msr_num) {
-                    const int32_t j = tas->h_job[c.tensor];
-                    if (!(swapped[j] * opt.msr_den <= opt.msr_num[j] * tot)) continue;
-                }
-                cand.push_back(Cand{c.tensor, c.score, tas->h_size[c.tensor], c.wo, c.wi});
-            }
-            // candidates are tried in the order (score desc, size desc, tensor asc); usually one of the
-            // first few is accepted, so a heap is popped instead of sorting them all
+            auto allowed = [&](const CandOut &c) {      // the job's swapping rate limit (section IV-C)
+                if (!opt.msr_num) return true;
+                const int32_t j = tas->h_job[c.tensor];
+                return swapped[j] * opt.msr_den <= opt.msr_num[j] * tot;
+            };
+            // candidates are tried in the order (score desc, size desc, tensor asc)
             auto later = [](const Cand &a, const Cand &b) {      // a comes after b
                 if (a.score != b.score) return a.score < b.score;
                 if (a.size != b.size) return a.size < b.size;
                 return a.tensor > b.tensor;
             };
-            std::make_heap(cand.begin(), cand.end(), later);
-
-            bool accepted = false;
-            for (auto end = cand.end(); end != cand.begin(); --end) {
-                std::pop_heap(cand.begin(), end, later);
-                const Cand &c = *(end - 1);
+            // 1 accepted, 0 cannot be placed around the peak, -1 error
+            auto place = [&](const Cand &c) -> int {
                 const int32_t i = c.tensor;
                 const int32_t q = c.wi;                          // p_{g+1}
                 // p_g: the touch point just before q in the tensor's list
@@ -219,24 +200,50 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
                 const int64_t x = tas->h_x[i];
                 int32_t o_placed = p, r_placed = q, a = -1, e = -1, cs = -1, d = -1;
                 if (x != 0) {
-                    if (!link.place_earliest(p + 1, q - 1, x, &a, &e)) continue;
-                    if (!link.place_latest(e + 1, q - 1, x, &cs, &d)) continue;
+                    if (!link.place_earliest(p + 1, q - 1, x, &a, &e)) return 0;
+                    if (!link.place_latest(e + 1, q - 1, x, &cs, &d)) return 0;
                     o_placed = e;
                     r_placed = d + 1;
                 }
-                if (!(o_placed < tstar && tstar < r_placed)) continue;
+                if (!(o_placed < tstar && tstar < r_placed)) return 0;
                 if (x != 0) {
                     link.occupy(a, e);
                     link.occupy(cs, d);
                 }
                 const int rc_append = append(i, o_placed, r_placed, 0);
-                if (rc_append != TENSILE_OK) { swap_error = rc_append; return false; }
+                if (rc_append != TENSILE_OK) { swap_error = rc_append; return -1; }
                 ++swapped[tas->h_job[i]];
                 ++swapped_total;
-                accepted = true;
-                break;
+                return 1;
+            };
+            // usually the very first candidate is accepted: find it by one pass over the record ...
+            bool have = false;
+            Cand first{};
+            for (int32_t k = 0; k < hdr->count; ++k) {
+                const CandOut &c = h_cands[k];
+                if (!allowed(c)) continue;
+                const Cand cur{c.tensor, c.score, tas->h_size[c.tensor], c.wo, c.wi};
+                if (!have || later(first, cur)) {
+                    first = cur;
+                    have = true;
+                }
             }
-                        return accepted;
+            if (!have) return false;
+            int got = place(first);
+            if (got != 0) return got > 0;
+            // ... and only when it cannot be placed order the rest (a heap is popped instead of sorting them all)
+            cand.clear();
+            for (int32_t k = 0; k < hdr->count; ++k) {
+                const CandOut &c = h_cands[k];
+                if (allowed(c) && c.tensor != first.tensor) cand.push_back(Cand{c.tensor, c.score, tas->h_size[c.tensor], c.wo, c.wi});
+            }
+            std::make_heap(cand.begin(), cand.end(), later);
+            for (auto end = cand.end(); end != cand.begin(); --end) {
+                std::pop_heap(cand.begin(), end, later);
+                got = place(*(end - 1));
+                if (got != 0) return got > 0;
+            }
+            return false;
         };
 
         bool swap_phase = true;
@@ -248,9 +255,13 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
             pl.n_intervals = n;
             // the first footprint comes from the whole plan; afterwards exactly one interval has joined
             // since the last analysis and only its window of the row is brought up to date
-            int rc = it == 0 ? tensile_eval_plans(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr)
-                             : tensile_apply_intervals(tas, 1, d_t.p + (n - 1), d_o.p + (n - 1), d_r.p + (n - 1), d_res.p,
-                                                       d_peak.p, d_arg.p, d_min.p, nullptr);
+            int rc;
+            if (it == 0) {
+                rc = tensile_eval_plans(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr);
+            } else {
+                const ApplyAppend last_one{iv_tensor[n - 1], iv_out[n - 1], iv_in[n - 1], n - 1, d_t.p, d_o.p, d_r.p, d_offs.p};
+                rc = launch_apply(tas, 1, nullptr, nullptr, nullptr, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr, &last_one);
+            }
             if (rc != TENSILE_OK) return rc;
             if (last) {
                 hipLaunchKernelGGL(peak_only_kernel, dim3(1), dim3(1), 0, nullptr, d_peak.p, d_arg.p, d_hdr.p);
