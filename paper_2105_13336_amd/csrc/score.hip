@@ -278,7 +278,18 @@ __device__ unsigned long long g_score_prof[8];
 
 // kBigT: the table of block maxima does not fit in LDS and lives in global scratch.
 // kVec: the footprint rows are 16-byte aligned and T is even (two steps per load).
-template <bool kBigT, bool kVec>
+// A load whose address is the same in every lane, from memory that no kernel writes during this
+// launch: through the constant address space it goes to the scalar unit and its result lives in
+// scalar registers (as a vector load it would hold one register per lane for as long as the value lives).
+template <typename T>
+__device__ __forceinline__ T uniform_load(const T *p, int64_t i) {
+    typedef const T __attribute__((address_space(4))) *const_ptr;
+    return ((const_ptr)p)[i];
+}
+
+// kCompact: one plan, records instead of rows (see launch_score); a separate instantiation so that the
+// batch kernel carries none of it (with both in one kernel the register allocator spilled once per plan).
+template <bool kBigT, bool kVec, bool kCompact>
 __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
     __shared__ int64_t acc[kMaxLocal];
     __shared__ int32_t lo_list[kMaxLocal];      // o of the slice's entries (its o order is the entries' own order)
@@ -305,8 +316,8 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         int tid = threadIdx.x;
         asm volatile("" : "+v"(tid));
         const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-        const int32_t tstar = a.argmax[b];
-        const int64_t P = a.peak[b];
+        const int32_t tstar = uniform_load(a.argmax, b);
+        const int64_t P = uniform_load(a.peak, b);
         const int64_t *MF = a.resident + static_cast<int64_t>(b) * a.T;
         int64_t *score = a.score + static_cast<int64_t>(b) * a.N;
         int32_t *wout = a.win_out ? a.win_out + static_cast<int64_t>(b) * a.N : nullptr;
@@ -316,9 +327,9 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         // once, in step 4; otherwise they are cleared here and the candidates written over them.
         const bool has_peak = tstar >= 0 && tstar < a.T;     // else not produced by the evaluator: no candidate
         const int32_t bk = has_peak ? tstar >> a.bucket_shift : 0;
-        const int32_t e0 = a.bucket_off[bk], n_e = has_peak ? a.bucket_off[bk + 1] - e0 : 0;
+        const int32_t e0 = uniform_load(a.bucket_off, bk), n_e = has_peak ? uniform_load(a.bucket_off, bk + 1) - e0 : 0;
         const bool staged = n_e <= kMaxLocal;
-        if (a.compact) {                            // (B == 1: one plan per launch)
+        if (kCompact) {                             // (B == 1: one plan per launch)
             if (tid == 0) n_compact = 0;
             if (n_e == 0 && tid == 0) *a.hdr = ScoreHeader{P, tstar, 0};
         } else if (n_e == 0 || !staged) {
@@ -327,9 +338,10 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
             if (win) fill_row<int32_t>(win, a.N, -1, tid);
         }
         if (n_e == 0) continue;                    // no gap around t* can be swapped in time
-        const int32_t slice0 = a.slice_first[bk];
-        const int2 hd = a.hash_dir[bk];
-        int64_t k0 = a.plan_offsets[b], k1 = a.plan_offsets[b + 1];
+        const int32_t slice0 = uniform_load(a.slice_first, bk);
+        const int32_t *hash_dir = reinterpret_cast<const int32_t *>(a.hash_dir);
+        const int2 hd = make_int2(uniform_load(hash_dir, 2 * bk), uniform_load(hash_dir, 2 * bk + 1));
+        int64_t k0 = uniform_load(a.plan_offsets, b), k1 = uniform_load(a.plan_offsets, b + 1);
         if (k0 < 0) k0 = 0;
         if (k1 > a.n_intervals) k1 = a.n_intervals;
         PROF_MARK(0);
@@ -340,7 +352,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
             const int32_t *wp = a.wave_ptr + static_cast<int64_t>(slice_id) * 4 * (kWaves + 1);
             // the wavefronts' spans of the row: the slice's own boundaries (multiples of kMini, the last one T),
             // chosen when the index is built so that steps and entries together are spread evenly
-            const int32_t span_lo = wp[3 * (kWaves + 1) + wave], span_hi = wp[3 * (kWaves + 1) + wave + 1];
+            const int32_t span_lo = uniform_load(wp, 3 * (kWaves + 1) + wave), span_hi = uniform_load(wp, 3 * (kWaves + 1) + wave + 1);
             __syncthreads();   // the previous plan or slice has finished with acc, tab, span_max, the filter, the lists
             for (int32_t k = tid; k < n_slice; k += kThreads) acc[k] = INT64_MIN;
             if (lists_of != slice_id) {
@@ -412,8 +424,8 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
 
             // ---- 3: stream the row (no barrier needed after step 2: +inf survives every max)
             {
-                const int32_t lo_begin = wp[wave], lo_end = wp[wave + 1];
-                const int32_t hi_begin = wp[kWaves + 1 + wave], hi_end = wp[kWaves + 1 + wave + 1];
+                const int32_t lo_begin = uniform_load(wp, wave), lo_end = uniform_load(wp, wave + 1);
+                const int32_t hi_begin = uniform_load(wp, kWaves + 1 + wave), hi_end = uniform_load(wp, kWaves + 1 + wave + 1);
                 int64_t m;
                 if (kBigT)
                     m = stream_span<kVec>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
@@ -454,7 +466,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                     const int64_t sz = a.cand_size[e];
                     const int64_t v = acc[k];
                     if (!(c.z < tstar && tstar < c.y) || v == INT64_MAX) continue;
-                    if (a.compact) {
+                    if (kCompact) {
                         a.compact[atomicAdd(&n_compact, 1)] = ScoreCand{final_score(c, sz, v), c.w, c.z, c.y, 0};
                         continue;
                     }
@@ -469,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
                 // pieces of the rows, so that each output line goes to memory once.  The entries in tensor
                 // order, their o and q are all in LDS: this part reads nothing from global memory, and no
                 // wait for a load ever holds back the stores queued before it.
-                if (a.compact) {
+                if (kCompact) {
                     for (int32_t k = tid; k < n_e; k += kThreads) {
                         const int4 c = a.cand[e0 + k];
                         const int64_t sz = a.cand_size[e0 + k];
@@ -556,7 +568,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
             }
             PROF_MARK(5);
         }
-        if (a.compact) {
+        if (kCompact) {
             __syncthreads();
             if (tid == 0) *a.hdr = ScoreHeader{P, tstar, n_compact};
         }
@@ -576,8 +588,8 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     int &per_cu = per_cu_of[big_t ? 1 : 0];
     if (per_cu == 0) {
         int n = 0;
-        if (big_t) TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<true, true>, kThreads, 0));
-        else TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<false, true>, kThreads, 0));
+        if (big_t) TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<true, true, false>, kThreads, 0));
+        else TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<false, true, false>, kThreads, 0));
         per_cu = n > 0 ? n : 1;
     }
     const int64_t resident_blocks = static_cast<int64_t>(tas->num_cus) * per_cu;
@@ -609,13 +621,19 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
         }
         a.tab_scratch = sc.score_tab.p;
     }
+#define TS_LAUNCH_SCORE(BIG, VEC)                                                                                      \
+    do {                                                                                                               \
+        if (compact) hipLaunchKernelGGL((score_kernel<BIG, VEC, true>), dim3(blocks), dim3(kThreads), 0, stream, a);   \
+        else hipLaunchKernelGGL((score_kernel<BIG, VEC, false>), dim3(blocks), dim3(kThreads), 0, stream, a);          \
+    } while (0)
     if (big_t) {
-        if (a.vec16) hipLaunchKernelGGL((score_kernel<true, true>), dim3(blocks), dim3(kThreads), 0, stream, a);
-        else hipLaunchKernelGGL((score_kernel<true, false>), dim3(blocks), dim3(kThreads), 0, stream, a);
+        if (a.vec16) TS_LAUNCH_SCORE(true, true);
+        else TS_LAUNCH_SCORE(true, false);
     } else {
-        if (a.vec16) hipLaunchKernelGGL((score_kernel<false, true>), dim3(blocks), dim3(kThreads), 0, stream, a);
-        else hipLaunchKernelGGL((score_kernel<false, false>), dim3(blocks), dim3(kThreads), 0, stream, a);
+        if (a.vec16) TS_LAUNCH_SCORE(false, true);
+        else TS_LAUNCH_SCORE(false, false);
     }
+#undef TS_LAUNCH_SCORE
     TS_HIP(hipGetLastError());
     return TENSILE_OK;
 }
