@@ -116,7 +116,12 @@ int tensile_tas_base_timeline(const tensile_tas *tas, int64_t *mf0_host);
 
 /* A batch of B plans in CSR form.  DEVICE pointers, caller-owned, read-only.
  * Intervals of plan b are entries plan_offsets[b] .. plan_offsets[b+1]-1, in
- * any order. */
+ * any order.  Performance note: the kernels size their per-thread interval
+ * lists from n_intervals / B, the only length the host knows without reading
+ * the offsets back.  A batch that is a window into larger arrays (offsets that
+ * start far above 0 or end far below n_intervals) is still evaluated exactly,
+ * but with lists sized for plans it does not hold; pass the window's own
+ * arrays and rebased offsets instead. */
 typedef struct {
     int32_t B;                   /* plans, >= 0                                                     */
     int64_t n_intervals;         /* length of the four interval arrays (host-known)                 */
