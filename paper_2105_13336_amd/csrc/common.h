@@ -97,6 +97,10 @@ struct Scratch {
     DevBuf<int32_t> link_acc;      // link: one row per workgroup where the passes of a long plan add up
 };
 
+// C for the link kernel's searches (see link.hip): blocks of kLinkCBlock consecutive values, each block's six
+// differences packed into 16 bytes, 21 bits each (built when every operator latency is below 2^21 ns).
+constexpr int kLinkCBlock = 7;
+
 // Per-job tables of tensile_eval_plans_per_job (see tas.hip), job-major.
 struct JobTables {
     bool built = false;
@@ -158,6 +162,8 @@ struct tensile_tas {
     tensile::DevBuf<uint32_t> d_size_units;   // empty when the sizes do not fit (see EvalArgs)
     int32_t size_shift = 0;
     tensile::DevBuf<int32_t> d_touch;
+    tensile::DevBuf<uint4> d_Cpack;           // [T / kLinkCBlock + 1] when c_packed
+    bool c_packed = false;
     tensile::CandIndex index;                 // swap candidates: o = earliest feasible swap-out step
     // recomputation candidates (every gap, o = p), built by the first tensile_score_recompute
     mutable tensile::CandIndex recompute_index;

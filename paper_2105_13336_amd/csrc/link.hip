@@ -12,18 +12,28 @@
 //
 // One persistent workgroup of 1024 threads per CU walks the plans slot, slot + grid, ...:
 //  * the start step of a transfer is a search in C: first in a table of every stride-th value kept in
-//    LDS for the whole launch (8192 entries), then log2(stride) probes of C itself (L2 resident); a
-//    thread's twelve searches run in lockstep, one probe each per round, so that their latencies overlap;
+//    LDS for the whole launch (up to 7167 entries), then, when every operator latency is below 2^21 ns,
+//    one 16-byte load of the block of seven values the table entry starts (see link_kernel), else
+//    log2(stride) probes of C itself (L2 resident); a thread's twelve searches run in lockstep, one
+//    probe each per round, so that their latencies overlap;
 //  * the four endpoints of an interval (+1 at s, -1 at o+1, +1 at s', -1 at r) stay in registers, six
 //    intervals per thread; a longer plan takes several passes of 6144 intervals, each over all tiles,
 //    and the passes add up in the output row (or in a scratch row per workgroup when no rows are
 //    wanted): occupancy is additive over the intervals;
-//  * per tile of 8192 steps: scatter into an int32 difference tile in LDS, barrier, each lane scans its
-//    8 cells (and zeroes them for the next tile), DPP wave scan, wave totals through LDS, barrier,
-//    reduce (max, earliest argmax, steps occupied twice), and the row leaves through a per-wavefront
-//    staging area as 16 contiguous bytes per lane;
+//  * per tile of 32768 steps: scatter into a difference tile in LDS that packs two steps into one 32-bit
+//    word (16-bit counters: a pass holds at most 12288 endpoints, so every count and every prefix of
+//    counts fits; the adds are done on the whole word, +-1 or +-65536, and the two halves are taken apart
+//    after the scatter, which is exact because sums are linear modulo 2^32), barrier; each wavefront owns
+//    2048 consecutive steps of the tile as four blocks of 512: per block each lane takes one 16-byte
+//    granule (8 steps), clears it for the next tile, scans locally and across the wave (DPP), blocks
+//    chained through the wavefront's running total; wave totals through LDS, barrier; then per block
+//    reduce (max, earliest argmax, steps occupied twice) and the row leaves through a per-wavefront
+//    staging area as 16 contiguous bytes per lane.  Large tiles matter because every tile tests every
+//    endpoint held in registers: the scatter of a 50,000-step row costs two rounds instead of seven;
 //  * reuse: a table of the earliest swap-out step per tensor (one row of N entries per workgroup in
 //    global memory, L2 atomics) is filled before a plan's first pass and cleaned after its last.
+#include <cstdlib>
+
 #include "common.h"
 #include "wave_ops.h"
 
@@ -32,17 +42,23 @@ namespace tensile {
 namespace {
 
 constexpr int kThr = 1024, kWaves = kThr / 64;
-constexpr int kVpt = 8;                              // steps per lane per tile
-constexpr int kTile = kThr * kVpt;                   // 8192
+constexpr int kVpt = 8;                              // steps per lane per block (one 16-byte granule of packed counters)
+constexpr int kSub = 4;                              // blocks per wavefront and tile
+constexpr int kBlock = 64 * kVpt;                    // 512 steps
+constexpr int kWaveSteps = kSub * kBlock;            // 2048 steps per wavefront and tile
+constexpr int kTile = kWaves * kWaveSteps;           // 32768
+constexpr int kTileWords = kTile / 2;                // two 16-bit counters per word: 64 KB
 constexpr int kR = 6;                                // intervals per thread and pass
-constexpr int kPass = kR * kThr;                     // 6144
-constexpr int kTabBits = 13, kTabMax = 1 << kTabBits; // entries of the coarse table of C (64 KB of LDS)
-// LDS layouts are skewed by one 16-byte granule per 16 granules (cell u lives at u + 4 * (u >> 6)): both
+constexpr int kPass = kR * kThr;                     // 6144 (at most 2 * kPass endpoints per step: far below 2^15)
+// Coarse table of C in LDS: the descent runs over kTabBits bits, indices are clamped to the last entry,
+// which always holds +inf (the host keeps the number of real entries below kTabMax).
+constexpr int kTabBits = 13, kTabMax = 7168;
+static_assert(kTabMax <= (1 << kTabBits) && 2 * kPass < (1 << 15), "table descent / 16-bit counters");
+// The staging area is skewed by one 16-byte granule per 16 granules (cell u lives at u + 4 * (u >> 6)): both
 // the lane-contiguous pattern (8 cells per lane) and the striped one (one granule per lane) are then
-// free of bank conflicts.  A lane's two granules never straddle a multiple of 16.
-constexpr int kTileCells = kTile + 4 * (kTile >> 6);
-constexpr int kStageCells = 64 * kVpt + 4 * ((64 * kVpt) >> 6);   // 544 per wavefront
-__device__ __forceinline__ uint32_t skew(uint32_t u) { return u + ((u >> 6) << 2); }
+// free of bank conflicts.  A lane's two granules never straddle a multiple of 16.  The difference tile
+// needs no skew: it is read one granule per lane, lanes side by side.
+constexpr int kStageCells = kBlock + 4 * (kBlock >> 6);   // 544 per wavefront
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
@@ -56,7 +72,9 @@ struct LinkArgs {
     const int64_t *C;              // [T+1]
     const int64_t *x;              // [N]
     int32_t tab_stride, n_tab;     // coarse table: C[k * tab_stride], k < n_tab
-    int32_t fine_bits;             // ceil(log2(tab_stride))
+    int32_t fine_bits;             // probe rounds after the table: ceil(log2(tab_stride)), packed: ceil(log2(blocks_per_entry))
+    const uint4 *Cpack;            // packed mode: per block of kCBlock steps the differences of its C values (see tas.hip)
+    int32_t blocks_per_entry;      // packed mode: tab_stride / kCBlock
     int32_t *first_out;            // [grid][N], INT32_MAX everywhere between plans (reuse only)
     int32_t *acc_rows;             // [grid][T] scratch rows for plans of several passes when link == null
     int32_t *link;                 // [B*T] or null
@@ -90,15 +108,22 @@ __device__ unsigned long long g_link_prof[8];
 #define LINK_MARK(k) do { } while (0)
 #endif
 
+// kPacked: every operator latency is below 2^21 ns and the host has packed C in blocks of kLinkCBlock = 7
+// steps, 16 bytes each: the six 21-bit differences between the block's values.  A search then ends with
+// ONE 16-byte load (the block's first value comes from the table or from the last probe) instead of three
+// dependent 8-byte probes; with the table covering every block (rows up to 50,168 steps) it is the only
+// load of the search.  The searches are bound by the number of scattered loads (the texture unit takes
+// one lane's cache line per cycle), not by their latency.
+template <bool kPacked>
 __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
-    __shared__ __attribute__((aligned(16))) int32_t delta[kTileCells];
+    __shared__ __attribute__((aligned(16))) uint32_t delta[kTileWords];
     __shared__ __attribute__((aligned(16))) int32_t stage_all[kWaves * kStageCells];
     __shared__ int64_t tab[kTabMax];
     __shared__ int32_t wave_tot[kWaves];
     __shared__ int32_t red_mx[kWaves], red_arg[kWaves], red_over[kWaves];
 
     for (int k = threadIdx.x; k < kTabMax; k += kThr) tab[k] = k < a.n_tab ? a.C[static_cast<int64_t>(k) * a.tab_stride] : INT64_MAX;
-    for (int u = threadIdx.x; u < kTileCells; u += kThr) delta[u] = 0;
+    for (int u = threadIdx.x; u < kTileWords; u += kThr) delta[u] = 0;
     __syncthreads();
 
     // C[k] through the uniform base and a 32-bit byte offset (the host keeps T below 2^28): no 64-bit
@@ -116,9 +141,6 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
         int tid_now = threadIdx.x;
         asm volatile("" : "+v"(tid_now));
         const int tid = tid_now, lane = tid & 63, wave = tid >> 6;
-        const int my = tid * kVpt;
-        const int my_cell = static_cast<int>(skew(my));
-        int32_t *stage = stage_all + wave * kStageCells;
         int64_t k0 = a.plan_offsets[plan], k1 = a.plan_offsets[plan + 1];
         if (k0 < 0) k0 = 0;
         if (k1 > a.n_intervals) k1 = a.n_intervals;
@@ -146,7 +168,7 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
 
         for (int64_t pass = 0; pass < n_pass; ++pass) {
             const bool first = pass == 0, last = pass == n_pass - 1;
-            // ---- this pass's intervals: endpoints in the skewed numbering, UINT32_MAX = none.
+            // ---- this pass's intervals: their endpoints (steps), UINT32_MAX = none.
             // Every load is issued for all kR intervals before the first is used, at clamped indices, and the
             // 2 * kR searches (start of the swap-out, start of the swap-in) advance together, one probe
             // each per round: a search alone is a chain of dependent memory latencies.
@@ -160,7 +182,7 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
                 uint32_t kind[kR];
 #pragma unroll
                 for (int j = 0; j < kR; ++j) {
-                    const uint32_t k = tid * kR + j;
+                    const uint32_t k = j * kThr + tid;   // (lanes side by side: every load is two whole lines per wavefront)
                     ok[j] = k < len;
                     const int64_t kc = kb + (ok[j] ? k : 0);
                     const bool any = len > 0;
@@ -203,34 +225,100 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
                         const uint32_t cand = pos[j][q] | (1u << bit);
-                        pos[j][q] = tab[cand] <= v[j][q] ? cand : pos[j][q];
+                        pos[j][q] = tab[cand < kTabMax - 1 ? cand : kTabMax - 1] <= v[j][q] ? cand : pos[j][q];
                     }
                 }
             }
-            // fine: from the block's first step, forward by decreasing powers of two while C stays <= v.  C increases,
-            // so a probe beyond the block (or beyond the transfer's end) fails by itself; only the array's end needs a guard.
             LINK_MARK(3);
-#pragma unroll
-            for (int j = 0; j < kR; ++j) {
-                pos[j][0] *= a.tab_stride;
-                pos[j][1] *= a.tab_stride;
-            }
-            for (int bit = a.fine_bits - 1; bit >= 0; --bit) {   // (uniform)
-                int64_t c[kR][2];
+            if constexpr (!kPacked) {
+                // fine: from the block's first step, forward by decreasing powers of two while C stays <= v.  C increases,
+                // so a probe beyond the block (or beyond the transfer's end) fails by itself; only the array's end needs a guard.
 #pragma unroll
                 for (int j = 0; j < kR; ++j) {
+                    pos[j][0] *= a.tab_stride;
+                    pos[j][1] *= a.tab_stride;
+                }
+                for (int bit = a.fine_bits - 1; bit >= 0; --bit) {   // (uniform)
+                    int64_t c[kR][2];
 #pragma unroll
-                    for (int q = 0; q < 2; ++q) {
-                        const uint32_t at = pos[j][q] + (1u << bit);
-                        c[j][q] = c_at(at <= static_cast<uint32_t>(a.T) ? at : static_cast<uint32_t>(a.T));
+                    for (int j = 0; j < kR; ++j) {
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            const uint32_t at = pos[j][q] + (1u << bit);
+                            c[j][q] = c_at(at <= static_cast<uint32_t>(a.T) ? at : static_cast<uint32_t>(a.T));
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < kR; ++j) {
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            const uint32_t at = pos[j][q] + (1u << bit);
+                            pos[j][q] = (at <= static_cast<uint32_t>(a.T) && c[j][q] <= v[j][q]) ? at : pos[j][q];
+                        }
                     }
                 }
+            } else {
+                // from table entries to blocks; probes of the blocks' first values when the table skips blocks
 #pragma unroll
                 for (int j = 0; j < kR; ++j) {
+                    pos[j][0] *= a.blocks_per_entry;
+                    pos[j][1] *= a.blocks_per_entry;
+                }
+                const uint32_t last_block = static_cast<uint32_t>(a.T) / kLinkCBlock;
+                for (int bit = a.fine_bits - 1; bit >= 0; --bit) {   // (uniform; no round when the table has every block)
+                    int64_t c[kR][2];
 #pragma unroll
-                    for (int q = 0; q < 2; ++q) {
-                        const uint32_t at = pos[j][q] + (1u << bit);
-                        pos[j][q] = (at <= static_cast<uint32_t>(a.T) && c[j][q] <= v[j][q]) ? at : pos[j][q];
+                    for (int j = 0; j < kR; ++j) {
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            const uint32_t at = pos[j][q] + (1u << bit);
+                            c[j][q] = c_at((at <= last_block ? at : last_block) * kLinkCBlock);
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < kR; ++j) {
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            const uint32_t at = pos[j][q] + (1u << bit);
+                            pos[j][q] = (at <= last_block && c[j][q] <= v[j][q]) ? at : pos[j][q];
+                        }
+                    }
+                }
+                // v relative to the block's first value
+                if (a.blocks_per_entry == 1) {
+#pragma unroll
+                    for (int j = 0; j < kR; ++j) {
+                        v[j][0] -= tab[pos[j][0]];
+                        v[j][1] -= tab[pos[j][1]];
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < kR; ++j) {
+                        v[j][0] -= c_at(pos[j][0] * kLinkCBlock);
+                        v[j][1] -= c_at(pos[j][1] * kLinkCBlock);
+                    }
+                }
+                // the block's record: how many of its further values are <= v
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    uint4 rec[kR];
+#pragma unroll
+                    for (int j = 0; j < kR; ++j)
+                        rec[j] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(a.Cpack) + pos[j][q] * 16u);
+#pragma unroll
+                    for (int j = 0; j < kR; ++j) {
+                        constexpr uint32_t kM = (1u << 21) - 1;
+                        const uint4 w = rec[j];
+                        const int64_t rest = v[j][q];
+                        const int32_t lim = rest < 0 ? -1 : rest > INT32_MAX ? INT32_MAX : static_cast<int32_t>(rest);
+                        int32_t sum = static_cast<int32_t>(w.x & kM), n = sum <= lim;
+                        sum += static_cast<int32_t>(((w.x >> 21) | (w.y << 11)) & kM); n += sum <= lim;
+                        sum += static_cast<int32_t>((w.y >> 10) & kM); n += sum <= lim;
+                        sum += static_cast<int32_t>(((w.y >> 31) | (w.z << 1)) & kM); n += sum <= lim;
+                        sum += static_cast<int32_t>(((w.z >> 20) | (w.w << 12)) & kM); n += sum <= lim;
+                        sum += static_cast<int32_t>((w.w >> 9) & kM); n += sum <= lim;
+                        const uint32_t at = pos[j][q] * kLinkCBlock + static_cast<uint32_t>(n);
+                        pos[j][q] = at <= static_cast<uint32_t>(a.T) ? at : static_cast<uint32_t>(a.T);
                     }
                 }
             }
@@ -240,12 +328,12 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
                 if (ok[j]) {
                     const int32_t s = static_cast<int32_t>(pos[j][0]), s2 = static_cast<int32_t>(pos[j][1]);
                     if (charged[j]) {
-                        e[j][0] = skew(static_cast<uint32_t>(s));
-                        e[j][1] = skew(static_cast<uint32_t>(iv_o[j] + 1));
+                        e[j][0] = static_cast<uint32_t>(s);
+                        e[j][1] = static_cast<uint32_t>(iv_o[j] + 1);
                         lo_t = s < lo_t ? s : lo_t;
                     }
-                    e[j][2] = skew(static_cast<uint32_t>(s2));
-                    e[j][3] = skew(static_cast<uint32_t>(iv_r[j]));
+                    e[j][2] = static_cast<uint32_t>(s2);
+                    e[j][3] = static_cast<uint32_t>(iv_r[j]);
                     lo_t = s2 < lo_t ? s2 : lo_t;
                     hi_t = iv_r[j] > hi_t ? iv_r[j] : hi_t;
                 }
@@ -256,35 +344,52 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
             for (int32_t tile_lo = 0; tile_lo < a.T; tile_lo += kTile) {
                 const int32_t tile_hi = a.T - tile_lo < kTile ? a.T : tile_lo + kTile;
                 const uint32_t tile_n = static_cast<uint32_t>(tile_hi - tile_lo);
+                // (per-lane addresses are derived afresh in every tile, see above: otherwise one 64-bit address per
+                // block and output array is computed per plan and spilled)
+                int tid_tile = tid;
+                asm volatile("" : "+v"(tid_tile));
+                const int lane = tid_tile & 63, wave = __builtin_amdgcn_readfirstlane(tid_tile >> 6);
+                int32_t *stage = stage_all + wave * kStageCells;
                 // ---- scatter (a wavefront none of whose lanes has an endpoint in range skips it)
                 const bool mine = hi_t >= tile_lo && lo_t < tile_hi;
                 if (__builtin_amdgcn_ballot_w64(mine) != 0) {
-                    const uint32_t base_cell = skew(static_cast<uint32_t>(tile_lo)), n_cell = skew(tile_n);
 #pragma unroll
                     for (int j = 0; j < kR; ++j) {
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
-                            const uint32_t u = e[j][q] - base_cell;
-                            if (u < n_cell) atomicAdd(&delta[u], (q & 1) ? -1 : 1);
+                            const uint32_t u = e[j][q] - static_cast<uint32_t>(tile_lo);
+                            const uint32_t one = (q & 1) ? 0xffffffffu : 1u;          // -1 or +1 ...
+                            if (u < tile_n) atomicAdd(&delta[u >> 1], one << (16 * (u & 1)));   // ... on the step's half
                         }
                     }
                 }
                 __syncthreads();
                 LINK_MARK(5);
-                // ---- this lane's 8 cells: read, clear for the next tile, local scan, wave scan
-                int32_t v[kVpt];
-                {
-                    i32x4 *cell = reinterpret_cast<i32x4 *>(&delta[my_cell]);
-                    const i32x4 c0 = cell[0], c1 = cell[1];
-                    cell[0] = i32x4{0, 0, 0, 0};
-                    cell[1] = i32x4{0, 0, 0, 0};
-                    v[0] = c0[0]; v[1] = c0[1]; v[2] = c0[2]; v[3] = c0[3];
-                    v[4] = c1[0]; v[5] = c1[1]; v[6] = c1[2]; v[7] = c1[3];
-                }
+                // ---- the wavefront's four blocks: read, clear for the next tile, take the halves apart, local
+                // scan, wave scan; v = sums from the wavefront's first step on
+                int32_t v[kSub][kVpt];
+                int32_t run = 0;   // (wave-uniform)
 #pragma unroll
-                for (int j = 1; j < kVpt; ++j) v[j] += v[j - 1];
-                const int32_t incl = wave_scan_add32(v[kVpt - 1]);
-                if (lane == 63) wave_tot[wave] = incl;
+                for (int g = 0; g < kSub; ++g) {
+                    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                    u32x4 *cell = reinterpret_cast<u32x4 *>(&delta[wave * (kWaveSteps / 2) + g * (kBlock / 2) + 4 * lane]);
+                    const u32x4 c = *cell;
+                    *cell = u32x4{0, 0, 0, 0};
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        const int32_t lo = static_cast<int16_t>(c[h] & 0xffffu);
+                        v[g][2 * h] = lo;
+                        v[g][2 * h + 1] = static_cast<int32_t>(c[h] - static_cast<uint32_t>(lo)) >> 16;
+                    }
+#pragma unroll
+                    for (int j = 1; j < kVpt; ++j) v[g][j] += v[g][j - 1];
+                    const int32_t incl = wave_scan_add32(v[g][kVpt - 1]);
+                    const int32_t before_me = run + incl - v[g][kVpt - 1];
+#pragma unroll
+                    for (int j = 0; j < kVpt; ++j) v[g][j] += before_me;
+                    run += __builtin_amdgcn_readlane(incl, 63);
+                }
+                if (lane == 0) wave_tot[wave] = run;
                 __syncthreads();
                 int32_t before = 0, total = 0;
 #pragma unroll
@@ -293,58 +398,62 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
                     before += w < wave ? t : 0;
                     total += t;
                 }
-                const int32_t base = carry + before + incl - v[kVpt - 1];
+                const int32_t base = carry + before;
                 carry += total;
 #pragma unroll
-                for (int j = 0; j < kVpt; ++j) v[j] += base;
-                const int32_t t0 = tile_lo + my;
-                // ---- earlier passes of a long plan
-                if (!first) {
+                for (int g = 0; g < kSub; ++g) {
+                    const int32_t block_t0 = tile_lo + wave * kWaveSteps + g * kBlock;   // (wave-uniform)
+                    if (block_t0 >= tile_hi) break;
+                    const int32_t t0 = block_t0 + kVpt * lane;
 #pragma unroll
-                    for (int j = 0; j < kVpt; ++j)
-                        if (t0 + j < tile_hi) v[j] += __hip_atomic_load(&acc[t0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-                if (!last) {
+                    for (int j = 0; j < kVpt; ++j) v[g][j] += base;
+                    // ---- earlier passes of a long plan
+                    if (!first) {
 #pragma unroll
-                    for (int j = 0; j < kVpt; ++j)
-                        if (t0 + j < tile_hi) __hip_atomic_store(&acc[t0 + j], v[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    continue;   // (block-uniform; the next pass reads these sums back in the same lanes)
-                }
-                // ---- reduce
-#pragma unroll
-                for (int j = 0; j < kVpt; ++j) {
-                    if (t0 + j < tile_hi) {
-                        if (v[j] > best_mx) {
-                            best_mx = v[j];
-                            best_arg = t0 + j;
-                        }
-                        over += v[j] >= 2 ? 1 : 0;
+                        for (int j = 0; j < kVpt; ++j)
+                            if (t0 + j < tile_hi) v[g][j] += __hip_atomic_load(&acc[t0 + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
-                }
-                // ---- the row: through the wavefront's staging area, 16 contiguous bytes per lane
-                if (row) {
-                    __builtin_amdgcn_wave_barrier();
-                    i32x4 *mine_out = reinterpret_cast<i32x4 *>(stage + 8 * lane + 4 * (lane >> 3));
-                    mine_out[0] = i32x4{v[0], v[1], v[2], v[3]};
-                    mine_out[1] = i32x4{v[4], v[5], v[6], v[7]};
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    const int32_t wave_t0 = tile_lo + wave * (64 * kVpt);
-                    const bool wide = (reinterpret_cast<uintptr_t>(row + wave_t0) & 15) == 0 && wave_t0 + 64 * kVpt <= tile_hi;
+                    if (!last) {
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const i32x4 xv = (reinterpret_cast<const i32x4 *>(stage) + lane + (lane >> 4))[68 * j];
-                        const int32_t t = wave_t0 + 4 * (j * 64 + lane);
-                        if (wide) {
-                            *reinterpret_cast<i32x4 *>(row + t) = xv;
-                        } else {
+                        for (int j = 0; j < kVpt; ++j)
+                            if (t0 + j < tile_hi) __hip_atomic_store(&acc[t0 + j], v[g][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        continue;   // (block-uniform; the next pass reads these sums back in the same lanes)
+                    }
+                    // ---- reduce
 #pragma unroll
-                            for (int q = 0; q < 4; ++q)
-                                if (t + q < tile_hi) row[t + q] = xv[q];
+                    for (int j = 0; j < kVpt; ++j) {
+                        if (t0 + j < tile_hi) {
+                            if (v[g][j] > best_mx) {
+                                best_mx = v[g][j];
+                                best_arg = t0 + j;
+                            }
+                            over += v[g][j] >= 2 ? 1 : 0;
                         }
                     }
-                    __builtin_amdgcn_wave_barrier();
+                    // ---- the row: through the wavefront's staging area, 16 contiguous bytes per lane
+                    if (row) {
+                        __builtin_amdgcn_wave_barrier();
+                        i32x4 *mine_out = reinterpret_cast<i32x4 *>(stage + 8 * lane + 4 * (lane >> 3));
+                        mine_out[0] = i32x4{v[g][0], v[g][1], v[g][2], v[g][3]};
+                        mine_out[1] = i32x4{v[g][4], v[g][5], v[g][6], v[g][7]};
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        const bool wide = (reinterpret_cast<uintptr_t>(row + block_t0) & 15) == 0 && block_t0 + kBlock <= tile_hi;
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const i32x4 xv = (reinterpret_cast<const i32x4 *>(stage) + lane + (lane >> 4))[68 * j];
+                            const int32_t t = block_t0 + 4 * (j * 64 + lane);
+                            if (wide) {
+                                *reinterpret_cast<i32x4 *>(row + t) = xv;
+                            } else {
+#pragma unroll
+                                for (int q = 0; q < 4; ++q)
+                                    if (t + q < tile_hi) row[t + q] = xv[q];
+                            }
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                    }
                 }
                 LINK_MARK(6);
             }
@@ -391,6 +500,11 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
     }
 }
 
+int env_int(const char *name, int fallback) {
+    const char *v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
+
 // Without latencies nothing is transferred in measurable time: every output is zero.
 __global__ void link_zero_kernel(int64_t n_rows, int32_t *link, int32_t B, int32_t *peak, int32_t *argmax, int32_t *overbooked) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
@@ -426,10 +540,20 @@ int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, 
     a.plan_offsets = plans->plan_offsets;
     a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in; a.iv_kind = plans->iv_kind;
     a.C = tas->d_C.p; a.x = tas->d_x.p;
-    a.tab_stride = static_cast<int32_t>((static_cast<int64_t>(T) + kTabMax) / kTabMax);   // ceil((T + 1) / kTabMax)
-    a.n_tab = static_cast<int32_t>(static_cast<int64_t>(T) / a.tab_stride + 1);           // entries k with k * stride <= T
+    constexpr int kTabReal = kTabMax - 1;   // the last entry stays +inf
+    const bool packed = tas->c_packed && env_int("TENSILE_LINK_PACKED", 1) != 0;   // (0: testing aid, the probe search)
     a.fine_bits = 0;
-    while ((1 << a.fine_bits) < a.tab_stride) ++a.fine_bits;
+    if (packed) {
+        const int64_t n_blocks = static_cast<int64_t>(T) / kLinkCBlock + 1;
+        a.blocks_per_entry = static_cast<int32_t>((n_blocks + kTabReal - 1) / kTabReal);
+        a.tab_stride = a.blocks_per_entry * kLinkCBlock;
+        a.Cpack = tas->d_Cpack.p;
+        while ((1 << a.fine_bits) < a.blocks_per_entry) ++a.fine_bits;
+    } else {
+        a.tab_stride = static_cast<int32_t>((static_cast<int64_t>(T) + kTabReal) / kTabReal);   // ceil((T + 1) / kTabReal)
+        while ((1 << a.fine_bits) < a.tab_stride) ++a.fine_bits;
+    }
+    a.n_tab = static_cast<int32_t>(static_cast<int64_t>(T) / a.tab_stride + 1);   // entries k with k * stride <= T: at most kTabReal
     const int32_t grid = B < tas->num_cus ? B : tas->num_cus;
     Scratch &sc = tas->scratch;
     if (reuse) {
@@ -452,7 +576,8 @@ int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, 
         a.acc_rows = sc.link_acc.p;
     }
     a.link = link; a.peak = peak; a.argmax = argmax; a.overbooked = overbooked;
-    hipLaunchKernelGGL(link_kernel, dim3(grid), dim3(kThr), 0, stream, a);
+    if (packed) hipLaunchKernelGGL(link_kernel<true>, dim3(grid), dim3(kThr), 0, stream, a);
+    else hipLaunchKernelGGL(link_kernel<false>, dim3(grid), dim3(kThr), 0, stream, a);
     TS_HIP(hipGetLastError());
     return TENSILE_OK;
 }

@@ -480,6 +480,29 @@ int build_times_and_index(tensile_tas *h, const int64_t *step_ns) {
     h->h_x.resize(static_cast<size_t>(N));
     TS_HIP(hipMemcpy(h->h_C.data(), h->d_C.p, (static_cast<size_t>(T) + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
     if (N > 0) TS_HIP(hipMemcpy(h->h_x.data(), h->d_x.p, static_cast<size_t>(N) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    // C packed for the link kernel: block b holds, 21 bits each, C[7b+1]-C[7b] .. C[7b+6]-C[7b+5] (0 past C[T])
+    h->c_packed = false;
+    if (h->timed) {
+        constexpr int kBits = 21;
+        const std::vector<int64_t> &C = h->h_C;
+        bool fits = true;
+        for (int32_t t = 0; t < T && fits; ++t) fits = C[t + 1] - C[t] < (int64_t{1} << kBits);
+        if (fits) {
+            std::vector<uint4> rec(static_cast<size_t>(T) / kLinkCBlock + 1);
+            for (size_t b = 0; b < rec.size(); ++b) {
+                unsigned __int128 bits = 0;
+                for (int j = 0; j + 1 < kLinkCBlock; ++j) {
+                    const int64_t k = static_cast<int64_t>(b) * kLinkCBlock + j;
+                    const uint64_t d = k + 1 <= T ? static_cast<uint64_t>(C[k + 1] - C[k]) : 0;
+                    bits |= static_cast<unsigned __int128>(d) << (kBits * j);
+                }
+                rec[b] = make_uint4(static_cast<uint32_t>(bits), static_cast<uint32_t>(bits >> 32), static_cast<uint32_t>(bits >> 64),
+                                    static_cast<uint32_t>(bits >> 96));
+            }
+            TS_HIP(h->d_Cpack.upload(rec.data(), rec.size()));
+            h->c_packed = true;
+        }
+    }
     return TENSILE_OK;
 }
 

@@ -323,6 +323,46 @@ def test_link_occupancy_shapes(T, B, reuse):
     check_link(tas, pl, reuse, label=f"link T={T}")
 
 
+@pytest.mark.parametrize("T,B,packed", [(32767, 3, 1), (32768, 3, 1), (32769, 4, 1), (50168, 3, 1), (50169, 3, 1), (65537, 3, 1),
+                                         (120001, 2, 1), (32769, 3, 0), (120001, 2, 0)])
+def test_link_occupancy_long_rows(T, B, packed, monkeypatch):
+    """Edges of the 32768-step tile, rows whose table of C covers every block of seven steps (up to 50,168
+    steps) and rows where it skips blocks, with the packed differences of C and with the probe search."""
+    monkeypatch.setenv("TENSILE_LINK_PACKED", str(packed))
+    tas = small_random_tas(4300 + T, N=200, T=T, max_acc=6, timed=True)
+    pl = merged_plans(tas, B, 31, p_swap=0.8)
+    say(f"link long rows T={T} B={B} packed={packed} K={pl.n_intervals}")
+    check_link(tas, pl, bool(T & 1), label=f"link T={T} packed={packed}")
+
+
+def test_link_occupancy_with_latencies_too_long_to_pack():
+    """Operator latencies of 2^21 ns and more cannot be packed: the probe search runs, also after an update
+    of the latencies of a loaded sequence switched the handle from one form to the other."""
+    tas = small_random_tas(4400, N=120, T=9001, max_acc=5, timed=True)
+    pl = merged_plans(tas, 5, 41, p_swap=0.7)
+    h = P.tas_load(tas)
+    check_link(tas, pl, False, h=h, label="link short latencies")
+    slow = tas.step_ns * 3000                      # up to 3 ms per step
+    assert slow.max() >= 1 << 21
+    P.tensile_tas_update_latencies(h, slow, tas.link_bytes_per_us // 3000 + 1)
+    tas.step_ns, tas.link_bytes_per_us = slow, tas.link_bytes_per_us // 3000 + 1
+    say("link: latencies updated to >= 2^21 ns")
+    check_link(tas, pl, True, h=h, label="link long latencies")
+    fast = np.minimum(slow // 3000 + 1, (1 << 21) - 1)
+    P.tensile_tas_update_latencies(h, fast, 50_000)
+    tas.step_ns, tas.link_bytes_per_us = fast, 50_000
+    say("link: latencies updated back")
+    check_link(tas, pl, False, h=h, label="link short latencies again")
+    # exactly at the limit of the packed form: 2^21 - 1 fits, 2^21 does not
+    for top in ((1 << 21) - 1, 1 << 21):
+        edge = fast.copy()
+        edge[::97] = top
+        P.tensile_tas_update_latencies(h, edge, 50_000)
+        tas.step_ns = edge
+        check_link(tas, pl, True, h=h, label=f"link latency {top}")
+    h.close()
+
+
 def test_link_occupancy_long_plans_take_several_passes():
     """Plans of more than 6144 intervals (the registers of one pass), with and without rows."""
     tas = small_random_tas(4100, N=400, T=9000, max_acc=6, timed=True)
