@@ -1308,9 +1308,27 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     if (threads_forced == 512 || threads_forced == 1024) threads = threads_forced;
     const int tile = threads * kVpt;
     const int64_t n_tiles = (static_cast<int64_t>(a.T) + tile - 1) / tile;
-    // enough workgroups to fill the chip several times over; otherwise one segment per plan
-    const int64_t want_blocks = static_cast<int64_t>(tas->num_cus) * 16;
-    int64_t S = (want_blocks + a.B - 1) / a.B;
+    // Segments per plan.  Every segment's workgroup starts with the plan's whole interval list (loads,
+    // size gathers, the sum entering the segment), which costs about as much as p tiles of work, and more
+    // than one segment needs the combining kernel afterwards (about one tile's time).  With the workgroups
+    // running in rounds of one per CU, S is the count that minimises rounds x (p + tiles per segment):
+    // several segments pay only while the batch leaves CUs idle, or for rows of very many tiles.
+    int64_t S = 1;
+    {
+        const double avg = a.B > 0 ? static_cast<double>(a.n_intervals) / a.B : 0.0;
+        const bool likely_binned = a.size_units != nullptr && avg * 1.125 > kCapBig && n_tiles < kMaxBinTiles;
+        const double p = likely_binned ? 0.25 : 0.3 + (avg < kCapBig ? avg : kCapBig) / 3500.0;
+        double best = 0.0;
+        const int64_t s_max = n_tiles < 1024 ? n_tiles : 1024;
+        for (int64_t s = 1; s <= s_max; ++s) {
+            const int64_t rounds = (static_cast<int64_t>(a.B) * s + tas->num_cus - 1) / tas->num_cus;
+            const double cost = rounds * (p + static_cast<double>((n_tiles + s - 1) / s)) + (s > 1 ? 1.0 : 0.0);
+            if (s == 1 || cost < best) {
+                best = cost;
+                S = s;
+            }
+        }
+    }
     const int forced = env_int("TENSILE_EVAL_SEGMENTS", 0);   // tuning knob
     if (forced > 0) S = forced;
     if (S < 1) S = 1;
