@@ -387,6 +387,9 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
             if constexpr (kPrev) store_part(tile_lo - kTile, tile_lo, 3);
             return;
         }
+        // (the last quarter goes out here rather than at the end of the iteration, where the next
+        // iteration's first quarter would follow it at once: measured 0.6 % faster)
+        if constexpr (kPrev) store_part(tile_lo - kTile, tile_lo, 3);
         // prefix over the wave totals: the first lanes scan them, then every lane picks the
         // sum of the waves before its own and the tile total by lane index
         int64_t tot = wave_tot[lane & (kWaves - 1)];
@@ -451,10 +454,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
 
         // ---- park the results in the wave's staging area (lane-contiguous, skewed); they are
         // stored during the next iteration, or after the loop
-        if constexpr (kPrev) {
-            store_part(tile_lo - kTile, tile_lo, 3);
-            __builtin_amdgcn_wave_barrier();
-        }
+        if constexpr (kPrev) __builtin_amdgcn_wave_barrier();
         if constexpr (kStore) {
             ll2 *mine_out = reinterpret_cast<ll2 *>(stage + lane * kVpt + 2 * (lane >> 2));
 #pragma unroll
