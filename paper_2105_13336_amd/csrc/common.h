@@ -34,9 +34,10 @@ struct DevBuf {
         p = nullptr;
         n = 0;
     }
-    // (Re)allocate to hold at least `count` elements; contents are not kept.
+    // (Re)allocate to hold at least `count` elements; contents are not kept.  The pointer is valid
+    // afterwards even for count == 0 (one element), so kernels may issue clamped loads from it.
     hipError_t reserve(size_t count) {
-        if (count <= n) return hipSuccess;
+        if (p && count <= n) return hipSuccess;
         release();
         hipError_t e = hipMalloc(reinterpret_cast<void **>(&p), (count ? count : 1) * sizeof(T));
         if (e == hipSuccess) n = count;

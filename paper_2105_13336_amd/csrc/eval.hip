@@ -132,8 +132,14 @@ __device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o,
 // every path through the tile loop issues the same memory operations.
 // kBinned: the batch went through bin_kernel first; nothing is kept in registers (R is 1 and unused),
 // every tile reads its own records.  Every plan of the batch is taken.
-template <int kThr, int R, bool kTail, bool kNarrow, int kOut, bool kBinned = false>
+// kBinFast (with kBinned): no tile of the segment holds more than kBinFastRecs * kThr records, so a tile's
+// records are two unconditional loads per thread, requested one tile ahead, and the tile offsets come
+// through the scalar unit: the tile loop then issues a fixed set of memory instructions like the common
+// kernel's, instead of waiting for two dependent loads (and with them for every store) in every tile.
+constexpr int kBinFastRecs = 2;
+template <int kThr, int R, bool kTail, bool kNarrow, int kOut, bool kBinned = false, bool kBinFast = false>
 __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
+    static_assert(!kBinFast || kBinned, "kBinFast is a form of the binned kernel");
     constexpr bool kStore = kOut != 0, kVec16 = kOut == 2;
     constexpr int kWaves = Geom<kThr>::kWaves, kTile = Geom<kThr>::kTile, kTileCells = Geom<kThr>::kTileCells;
     // the tile, followed by 64 "trash" cells: a lane whose endpoint lies outside the tile adds to
@@ -273,6 +279,23 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
 
     Best best{INT64_MIN, INT64_MAX, INT32_MAX};
     int64_t *row = kStore ? a.resident + static_cast<int64_t>(plan) * a.T : nullptr;
+
+    // kBinFast: the records of the tile at hand (two per thread) and where they start and end in the plan's
+    // records; loads are clamped into the plan's records (into the batch's when the plan has none)
+    typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+    const const_i32_ptr tile_off =
+        kBinFast ? (const_i32_ptr)(a.tile_off + static_cast<int64_t>(plan) * (a.n_tiles + 1)) : nullptr;
+    const uint32_t n_rec = static_cast<uint32_t>(2 * (k1 - k0));
+    const int2 *plan_recs = (kBinFast && n_rec) ? a.recs + 2 * k0 : a.recs;
+    auto rec_at = [&](uint32_t k) { return plan_recs[k < n_rec ? k : (n_rec ? n_rec - 1 : 0)]; };
+    int2 rec_cur[kBinFastRecs];
+    int32_t rec_lo = 0, rec_hi = 0;   // (uniform)
+    if constexpr (kBinFast) {
+        rec_lo = tile_off[seg_lo / kTile];
+        rec_hi = tile_off[seg_lo / kTile + 1];
+#pragma unroll
+        for (int j = 0; j < kBinFastRecs; ++j) rec_cur[j] = rec_at(static_cast<uint32_t>(rec_lo + j * kThr + tid));
+    }
     __syncthreads();   // the first tile's cells are in place
 
     // One quarter (granule row j of 4) of a tile's stores from the wave's staging area: 16
@@ -312,6 +335,14 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
 #pragma unroll
         for (int j = 0; j < kVpt / 2; ++j)
             fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kTile + my)[j];
+        int2 rec_next[kBinFastRecs];
+        int32_t next_hi = 0;
+        if constexpr (kBinFast) {   // the next tile's records (none past the last tile: its offsets are equal)
+            const int32_t t_next = tile_lo / kTile + 2;
+            next_hi = tile_off[t_next < a.n_tiles ? t_next : a.n_tiles];
+#pragma unroll
+            for (int j = 0; j < kBinFastRecs; ++j) rec_next[j] = rec_at(static_cast<uint32_t>(rec_hi + j * kThr + tid));
+        }
         constexpr bool kPrev = !kFirst && kStore;
         if constexpr (kPrev) {
             __builtin_amdgcn_wave_barrier();
@@ -348,7 +379,19 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
                 }
             }
         }
-        if constexpr (kBinned) {
+        if constexpr (kBinFast) {
+            const uint32_t trash = kTileCells + lane;
+#pragma unroll
+            for (int j = 0; j < kBinFastRecs; ++j) {
+                const int2 rec = rec_cur[j];
+                const bool valid = rec_lo + j * kThr + tid < rec_hi;
+                const int64_t bytes = static_cast<int64_t>(static_cast<uint64_t>(static_cast<uint32_t>(rec.y)) << a.size_shift);
+                lds_add(&delta[valid ? static_cast<uint32_t>(rec.x) & 0x7fffffffu : trash], !valid ? 0 : rec.x < 0 ? -bytes : bytes);
+                rec_cur[j] = rec_next[j];
+            }
+            rec_lo = rec_hi;
+            rec_hi = next_hi;
+        } else if constexpr (kBinned) {
             const int32_t *off = a.tile_off + static_cast<int64_t>(plan) * (a.n_tiles + 1) + tile_lo / kTile;
             const int2 *recs = a.recs + 2 * k0;
             for (int32_t k = off[0] + tid; k < off[1]; k += kThr) {
@@ -1012,9 +1055,19 @@ __global__ __launch_bounds__(1024) void bin_kernel(const EvalArgs a, int2 *recs_
     }
 }
 
-template <int kThr, int kOut>
+// Two launches per binned batch: kFast takes the plans none of whose tiles holds more records than the
+// fast form's two per thread, the other launch the rest; a workgroup whose plan belongs to the other
+// launch exits at once.  (Checked over the whole plan, not only the workgroup's segment, so that all
+// segments of a plan agree.)
+template <int kThr, int kOut, bool kFast>
 __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) void eval_binned_kernel(const EvalArgs a) {
-    eval_body<kThr, 1, false, true, kOut, true>(a, blockIdx.x);
+    const int64_t plan = (static_cast<int64_t>(blockIdx.x >> 3) / a.S) * 8 + (blockIdx.x & 7);   // as eval_body decodes it
+    if (plan >= a.B) return;
+    bool over = false;
+    const int32_t *off = a.tile_off + plan * (a.n_tiles + 1);
+    for (int32_t t = threadIdx.x; t < a.n_tiles; t += kThr) over = over || off[t + 1] - off[t] > kBinFastRecs * kThr;
+    if ((__syncthreads_or(over) != 0) == kFast) return;
+    eval_body<kThr, 1, false, true, kOut, true, kFast>(a, blockIdx.x);
 }
 
 // Combine the per-segment partials of each plan; segments are in time order, so
@@ -1057,9 +1110,16 @@ int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, i
         Scratch &sc = tas->scratch;
         hipLaunchKernelGGL(bin_kernel<kThr>, dim3(a.B), dim3(1024), 0, stream, a, sc.bin_recs.p, sc.bin_off.p, sc.bin_sum.p);
         TS_HIP(hipGetLastError());
-        if (out == 2) hipLaunchKernelGGL((eval_binned_kernel<kThr, 2>), grid, block, 0, stream, a);
-        else if (out == 1) hipLaunchKernelGGL((eval_binned_kernel<kThr, 1>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((eval_binned_kernel<kThr, 0>), grid, block, 0, stream, a);
+        if (out == 2) {
+            hipLaunchKernelGGL((eval_binned_kernel<kThr, 2, true>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL((eval_binned_kernel<kThr, 2, false>), grid, block, 0, stream, a);
+        } else if (out == 1) {
+            hipLaunchKernelGGL((eval_binned_kernel<kThr, 1, true>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL((eval_binned_kernel<kThr, 1, false>), grid, block, 0, stream, a);
+        } else {
+            hipLaunchKernelGGL((eval_binned_kernel<kThr, 0, true>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL((eval_binned_kernel<kThr, 0, false>), grid, block, 0, stream, a);
+        }
         TS_HIP(hipGetLastError());
         return TENSILE_OK;
     }
@@ -1386,6 +1446,7 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     const int bin_forced = env_int("TENSILE_EVAL_BINNED", -1);   // tuning knob: 0 = never, 1 = whenever possible
     if (bin_forced == 0) binned = false;
     if (bin_forced == 1) binned = narrow && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2);
+    if (a.n_intervals == 0) binned = false;   // nothing to bin (and no record for the binned kernel's clamped loads)
     if (binned) {
         Scratch &sc = tas->scratch;
         const size_t n_recs = 2 * static_cast<size_t>(a.n_intervals), n_off = static_cast<size_t>(a.B) * (n_tiles + 1),

@@ -130,6 +130,30 @@ def test_eval_geometries_and_binning(threads, binned, T, segs, monkeypatch):
     check_eval(tas, pl, label=f"threads={threads} binned={binned}")
 
 
+@pytest.mark.parametrize("threads,T,segs", [(512, 4097, 0), (1024, 20011, 2), (1024, 8192, 0)])
+def test_eval_binned_tiles_with_many_records(threads, T, segs, monkeypatch):
+    """The binned path takes a tile's records two per thread, one tile ahead; plans with a tile that holds
+    more go through its general form.  One batch with plans of both kinds, with empty plans, and with every
+    endpoint of a plan in one tile."""
+    monkeypatch.setenv("TENSILE_EVAL_THREADS", str(threads))
+    monkeypatch.setenv("TENSILE_EVAL_BINNED", "1")
+    if segs:
+        monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", str(segs))
+    tas = small_random_tas(2100 + T, N=400, T=T, max_acc=4, base_bytes=5)
+    base = make_plans(tas, 8, 9, p_swap=0.8)
+    lists = []
+    for b in range(8):
+        t, o, r, k = base.plan(b)
+        one = [(int(t[j]), int(o[j]), int(r[j]), int(k[j])) for j in range(len(t))]
+        reps = (0, 1, 4, 9, 1, 20, 0, 3)[b]           # x 250-300 intervals: up to ~6000 intervals, 12000 records
+        lists.append(one * reps)
+    # all endpoints of one plan at two steps of the first tile
+    lists.append([(0, int(tas.alloc_step[0]), int(tas.alloc_step[0]) + 2, 0)] * 3000)
+    pl = plans_from_lists(lists)
+    say(f"eval binned, crowded tiles: threads={threads} T={T} segs={segs} lengths={[len(x) for x in lists]}")
+    check_eval(tas, pl, label=f"binned crowded threads={threads}")
+
+
 @pytest.mark.parametrize("threads,T,B,slots,tail", [(1024, 20011, 23, 3, False), (512, 12291, 40, 7, False), (1024, 4097, 9, 2, False),
                                                      (512, 7, 33, 4, False), (1024, 8192, 12, 5, False), (512, 20012, 21, 2, True),
                                                      (1024, 50001, 11, 3, True), (512, 4096, 5, 8, False)])
