@@ -46,7 +46,40 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def ceilings() -> int:
+    """What plain library kernels reach on this machine over a buffer of the size of configs[3]'s footprint rows
+    (the practical ceilings the kernels are held against next to the 8 TB/s of the data sheet)."""
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    n = 16384 * 50000
+    a = torch.empty(n, dtype=torch.int64, device="cuda")
+    b = torch.empty(n, dtype=torch.int64, device="cuda")
+
+    def timed(f, reps=10):
+        f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    gb = n * 8 / 1e9
+    out = {"buffer_GB": gb}
+    for name, f, moved in (("fill", lambda: a.fill_(3), gb), ("copy", lambda: b.copy_(a), 2 * gb),
+                           ("max_reduction", lambda: a.max(), gb), ("add_one_out_of_place", lambda: torch.add(a, 1, out=b), 2 * gb),
+                           ("add_one_in_place", lambda: a.add_(1), 2 * gb)):
+        ms = timed(f)
+        out[name] = {"ms": ms, "GBps_moved": moved / ms * 1e3}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
+    if "--ceilings" in sys.argv[1:]:
+        return ceilings()
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -57,6 +90,8 @@ def main() -> int:
     ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-planner leg")
     ap.add_argument("--eval-only", action="store_true", help="steps run tensile_eval_plans alone (profiling aid)")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-job and recomputation rows (profiling aid)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the benchmark: time plain fill / copy / reduction kernels over 6.55 GB and print them")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build evaluates plans on ONE GPU (plans are independent; no multi-GPU path is built); "
