@@ -202,10 +202,14 @@ struct ScoreCand {
 };
 // (any_interval: an interval of the entry's tensor cancels the entry wherever it lies, not only inside the gap.
 //  compact != null, B == 1 only: instead of the dense rows, one record per tensor with a window, in no
-//  particular order, behind *hdr = {peak, peak step, number of records}; score/win_out/win_in are not touched.)
+//  particular order, behind *hdr = {peak, peak step, number of records}; score/win_out/win_in are not touched.
+//  hdr and compact may point into pinned host memory; with ready != null the kernel, once all of that is
+//  visible to the host, stores ready_value to *ready (system scope), so the host can wait for the word
+//  instead of the stream.)
 int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
-                 int32_t *win_in, hipStream_t stream, ScoreHeader *hdr = nullptr, ScoreCand *compact = nullptr);
+                 int32_t *win_in, hipStream_t stream, ScoreHeader *hdr = nullptr, ScoreCand *compact = nullptr,
+                 unsigned long long *ready = nullptr, unsigned long long ready_value = 0);
 // link.hip
 int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak, int32_t *argmax,
                 int32_t *overbooked, hipStream_t stream);

@@ -6,6 +6,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <chrono>
 
 namespace tensile {
 namespace {
@@ -74,14 +75,17 @@ struct Cand {
 
 typedef ScoreHeader Header;
 typedef ScoreCand CandOut;
-constexpr int32_t kFirstCopy = 4096;   // candidates fetched together with the header
 
 __global__ void peak_only_kernel(const int64_t *peak, const int32_t *arg, Header *hdr) { *hdr = Header{*peak, *arg, 0}; }
 
-// Pinned host memory that frees itself.
+// Pinned host memory that frees itself (after everything the device still does with it).
 struct PinnedBuf {
     void *p = nullptr;
-    ~PinnedBuf() { if (p) (void)hipHostFree(p); }
+    ~PinnedBuf() {
+        if (!p) return;
+        (void)hipDeviceSynchronize();
+        (void)hipHostFree(p);
+    }
     hipError_t reserve(size_t bytes) { return hipHostMalloc(&p, bytes, hipHostMallocDefault); }
 };
 
@@ -112,18 +116,27 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
         // device state: the growing plan (B = 1), one row of every output, the compacted candidates
         DevBuf<int64_t> d_offs, d_res, d_peak, d_min;
         DevBuf<int32_t> d_t, d_o, d_r, d_arg;
-        DevBuf<Header> d_hdr;           // header followed by the candidates, one allocation
+        DevBuf<Header> d_hdr;           // the header of the last analysis, which scores nothing
         TS_HIP(d_offs.reserve(2));
         TS_HIP(d_t.reserve(capacity)); TS_HIP(d_o.reserve(capacity)); TS_HIP(d_r.reserve(capacity));
         TS_HIP(d_res.reserve(T)); TS_HIP(d_peak.reserve(1)); TS_HIP(d_min.reserve(1)); TS_HIP(d_arg.reserve(1));
         static_assert(sizeof(Header) == 16 && sizeof(CandOut) == 24, "layout of the iteration record");
         const size_t rec_bytes = sizeof(Header) + static_cast<size_t>(N) * sizeof(CandOut);
-        TS_HIP(d_hdr.reserve((rec_bytes + sizeof(Header) - 1) / sizeof(Header)));
-        CandOut *d_cands = reinterpret_cast<CandOut *>(d_hdr.p + 1);
-        PinnedBuf h_rec;
+        TS_HIP(d_hdr.reserve(1));
+        // The iteration's record lives in pinned host memory and the scoring kernel writes it there itself,
+        // then stores the iteration's number to a word next to it: the host waits for that word instead of
+        // the stream (no copy to enqueue, no wake-up through the driver).
+        PinnedBuf h_rec, h_ready;
         TS_HIP(h_rec.reserve(rec_bytes));
+        TS_HIP(h_ready.reserve(64));
         const Header *hdr = static_cast<const Header *>(h_rec.p);
         const CandOut *h_cands = reinterpret_cast<const CandOut *>(hdr + 1);
+        volatile unsigned long long *ready = static_cast<volatile unsigned long long *>(h_ready.p);
+        *ready = 0;
+        void *rec_dev = nullptr, *ready_dev = nullptr;   // the same memory as the kernels address it
+        TS_HIP(hipHostGetDevicePointer(&rec_dev, h_rec.p, 0));
+        TS_HIP(hipHostGetDevicePointer(&ready_dev, h_ready.p, 0));
+        unsigned long long ready_seq = 0;
         if (n_initial > 0) {
             TS_HIP(hipMemcpy(d_t.p, iv_tensor, n_initial * 4, hipMemcpyHostToDevice));
             TS_HIP(hipMemcpy(d_o.p, iv_out, n_initial * 4, hipMemcpyHostToDevice));
@@ -149,16 +162,23 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
             // the scoring kernel writes the record itself: {peak, peak step, count}, then one entry per tensor with a window
             int rc = recompute_scores ? ensure_recompute_index(tas) : TENSILE_OK;
             if (rc != TENSILE_OK) return rc;
+            const unsigned long long want = ++ready_seq;
             rc = launch_score(tas, recompute_scores ? tas->recompute_index : tas->index, recompute_scores, &pl, d_res.p, d_peak.p,
-                              d_arg.p, nullptr, nullptr, nullptr, nullptr, d_hdr.p, d_cands);
+                              d_arg.p, nullptr, nullptr, nullptr, nullptr, static_cast<Header *>(rec_dev),
+                              reinterpret_cast<CandOut *>(static_cast<Header *>(rec_dev) + 1),
+                              static_cast<unsigned long long *>(ready_dev), want);
             if (rc != TENSILE_OK) return rc;
-            const size_t first_bytes = sizeof(Header) + static_cast<size_t>(std::min(N, kFirstCopy)) * sizeof(CandOut);
-            TS_HIP(hipMemcpyAsync(h_rec.p, d_hdr.p, first_bytes, hipMemcpyDeviceToHost, nullptr));
-            TS_HIP(hipStreamSynchronize(nullptr));
-            if (hdr->count > kFirstCopy) {
-                TS_HIP(hipMemcpyAsync(static_cast<char *>(h_rec.p) + first_bytes, reinterpret_cast<const char *>(d_hdr.p) + first_bytes,
-                                      static_cast<size_t>(hdr->count - kFirstCopy) * sizeof(CandOut), hipMemcpyDeviceToHost, nullptr));
-                TS_HIP(hipStreamSynchronize(nullptr));
+            // wait for the word; should it not arrive (a failed launch shows up in the stream), ask the stream
+            const auto t_start = std::chrono::steady_clock::now();
+            for (unsigned spins = 0; __atomic_load_n(const_cast<unsigned long long *>(ready), __ATOMIC_ACQUIRE) != want; ++spins) {
+                if ((spins & 0xfff) == 0xfff && std::chrono::steady_clock::now() - t_start > std::chrono::seconds(2)) {
+                    TS_HIP(hipStreamSynchronize(nullptr));
+                    if (__atomic_load_n(const_cast<unsigned long long *>(ready), __ATOMIC_ACQUIRE) != want) {
+                        set_error("greedy_plan: the scoring kernel finished without its record");
+                        return TENSILE_E_HIP;
+                    }
+                    break;
+                }
             }
             return TENSILE_OK;
         };

@@ -86,6 +86,8 @@ struct ScoreArgs {
     int64_t *tab_scratch;        // [gridDim.x][n_tab] when n_tab > kTabLds, else null
     ScoreHeader *hdr;            // compact mode (B == 1): records instead of rows, see launch_score
     ScoreCand *compact;
+    unsigned long long *ready;   // compact mode: receives ready_value when header and records are visible system-wide (may be null)
+    unsigned long long ready_value;
 };
 
 // row[0..n) = v with 16-byte stores where the row allows them
@@ -331,7 +333,13 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
         const bool staged = n_e <= kMaxLocal;
         if (kCompact) {                             // (B == 1: one plan per launch)
             if (tid == 0) n_compact = 0;
-            if (n_e == 0 && tid == 0) *a.hdr = ScoreHeader{P, tstar, 0};
+            if (n_e == 0 && tid == 0) {
+                *a.hdr = ScoreHeader{P, tstar, 0};
+                if (a.ready) {
+                    __threadfence_system();
+                    __hip_atomic_store(a.ready, a.ready_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+                }
+            }
         } else if (n_e == 0 || !staged) {
             fill_row<int64_t>(score, a.N, 0, tid);
             if (wout) fill_row<int32_t>(wout, a.N, -1, tid);
@@ -569,8 +577,15 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
             PROF_MARK(5);
         }
         if (kCompact) {
+            if (a.ready) __threadfence_system();   // this thread's records, before the barrier that precedes the signal
             __syncthreads();
-            if (tid == 0) *a.hdr = ScoreHeader{P, tstar, n_compact};
+            if (tid == 0) {
+                *a.hdr = ScoreHeader{P, tstar, n_compact};
+                if (a.ready) {
+                    __threadfence_system();
+                    __hip_atomic_store(a.ready, a.ready_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+                }
+            }
         }
     }
 }
@@ -579,7 +594,8 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
 
 int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
-                 int32_t *win_in, hipStream_t stream, ScoreHeader *hdr, ScoreCand *compact) {
+                 int32_t *win_in, hipStream_t stream, ScoreHeader *hdr, ScoreCand *compact, unsigned long long *ready,
+                 unsigned long long ready_value) {
     if (plans->B == 0 || tas->N == 0) return TENSILE_OK;
     if (compact && (plans->B != 1 || !hdr)) { set_error("score: the compact form takes one plan"); return TENSILE_E_INVAL; }
     // as many workgroups as the device keeps resident, the plans dealt evenly among them
@@ -612,6 +628,7 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     a.score = score; a.win_out = win_out; a.win_in = win_in;
     a.tab_scratch = nullptr;
     a.hdr = hdr; a.compact = compact;
+    a.ready = ready; a.ready_value = ready_value;
     if (a.n_tab > kTabLds) {
         Scratch &sc = tas->scratch;
         const size_t need = static_cast<size_t>(blocks) * static_cast<size_t>(a.n_tab);
