@@ -188,9 +188,8 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
 #pragma unroll
     for (int j = 0; j < kVpt / 2; ++j) fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + seg_lo + my)[j];
 
-    // ---- the plan's first R*threads intervals live in registers for the whole segment, R
-    // consecutive ones per thread: (first step without the bytes, first step with them again,
-    // size).  An interval that cannot be applied, or a slot past the end of the list, gets
+    // ---- the plan's first R*threads intervals live in registers for the whole segment, R per
+    // thread: (first step without the bytes, first step with them again, size).  An interval that cannot be applied, or a slot past the end of the list, gets
     // endpoints no tile contains.  [lo_t, hi_t] spans this thread's endpoints.
     // e0/e1 hold the endpoints in the skewed cell numbering of the LDS tile (skew is monotone and
     // additive over multiples of 32, so skew(e) - skew(tile_lo) is the cell inside the tile)
@@ -202,10 +201,13 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
         // clamped to 0) and issued back to back, then waited for once
         const int32_t *pt = a.iv_tensor + k0, *po = a.iv_out + k0, *pr = a.iv_in + k0;
         const uint32_t len = k1 - k0 < R * kThr ? static_cast<uint32_t>(k1 - k0) : R * kThr;
+        // a wavefront holds 64 * R consecutive intervals (close in time when the caller lists them by
+        // tensor, so that the wavefront can skip tiles), lanes side by side: every load is whole lines
+        const uint32_t slot0 = static_cast<uint32_t>(wave) * (64 * R) + lane;
         int32_t ti[R], vo[R], vr[R];
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const uint32_t k = tid * R + j;
+            const uint32_t k = slot0 + j * 64;
             const uint32_t kc = k < len ? k : len - 1;
             ti[j] = pt[kc];
             vo[j] = po[kc];
@@ -214,7 +216,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const bool ok = tid * R + j < len && applies(a, ti[j], vo[j], vr[j]);
+            const bool ok = slot0 + j * 64 < len && applies(a, ti[j], vo[j], vr[j]);
             ti[j] = ok ? ti[j] : -1;
         }
 #pragma unroll
@@ -641,7 +643,7 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         const int32_t *pt = some ? a.iv_tensor + k0 : none, *po = some ? a.iv_out + k0 : none, *pr = some ? a.iv_in + k0 : none;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const uint32_t k = L.tid * R + j;
+            const uint32_t k = static_cast<uint32_t>(L.wave) * (64 * R) + j * 64 + L.lane;   // (as in eval_body)
             const uint32_t kc = k < len ? k : len - 1;
             nti[j] = pt[kc];
             nvo[j] = po[kc];
@@ -652,7 +654,7 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         const uint32_t len = static_cast<uint32_t>(k1 - k0);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const bool ok = L.tid * R + j < len && applies(a, nti[j], nvo[j], nvr[j]);
+            const bool ok = static_cast<uint32_t>(L.wave) * (64 * R) + j * 64 + L.lane < len && applies(a, nti[j], nvo[j], nvr[j]);
             nvr[j] = ok ? nvr[j] : -1;
             nti[j] = ok ? nti[j] : 0;
         }
