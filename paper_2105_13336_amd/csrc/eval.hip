@@ -184,9 +184,15 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     int64_t *stage = stage_all + wave * kStageStride;
 
     // ---- first tile's cells: differences of the unscheduled timeline (dMF0 is padded to whole tiles)
+    // dMF0 is read and put into the cells one 16-byte granule per lane, lanes side by side (whole lines per
+    // load; 16 bytes at a 64-byte stride, the layout the scan reads, would touch four times as many): granule
+    // j * 64 + lane of the wavefront's 256, conflict-free in the skewed tile like the lane's own 4 granules.
+    // The wavefront's cells are only ever touched by the wavefront itself, and its LDS operations run in order.
+    const int fill_at = wave * (64 * kVpt) + 2 * lane;                  // + 128 * j: first step of granule j
+    const int fill_cell = fill_at + 2 * (fill_at >> 5);                // + 136 * j (128 steps and their skew)
     ll2 fill[kVpt / 2];
 #pragma unroll
-    for (int j = 0; j < kVpt / 2; ++j) fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + seg_lo + my)[j];
+    for (int j = 0; j < kVpt / 2; ++j) fill[j] = *reinterpret_cast<const ll2 *>(a.dMF0 + seg_lo + fill_at + 128 * j);
 
     // ---- the plan's first R*threads intervals live in registers for the whole segment, R per
     // thread: (first step without the bytes, first step with them again, size).  An interval that cannot be applied, or a slot past the end of the list, gets
@@ -246,7 +252,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
     const int64_t k_over = k0 + static_cast<int64_t>(R) * kThr;   // the rest is re-read per tile
 
 #pragma unroll
-    for (int j = 0; j < kVpt / 2; ++j) reinterpret_cast<ll2 *>(&delta[my_cell])[j] = fill[j];
+    for (int j = 0; j < kVpt / 2; ++j) *reinterpret_cast<ll2 *>(&delta[fill_cell + 136 * j]) = fill[j];
 
     // ---- footprint just before the segment: MF0 there plus the plan's deltas before it
     int64_t carry = 0;   // same value in every thread
@@ -336,7 +342,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
         // of the "next" tile is unconditional (what it brings is never scanned in that case).
 #pragma unroll
         for (int j = 0; j < kVpt / 2; ++j)
-            fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kTile + my)[j];
+            fill[j] = *reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kTile + fill_at + 128 * j);
         int2 rec_next[kBinFastRecs];
         int32_t next_hi = 0;
         if constexpr (kBinFast) {   // the next tile's records (none past the last tile: its offsets are equal)
@@ -413,14 +419,17 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int64_t w) {
         int64_t v[kVpt];
         int64_t incl = 0;
         if (wave_live) {
-            ll2 *cell = reinterpret_cast<ll2 *>(&delta[my_cell]);
+            const ll2 *cell = reinterpret_cast<const ll2 *>(&delta[my_cell]);
 #pragma unroll
             for (int j = 0; j < kVpt / 2; ++j) {
                 const ll2 x = cell[j];
-                cell[j] = fill[j];
                 v[2 * j] = x[0];
                 v[2 * j + 1] = x[1];
             }
+            // (all of the wavefront's reads are issued before the first of its writes)
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < kVpt / 2; ++j) *reinterpret_cast<ll2 *>(&delta[fill_cell + 136 * j]) = fill[j];
 #pragma unroll
             for (int j = 1; j < kVpt; ++j) v[j] += v[j - 1];
             incl = wave_scan_add(v[kVpt - 1]);
