@@ -585,8 +585,6 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     typedef SizeReg<kNarrow> SR;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int my = tid * kVpt;                  // this lane's first step of a tile
-    const int my_cell = my + 2 * (tid >> 2);    // ... and where it lives in the skewed tile
     const int64_t stride = gridDim.x;
     // The same per-lane numbers (and the wavefront's staging area), derived afresh from a copy of the thread id that the compiler cannot
     // trace back: every tile takes its own, so that none of them (nor the addresses built on them)
@@ -594,6 +592,7 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     // to avoid here: their reloads are vector memory loads, waited for together with every store.
     struct Ids {
         int tid, lane, wave, wave_u, my, my_cell;
+        int fill_at, fill_cell;   // the lane's granule of dMF0 (see eval_body): first step within the tile, cell; + 128 / 136 per j
         int64_t *stage;
     };
     auto fresh_ids = [&]() {
@@ -606,6 +605,8 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         L.wave_u = __builtin_amdgcn_readfirstlane(L.wave);
         L.my = t * kVpt;
         L.my_cell = L.my + 2 * (t >> 2);
+        L.fill_at = L.wave * (64 * kVpt) + 2 * L.lane;
+        L.fill_cell = L.fill_at + 2 * (L.fill_at >> 5);
         L.stage = stage_all + L.wave * kStageStride;
         return L;
     };
@@ -696,8 +697,11 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     int64_t plan = next_mine(blockIdx.x);
     if (plan >= a.B) return;   // (block-uniform)
     ll2 fill[kVpt / 2];
+    {
+        const Ids L0 = fresh_ids();
 #pragma unroll
-    for (int j = 0; j < kVpt / 2; ++j) fill[j] = reinterpret_cast<const ll2 *>(a.dMF0 + my)[j];
+        for (int j = 0; j < kVpt / 2; ++j) fill[j] = *reinterpret_cast<const ll2 *>(a.dMF0 + L0.fill_at + 128 * j);
+    }
     {
         int64_t k0, k1;
         list_of(plan, k0, k1);
@@ -708,8 +712,11 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         __builtin_amdgcn_sched_barrier(0);
         take_list();
     }
+    {
+        const Ids L0 = fresh_ids();
 #pragma unroll
-    for (int j = 0; j < kVpt / 2; ++j) reinterpret_cast<ll2 *>(&delta[my_cell])[j] = fill[j];
+        for (int j = 0; j < kVpt / 2; ++j) *reinterpret_cast<ll2 *>(&delta[L0.fill_cell + 136 * j]) = fill[j];
+    }
 
     int64_t carry = 0;
     Best best{INT64_MIN, INT64_MAX, INT32_MAX};
@@ -800,10 +807,10 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         // loads first: the cells of the tile that follows (the next plan's first one after a last
         // tile; dMF0 is padded to whole tiles), then the next plan's intervals
         {   // (uniform base plus a 32-bit byte offset: no 64-bit address is kept per L.lane)
-            const uint32_t at = static_cast<uint32_t>((kLast ? 0 : tile_lo + kTile) + L.my) * 8u;
-            const ll2 *cells = reinterpret_cast<const ll2 *>(reinterpret_cast<const char *>(a.dMF0) + at);
+            const uint32_t at = static_cast<uint32_t>((kLast ? 0 : tile_lo + kTile) + L.fill_at) * 8u;
+            const char *cells = reinterpret_cast<const char *>(a.dMF0) + at;
 #pragma unroll
-            for (int j = 0; j < kVpt / 2; ++j) fill[j] = cells[j];
+            for (int j = 0; j < kVpt / 2; ++j) fill[j] = *reinterpret_cast<const ll2 *>(cells + 1024 * j);
         }
         __builtin_amdgcn_wave_barrier();
         store_part(L, 0, prev_full);
@@ -837,21 +844,23 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         int64_t v[kVpt];
         int64_t incl = 0;
         {
-            ll2 *cell = reinterpret_cast<ll2 *>(&delta[L.my_cell]);
+            const ll2 *cell = reinterpret_cast<const ll2 *>(&delta[L.my_cell]);
             if (wave_live) {
 #pragma unroll
                 for (int j = 0; j < kVpt / 2; ++j) {
                     const ll2 x = cell[j];
-                    cell[j] = fill[j];
                     v[2 * j] = x[0];
                     v[2 * j + 1] = x[1];
                 }
+                __builtin_amdgcn_sched_barrier(0);   // (the wavefront's reads before its writes, as in eval_body)
+#pragma unroll
+                for (int j = 0; j < kVpt / 2; ++j) *reinterpret_cast<ll2 *>(&delta[L.fill_cell + 136 * j]) = fill[j];
 #pragma unroll
                 for (int j = 1; j < kVpt; ++j) v[j] += v[j - 1];
                 incl = wave_scan_add(v[kVpt - 1]);
             } else {   // (only in a row's ragged last tile: nothing to scan, but the next plan needs its cells)
 #pragma unroll
-                for (int j = 0; j < kVpt / 2; ++j) cell[j] = fill[j];
+                for (int j = 0; j < kVpt / 2; ++j) *reinterpret_cast<ll2 *>(&delta[L.fill_cell + 136 * j]) = fill[j];
 #pragma unroll
                 for (int j = 0; j < kVpt; ++j) v[j] = 0;
             }
