@@ -5,6 +5,8 @@
 #include "common.h"
 
 #include <algorithm>
+#include <atomic>
+#include <thread>
 #include <cstdarg>
 #include <cstdio>
 #include <new>
@@ -265,13 +267,23 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
         slice_first[b + 1] = slice_first[b] + (off[b + 1] - off[b] + kScoreMaxLocal - 1) / kScoreMaxLocal;
     std::vector<int32_t> wave_ptr(static_cast<size_t>(slice_first[nb]) * 4 * (kScoreWaves + 1));
     std::vector<int2> hash_dir(static_cast<size_t>(nb));
-    std::vector<int4> hash_slots;
     std::vector<uint32_t> filter(static_cast<size_t>(nb) * ix.filter_words, 0u);
-    std::vector<int32_t> order;
+    // every bucket's hash table has its place before any is filled: the buckets are then independent of each
+    // other and are worked on by several host threads (the sorts dominate the time this takes)
     ix.max_bucket = 0;
+    size_t hash_total = 0;
     for (int32_t b = 0; b < nb; ++b) {
-        const int32_t e0 = off[b], n = off[b + 1] - off[b];
+        const int32_t n = off[b + 1] - off[b];
         ix.max_bucket = std::max(ix.max_bucket, n);
+        int bits = 1;
+        while ((int64_t{1} << bits) < 2 * static_cast<int64_t>(n)) ++bits;
+        hash_dir[b] = make_int2(static_cast<int32_t>(hash_total), n > 0 ? bits : 0);
+        if (n > 0) hash_total += size_t{1} << bits;
+        if (hash_total > static_cast<size_t>(INT32_MAX)) { set_error("tas_load: candidate index too large"); return TENSILE_E_RANGE; }
+    }
+    std::vector<int4> hash_slots(hash_total, make_int4(-1, 0, 0, 0));
+    auto do_bucket = [&](int32_t b, std::vector<int32_t> &order) {
+        const int32_t e0 = off[b], n = off[b + 1] - off[b];
         int4 *c = cand.data() + e0;
         std::sort(c, c + n, [](const int4 &x, const int4 &y) {
             return x.z != y.z ? x.z < y.z : (x.w != y.w ? x.w < y.w : x.x < y.x);
@@ -332,13 +344,9 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
             }
         }
         // hash table: the entries of one tensor are inserted one after the other, the last flagged
-        int bits = 1;
-        while ((int64_t{1} << bits) < 2 * static_cast<int64_t>(n)) ++bits;
-        const size_t base = hash_slots.size();
-        hash_dir[b] = make_int2(static_cast<int32_t>(base), n > 0 ? bits : 0);
-        if (n == 0) continue;
-        if (base + (size_t{1} << bits) > static_cast<size_t>(INT32_MAX)) { set_error("tas_load: candidate index too large"); return TENSILE_E_RANGE; }
-        hash_slots.resize(base + (size_t{1} << bits), make_int4(-1, 0, 0, 0));
+        if (n == 0) return;
+        const size_t base = static_cast<size_t>(hash_dir[b].x);
+        const int bits = hash_dir[b].y;
         order.resize(n);
         for (int32_t k = 0; k < n; ++k) order[k] = k;
         std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return c[x].w != c[y].w ? c[x].w < c[y].w : x < y; });
@@ -352,6 +360,30 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
             const uint32_t fb = static_cast<uint32_t>(en.w) & (filter_bits - 1);
             filter[static_cast<size_t>(b) * ix.filter_words + (fb >> 5)] |= 1u << (fb & 31);
         }
+    };
+    {
+        unsigned n_threads = std::thread::hardware_concurrency();
+        n_threads = n_threads < 1 ? 1 : n_threads > 16 ? 16 : n_threads;
+        if (E < 50000 || nb < 4) n_threads = 1;
+        if (n_threads > static_cast<unsigned>(nb)) n_threads = static_cast<unsigned>(nb);
+        std::atomic<int32_t> next_bucket{0};
+        std::atomic<bool> failed{false};
+        auto worker = [&]() {
+            try {
+                std::vector<int32_t> order;
+                for (int32_t b; (b = next_bucket.fetch_add(1)) < nb;) do_bucket(b, order);
+            } catch (...) {
+                failed = true;
+            }
+        };
+        std::vector<std::thread> pool;
+        try {
+            for (unsigned k = 1; k < n_threads; ++k) pool.emplace_back(worker);
+        } catch (...) {   // (no more threads to be had: the ones there and this one do the work)
+        }
+        worker();
+        for (std::thread &t : pool) t.join();
+        if (failed) throw std::bad_alloc();
     }
     TS_HIP(ix.bucket_off.upload(off.data(), off.size()));
     TS_HIP(ix.cand.upload(cand.data(), E));
