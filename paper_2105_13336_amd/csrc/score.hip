@@ -40,6 +40,8 @@
 // Buckets with more entries than acc holds are processed in slices of kMaxLocal
 // entries, one full pass per slice; the index keeps the q order and the
 // wavefronts' start positions per slice.
+#include <cstdlib>
+
 #include "common.h"
 #include "wave_ops.h"
 
@@ -610,7 +612,11 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     }
     const int64_t resident_blocks = static_cast<int64_t>(tas->num_cus) * per_cu;
     const int64_t rounds = (plans->B + resident_blocks - 1) / resident_blocks;
-    const int32_t blocks = static_cast<int32_t>((plans->B + rounds - 1) / rounds);
+    int32_t blocks = static_cast<int32_t>((plans->B + rounds - 1) / rounds);
+    if (const char *forced = std::getenv("TENSILE_SCORE_BLOCKS")) {   // tuning knob: size of the grid (plans are dealt round-robin)
+        const long v = std::atol(forced);
+        if (v > 0) blocks = static_cast<int32_t>(v < plans->B ? v : plans->B);
+    }
     ScoreArgs a;
     a.T = tas->T; a.N = tas->N; a.B = plans->B;
     a.tspan = ix.tspan;
