@@ -525,6 +525,17 @@ def check_score(tas, pl, rows=None, h=None, label=""):
     return int((o0 >= 0).sum())
 
 
+@pytest.mark.parametrize("blocks", [1, 7, 100000])
+def test_score_grid_sizes(blocks, configs_small, monkeypatch):
+    """The scoring grid deals the plans round-robin over any number of workgroups: one for all plans, a few
+    with several plans each (lists and filters carried from plan to plan), one per plan."""
+    monkeypatch.setenv("TENSILE_SCORE_BLOCKS", str(blocks))
+    tas = configs_small[1]
+    pl = make_config_plans(1, tas, B=60)
+    say(f"score with a grid of {blocks}")
+    assert check_score(tas, pl, label=f"grid {blocks}") > 10
+
+
 @pytest.mark.parametrize("idx,B,rows", [(0, None, None), (1, 300, range(0, 300, 7)), (2, 40, range(0, 40, 5))])
 def test_score_configs(idx, B, rows, configs_small):
     tas = configs_small[idx]
