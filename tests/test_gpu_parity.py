@@ -505,6 +505,29 @@ def test_eval_heavy_collisions():
     check_eval(tas, plans_from_lists([ivs, ivs[:1500], []]))
 
 
+@pytest.mark.parametrize("T,B", [(5000, 9), (20011, 6)])
+def test_sizes_beyond_32_bits(T, B):
+    """Tensors of up to 64 GiB with odd byte counts: no common power of two brings the sizes into 32 bits, so
+    every kernel keeps them as int64 (both workgroup geometries; evaluation, scoring, the windowed update)."""
+    tas = small_random_tas(5100 + T, N=300, T=T, max_acc=5, timed=True, max_size=1 << 36, link_bytes_per_us=1 << 24)
+    assert int(tas.size_bytes.max()) > 1 << 33 and int((tas.size_bytes & 1).sum()) > 0
+    pl = make_plans(tas, B, 3, p_swap=0.6)
+    say(f"wide sizes T={T} B={B}")
+    h = P.tas_load(tas)
+    check_eval(tas, pl, h=h, label="wide sizes")
+    assert check_score(tas, pl, h=h, label="wide sizes") > 0
+    # one more interval per plan on the rows just evaluated
+    res, peak, arg, mn = gpu_eval(h, upload(pl))
+    r0 = res.cpu().numpy().copy()
+    t, o, r = extra_intervals(tas, B, 17)
+    P.tensile_apply_intervals(h, *(torch.from_numpy(x).cuda() for x in (t, o, r)), res, peak, arg, mn)
+    torch.cuda.synchronize()
+    p1, a1, m1 = O.apply_intervals(tas, t, o, r, r0)
+    assert np.array_equal(res.cpu().numpy(), r0) and np.array_equal(peak.cpu().numpy(), p1)
+    assert np.array_equal(arg.cpu().numpy(), a1) and np.array_equal(mn.cpu().numpy(), m1)
+    h.close()
+
+
 # --------------------------------------------------------------------- score
 
 def check_score(tas, pl, rows=None, h=None, label=""):
