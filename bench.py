@@ -92,6 +92,9 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip the per-job and recomputation rows (profiling aid)")
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the benchmark: time plain fill / copy / reduction kernels over 6.55 GB and print them")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="before the steps, launch one plain elementwise kernel (out = in + 1) that reads 2 GiB and writes "
+                         "2 GiB: the dispatch of known size that FETCH_SIZE / WRITE_SIZE of a counter run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build evaluates plans on ONE GPU (plans are independent; no multi-GPU path is built); "
@@ -113,6 +116,13 @@ def main() -> int:
     B, T, N, K = pl.B, tas.T, tas.N, pl.n_intervals
     log(f"{cfg.name}: B={B} T={T} N={N} intervals={K} tas_hash={tas_hash(tas):016x} plans_hash={plans_hash(pl):016x} "
         f"(generated in {time.time() - t0:.1f}s)")
+
+    if args.calibrate:      # caches are far smaller than 2 GiB, so every byte comes from and goes to HBM
+        cal_in = torch.zeros(1 << 28, dtype=torch.int64, device="cuda")
+        cal_out = torch.empty_like(cal_in)
+        torch.add(cal_in, 1, out=cal_out)
+        torch.cuda.synchronize()
+        del cal_in, cal_out
 
     h = P.tas_load(tas)
     dp = P.DevicePlans.from_numpy(pl.plan_offsets, pl.iv_tensor, pl.iv_out, pl.iv_in, pl.iv_kind)

@@ -559,6 +559,38 @@ def test_score_grid_sizes(blocks, configs_small, monkeypatch):
     assert check_score(tas, pl, label=f"grid {blocks}") > 10
 
 
+@pytest.mark.parametrize("blocks,B", [(2, 97), (5, 64), (0, 1100)])
+def test_score_given_peak_steps(blocks, B, configs_small, monkeypatch):
+    """Scoring takes the peak and its step as inputs, so any step may be given: both sides then apply the
+    definition to that step.  Peak steps spread over the whole sequence (consecutive plans of a workgroup
+    then look at different parts of the candidate index), some of them outside [0, T) = no candidate."""
+    if blocks:
+        monkeypatch.setenv("TENSILE_SCORE_BLOCKS", str(blocks))
+    tas = configs_small[1]
+    pl = make_config_plans(1, tas, B=B)
+    say(f"score with given peak steps, grid {blocks or 'default'}, B={B}")
+    h = P.tas_load(tas)
+    dp = upload(pl)
+    res, peak, arg, mn = gpu_eval(h, dp)
+    steps = prng.randint(4242, 1, np.arange(B), 0, tas.T - 1).astype(np.int32)
+    keep = np.arange(B) % 5 == 0                      # every fifth plan keeps its own peak step
+    a_host = np.where(keep, arg.cpu().numpy(), steps).astype(np.int32)
+    outside = np.arange(B) % 11 == 3
+    a_host[outside] = np.where(np.arange(B)[outside] % 2 == 0, -1, tas.T + 7)
+    arg2 = torch.from_numpy(a_host).cuda()
+    sc, wo, wi = gpu_score(h, dp, res, peak, arg2)
+    rows = [b for b in range(B) if not outside[b]][:: max(1, B // 120)]
+    r0, p0, _, _ = O.eval_plans(tas, pl.select(rows))
+    s0, o0, i0 = O.score_plans(tas, pl.select(rows), r0, p0, a_host[rows])
+    idx = torch.as_tensor(np.asarray(rows), device="cuda")
+    assert np.array_equal(sc[idx].cpu().numpy(), s0) and np.array_equal(wo[idx].cpu().numpy(), o0)
+    assert np.array_equal(wi[idx].cpu().numpy(), i0)
+    assert (o0 >= 0).sum() > 100 and len(np.unique(a_host[rows] >> 8)) > 8
+    out_idx = torch.as_tensor(np.flatnonzero(outside), device="cuda")
+    assert int(sc[out_idx].abs().sum()) == 0 and bool((wo[out_idx] == -1).all()) and bool((wi[out_idx] == -1).all())
+    h.close()
+
+
 @pytest.mark.parametrize("idx,B,rows", [(0, None, None), (1, 300, range(0, 300, 7)), (2, 40, range(0, 40, 5))])
 def test_score_configs(idx, B, rows, configs_small):
     tas = configs_small[idx]
