@@ -1003,6 +1003,7 @@ __global__ __launch_bounds__(kThr) void eval_tail_kernel(const EvalArgs a, const
 // sum entering a segment from the tile sums.  Records of a tile are in no particular order
 // (integer additions commute).
 constexpr int kMaxBinTiles = 4096;
+constexpr int kBinU = 4;   // intervals per thread and round of bin_kernel's passes
 
 template <int kThr>
 __global__ __launch_bounds__(1024) void bin_kernel(const EvalArgs a, int2 *recs_all, int32_t *tile_off, int64_t *tile_sum) {
@@ -1019,17 +1020,62 @@ __global__ __launch_bounds__(1024) void bin_kernel(const EvalArgs a, int2 *recs_
     for (int32_t t = tid; t <= nt; t += 1024) cnt[t] = 0;
     for (int32_t t = tid; t < nt; t += 1024) sum[t] = 0;
     __syncthreads();
-    for (int64_t k = k0 + tid; k < k1; k += 1024) {
-        const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
-        if (!applies(a, i, o, r)) continue;
-        const int64_t bytes = static_cast<int64_t>(static_cast<uint64_t>(a.size_units[i]) << a.size_shift);
-        if (o + 1 < a.T) {
-            atomicAdd(&cnt[(o + 1) / kTile], 1);
-            lds_sub(&sum[(o + 1) / kTile], bytes);
+    // Both passes take kBinU intervals per thread and round: their loads are issued together (at clamped
+    // indices, so unconditionally), then the size gathers together.  The rounds are counted per wavefront, so
+    // that all 64 lanes stay in the loop to its end (the wavefront-wide operations below need them).
+    const int64_t n_iv = k1 - k0;
+    auto load_round = [&](int64_t kb, int32_t (&i)[kBinU], int32_t (&o)[kBinU], int32_t (&r)[kBinU], uint32_t (&units)[kBinU]) {
+#pragma unroll
+        for (int u = 0; u < kBinU; ++u) {
+            const int64_t k = kb + u * 1024;
+            const int64_t kc = k < k1 ? k : k1 - 1;      // (only called on a list that is not empty)
+            i[u] = a.iv_tensor[kc];
+            o[u] = a.iv_out[kc];
+            r[u] = a.iv_in[kc];
         }
-        if (r < a.T) {
-            atomicAdd(&cnt[r / kTile], 1);
-            lds_add(&sum[r / kTile], bytes);
+#pragma unroll
+        for (int u = 0; u < kBinU; ++u) {
+            if (kb + u * 1024 >= k1 || !applies(a, i[u], o[u], r[u])) i[u] = -1;
+            units[u] = a.size_units[i[u] < 0 ? 0 : i[u]];
+        }
+    };
+    // A caller's list keeps the intervals of one tensor, and of tensors generated one after the other, together,
+    // so the 64 endpoints a wavefront holds at a time mostly fall into one or two tiles - and LDS atomics of 64
+    // lanes on one address take 64 turns.  The wavefront therefore handles its endpoints tile by tile: f(tile,
+    // lanes holding it, the lowest of them) once per distinct tile among the lanes with `active` set.
+    auto for_each_tile = [&](bool active, int32_t tl, auto f) {
+        uint64_t todo = __ballot(active);
+        while (todo) {   // (wave-uniform)
+            const int leader = __builtin_ctzll(todo);
+            const int32_t t = __builtin_amdgcn_readlane(tl, leader);
+            const uint64_t group = __ballot(active && tl == t);
+            f(t, group, leader);
+            todo &= ~group;
+        }
+    };
+    for (int64_t base = wave * 64; base < n_iv; base += kBinU * 1024) {
+        int32_t i[kBinU], o[kBinU], r[kBinU];
+        uint32_t units[kBinU];
+        load_round(k0 + base + lane, i, o, r, units);
+#pragma unroll
+        for (int u = 0; u < kBinU; ++u) {
+            const int64_t bytes = static_cast<int64_t>(static_cast<uint64_t>(units[u]) << a.size_shift);
+            const bool has_out = i[u] >= 0 && o[u] + 1 < a.T, has_in = i[u] >= 0 && r[u] < a.T;
+            const int32_t tl_out = (o[u] + 1) / kTile, tl_in = r[u] / kTile;
+            for_each_tile(has_out, tl_out, [&](int32_t t, uint64_t group, int leader) {
+                const int64_t tot = last_lane(wave_scan_add(has_out && tl_out == t ? bytes : 0));
+                if (lane == leader) {
+                    atomicAdd(&cnt[t], __popcll(group));
+                    lds_sub(&sum[t], tot);
+                }
+            });
+            for_each_tile(has_in, tl_in, [&](int32_t t, uint64_t group, int leader) {
+                const int64_t tot = last_lane(wave_scan_add(has_in && tl_in == t ? bytes : 0));
+                if (lane == leader) {
+                    atomicAdd(&cnt[t], __popcll(group));
+                    lds_add(&sum[t], tot);
+                }
+            });
         }
     }
     __syncthreads();
@@ -1060,17 +1106,29 @@ __global__ __launch_bounds__(1024) void bin_kernel(const EvalArgs a, int2 *recs_
     __syncthreads();
     // second pass: cnt[] now serves as the tiles' write cursors
     int2 *recs = recs_all + 2 * k0;
-    for (int64_t k = k0 + tid; k < k1; k += 1024) {
-        const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
-        if (!applies(a, i, o, r)) continue;
-        const int32_t units = static_cast<int32_t>(a.size_units[i]);
-        if (o + 1 < a.T) {
-            const int32_t tl = (o + 1) / kTile;
-            recs[atomicAdd(&cnt[tl], 1)] = make_int2(static_cast<int32_t>(skew(o + 1 - tl * kTile) | 0x80000000u), units);
-        }
-        if (r < a.T) {
-            const int32_t tl = r / kTile;
-            recs[atomicAdd(&cnt[tl], 1)] = make_int2(static_cast<int32_t>(skew(r - tl * kTile)), units);
+    const uint64_t lanes_below = (1ull << lane) - 1;
+    for (int64_t base = wave * 64; base < n_iv; base += kBinU * 1024) {
+        int32_t i[kBinU], o[kBinU], r[kBinU];
+        uint32_t units[kBinU];
+        load_round(k0 + base + lane, i, o, r, units);
+#pragma unroll
+        for (int u = 0; u < kBinU; ++u) {
+            const bool has_out = i[u] >= 0 && o[u] + 1 < a.T, has_in = i[u] >= 0 && r[u] < a.T;
+            const int32_t tl_out = (o[u] + 1) / kTile, tl_in = r[u] / kTile;
+            // the group's records go to consecutive places: one atomic per group reserves them
+            for_each_tile(has_out, tl_out, [&](int32_t t, uint64_t group, int leader) {
+                int32_t at = 0;
+                if (lane == leader) at = atomicAdd(&cnt[t], __popcll(group));
+                at = __builtin_amdgcn_readlane(at, leader) + __popcll(group & lanes_below);
+                if (has_out && tl_out == t)
+                    recs[at] = make_int2(static_cast<int32_t>(skew(o[u] + 1 - t * kTile) | 0x80000000u), static_cast<int32_t>(units[u]));
+            });
+            for_each_tile(has_in, tl_in, [&](int32_t t, uint64_t group, int leader) {
+                int32_t at = 0;
+                if (lane == leader) at = atomicAdd(&cnt[t], __popcll(group));
+                at = __builtin_amdgcn_readlane(at, leader) + __popcll(group & lanes_below);
+                if (has_in && tl_in == t) recs[at] = make_int2(static_cast<int32_t>(skew(r[u] - t * kTile)), static_cast<int32_t>(units[u]));
+            });
         }
     }
 }
