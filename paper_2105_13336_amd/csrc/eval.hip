@@ -1440,15 +1440,17 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
                 hipStream_t stream) {
     EvalArgs a = proto;
     if (a.B == 0) return TENSILE_OK;
-    // geometry: short rows get the small workgroups (see the top of the file).  So do batches of at least two
-    // plans per CU when they write no rows or their rows have at most 32,768 steps: two workgroups per CU
-    // cover each other's start (measured on 24,000-step rows, 8,192 plans: 0.49 -> 0.43 ms; on 50,000-step
-    // rows without row output, 16,384 plans: 1.06 -> 0.91 ms per pass; with row output the two geometries are
-    // level there, and 1024 threads ahead by 3 % on 2,048-4,096 plans).
+    // geometry: short rows get the small workgroups (see the top of the file).  So do batches of more than one
+    // plan per CU when they write no rows or their rows have at most 32,768 steps: two workgroups per CU cover
+    // each other's start.  Measured: 24,000-step rows, 8,192 plans 0.49 -> 0.43 ms, 384 plans 30.9 -> 26.5 us;
+    // 50,000-step rows without row output, 16,384 plans 1.06 -> 0.91 ms per pass, 384 plans 39.0 -> 35.9 us.
+    // With row output the two geometries are within 3 % of each other on 50,000-step rows whatever the batch,
+    // and with at most one plan per CU the large geometry and its segments are ahead (256 plans: 29 vs 34 us).
     int threads = a.T <= kSmallGeometryMaxT ? 512 : 1024;
-    if (a.B >= 2 * static_cast<int64_t>(tas->num_cus) && (!a.resident || a.T <= 2 * kSmallGeometryMaxT)) threads = 512;
+    if (a.B > tas->num_cus && (!a.resident || a.T <= 2 * kSmallGeometryMaxT)) threads = 512;
     const int threads_forced = env_int("TENSILE_EVAL_THREADS", 0);   // tuning knob
     if (threads_forced == 512 || threads_forced == 1024) threads = threads_forced;
+    const bool small_for_batch = threads == 512 && a.T > kSmallGeometryMaxT;
     const int tile = threads * kVpt;
     const int64_t n_tiles = (static_cast<int64_t>(a.T) + tile - 1) / tile;
     // Segments per plan.  Every segment's workgroup starts with the plan's whole interval list (loads,
@@ -1464,7 +1466,9 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
         double best = 0.0;
         const int64_t s_max = n_tiles < 1024 ? n_tiles : 1024;
         for (int64_t s = 1; s <= s_max; ++s) {
-            const int64_t rounds = (static_cast<int64_t>(a.B) * s + tas->num_cus - 1) / tas->num_cus;
+            // (the small geometry chosen for the size of the batch: two workgroups per CU run side by side)
+            const int64_t slots = small_for_batch ? 2 * static_cast<int64_t>(tas->num_cus) : tas->num_cus;
+            const int64_t rounds = (static_cast<int64_t>(a.B) * s + slots - 1) / slots;
             const double cost = rounds * (p + static_cast<double>((n_tiles + s - 1) / s)) + (s > 1 ? 1.0 : 0.0);
             if (s == 1 || cost < best) {
                 best = cost;
