@@ -3,6 +3,7 @@
 // latency C, transfer times x, earliest swap-out step per gap).  Also the C-ABI
 // entry points that are thin argument checks around the kernels.
 #include "common.h"
+#include "wave_ops.h"
 
 #include <algorithm>
 #include <atomic>
@@ -41,37 +42,41 @@ __global__ void transfer_time_kernel(int32_t N, const int64_t *size, int64_t lin
     x[i] = link_bytes_per_us > 0 ? (size[i] * 1000 + link_bytes_per_us - 1) / link_bytes_per_us : 0;
 }
 
-// C[0] = 0, C[t+1] = C[t] + step_ns[t]; one workgroup, 1024 steps per iteration.
-__global__ __launch_bounds__(256) void cumulative_latency_kernel(int32_t T, const int64_t *step_ns, int64_t *C) {
-    __shared__ int64_t wave_tot[2][4];
+// C[0] = 0, C[t+1] = C[t] + step_ns[t]; one workgroup of 1024 threads, 8192 steps per iteration (8 consecutive
+// steps per thread), the next iteration's steps requested before this one's are summed.
+__global__ __launch_bounds__(1024) void cumulative_latency_kernel(int32_t T, const int64_t *step_ns, int64_t *C) {
+    constexpr int kPer = 8, kChunk = 1024 * kPer, kWavesC = 16;
+    __shared__ int64_t wave_tot[2][kWavesC];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int64_t carry = 0;
     int buf = 0;
     if (tid == 0) C[0] = 0;
-    for (int32_t t0 = 0; t0 < T; t0 += 1024) {
-        const int32_t t = t0 + tid * 4;
-        int64_t v[4];
+    auto load = [&](int64_t t, int64_t (&x)[kPer]) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = (t + j < T && step_ns) ? step_ns[t + j] : 0;
+        for (int j = 0; j < kPer; ++j) x[j] = (step_ns && t + j < T) ? step_ns[t + j] : 0;
+    };
+    int64_t next[kPer];
+    load(static_cast<int64_t>(tid) * kPer, next);
+    for (int64_t t0 = 0; t0 < T; t0 += kChunk) {
+        const int64_t t = t0 + static_cast<int64_t>(tid) * kPer;
+        int64_t v[kPer];
 #pragma unroll
-        for (int j = 1; j < 4; ++j) v[j] += v[j - 1];
-        int64_t incl = v[3];
+        for (int j = 0; j < kPer; ++j) v[j] = next[j];
+        load(t + kChunk, next);
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int64_t y = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += y;
-        }
+        for (int j = 1; j < kPer; ++j) v[j] += v[j - 1];
+        const int64_t incl = wave_scan_add(v[kPer - 1]);
         if (lane == 63) wave_tot[buf][wave] = incl;
         __syncthreads();
-        int64_t pre = carry + incl - v[3];
+        int64_t pre = carry + incl - v[kPer - 1];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < kWavesC; ++w) {
             const int64_t tw = wave_tot[buf][w];
             if (w < wave) pre += tw;
             carry += tw;
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < kPer; ++j)
             if (t + j < T) C[t + j + 1] = pre + v[j];
         buf ^= 1;
     }
@@ -489,7 +494,7 @@ int build_times_and_index(tensile_tas *h, const int64_t *step_ns) {
     {
         DevBuf<int64_t> step;
         if (h->timed) TS_HIP(step.upload(step_ns, T));
-        hipLaunchKernelGGL(cumulative_latency_kernel, dim3(1), dim3(256), 0, 0, T, h->timed ? step.p : nullptr, h->d_C.p);
+        hipLaunchKernelGGL(cumulative_latency_kernel, dim3(1), dim3(1024), 0, 0, T, h->timed ? step.p : nullptr, h->d_C.p);
         if (N > 0)
             hipLaunchKernelGGL(transfer_time_kernel, dim3((N + 255) / 256), dim3(256), 0, 0, N, h->d_size.p,
                                h->link_bytes_per_us, h->d_x.p);
