@@ -4,9 +4,11 @@
 // (max, earliest argmax, min) on the way.
 //
 // Work decomposition.  A workgroup owns one (plan, segment): `tiles_per_seg`
-// consecutive tiles of 8 steps per thread.  Two geometries are compiled: 1024 threads
-// with 8192-step tiles (one workgroup per CU: long rows) and 512 threads with 4096-step
-// tiles (two workgroups per CU, so that one can load while the other scans: short rows).  The running sum that
+// consecutive tiles of 8 steps per thread.  Three geometries are compiled: 1024 threads
+// with 8192-step tiles (one workgroup per CU: long rows), 512 threads with 4096-step
+// tiles (two workgroups per CU, so that one can load while the other scans: short rows, and
+// batches of more plans than CUs when they write no rows) and 256 threads with 2048-step tiles
+// (four per CU: large batches of short rows and short plans; see launch_eval).  The running sum that
 // enters a segment is MF0 just before it plus the plan's deltas before it, which
 // the workgroup takes straight from the plan's intervals (an interval
 // contributes -size if its out+1 lies before the segment and +size if its in
@@ -1249,6 +1251,32 @@ int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, i
     return TENSILE_OK;
 }
 
+// The smallest geometry: 256 threads, 2048-step tiles, 36 KB of LDS, four workgroups per CU.  Only the common
+// kernel with 8 intervals per thread (plans of up to 2048 intervals; longer ones go to the tail kernel).
+int launch_tiny_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, int out, bool narrow, hipStream_t stream) {
+    constexpr int kThr = 256;
+    const dim3 grid(static_cast<uint32_t>(blocks)), block(kThr);
+    const int64_t resident = static_cast<int64_t>(tas->num_cus) * (1024 / kThr);
+    const dim3 tgrid(static_cast<uint32_t>(blocks < resident ? blocks : resident));
+#define TS_LAUNCH_TINY(NARROW, OUT)                                                                                  \
+    do {                                                                                                             \
+        hipLaunchKernelGGL((eval_kernel<kThr, kCapSmall / kThr, NARROW, OUT>), grid, block, 0, stream, a);           \
+        hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, OUT>), tgrid, block, 0, stream, a, blocks);               \
+    } while (0)
+    if (narrow) {
+        if (out == 2) TS_LAUNCH_TINY(true, 2);
+        else if (out == 1) TS_LAUNCH_TINY(true, 1);
+        else TS_LAUNCH_TINY(true, 0);
+    } else {
+        if (out == 2) TS_LAUNCH_TINY(false, 2);
+        else if (out == 1) TS_LAUNCH_TINY(false, 1);
+        else TS_LAUNCH_TINY(false, 0);
+    }
+#undef TS_LAUNCH_TINY
+    TS_HIP(hipGetLastError());
+    return TENSILE_OK;
+}
+
 // ---- one more interval per plan: windowed update -----------------------------------------
 // The rows exist already; plan b gains the interval (tensor[b], out[b], in[b]).  A workgroup takes a
 // run of 8192-step chunks of one row: 16 contiguous bytes per lane and load, one chunk ahead; the
@@ -1446,10 +1474,26 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     // 50,000-step rows without row output, 16,384 plans 1.06 -> 0.91 ms per pass, 384 plans 39.0 -> 35.9 us.
     // With row output the two geometries are within 3 % of each other on 50,000-step rows whatever the batch,
     // and with at most one plan per CU the large geometry and its segments are ahead (256 plans: 29 vs 34 us).
+    // intervals kept in registers by the common kernel: sized for the average plan with some
+    // slack; longer plans are left to the tail kernel
+    const int64_t avg_k = (a.n_intervals + a.B - 1) / a.B;
+    int64_t need = avg_k + avg_k / 8;
+    const int r_forced = env_int("TENSILE_EVAL_R", 0);   // tuning knob: registers per thread at 1024 threads
+    if (r_forced > 0) need = static_cast<int64_t>(r_forced) * 1024;
+    const int cap = need <= kCapSmall ? kCapSmall : need <= kCapMid ? kCapMid : kCapBig;
+    const int bin_forced = env_int("TENSILE_EVAL_BINNED", -1);   // tuning knob: 0 = never, 1 = whenever possible
     int threads = a.T <= kSmallGeometryMaxT ? 512 : 1024;
     if (a.B > tas->num_cus && (!a.resident || a.T <= 2 * kSmallGeometryMaxT)) threads = 512;
     const int threads_forced = env_int("TENSILE_EVAL_THREADS", 0);   // tuning knob
     if (threads_forced == 512 || threads_forced == 1024) threads = threads_forced;
+    // Rows up to 16,384 steps in batches of at least four plans per CU, plans short enough for 8 intervals per
+    // thread: 256 threads, four workgroups per CU (it has neither a binned nor a persistent form).  Four
+    // workgroups cover each other's starts better than two, and short rows waste less of their last tile:
+    // 4,096 plans of 6,000 steps 70.8 -> 51.9 us, of 1,000 steps 46.9 -> 29.5, of 16,384 steps 157 -> 146;
+    // on 300 plans the 512-thread geometry is level or ahead.
+    const bool tiny_ok = cap == kCapSmall && bin_forced != 1;
+    if (tiny_ok && threads_forced == 0 && a.T <= kSmallGeometryMaxT && a.B >= 4 * static_cast<int64_t>(tas->num_cus)) threads = 256;
+    if (threads_forced == 256 && tiny_ok) threads = 256;
     const bool small_for_batch = threads == 512 && a.T > kSmallGeometryMaxT;
     const int tile = threads * kVpt;
     const int64_t n_tiles = (static_cast<int64_t>(a.T) + tile - 1) / tile;
@@ -1511,13 +1555,6 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     const int out = !a.resident ? 0
                     : ((a.T % 2 == 0) && (reinterpret_cast<uintptr_t>(a.resident) % 16 == 0)) ? 2 : 1;
     const bool narrow = a.size_units != nullptr;
-    // intervals kept in registers by the common kernel: sized for the average plan with some
-    // slack; longer plans are left to the tail kernel
-    const int64_t avg_k = (a.n_intervals + a.B - 1) / a.B;
-    int64_t need = avg_k + avg_k / 8;
-    const int r_forced = env_int("TENSILE_EVAL_R", 0);   // tuning knob: registers per thread at 1024 threads
-    if (r_forced > 0) need = static_cast<int64_t>(r_forced) * 1024;
-    const int cap = need <= kCapSmall ? kCapSmall : need <= kCapMid ? kCapMid : kCapBig;
     a.tail_threshold = cap;
     {
         Scratch &sc = tas->scratch;
@@ -1530,7 +1567,6 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     }
     // a batch whose average plan does not fit the registers is binned by tile first
     bool binned = narrow && need > kCapBig && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2);
-    const int bin_forced = env_int("TENSILE_EVAL_BINNED", -1);   // tuning knob: 0 = never, 1 = whenever possible
     if (bin_forced == 0) binned = false;
     if (bin_forced == 1) binned = narrow && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2);
     if (a.n_intervals == 0) binned = false;   // nothing to bin (and no record for the binned kernel's clamped loads)
@@ -1555,8 +1591,9 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     const int pers_forced = env_int("TENSILE_EVAL_PERSISTENT", -1);   // tuning knob: 0 = never, 1 = whenever possible
     if (pers_forced == 0) persistent = false;
     if (pers_forced == 1) persistent = pers_ok;
-    const int rc = threads == 512 ? launch_geometry<512>(tas, a, blocks, cap, out, narrow, binned, persistent, stream)
-                                  : launch_geometry<1024>(tas, a, blocks, cap, out, narrow, binned, persistent, stream);
+    const int rc = threads == 256   ? launch_tiny_geometry(tas, a, blocks, out, narrow, stream)
+                   : threads == 512 ? launch_geometry<512>(tas, a, blocks, cap, out, narrow, binned, persistent, stream)
+                                    : launch_geometry<1024>(tas, a, blocks, cap, out, narrow, binned, persistent, stream);
     if (rc != TENSILE_OK) return rc;
     if (S > 1) {
         const int fthreads = 256;

@@ -115,9 +115,11 @@ def test_eval_shapes_and_segments(T, B, segs, monkeypatch):
 
 
 @pytest.mark.parametrize("threads,binned,T,segs", [(512, 0, 20011, 0), (1024, 0, 4097, 0), (512, 1, 12291, 0),
-                                                    (1024, 1, 20011, 2), (512, 1, 7, 0), (1024, 1, 50001, 3)])
+                                                    (1024, 1, 20011, 2), (512, 1, 7, 0), (1024, 1, 50001, 3),
+                                                    (256, 0, 20011, 0), (256, 0, 4097, 2), (256, 0, 2048, 0), (256, 0, 7, 0),
+                                                    (256, 0, 12291, 4)])
 def test_eval_geometries_and_binning(threads, binned, T, segs, monkeypatch):
-    """Both workgroup geometries on rows they would not get by default, and the binned path (endpoints
+    """The workgroup geometries on rows they would not get by default, and the binned path (endpoints
     sorted by tile first) on short and ragged rows, with and without several segments per plan."""
     monkeypatch.setenv("TENSILE_EVAL_THREADS", str(threads))
     monkeypatch.setenv("TENSILE_EVAL_BINNED", str(binned))
@@ -182,9 +184,33 @@ def test_eval_persistent_grid(threads, T, B, slots, tail, monkeypatch):
     check_eval(tas, pl, label=f"persistent threads={threads} T={T}")
 
 
+def test_eval_smallest_geometry_with_long_plans(monkeypatch):
+    """256-thread workgroups hold 2048 intervals of a plan; longer plans of the batch go to the tail kernel,
+    empty ones stay; rows and peaks-only; ragged and whole last tiles."""
+    monkeypatch.setenv("TENSILE_EVAL_THREADS", "256")
+    for T in (6000, 4096, 2049):
+        tas = small_random_tas(4100 + T, N=300, T=T, max_acc=4, base_bytes=5)
+        B = 19
+        base = make_plans(tas, B, 11, p_swap=0.7)
+        lists = [[(int(base.iv_tensor[k]), int(base.iv_out[k]), int(base.iv_in[k]), int(base.iv_kind[k]))
+                  for k in range(int(base.plan_offsets[b]), int(base.plan_offsets[b + 1]))] for b in range(B)]
+        lists[1] = []
+        lists[B - 1] = []
+        for b in (0, 7, B - 2):
+            lists[b] = (lists[b] * (2100 // len(lists[b]) + 1))[:2100 + 40 * b]
+        pl = plans_from_lists(lists)
+        say(f"eval 256 threads with long plans T={T} K={pl.n_intervals}")
+        h = P.tas_load(tas)
+        check_eval(tas, pl, h=h, label=f"256 threads T={T}")
+        _, p0, a0, _ = O.eval_plans(tas, pl, want_resident=False)
+        _, peak, arg, _ = gpu_eval(h, upload(pl), want_resident=False, want_min=False)
+        assert np.array_equal(peak.cpu().numpy(), p0) and np.array_equal(arg.cpu().numpy(), a0)
+        h.close()
+
+
 # ---- seeded sweep over shapes and launch variants ----------------------------------------------
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", range(30))
 def test_random_shapes_and_variants(case, monkeypatch):
     """Every entry point on a seeded random shape (row length, batch, density, odd/even T) under a random
     choice of the evaluator's launch variants (geometry, segments, binning, persistent grid)."""
@@ -193,7 +219,7 @@ def test_random_shapes_and_variants(case, monkeypatch):
     B = int(rng.integers(1, 24))
     N = max(1, min(int(rng.integers(1, 500)), T // 2))
     timed = bool(rng.integers(0, 2))
-    threads = int(rng.choice([0, 512, 1024]))
+    threads = int(rng.choice([0, 512, 1024])) if case < 24 else 256
     segs = int(rng.choice([0, 0, 1, 2, 3]))
     binned = int(rng.choice([-1, -1, 0, 1]))
     pers = int(rng.choice([-1, 0, 1]))
