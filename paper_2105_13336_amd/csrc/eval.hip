@@ -1234,7 +1234,7 @@ int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, i
     TS_HIP(hipGetLastError());
 #undef TS_LAUNCH_EVAL
 #undef TS_LAUNCH_OUT
-    {
+    if (a.n_intervals > a.tail_threshold) {   // (otherwise no plan can be longer than the registers hold)
         const int64_t resident = static_cast<int64_t>(tas->num_cus) * (1024 / kThr);
         const dim3 tgrid(static_cast<uint32_t>(blocks < resident ? blocks : resident));
 #define TS_LAUNCH_TAIL(NARROW)                                                                                            \
@@ -1261,7 +1261,8 @@ int launch_tiny_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t bloc
 #define TS_LAUNCH_TINY(NARROW, OUT)                                                                                  \
     do {                                                                                                             \
         hipLaunchKernelGGL((eval_kernel<kThr, kCapSmall / kThr, NARROW, OUT>), grid, block, 0, stream, a);           \
-        hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, OUT>), tgrid, block, 0, stream, a, blocks);               \
+        if (a.n_intervals > a.tail_threshold) /* else no plan can be longer than the registers hold */              \
+            hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, OUT>), tgrid, block, 0, stream, a, blocks);           \
     } while (0)
     if (narrow) {
         if (out == 2) TS_LAUNCH_TINY(true, 2);
