@@ -35,11 +35,24 @@
  * code, never throws or aborts; tensile_last_error() gives a thread-local
  * message for the last failure.  "HOST" / "DEVICE" says where a pointer must
  * live.  Device buffers are caller-owned (any HIP allocation, e.g. a torch
- * tensor's data_ptr()).  eval/score are asynchronous: they enqueue on the
- * given HIP stream (hipStream_t passed as void*, NULL = the default stream) and
- * return.  They use scratch memory owned by the TAS handle, sized on first use
- * (that call may allocate and synchronise): calls that share a handle must be
- * ordered on one stream or serialised by the caller.
+ * tensor's data_ptr()).  eval/score/link/apply are asynchronous: they enqueue
+ * on the given HIP stream (hipStream_t passed as void*, NULL = the default
+ * stream) and return; they never wait for the device.
+ *
+ * Concurrency.  A loaded handle is read-only for every entry point except
+ * tensile_tas_update_latencies and tensile_tas_free: any number of host
+ * threads may call the others on one handle at the same time, on the same or
+ * on different streams.  Scratch memory (partial results, flags, staging) is
+ * kept per (handle, stream): calls on one stream run in order and share it,
+ * calls on different streams use different memory.  A call that needs more
+ * scratch than any earlier call on its stream allocates it (hipMalloc; the
+ * memory it replaces is kept until the handle is freed, since kernels enqueued
+ * earlier may still use it); a caller that cannot allocate at some point (a
+ * stream being captured into a graph, say) first makes one call of the largest
+ * shape on that stream.  The two tables
+ * that are built on first use (tensile_score_recompute,
+ * tensile_eval_plans_per_job) are built by whichever thread comes first while
+ * the others wait.  A stream must outlive the calls enqueued on it.
  */
 #ifndef TENSILE_H
 #define TENSILE_H
@@ -291,6 +304,26 @@ typedef struct {
 int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes, const tensile_greedy_opts *opts,
                         int32_t capacity, int32_t n_initial, int32_t *iv_tensor, int32_t *iv_out, int32_t *iv_in,
                         uint8_t *iv_kind, int32_t *n_intervals, int64_t *peak_trace, int64_t *final_peak);
+
+/* --------------------------------------------------- testing and tuning aids */
+
+/* Forces a launch choice that the library otherwise makes from the shape of the
+ * batch (results never depend on it; used by the parity tests to reach every
+ * kernel variant on small inputs, and by tuning runs).  Process-wide; set it
+ * while no call is in flight.  The library never reads the environment.
+ *   "eval_threads"    256 / 512 / 1024: workgroup geometry of the evaluation kernel (0 = automatic)
+ *   "eval_segments"   segments per plan (0 = automatic)
+ *   "eval_binned"     0 never sort a batch's endpoints by tile first, 1 whenever possible (-1 = automatic)
+ *   "eval_persistent" 0 never use the persistent grid, 1 whenever possible (-1 = automatic)
+ *   "eval_slots"      size of the persistent grid (0 = automatic)
+ *   "eval_r"          intervals per thread kept in registers (0 = automatic)
+ *   "score_blocks"    size of the scoring grid (0 = automatic)
+ *   "link_packed"     0: search the cumulative latencies themselves even when their packed form exists (1 = automatic)
+ * TENSILE_E_INVAL for an unknown name. */
+int tensile_tuning_set(const char *knob, int value);
+
+/* Back to the automatic choices. */
+void tensile_tuning_reset(void);
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,7 @@ EXPORTS = ["tensile_last_error", "tensile_version", "tensile_tas_load", "tensile
            "tensile_tas_update_latencies",
            "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_eval_link", "tensile_apply_intervals", "tensile_score_candidates", "tensile_score_recompute",
            "tensile_validate_plans",
-           "tensile_greedy_plan"]
+           "tensile_greedy_plan", "tensile_tuning_set", "tensile_tuning_reset"]
 
 
 class TensileError(RuntimeError):
@@ -58,6 +58,8 @@ def _load():
     lib.tensile_last_error.restype = ctypes.c_char_p
     lib.tensile_tas_free.restype = None
     lib.tensile_tas_free.argtypes = [ctypes.c_void_p]
+    lib.tensile_tuning_reset.restype = None
+    lib.tensile_tuning_set.argtypes = [ctypes.c_char_p, ctypes.c_int]
     return lib
 
 
@@ -194,6 +196,14 @@ def tensile_eval_plans(h: TasHandle, plans: DevicePlans, resident: Optional[torc
                                    _dp(min_resident, torch.int64, B, "min_resident"), _stream(stream)))
 
 
+def tensile_tuning_set(knob: str, value: int) -> None:
+    _check(_lib.tensile_tuning_set(knob.encode(), ctypes.c_int(int(value))))
+
+
+def tensile_tuning_reset() -> None:
+    _lib.tensile_tuning_reset()
+
+
 def tensile_eval_plans_per_job(h: TasHandle, plans: DevicePlans, job_peak: torch.Tensor,
                                job_argmax: Optional[torch.Tensor] = None, sum_peak: Optional[torch.Tensor] = None,
                                stream=None) -> None:
@@ -271,6 +281,8 @@ def tensile_greedy_plan(h: TasHandle, budget_bytes: int = 0, max_iters: int = 0,
         t[:n0], o[:n0], r[:n0], k[:n0] = initial
     trace = np.zeros(cap - n0 + 1, dtype=np.int64)
     num = _np(msr_num, np.int64)
+    if num is not None and num.shape != (h.J,):
+        raise TensileError(TENSILE_E_INVAL, f"msr_num: need one entry per job ({h.J})")
     opts = _GreedyOpts(int(max_iters), int(min_iters), int(bool(stop_at_budget)), _hp(num), int(msr_den), int(bool(recompute)))
     n, fp = ctypes.c_int32(), ctypes.c_int64()
     _check(_lib.tensile_greedy_plan(h.ptr, ctypes.c_int64(int(budget_bytes)), ctypes.byref(opts), ctypes.c_int32(cap),

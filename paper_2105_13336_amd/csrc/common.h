@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <map>
+#include <memory>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -25,14 +28,16 @@ template <typename T>
 struct DevBuf {
     T *p = nullptr;
     size_t n = 0;
+    bool owned = true;   // false: a view into memory somebody else owns (never freed here)
     DevBuf() = default;
     DevBuf(const DevBuf &) = delete;
     DevBuf &operator=(const DevBuf &) = delete;
     ~DevBuf() { release(); }
     void release() {
-        if (p) (void)hipFree(p);
+        if (p && owned) (void)hipFree(p);
         p = nullptr;
         n = 0;
+        owned = true;
     }
     // (Re)allocate to hold at least `count` elements; contents are not kept.  The pointer is valid
     // afterwards even for count == 0 (one element), so kernels may issue clamped loads from it.
@@ -83,11 +88,22 @@ struct EvalArgs {
     int32_t n_tiles;
 };
 
-struct Scratch {
-    DevBuf<int64_t> part_max, part_min;
+// Scratch memory of one call chain: partial results, flags and staging that the kernels need beyond the
+// caller's inputs and outputs.  A handle keeps one Workspace per HIP stream it has been called with: calls
+// enqueued on one stream run one after the other and share it, calls on different streams never touch the
+// same memory.  `mu` is held while a call sizes the buffers and enqueues its kernels, so two host threads
+// that use the same stream enqueue whole calls, never interleaved ones.  A buffer that has to grow is
+// replaced (at least doubled) and the old one is parked in `retired` until the handle is freed: kernels
+// enqueued earlier may still read it, and nothing here ever waits for the device.
+// fixed_base != null: the workspace lives in a preallocated region of fixed_bytes (see eval.hip, the entry
+// point that allocates nothing); buffers are then carved out of it per call and never grow.
+struct Workspace {
+    std::mutex mu;
+    hipStream_t stream = nullptr;
+    DevBuf<int64_t> part_max, part_min;   // eval / windowed update: per-segment partials
     DevBuf<int32_t> part_arg;
-    DevBuf<unsigned long long> tail_flag;   // eval: see EvalArgs::tail_flag
-    unsigned long long epoch = 0;
+    DevBuf<unsigned long long> tail_flag;   // eval: see EvalArgs::tail_flag (zero when allocated, then monotone)
+    unsigned long long epoch = 0;           // launches of the evaluation kernel through this workspace
     DevBuf<int64_t> score_tab;     // score: per-workgroup sub-span maxima when they do not fit in LDS
     DevBuf<int32_t> job_arg;       // per-job evaluation: peak steps when the caller does not want them
     DevBuf<int2> bin_recs;         // eval, binned mode: see EvalArgs
@@ -96,7 +112,39 @@ struct Scratch {
     DevBuf<unsigned int> apply_tickets;   // windowed update: finished runs per row (zero between launches)
     DevBuf<int32_t> link_first;    // link: earliest swap-out step per tensor, one row per workgroup (INT32_MAX between plans)
     DevBuf<int32_t> link_acc;      // link: one row per workgroup where the passes of a long plan add up
+    std::vector<void *> retired;
+    char *fixed_base = nullptr;
+    size_t fixed_bytes = 0, fixed_used = 0;
+    ~Workspace();
+    // Make `b` hold at least `count` elements (contents are not kept).  *fresh, when given, says whether the
+    // memory is new (the caller then initialises it on the stream).  TENSILE_OK, or an error code with the
+    // message set (TENSILE_E_CAPACITY in a fixed workspace that is too small).
+    template <typename T>
+    int provide(DevBuf<T> &b, size_t count, const char *what, bool *fresh = nullptr);
+    void begin_call() { fixed_used = fixed_base ? 256 : 0; }   // fixed: everything behind the flag's line is carved anew
 };
+
+// RAII: the workspace of (handle, stream), locked for the duration of one call's enqueueing.
+struct WorkspaceLock {
+    Workspace *ws = nullptr;
+    std::unique_lock<std::mutex> lock;
+    Workspace *operator->() const { return ws; }
+    Workspace &operator*() const { return *ws; }
+};
+
+// Launch choices that tests and tuning runs may force (tensile_tuning_set); 0 / -1 = the library decides.
+// Process-wide; never read from the environment.
+struct Tuning {
+    int eval_r = 0;            // intervals per thread kept in registers at 1024 threads
+    int eval_binned = -1;      // 0 never bin, 1 bin whenever possible
+    int eval_threads = 0;      // 256 / 512 / 1024
+    int eval_segments = 0;     // segments per plan
+    int eval_persistent = -1;  // 0 never, 1 whenever possible
+    int eval_slots = 0;        // size of the persistent grid
+    int score_blocks = 0;      // size of the scoring grid
+    int link_packed = 1;       // 0: search C itself even when its packed form exists
+};
+extern Tuning g_tuning;
 
 // C for the link kernel's searches (see link.hip): blocks of kLinkCBlock consecutive values, each block's six
 // differences packed into 16 bytes, 21 bits each (built when every operator latency is below 2^21 ns).
@@ -167,6 +215,7 @@ struct tensile_tas {
     bool c_packed = false;
     tensile::CandIndex index;                 // swap candidates: o = earliest feasible swap-out step
     // recomputation candidates (every gap, o = p), built by the first tensile_score_recompute
+    mutable std::mutex lazy_mu;               // guards the two tables that are built on first use
     mutable tensile::CandIndex recompute_index;
     mutable bool recompute_index_built = false;
     std::vector<int32_t> h_gp, h_gq, h_gt;    // gaps of length >= 2 in tensor order (host)
@@ -174,21 +223,30 @@ struct tensile_tas {
     // host copies used by the greedy driver and the validator
     std::vector<int64_t> h_size, h_C, h_x, h_touch_off;
     std::vector<int32_t> h_touch, h_job;
-    mutable tensile::Scratch scratch;
+    // one workspace per stream this handle has been called with (see Workspace)
+    mutable std::mutex ws_mu;
+    mutable std::map<hipStream_t, std::unique_ptr<tensile::Workspace>> workspaces;
 };
 
 namespace tensile {
 
+// workspace.hip
+// The workspace of (handle, stream), created on first use, locked until the returned object goes away.
+WorkspaceLock acquire_workspace(const tensile_tas *tas, hipStream_t stream);
+// dst[0..n) = value, 32-bit words, by a small kernel on the stream (not a memset node: callers may capture).
+int fill_words(hipStream_t stream, void *dst, size_t n_words, uint32_t value);
+
+// Every launch_* below enqueues on ws.stream and takes its scratch from ws (locked by the caller).
 // eval.hip
-int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, int32_t *argmax, int64_t *min_resident,
-                hipStream_t stream);
+int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, int64_t *peak, int32_t *argmax,
+                int64_t *min_resident);
 struct ApplyAppend {   // see launch_apply
     int32_t tensor, out, in, n;
     int32_t *plan_t, *plan_o, *plan_r;
     int64_t *plan_offs;
 };
-int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const int32_t *out, const int32_t *in,
-                 int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream,
+int launch_apply(const tensile_tas *tas, Workspace &ws, int32_t B, const int32_t *tensor, const int32_t *out,
+                 const int32_t *in, int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident,
                  const ApplyAppend *append_to = nullptr);
 // score.hip
 // What one greedy iteration brings back from the device: the peak, its step and the tensors with a window.
@@ -206,14 +264,15 @@ struct ScoreCand {
 //  hdr and compact may point into pinned host memory; with ready != null the kernel, once all of that is
 //  visible to the host, stores ready_value to *ready (system scope), so the host can wait for the word
 //  instead of the stream.)
-int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
+int launch_score(const tensile_tas *tas, Workspace &ws, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
-                 int32_t *win_in, hipStream_t stream, ScoreHeader *hdr = nullptr, ScoreCand *compact = nullptr,
+                 int32_t *win_in, ScoreHeader *hdr = nullptr, ScoreCand *compact = nullptr,
                  unsigned long long *ready = nullptr, unsigned long long ready_value = 0);
 // link.hip
-int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak, int32_t *argmax,
-                int32_t *overbooked, hipStream_t stream);
+int launch_link(const tensile_tas *tas, Workspace &ws, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak,
+                int32_t *argmax, int32_t *overbooked);
 // tas.hip
+int check_plans(const tensile_tas *tas, const tensile_plans *plans, const char *who);   // argument checks shared by the entry points
 int build_times_and_index(tensile_tas *tas, const int64_t *step_ns_host);
 int ensure_recompute_index(const tensile_tas *tas);
 

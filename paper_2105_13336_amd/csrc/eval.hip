@@ -51,7 +51,6 @@
 #include "common.h"
 #include "wave_ops.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace tensile {
@@ -1175,20 +1174,14 @@ __global__ void eval_finalize_kernel(int32_t B, int32_t S, const int64_t *part_m
 
 constexpr int kSmallGeometryMaxT = 16384;   // rows up to this length use the 512-thread geometry
 
-int env_int(const char *name, int fallback) {
-    const char *s = std::getenv(name);
-    if (!s || !*s) return fallback;
-    return std::atoi(s);
-}
-
 // The launches of one geometry: common kernel (three register capacities), tail kernel.
 template <int kThr>
-int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, int cap, int out, bool narrow, bool binned,
-                    bool persistent, hipStream_t stream) {
+int launch_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, int64_t blocks, int cap, int out, bool narrow,
+                    bool binned, bool persistent) {
+    const hipStream_t stream = ws.stream;
     dim3 grid(static_cast<uint32_t>(blocks)), block(kThr);
     if (binned) {
-        Scratch &sc = tas->scratch;
-        hipLaunchKernelGGL(bin_kernel<kThr>, dim3(a.B), dim3(1024), 0, stream, a, sc.bin_recs.p, sc.bin_off.p, sc.bin_sum.p);
+        hipLaunchKernelGGL(bin_kernel<kThr>, dim3(a.B), dim3(1024), 0, stream, a, ws.bin_recs.p, ws.bin_off.p, ws.bin_sum.p);
         TS_HIP(hipGetLastError());
         if (out == 2) {
             hipLaunchKernelGGL((eval_binned_kernel<kThr, 2, true>), grid, block, 0, stream, a);
@@ -1223,8 +1216,7 @@ int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, i
     if (kThr == 512 && cap != kCapSmall) persistent = false;
     if (persistent) {   // one workgroup per resident slot, the plans dealt evenly among them
         int64_t slots = static_cast<int64_t>(tas->num_cus) * (1024 / kThr);
-        const int slots_forced = env_int("TENSILE_EVAL_SLOTS", 0);   // tuning knob: size of the persistent grid
-        if (slots_forced > 0) slots = slots_forced;
+        if (g_tuning.eval_slots > 0) slots = g_tuning.eval_slots;
         const int64_t rounds = (blocks + slots - 1) / slots;
         grid = dim3(static_cast<uint32_t>((blocks + rounds - 1) / rounds));
     }
@@ -1253,8 +1245,9 @@ int launch_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, i
 
 // The smallest geometry: 256 threads, 2048-step tiles, 36 KB of LDS, four workgroups per CU.  Only the common
 // kernel with 8 intervals per thread (plans of up to 2048 intervals; longer ones go to the tail kernel).
-int launch_tiny_geometry(const tensile_tas *tas, const EvalArgs &a, int64_t blocks, int out, bool narrow, hipStream_t stream) {
+int launch_tiny_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, int64_t blocks, int out, bool narrow) {
     constexpr int kThr = 256;
+    const hipStream_t stream = ws.stream;
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kThr);
     const int64_t resident = static_cast<int64_t>(tas->num_cus) * (1024 / kThr);
     const dim3 tgrid(static_cast<uint32_t>(blocks < resident ? blocks : resident));
@@ -1413,10 +1406,11 @@ __global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(const ApplyAr
 
 // append_to: null, or the device arrays {tensor, out, in} and offsets of a one-plan batch that receive the
 // interval (one_tensor, one_out, one_in) at position plan_n (B must be 1; the device arrays of intervals are not read)
-int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const int32_t *out, const int32_t *in,
-                 int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident, hipStream_t stream,
+int launch_apply(const tensile_tas *tas, Workspace &ws, int32_t B, const int32_t *tensor, const int32_t *out,
+                 const int32_t *in, int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident,
                  const ApplyAppend *append_to) {
     if (B == 0) return TENSILE_OK;
+    const hipStream_t stream = ws.stream;
     const int32_t T = tas->T;
     // a row is cut into runs of chunks, one workgroup each: one run per row when the batch fills the chip by
     // itself (no partials), otherwise enough runs for about four workgroups per CU
@@ -1435,21 +1429,16 @@ int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const
     a.size = tas->d_size.p; a.tensor = tensor; a.out = out; a.in = in; a.resident = resident;
     a.peak = peak; a.argmax = argmax; a.min_resident = min_resident;
     if (S > 1) {
-        Scratch &sc = tas->scratch;
         const size_t n = static_cast<size_t>(blocks);
-        if (sc.part_max.n < n || sc.part_arg.n < n || sc.part_min.n < n) {
-            TS_HIP(hipDeviceSynchronize());   // an earlier launch may still read the old buffers
-            TS_HIP(sc.part_max.reserve(n));
-            TS_HIP(sc.part_arg.reserve(n));
-            TS_HIP(sc.part_min.reserve(n));
-        }
-        if (sc.apply_tickets.n < static_cast<size_t>(B)) {
-            TS_HIP(hipDeviceSynchronize());
-            TS_HIP(sc.apply_tickets.reserve(static_cast<size_t>(B)));
-            TS_HIP(hipMemset(sc.apply_tickets.p, 0, sc.apply_tickets.n * sizeof(unsigned int)));
-        }
-        a.part_max = sc.part_max.p; a.part_arg = sc.part_arg.p; a.part_min = sc.part_min.p;
-        a.tickets = sc.apply_tickets.p;
+        int rc = ws.provide(ws.part_max, n, "apply_intervals: partial maxima");
+        if (rc == TENSILE_OK) rc = ws.provide(ws.part_arg, n, "apply_intervals: partial peak steps");
+        if (rc == TENSILE_OK) rc = ws.provide(ws.part_min, n, "apply_intervals: partial minima");
+        bool fresh = false;
+        if (rc == TENSILE_OK) rc = ws.provide(ws.apply_tickets, static_cast<size_t>(B), "apply_intervals: tickets", &fresh);
+        if (rc == TENSILE_OK && fresh) rc = fill_words(stream, ws.apply_tickets.p, ws.apply_tickets.n, 0u);   // (kernels leave them at zero)
+        if (rc != TENSILE_OK) return rc;
+        a.part_max = ws.part_max.p; a.part_arg = ws.part_arg.p; a.part_min = ws.part_min.p;
+        a.tickets = ws.apply_tickets.p;
     }
     if (append_to) {
         if (B != 1) { set_error("apply_intervals: appending takes one plan"); return TENSILE_E_INVAL; }
@@ -1465,10 +1454,11 @@ int launch_apply(const tensile_tas *tas, int32_t B, const int32_t *tensor, const
     return TENSILE_OK;
 }
 
-int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, int32_t *argmax, int64_t *min_resident,
-                hipStream_t stream) {
+int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, int64_t *peak, int32_t *argmax,
+                int64_t *min_resident) {
     EvalArgs a = proto;
     if (a.B == 0) return TENSILE_OK;
+    const hipStream_t stream = ws.stream;
     // geometry: short rows get the small workgroups (see the top of the file).  So do batches of more than one
     // plan per CU when they write no rows or their rows have at most 32,768 steps: two workgroups per CU cover
     // each other's start.  Measured: 24,000-step rows, 8,192 plans 0.49 -> 0.43 ms, 384 plans 30.9 -> 26.5 us;
@@ -1479,13 +1469,13 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
     // slack; longer plans are left to the tail kernel
     const int64_t avg_k = (a.n_intervals + a.B - 1) / a.B;
     int64_t need = avg_k + avg_k / 8;
-    const int r_forced = env_int("TENSILE_EVAL_R", 0);   // tuning knob: registers per thread at 1024 threads
+    const int r_forced = g_tuning.eval_r;   // tuning knob: intervals per thread in registers at 1024 threads
     if (r_forced > 0) need = static_cast<int64_t>(r_forced) * 1024;
     const int cap = need <= kCapSmall ? kCapSmall : need <= kCapMid ? kCapMid : kCapBig;
-    const int bin_forced = env_int("TENSILE_EVAL_BINNED", -1);   // tuning knob: 0 = never, 1 = whenever possible
+    const int bin_forced = g_tuning.eval_binned;   // tuning knob: 0 = never, 1 = whenever possible
     int threads = a.T <= kSmallGeometryMaxT ? 512 : 1024;
     if (a.B > tas->num_cus && (!a.resident || a.T <= 2 * kSmallGeometryMaxT)) threads = 512;
-    const int threads_forced = env_int("TENSILE_EVAL_THREADS", 0);   // tuning knob
+    const int threads_forced = g_tuning.eval_threads;   // tuning knob
     if (threads_forced == 512 || threads_forced == 1024) threads = threads_forced;
     // Rows up to 16,384 steps in batches of at least four plans per CU, plans short enough for 8 intervals per
     // thread: 256 threads, four workgroups per CU (it has neither a binned nor a persistent form).  Four
@@ -1521,7 +1511,7 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
             }
         }
     }
-    const int forced = env_int("TENSILE_EVAL_SEGMENTS", 0);   // tuning knob
+    const int forced = g_tuning.eval_segments;   // tuning knob
     if (forced > 0) S = forced;
     if (S < 1) S = 1;
     if (S > n_tiles) S = n_tiles;
@@ -1541,60 +1531,67 @@ int launch_eval(const tensile_tas *tas, const EvalArgs &proto, int64_t *peak, in
         a.out_arg = argmax;
         a.out_min = min_resident;
     } else {
-        Scratch &sc = tas->scratch;
         const size_t n = static_cast<size_t>(a.B) * static_cast<size_t>(S);
-        if (sc.part_max.n < n || sc.part_arg.n < n || sc.part_min.n < n) {
-            TS_HIP(hipDeviceSynchronize());   // an earlier launch may still read the old buffers
-            TS_HIP(sc.part_max.reserve(n));
-            TS_HIP(sc.part_arg.reserve(n));
-            TS_HIP(sc.part_min.reserve(n));
-        }
-        a.out_max = sc.part_max.p;
-        a.out_arg = sc.part_arg.p;
-        a.out_min = sc.part_min.p;
+        int rc = ws.provide(ws.part_max, n, "eval: partial maxima");
+        if (rc == TENSILE_OK) rc = ws.provide(ws.part_arg, n, "eval: partial peak steps");
+        if (rc == TENSILE_OK) rc = ws.provide(ws.part_min, n, "eval: partial minima");
+        if (rc != TENSILE_OK) return rc;
+        a.out_max = ws.part_max.p;
+        a.out_arg = ws.part_arg.p;
+        a.out_min = ws.part_min.p;
     }
     const int out = !a.resident ? 0
                     : ((a.T % 2 == 0) && (reinterpret_cast<uintptr_t>(a.resident) % 16 == 0)) ? 2 : 1;
     const bool narrow = a.size_units != nullptr;
     a.tail_threshold = cap;
-    {
-        Scratch &sc = tas->scratch;
-        if (!sc.tail_flag.p) {
-            TS_HIP(sc.tail_flag.reserve(1));
-            TS_HIP(hipMemset(sc.tail_flag.p, 0, sizeof(unsigned long long)));
+    if (!ws.fixed_base) {   // (a fixed workspace brings its flag: zero when the code object is loaded, then monotone)
+        bool fresh = false;
+        const int rc = ws.provide(ws.tail_flag, 1, "eval: launch flag", &fresh);
+        if (rc == TENSILE_OK && fresh) {
+            const int rc_fill = fill_words(stream, ws.tail_flag.p, 2, 0u);
+            if (rc_fill != TENSILE_OK) return rc_fill;
         }
-        a.tail_flag = sc.tail_flag.p;
-        a.epoch = ++sc.epoch;
+        if (rc != TENSILE_OK) return rc;
     }
+    a.tail_flag = ws.tail_flag.p;
+    a.epoch = ++ws.epoch;
     // a batch whose average plan does not fit the registers is binned by tile first
     bool binned = narrow && need > kCapBig && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2);
     if (bin_forced == 0) binned = false;
     if (bin_forced == 1) binned = narrow && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2);
     if (a.n_intervals == 0) binned = false;   // nothing to bin (and no record for the binned kernel's clamped loads)
     if (binned) {
-        Scratch &sc = tas->scratch;
         const size_t n_recs = 2 * static_cast<size_t>(a.n_intervals), n_off = static_cast<size_t>(a.B) * (n_tiles + 1),
                      n_sum = static_cast<size_t>(a.B) * n_tiles;
-        if (sc.bin_recs.n < n_recs || sc.bin_off.n < n_off || sc.bin_sum.n < n_sum) {
-            TS_HIP(hipDeviceSynchronize());
-            TS_HIP(sc.bin_recs.reserve(n_recs));
-            TS_HIP(sc.bin_off.reserve(n_off));
-            TS_HIP(sc.bin_sum.reserve(n_sum));
+        if (ws.fixed_base) {
+            // a preallocated workspace that cannot hold the sorted records: the plans are evaluated from their
+            // lists as they are (the tail kernel re-reads them per tile), slower but in no need of scratch
+            const size_t need = (n_recs * sizeof(int2) + 255) / 256 * 256 + (n_off * sizeof(int32_t) + 255) / 256 * 256 +
+                                (n_sum * sizeof(int64_t) + 255) / 256 * 256;
+            if (need > ws.fixed_bytes - ws.fixed_used) binned = false;
         }
-        a.recs = sc.bin_recs.p;
-        a.tile_off = sc.bin_off.p;
-        a.tile_sum = sc.bin_sum.p;
+    }
+    if (binned) {
+        const size_t n_recs = 2 * static_cast<size_t>(a.n_intervals), n_off = static_cast<size_t>(a.B) * (n_tiles + 1),
+                     n_sum = static_cast<size_t>(a.B) * n_tiles;
+        int rc = ws.provide(ws.bin_recs, n_recs, "eval: sorted endpoint records");
+        if (rc == TENSILE_OK) rc = ws.provide(ws.bin_off, n_off, "eval: tile offsets");
+        if (rc == TENSILE_OK) rc = ws.provide(ws.bin_sum, n_sum, "eval: tile sums");
+        if (rc != TENSILE_OK) return rc;
+        a.recs = ws.bin_recs.p;
+        a.tile_off = ws.bin_off.p;
+        a.tile_sum = ws.bin_sum.p;
         a.n_tiles = static_cast<int32_t>(n_tiles);
     }
     // several plans per resident workgroup: the persistent kernel (it addresses a row's bytes with 32 bits)
     const bool pers_ok = S == 1 && !binned && a.N > 0 && a.T <= (1 << 28);
     bool persistent = pers_ok && out == 0 && a.B >= 4 * static_cast<int64_t>(tas->num_cus);
-    const int pers_forced = env_int("TENSILE_EVAL_PERSISTENT", -1);   // tuning knob: 0 = never, 1 = whenever possible
+    const int pers_forced = g_tuning.eval_persistent;   // tuning knob: 0 = never, 1 = whenever possible
     if (pers_forced == 0) persistent = false;
     if (pers_forced == 1) persistent = pers_ok;
-    const int rc = threads == 256   ? launch_tiny_geometry(tas, a, blocks, out, narrow, stream)
-                   : threads == 512 ? launch_geometry<512>(tas, a, blocks, cap, out, narrow, binned, persistent, stream)
-                                    : launch_geometry<1024>(tas, a, blocks, cap, out, narrow, binned, persistent, stream);
+    const int rc = threads == 256   ? launch_tiny_geometry(tas, ws, a, blocks, out, narrow)
+                   : threads == 512 ? launch_geometry<512>(tas, ws, a, blocks, cap, out, narrow, binned, persistent)
+                                    : launch_geometry<1024>(tas, ws, a, blocks, cap, out, narrow, binned, persistent);
     if (rc != TENSILE_OK) return rc;
     if (S > 1) {
         const int fthreads = 256;

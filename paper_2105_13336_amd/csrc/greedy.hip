@@ -109,6 +109,14 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
     }
     const tensile_greedy_opts defaults{0, 100, 0, nullptr, 1};
     const tensile_greedy_opts &opt = opts ? *opts : defaults;
+    if (opt.msr_num && opt.msr_den <= 0) {
+        set_error("greedy_plan: msr_den must be positive when msr_num is given");
+        return TENSILE_E_INVAL;
+    }
+    if (opt.msr_num) {
+        for (int32_t j = 0; j < tas->J; ++j)
+            if (opt.msr_num[j] < 0) { set_error("greedy_plan: msr_num[%d] is negative", j); return TENSILE_E_INVAL; }
+    }
     const int32_t T = tas->T, N = tas->N;
     const int32_t max_new = opt.max_iters > 0 ? opt.max_iters : INT32_MAX;
 
@@ -163,10 +171,13 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
             int rc = recompute_scores ? ensure_recompute_index(tas) : TENSILE_OK;
             if (rc != TENSILE_OK) return rc;
             const unsigned long long want = ++ready_seq;
-            rc = launch_score(tas, recompute_scores ? tas->recompute_index : tas->index, recompute_scores, &pl, d_res.p, d_peak.p,
-                              d_arg.p, nullptr, nullptr, nullptr, nullptr, static_cast<Header *>(rec_dev),
-                              reinterpret_cast<CandOut *>(static_cast<Header *>(rec_dev) + 1),
-                              static_cast<unsigned long long *>(ready_dev), want);
+            {
+                WorkspaceLock ws = acquire_workspace(tas, nullptr);
+                rc = launch_score(tas, *ws, recompute_scores ? tas->recompute_index : tas->index, recompute_scores, &pl, d_res.p,
+                                  d_peak.p, d_arg.p, nullptr, nullptr, nullptr, static_cast<Header *>(rec_dev),
+                                  reinterpret_cast<CandOut *>(static_cast<Header *>(rec_dev) + 1),
+                                  static_cast<unsigned long long *>(ready_dev), want);
+            }
             if (rc != TENSILE_OK) return rc;
             // wait for the word; should it not arrive (a failed launch shows up in the stream), ask the stream
             const auto t_start = std::chrono::steady_clock::now();
@@ -280,7 +291,8 @@ extern "C" int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes,
                 rc = tensile_eval_plans(tas, &pl, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr);
             } else {
                 const ApplyAppend last_one{iv_tensor[n - 1], iv_out[n - 1], iv_in[n - 1], n - 1, d_t.p, d_o.p, d_r.p, d_offs.p};
-                rc = launch_apply(tas, 1, nullptr, nullptr, nullptr, d_res.p, d_peak.p, d_arg.p, d_min.p, nullptr, &last_one);
+                WorkspaceLock ws = acquire_workspace(tas, nullptr);
+                rc = launch_apply(tas, *ws, 1, nullptr, nullptr, nullptr, d_res.p, d_peak.p, d_arg.p, d_min.p, &last_one);
             }
             if (rc != TENSILE_OK) return rc;
             if (last) {

@@ -32,8 +32,6 @@
 //    endpoint held in registers: the scatter of a 50,000-step row costs two rounds instead of seven;
 //  * reuse: a table of the earliest swap-out step per tensor (one row of N entries per workgroup in
 //    global memory, L2 atomics) is filled before a plan's first pass and cleaned after its last.
-#include <cstdlib>
-
 #include "common.h"
 #include "wave_ops.h"
 
@@ -500,11 +498,6 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
     }
 }
 
-int env_int(const char *name, int fallback) {
-    const char *v = std::getenv(name);
-    return (v && *v) ? std::atoi(v) : fallback;
-}
-
 // Without latencies nothing is transferred in measurable time: every output is zero.
 __global__ void link_zero_kernel(int64_t n_rows, int32_t *link, int32_t B, int32_t *peak, int32_t *argmax, int32_t *overbooked) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
@@ -523,8 +516,9 @@ __global__ void link_fill_kernel(int32_t *p, int64_t n, int32_t v) {
 
 }  // namespace
 
-int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak, int32_t *argmax,
-                int32_t *overbooked, hipStream_t stream) {
+int launch_link(const tensile_tas *tas, Workspace &ws, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak,
+                int32_t *argmax, int32_t *overbooked) {
+    const hipStream_t stream = ws.stream;
     const int32_t B = plans->B, T = tas->T;
     if (B == 0) return TENSILE_OK;
     if (T > (1 << 28)) { set_error("eval_link: T = %d exceeds 2^28 steps", T); return TENSILE_E_RANGE; }
@@ -541,7 +535,7 @@ int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, 
     a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in; a.iv_kind = plans->iv_kind;
     a.C = tas->d_C.p; a.x = tas->d_x.p;
     constexpr int kTabReal = kTabMax - 1;   // the last entry stays +inf
-    const bool packed = tas->c_packed && env_int("TENSILE_LINK_PACKED", 1) != 0;   // (0: testing aid, the probe search)
+    const bool packed = tas->c_packed && g_tuning.link_packed != 0;   // (0: testing aid, the probe search)
     a.fine_bits = 0;
     if (packed) {
         const int64_t n_blocks = static_cast<int64_t>(T) / kLinkCBlock + 1;
@@ -555,25 +549,23 @@ int launch_link(const tensile_tas *tas, const tensile_plans *plans, bool reuse, 
     }
     a.n_tab = static_cast<int32_t>(static_cast<int64_t>(T) / a.tab_stride + 1);   // entries k with k * stride <= T: at most kTabReal
     const int32_t grid = B < tas->num_cus ? B : tas->num_cus;
-    Scratch &sc = tas->scratch;
     if (reuse) {
         const size_t need = static_cast<size_t>(grid) * static_cast<size_t>(tas->N);
-        if (sc.link_first.n < need) {
-            TS_HIP(hipDeviceSynchronize());   // an earlier launch may still use the old table
-            TS_HIP(sc.link_first.reserve(need));
-            hipLaunchKernelGGL(link_fill_kernel, dim3(tas->num_cus * 4), dim3(256), 0, stream, sc.link_first.p,
-                               static_cast<int64_t>(sc.link_first.n), INT32_MAX);
+        bool fresh = false;
+        const int rc = ws.provide(ws.link_first, need, "eval_link: earliest swap-out table", &fresh);
+        if (rc != TENSILE_OK) return rc;
+        if (fresh) {   // (the kernel leaves the table as it found it)
+            hipLaunchKernelGGL(link_fill_kernel, dim3(tas->num_cus * 4), dim3(256), 0, stream, ws.link_first.p,
+                               static_cast<int64_t>(ws.link_first.n), INT32_MAX);
             TS_HIP(hipGetLastError());
         }
-        a.first_out = sc.link_first.p;
+        a.first_out = ws.link_first.p;
     }
     if (!link && plans->n_intervals > kPass) {   // some plan may need several passes
         const size_t need = static_cast<size_t>(grid) * static_cast<size_t>(T);
-        if (sc.link_acc.n < need) {
-            TS_HIP(hipDeviceSynchronize());
-            TS_HIP(sc.link_acc.reserve(need));
-        }
-        a.acc_rows = sc.link_acc.p;
+        const int rc = ws.provide(ws.link_acc, need, "eval_link: accumulation rows");
+        if (rc != TENSILE_OK) return rc;
+        a.acc_rows = ws.link_acc.p;
     }
     a.link = link; a.peak = peak; a.argmax = argmax; a.overbooked = overbooked;
     if (packed) hipLaunchKernelGGL(link_kernel<true>, dim3(grid), dim3(kThr), 0, stream, a);

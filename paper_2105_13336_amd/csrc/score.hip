@@ -40,7 +40,7 @@
 // Buckets with more entries than acc holds are processed in slices of kMaxLocal
 // entries, one full pass per slice; the index keeps the q order and the
 // wavefronts' start positions per slice.
-#include <cstdlib>
+#include <atomic>
 
 #include "common.h"
 #include "wave_ops.h"
@@ -594,29 +594,29 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const ScoreArgs a) {
 
 }  // namespace
 
-int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
+int launch_score(const tensile_tas *tas, Workspace &ws, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
-                 int32_t *win_in, hipStream_t stream, ScoreHeader *hdr, ScoreCand *compact, unsigned long long *ready,
+                 int32_t *win_in, ScoreHeader *hdr, ScoreCand *compact, unsigned long long *ready,
                  unsigned long long ready_value) {
     if (plans->B == 0 || tas->N == 0) return TENSILE_OK;
+    const hipStream_t stream = ws.stream;
     if (compact && (plans->B != 1 || !hdr)) { set_error("score: the compact form takes one plan"); return TENSILE_E_INVAL; }
     // as many workgroups as the device keeps resident, the plans dealt evenly among them
     const bool big_t = (tas->T + kMini - 1) / kMini > kTabLds;
-    static int per_cu_of[2] = {0, 0};
-    int &per_cu = per_cu_of[big_t ? 1 : 0];
+    static std::atomic<int> per_cu_of[2];   // (0 = not asked yet; every thread that asks stores the same answer)
+    int per_cu = per_cu_of[big_t ? 1 : 0].load(std::memory_order_relaxed);
     if (per_cu == 0) {
         int n = 0;
         if (big_t) TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<true, true, false>, kThreads, 0));
         else TS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_kernel<false, true, false>, kThreads, 0));
         per_cu = n > 0 ? n : 1;
+        per_cu_of[big_t ? 1 : 0].store(per_cu, std::memory_order_relaxed);
     }
     const int64_t resident_blocks = static_cast<int64_t>(tas->num_cus) * per_cu;
     const int64_t rounds = (plans->B + resident_blocks - 1) / resident_blocks;
     int32_t blocks = static_cast<int32_t>((plans->B + rounds - 1) / rounds);
-    if (const char *forced = std::getenv("TENSILE_SCORE_BLOCKS")) {   // tuning knob: size of the grid (plans are dealt round-robin)
-        const long v = std::atol(forced);
-        if (v > 0) blocks = static_cast<int32_t>(v < plans->B ? v : plans->B);
-    }
+    if (const int v = g_tuning.score_blocks; v > 0)   // tuning knob: size of the grid (plans are dealt round-robin)
+        blocks = v < plans->B ? v : plans->B;
     ScoreArgs a;
     a.T = tas->T; a.N = tas->N; a.B = plans->B;
     a.tspan = ix.tspan;
@@ -636,13 +636,10 @@ int launch_score(const tensile_tas *tas, const CandIndex &ix, bool any_interval,
     a.hdr = hdr; a.compact = compact;
     a.ready = ready; a.ready_value = ready_value;
     if (a.n_tab > kTabLds) {
-        Scratch &sc = tas->scratch;
         const size_t need = static_cast<size_t>(blocks) * static_cast<size_t>(a.n_tab);
-        if (sc.score_tab.n < need) {
-            TS_HIP(hipDeviceSynchronize());
-            TS_HIP(sc.score_tab.reserve(need));
-        }
-        a.tab_scratch = sc.score_tab.p;
+        const int rc = ws.provide(ws.score_tab, need, "score: block maxima");
+        if (rc != TENSILE_OK) return rc;
+        a.tab_scratch = ws.score_tab.p;
     }
 #define TS_LAUNCH_SCORE(BIG, VEC)                                                                                      \
     do {                                                                                                               \

@@ -125,7 +125,8 @@ __global__ void lifetime_intervals_kernel(int32_t N, const int64_t *size, const 
     iv_in[i] = free_step[i] + 1;
 }
 
-int check_latencies(const char *who, int32_t T, int32_t N, const int64_t *step_ns, int64_t link_bytes_per_us) {
+int check_latencies(const char *who, int32_t T, int32_t N, const int64_t *size_bytes, const int64_t *step_ns,
+                    int64_t link_bytes_per_us) {
     if (!step_ns) return TENSILE_OK;
     if (link_bytes_per_us <= 0) {
         set_error("%s: link_bytes_per_us must be positive when step_ns is given", who);
@@ -137,6 +138,15 @@ int check_latencies(const char *who, int32_t T, int32_t N, const int64_t *step_n
         if (__builtin_add_overflow(sum, step_ns[t], &sum)) { set_error("%s: step_ns sums past int64", who); return TENSILE_E_RANGE; }
     }
     if (N > 0 && sum > INT64_MAX / 4) { set_error("%s: total latency too large", who); return TENSILE_E_RANGE; }
+    // a transfer time x_i = ceil(size_i * 1000 / link) is added to cumulative latencies: keep it in the same range
+    for (int32_t i = 0; i < N; ++i) {
+        const int64_t x = (size_bytes[i] * 1000 + link_bytes_per_us - 1) / link_bytes_per_us;   // (size * 1000 fits: checked at load)
+        if (x > INT64_MAX / 4) {
+            set_error("%s: the transfer of tensor %d over a link of %lld bytes/us takes too long to represent", who, i,
+                      static_cast<long long>(link_bytes_per_us));
+            return TENSILE_E_RANGE;
+        }
+    }
     return TENSILE_OK;
 }
 
@@ -182,7 +192,7 @@ int validate_desc(const tensile_tas_desc *d) {
             return TENSILE_E_RANGE;
         }
     }
-    return check_latencies("tas_load", d->T, d->N, d->step_ns, d->link_bytes_per_us);
+    return check_latencies("tas_load", d->T, d->N, d->size_bytes, d->step_ns, d->link_bytes_per_us);
 }
 
 // The unscheduled timeline of the tensors with the given sizes on top of a constant `base`, with the
@@ -212,8 +222,11 @@ int build_timeline(const tensile_tas *h, const int64_t *d_size, int64_t base_val
     a.T = T; a.N = N; a.B = 1; a.o_min = -1; a.n_intervals = N;
     a.plan_offsets = offs.p; a.iv_tensor = it.p; a.iv_out = io.p; a.iv_in = ir.p;
     a.size = neg.p; a.size_units = nullptr; a.MF0 = base.p; a.dMF0 = dbase.p; a.resident = MF_out;
-    int rc = launch_eval(h, a, peak.p, arg.p, mn.p, nullptr);
-    if (rc != TENSILE_OK) return rc;
+    {
+        WorkspaceLock ws = acquire_workspace(h, nullptr);
+        const int rc = launch_eval(h, *ws, a, peak.p, arg.p, mn.p);
+        if (rc != TENSILE_OK) return rc;
+    }
     if (peak_host) TS_HIP(hipMemcpy(peak_host, peak.p, sizeof(int64_t), hipMemcpyDeviceToHost));
     if (arg_host) TS_HIP(hipMemcpy(arg_host, arg.p, sizeof(int32_t), hipMemcpyDeviceToHost));
     hipLaunchKernelGGL(difference_kernel, dim3((T + 255) / 256), dim3(256), 0, 0, T, MF_out, dMF_out);
@@ -544,9 +557,9 @@ int build_times_and_index(tensile_tas *h, const int64_t *step_ns) {
 }
 
 // The index of the recomputation candidates: every gap, released right after the access that
-// opens it (o = p).  Built on first use; the handle is otherwise immutable, so concurrent first
-// calls on one handle are the caller's to avoid.
+// opens it (o = p).  Built on first use, by whichever caller comes first (the others wait).
 int ensure_recompute_index(const tensile_tas *tas) {
+    std::lock_guard<std::mutex> once(tas->lazy_mu);
     if (tas->recompute_index_built) return TENSILE_OK;
     try {
         int rc = build_candidate_index(tas, tas->recompute_index, tas->h_gp, tas->h_gq, tas->h_gt, tas->h_gp);
@@ -563,6 +576,7 @@ int ensure_recompute_index(const tensile_tas *tas) {
 // zero (an interval on such a tensor then changes nothing), and each job's own unscheduled timeline
 // without the base bytes.  Built on first use (see ensure_recompute_index about concurrency).
 int ensure_job_tables(const tensile_tas *tas) {
+    std::lock_guard<std::mutex> once(tas->lazy_mu);
     JobTables &jt = tas->job_tables;
     if (jt.built) return TENSILE_OK;
     const int32_t T = tas->T, N = tas->N, J = tas->J;
@@ -613,6 +627,8 @@ __global__ void sum_job_peaks_kernel(int32_t B, int32_t J, int64_t base, const i
     sum_peak[b] = s;
 }
 
+}  // namespace
+
 int check_plans(const tensile_tas *tas, const tensile_plans *plans, const char *who) {
     if (!tas || !plans) { set_error("%s: NULL handle or plans", who); return TENSILE_E_INVAL; }
     if (plans->B < 0 || plans->n_intervals < 0) { set_error("%s: negative B or n_intervals", who); return TENSILE_E_INVAL; }
@@ -624,7 +640,6 @@ int check_plans(const tensile_tas *tas, const tensile_plans *plans, const char *
     return TENSILE_OK;
 }
 
-}  // namespace
 }  // namespace tensile
 
 using namespace tensile;
@@ -664,7 +679,7 @@ void tensile_tas_free(tensile_tas *tas) {
 
 int tensile_tas_update_latencies(tensile_tas *tas, const int64_t *step_ns, int64_t link_bytes_per_us) {
     if (!tas) { set_error("tas_update_latencies: NULL handle"); return TENSILE_E_INVAL; }
-    int rc = check_latencies("tas_update_latencies", tas->T, tas->N, step_ns, link_bytes_per_us);
+    int rc = check_latencies("tas_update_latencies", tas->T, tas->N, tas->h_size.data(), step_ns, link_bytes_per_us);
     if (rc != TENSILE_OK) return rc;
     TS_HIP(hipDeviceSynchronize());     // earlier launches may still read the tables replaced below
     tas->timed = step_ns != nullptr;
@@ -702,7 +717,8 @@ int tensile_eval_plans(const tensile_tas *tas, const tensile_plans *plans, int64
     a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;
     a.size = tas->d_size.p; a.size_units = tas->d_size_units.p; a.size_shift = tas->size_shift;
     a.MF0 = tas->d_MF0.p; a.dMF0 = tas->d_dMF0.p; a.resident = resident;
-    return launch_eval(tas, a, peak, argmax, min_resident, static_cast<hipStream_t>(hip_stream));
+    WorkspaceLock ws = acquire_workspace(tas, static_cast<hipStream_t>(hip_stream));
+    return launch_eval(tas, *ws, a, peak, argmax, min_resident);
 }
 
 int tensile_eval_plans_per_job(const tensile_tas *tas, const tensile_plans *plans, int64_t *job_peak, int32_t *job_argmax,
@@ -716,14 +732,11 @@ int tensile_eval_plans_per_job(const tensile_tas *tas, const tensile_plans *plan
     const JobTables &jt = tas->job_tables;
     const int32_t B = plans->B, J = tas->J;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    WorkspaceLock ws = acquire_workspace(tas, stream);
     if (!job_argmax) {
-        Scratch &sc = tas->scratch;
-        const size_t need = static_cast<size_t>(J) * B;
-        if (sc.job_arg.n < need) {
-            TS_HIP(hipDeviceSynchronize());
-            TS_HIP(sc.job_arg.reserve(need));
-        }
-        job_argmax = sc.job_arg.p;
+        rc = ws->provide(ws->job_arg, static_cast<size_t>(J) * B, "eval_plans_per_job: peak steps");
+        if (rc != TENSILE_OK) return rc;
+        job_argmax = ws->job_arg.p;
     }
     for (int32_t j = 0; j < J; ++j) {      // one pass of the evaluation kernel per job, footprint rows not written
         EvalArgs a{};
@@ -736,7 +749,7 @@ int tensile_eval_plans_per_job(const tensile_tas *tas, const tensile_plans *plan
         a.MF0 = jt.MF0.p + static_cast<size_t>(j) * tas->T;
         a.dMF0 = jt.dMF0.p + static_cast<size_t>(j) * jt.T_pad;
         a.resident = nullptr;
-        rc = launch_eval(tas, a, job_peak + static_cast<size_t>(j) * B, job_argmax + static_cast<size_t>(j) * B, nullptr, stream);
+        rc = launch_eval(tas, *ws, a, job_peak + static_cast<size_t>(j) * B, job_argmax + static_cast<size_t>(j) * B, nullptr);
         if (rc != TENSILE_OK) return rc;
     }
     if (sum_peak) {
@@ -757,8 +770,8 @@ int tensile_apply_intervals(const tensile_tas *tas, int32_t B, const int32_t *te
         set_error("apply_intervals: tensor, out_step, in_step, resident, peak and argmax are required");
         return TENSILE_E_INVAL;
     }
-    return launch_apply(tas, B, tensor, out_step, in_step, resident, peak, argmax, min_resident,
-                        static_cast<hipStream_t>(hip_stream));
+    WorkspaceLock ws = acquire_workspace(tas, static_cast<hipStream_t>(hip_stream));
+    return launch_apply(tas, *ws, B, tensor, out_step, in_step, resident, peak, argmax, min_resident);
 }
 
 int tensile_eval_link(const tensile_tas *tas, const tensile_plans *plans, int32_t reuse_host_copies, int32_t *link,
@@ -767,8 +780,8 @@ int tensile_eval_link(const tensile_tas *tas, const tensile_plans *plans, int32_
     if (rc != TENSILE_OK) return rc;
     if (plans->B == 0) return TENSILE_OK;
     if (!link_peak) { set_error("eval_link: link_peak is required"); return TENSILE_E_INVAL; }
-    return launch_link(tas, plans, reuse_host_copies != 0, link, link_peak, link_argmax, overbooked,
-                       static_cast<hipStream_t>(hip_stream));
+    WorkspaceLock ws = acquire_workspace(tas, static_cast<hipStream_t>(hip_stream));
+    return launch_link(tas, *ws, plans, reuse_host_copies != 0, link, link_peak, link_argmax, overbooked);
 }
 
 int tensile_score_candidates(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident,
@@ -781,8 +794,8 @@ int tensile_score_candidates(const tensile_tas *tas, const tensile_plans *plans,
         set_error("score_candidates: resident, peak, argmax and score are required");
         return TENSILE_E_INVAL;
     }
-    return launch_score(tas, tas->index, false, plans, resident, peak, argmax, score, win_out, win_in,
-                        static_cast<hipStream_t>(hip_stream));
+    WorkspaceLock ws = acquire_workspace(tas, static_cast<hipStream_t>(hip_stream));
+    return launch_score(tas, *ws, tas->index, false, plans, resident, peak, argmax, score, win_out, win_in);
 }
 
 int tensile_score_recompute(const tensile_tas *tas, const tensile_plans *plans, const int64_t *resident,
@@ -797,8 +810,8 @@ int tensile_score_recompute(const tensile_tas *tas, const tensile_plans *plans, 
     }
     rc = ensure_recompute_index(tas);
     if (rc != TENSILE_OK) return rc;
-    return launch_score(tas, tas->recompute_index, true, plans, resident, peak, argmax, score, win_out, win_in,
-                        static_cast<hipStream_t>(hip_stream));
+    WorkspaceLock ws = acquire_workspace(tas, static_cast<hipStream_t>(hip_stream));
+    return launch_score(tas, *ws, tas->recompute_index, true, plans, resident, peak, argmax, score, win_out, win_in);
 }
 
 int tensile_validate_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *first_bad, int32_t *reason) {

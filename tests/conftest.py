@@ -18,3 +18,11 @@ def configs_small():
     """TAS of configurations 0-2 (cheap to build), built once per session."""
     from workloads import make_tas
     return {i: make_tas(i) for i in range(3)}
+
+
+@pytest.fixture
+def tuning():
+    """Forces launch choices of the library for one test (tensile_tuning_set) and puts the automatic ones back."""
+    import paper_2105_13336_amd as P
+    yield P.tensile_tuning_set
+    P.tensile_tuning_reset()

@@ -102,11 +102,11 @@ def test_eval_elementwise(idx, B, configs_small):
 
 @pytest.mark.parametrize("T,B,segs", [(1, 3, 0), (2, 2, 0), (7, 5, 0), (4095, 4, 0), (4096, 4, 0), (4097, 4, 0),
                                       (12289, 9, 0), (12291, 2, 0), (20011, 3, 3), (20011, 17, 2), (50001, 2, 0)])
-def test_eval_shapes_and_segments(T, B, segs, monkeypatch):
+def test_eval_shapes_and_segments(T, B, segs, tuning):
     """Odd and even T (8- and 16-byte stores), ragged tails, one tile, tile edges, several
     tiles per segment and several segments per plan (finalize kernel)."""
     if segs:
-        monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", str(segs))
+        tuning("eval_segments", segs)
     N = max(1, min(400, T // 2))
     tas = small_random_tas(1000 + T, N=N, T=T, max_acc=4 if T > 8 else 1, base_bytes=7)
     pl = make_plans(tas, B, 5, p_swap=0.7)
@@ -118,13 +118,13 @@ def test_eval_shapes_and_segments(T, B, segs, monkeypatch):
                                                     (1024, 1, 20011, 2), (512, 1, 7, 0), (1024, 1, 50001, 3),
                                                     (256, 0, 20011, 0), (256, 0, 4097, 2), (256, 0, 2048, 0), (256, 0, 7, 0),
                                                     (256, 0, 12291, 4)])
-def test_eval_geometries_and_binning(threads, binned, T, segs, monkeypatch):
+def test_eval_geometries_and_binning(threads, binned, T, segs, tuning):
     """The workgroup geometries on rows they would not get by default, and the binned path (endpoints
     sorted by tile first) on short and ragged rows, with and without several segments per plan."""
-    monkeypatch.setenv("TENSILE_EVAL_THREADS", str(threads))
-    monkeypatch.setenv("TENSILE_EVAL_BINNED", str(binned))
+    tuning("eval_threads", threads)
+    tuning("eval_binned", binned)
     if segs:
-        monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", str(segs))
+        tuning("eval_segments", segs)
     N = max(1, min(400, T // 2))
     tas = small_random_tas(2000 + T, N=N, T=T, max_acc=4 if T > 8 else 1, base_bytes=11)
     pl = make_plans(tas, 6, 7, p_swap=0.7)
@@ -133,14 +133,14 @@ def test_eval_geometries_and_binning(threads, binned, T, segs, monkeypatch):
 
 
 @pytest.mark.parametrize("threads,T,segs", [(512, 4097, 0), (1024, 20011, 2), (1024, 8192, 0)])
-def test_eval_binned_tiles_with_many_records(threads, T, segs, monkeypatch):
+def test_eval_binned_tiles_with_many_records(threads, T, segs, tuning):
     """The binned path takes a tile's records two per thread, one tile ahead; plans with a tile that holds
     more go through its general form.  One batch with plans of both kinds, with empty plans, and with every
     endpoint of a plan in one tile."""
-    monkeypatch.setenv("TENSILE_EVAL_THREADS", str(threads))
-    monkeypatch.setenv("TENSILE_EVAL_BINNED", "1")
+    tuning("eval_threads", threads)
+    tuning("eval_binned", 1)
     if segs:
-        monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", str(segs))
+        tuning("eval_segments", segs)
     tas = small_random_tas(2100 + T, N=400, T=T, max_acc=4, base_bytes=5)
     base = make_plans(tas, 8, 9, p_swap=0.8)
     lists = []
@@ -159,15 +159,15 @@ def test_eval_binned_tiles_with_many_records(threads, T, segs, monkeypatch):
 @pytest.mark.parametrize("threads,T,B,slots,tail", [(1024, 20011, 23, 3, False), (512, 12291, 40, 7, False), (1024, 4097, 9, 2, False),
                                                      (512, 7, 33, 4, False), (1024, 8192, 12, 5, False), (512, 20012, 21, 2, True),
                                                      (1024, 50001, 11, 3, True), (512, 4096, 5, 8, False)])
-def test_eval_persistent_grid(threads, T, B, slots, tail, monkeypatch):
+def test_eval_persistent_grid(threads, T, B, slots, tail, tuning):
     """The persistent kernel (several plans per workgroup, the next plan's intervals loaded during the
     current plan's last tile) with a grid forced small: ragged and whole last tiles, one tile per row,
     plans without intervals in the middle and at the end of a workgroup's walk, more workgroups than
     plans, and (tail) plans too long for the registers, which it must leave to the tail kernel."""
-    monkeypatch.setenv("TENSILE_EVAL_THREADS", str(threads))
-    monkeypatch.setenv("TENSILE_EVAL_PERSISTENT", "1")
-    monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", "1")
-    monkeypatch.setenv("TENSILE_EVAL_SLOTS", str(slots))
+    tuning("eval_threads", threads)
+    tuning("eval_persistent", 1)
+    tuning("eval_segments", 1)
+    tuning("eval_slots", slots)
     N = max(1, min(400, T // 2))
     tas = small_random_tas(3000 + T, N=N, T=T, max_acc=4 if T > 8 else 1, base_bytes=13)
     base = make_plans(tas, B, 9, p_swap=0.7)
@@ -184,10 +184,10 @@ def test_eval_persistent_grid(threads, T, B, slots, tail, monkeypatch):
     check_eval(tas, pl, label=f"persistent threads={threads} T={T}")
 
 
-def test_eval_smallest_geometry_with_long_plans(monkeypatch):
+def test_eval_smallest_geometry_with_long_plans(tuning):
     """256-thread workgroups hold 2048 intervals of a plan; longer plans of the batch go to the tail kernel,
     empty ones stay; rows and peaks-only; ragged and whole last tiles."""
-    monkeypatch.setenv("TENSILE_EVAL_THREADS", "256")
+    tuning("eval_threads", 256)
     for T in (6000, 4096, 2049):
         tas = small_random_tas(4100 + T, N=300, T=T, max_acc=4, base_bytes=5)
         B = 19
@@ -211,7 +211,7 @@ def test_eval_smallest_geometry_with_long_plans(monkeypatch):
 # ---- seeded sweep over shapes and launch variants ----------------------------------------------
 
 @pytest.mark.parametrize("case", range(30))
-def test_random_shapes_and_variants(case, monkeypatch):
+def test_random_shapes_and_variants(case, tuning):
     """Every entry point on a seeded random shape (row length, batch, density, odd/even T) under a random
     choice of the evaluator's launch variants (geometry, segments, binning, persistent grid)."""
     rng = np.random.default_rng(9000 + case)
@@ -224,14 +224,14 @@ def test_random_shapes_and_variants(case, monkeypatch):
     binned = int(rng.choice([-1, -1, 0, 1]))
     pers = int(rng.choice([-1, 0, 1]))
     if threads:
-        monkeypatch.setenv("TENSILE_EVAL_THREADS", str(threads))
+        tuning("eval_threads", threads)
     if segs:
-        monkeypatch.setenv("TENSILE_EVAL_SEGMENTS", str(segs))
+        tuning("eval_segments", segs)
     if binned >= 0:
-        monkeypatch.setenv("TENSILE_EVAL_BINNED", str(binned))
+        tuning("eval_binned", binned)
     if pers >= 0:
-        monkeypatch.setenv("TENSILE_EVAL_PERSISTENT", str(pers))
-        monkeypatch.setenv("TENSILE_EVAL_SLOTS", str(int(rng.integers(1, 6))))
+        tuning("eval_persistent", pers)
+        tuning("eval_slots", int(rng.integers(1, 6)))
     tas = small_random_tas(9100 + case, N=N, T=T, max_acc=int(rng.integers(1, 7)) if T > 8 else 1, timed=timed,
                            base_bytes=int(rng.integers(0, 1000)))
     pl = merged_plans(tas, B, 50 + case, p_swap=float(rng.uniform(0.05, 0.95))) if T > 2 else plans_from_lists([[]] * B)
@@ -375,10 +375,10 @@ def test_link_occupancy_shapes(T, B, reuse):
 
 @pytest.mark.parametrize("T,B,packed", [(32767, 3, 1), (32768, 3, 1), (32769, 4, 1), (50168, 3, 1), (50169, 3, 1), (65537, 3, 1),
                                          (120001, 2, 1), (32769, 3, 0), (120001, 2, 0)])
-def test_link_occupancy_long_rows(T, B, packed, monkeypatch):
+def test_link_occupancy_long_rows(T, B, packed, tuning):
     """Edges of the 32768-step tile, rows whose table of C covers every block of seven steps (up to 50,168
     steps) and rows where it skips blocks, with the packed differences of C and with the probe search."""
-    monkeypatch.setenv("TENSILE_LINK_PACKED", str(packed))
+    tuning("link_packed", packed)
     tas = small_random_tas(4300 + T, N=200, T=T, max_acc=6, timed=True)
     pl = merged_plans(tas, B, 31, p_swap=0.8)
     say(f"link long rows T={T} B={B} packed={packed} K={pl.n_intervals}")
@@ -465,8 +465,8 @@ def test_link_of_a_greedy_plan_is_exclusive(configs_small):
     h.close()
 
 
-def test_eval_binned_config(configs_small, monkeypatch):
-    monkeypatch.setenv("TENSILE_EVAL_BINNED", "1")
+def test_eval_binned_config(configs_small, tuning):
+    tuning("eval_binned", 1)
     tas = configs_small[2]
     pl = make_config_plans(2, tas, B=64)
     say("eval binned config 2")
@@ -575,10 +575,10 @@ def check_score(tas, pl, rows=None, h=None, label=""):
 
 
 @pytest.mark.parametrize("blocks", [1, 7, 100000])
-def test_score_grid_sizes(blocks, configs_small, monkeypatch):
+def test_score_grid_sizes(blocks, configs_small, tuning):
     """The scoring grid deals the plans round-robin over any number of workgroups: one for all plans, a few
     with several plans each (lists and filters carried from plan to plan), one per plan."""
-    monkeypatch.setenv("TENSILE_SCORE_BLOCKS", str(blocks))
+    tuning("score_blocks", blocks)
     tas = configs_small[1]
     pl = make_config_plans(1, tas, B=60)
     say(f"score with a grid of {blocks}")
@@ -586,12 +586,12 @@ def test_score_grid_sizes(blocks, configs_small, monkeypatch):
 
 
 @pytest.mark.parametrize("blocks,B", [(2, 97), (5, 64), (0, 1100)])
-def test_score_given_peak_steps(blocks, B, configs_small, monkeypatch):
+def test_score_given_peak_steps(blocks, B, configs_small, tuning):
     """Scoring takes the peak and its step as inputs, so any step may be given: both sides then apply the
     definition to that step.  Peak steps spread over the whole sequence (consecutive plans of a workgroup
     then look at different parts of the candidate index), some of them outside [0, T) = no candidate."""
     if blocks:
-        monkeypatch.setenv("TENSILE_SCORE_BLOCKS", str(blocks))
+        tuning("score_blocks", blocks)
     tas = configs_small[1]
     pl = make_config_plans(1, tas, B=B)
     say(f"score with given peak steps, grid {blocks or 'default'}, B={B}")
