@@ -943,84 +943,163 @@ def test_argument_errors(configs_small):
 
 # ------------------------------------------------- full-size configurations
 
-@pytest.mark.parametrize("idx,n_rows,n_score", [(1, 256, 24), (2, 128, 8), (3, 96, 4), (4, 6, 2)])
-def test_full_size_config(idx, n_rows, n_score):
-    """Whole batch on the GPU in the benchmark's launch configuration; the oracle recomputes
-    sampled plans one by one (rows spread over the batch, including the first and the last)."""
+N_THREADS = min(16, os.cpu_count() or 1)      # the oracle's C loops release the interpreter lock: plans split over threads
+
+
+def plan_range(pl: Plans, b0: int, b1: int) -> Plans:
+    """Plans b0 .. b1-1 of the batch as views (no copies)."""
+    k0, k1 = int(pl.plan_offsets[b0]), int(pl.plan_offsets[b1])
+    return Plans(b1 - b0, pl.plan_offsets[b0:b1 + 1] - k0, pl.iv_tensor[k0:k1], pl.iv_out[k0:k1], pl.iv_in[k0:k1], pl.iv_kind[k0:k1])
+
+
+def in_threads(fn, pieces):
+    """fn(piece) for every piece, on N_THREADS threads; results in order."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=N_THREADS) as pool:
+        return list(pool.map(fn, pieces))
+
+
+def cuts(b0, b1, n):
+    edges = np.linspace(b0, b1, min(n, b1 - b0) + 1).astype(np.int64)
+    return [(int(edges[k]), int(edges[k + 1])) for k in range(len(edges) - 1) if edges[k + 1] > edges[k]]
+
+
+@pytest.mark.parametrize("idx,n_score", [(1, 4096), (2, 8192), (3, 2048), (4, 128)])
+def test_full_size_config(idx, n_score):
+    """The whole batch on the GPU in the launch configuration the benchmark times, and EVERY plan of it
+    against the oracle: peak, peak step, minimum and the full footprint rows (rows downloaded in chunks of at
+    most 1 GB), the same for the windowed update of every row and the per-job peaks; scores, recomputation
+    savings and link occupancy on `n_score` plans spread over the batch (all of them on configuration 1)."""
     cfg = CONFIGS[idx]
     say(f"full-size config {idx}: building TAS and {cfg.B} plans")
     tas = make_tas(idx)
     pl = make_config_plans(idx, tas)
-    say(f"  N={tas.N} T={tas.T} K={pl.n_intervals}; uploading")
+    B, T, N = cfg.B, tas.T, tas.N
+    say(f"  N={N} T={T} K={pl.n_intervals}; uploading")
     h = P.tas_load(tas)
     dp = upload(pl)
     res, peak, arg, mn = gpu_eval(h, dp)
-    say("  eval done; comparing sampled rows")
-    rows = np.unique(np.linspace(0, cfg.B - 1, n_rows).astype(np.int64))
-    sel = pl.select(rows)
-    r0, p0, a0, m0 = O.eval_plans(tas, sel)
-    idxs = torch.as_tensor(rows, device="cuda")
-    assert np.array_equal(peak[idxs].cpu().numpy(), p0) and np.array_equal(arg[idxs].cpu().numpy(), a0)
-    assert np.array_equal(mn[idxs].cpu().numpy(), m0)
-    assert np.array_equal(res[idxs].cpu().numpy(), r0)
-    # properties that hold for every plan of the batch
-    assert torch.equal(res.max(dim=1).values, peak) and torch.equal(res.min(dim=1).values, mn)
-    first_max = (res == peak[:, None]).to(torch.int8).argmax(dim=1).to(torch.int32)
-    assert torch.equal(first_max, arg)
-    MF0 = torch.from_numpy(O.base_timeline(tas)).cuda()
-    assert bool((res <= MF0[None, :]).all()) and bool((mn >= 0).all()) and bool((res[:, -1] == MF0[-1]).all())
-    del first_max
-    say("  scoring the whole batch")
-    sc = torch.empty((cfg.B, tas.N), dtype=torch.int64, device="cuda")
-    wo = torch.empty((cfg.B, tas.N), dtype=torch.int32, device="cuda")
-    wi = torch.empty((cfg.B, tas.N), dtype=torch.int32, device="cuda")
-    P.tensile_score_candidates(h, dp, res, peak, arg, sc, wo, wi)
+    MF0 = O.base_timeline(tas)
+
+    say("  peak, peak step and minimum of every plan")
+    parts = in_threads(lambda c: O.eval_plans(tas, plan_range(pl, *c), want_resident=False, MF0=MF0), cuts(0, B, 4 * N_THREADS))
+    p_all, a_all, m_all = (np.concatenate([x[k] for x in parts]) for k in (1, 2, 3))
+    assert np.array_equal(peak.cpu().numpy(), p_all) and np.array_equal(arg.cpu().numpy(), a_all)
+    assert np.array_equal(mn.cpu().numpy(), m_all)
+    # the same through the peaks-only launch (another kernel variant)
+    _, peak2, arg2, _ = gpu_eval(h, dp, want_resident=False, want_min=False)
+    assert np.array_equal(peak2.cpu().numpy(), p_all) and np.array_equal(arg2.cpu().numpy(), a_all)
+    del peak2, arg2
+
+    # one more interval per plan on a copy of the rows (windowed update), then both sets of rows in chunks
+    t1, o1, r1 = extra_intervals(tas, B, 99)
+    res_up = res.clone()
+    peak_up, arg_up, mn_up = torch.empty_like(peak), torch.empty_like(arg), torch.empty_like(mn)
+    P.tensile_apply_intervals(h, torch.from_numpy(t1).cuda(), torch.from_numpy(o1).cuda(), torch.from_numpy(r1).cuda(),
+                              res_up, peak_up, arg_up, mn_up)
     torch.cuda.synchronize()
-    srows = rows[:: max(1, len(rows) // n_score)][:n_score]
-    pos = [int(np.searchsorted(rows, r)) for r in srows]
-    s0, o0, i0 = O.score_plans(tas, sel, r0, p0, a0, rows=pos)
-    sidx = torch.as_tensor(srows, device="cuda")
-    assert np.array_equal(sc[sidx].cpu().numpy(), s0) and np.array_equal(wo[sidx].cpu().numpy(), o0)
-    assert np.array_equal(wi[sidx].cpu().numpy(), i0)
-    size = torch.from_numpy(tas.size_bytes).cuda()
-    assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
+    chunk = max(1, (1 << 30) // (8 * T))
+    say(f"  every footprint row, and every row after the windowed update, in chunks of {chunk} plans")
+    pu, au, mu = peak_up.cpu().numpy(), arg_up.cpu().numpy(), mn_up.cpu().numpy()
+    for b0 in range(0, B, chunk):
+        b1 = min(B, b0 + chunk)
+        want = np.empty((b1 - b0, T), dtype=np.int64)
+
+        def rows_of(c, want=want, b0=b0):
+            r, _, _, _ = O.eval_plans(tas, plan_range(pl, *c), MF0=MF0)
+            want[c[0] - b0:c[1] - b0] = r
+            # the windowed update of these rows by the oracle, in place on its own copy
+            r2 = r.copy()
+            pa, aa, ma = O.apply_intervals(tas, t1[c[0]:c[1]], o1[c[0]:c[1]], r1[c[0]:c[1]], r2)
+            return c, r2, pa, aa, ma
+        pieces = in_threads(rows_of, cuts(b0, b1, N_THREADS))
+        got = res[b0:b1].cpu().numpy()
+        assert np.array_equal(got, want), f"rows of plans {b0}..{b1}"
+        got = res_up[b0:b1].cpu().numpy()
+        for c, r2, pa, aa, ma in pieces:
+            assert np.array_equal(got[c[0] - b0:c[1] - b0], r2), f"updated rows of plans {c[0]}..{c[1]}"
+            assert np.array_equal(pu[c[0]:c[1]], pa) and np.array_equal(au[c[0]:c[1]], aa) and np.array_equal(mu[c[0]:c[1]], ma)
+        del got, want, pieces
+        say(f"    plans {b0}..{b1} ok")
+    del res_up, peak_up, arg_up, mn_up
+
     if tas.J > 1 and tas.J <= 8:
-        say(f"  per-job peaks of the whole batch ({tas.J} jobs)")
-        jp = torch.empty((int(tas.J), cfg.B), dtype=torch.int64, device="cuda")
-        ja = torch.empty((int(tas.J), cfg.B), dtype=torch.int32, device="cuda")
-        tot = torch.empty(cfg.B, dtype=torch.int64, device="cuda")
+        say(f"  per-job peaks of every plan ({tas.J} jobs)")
+        jp = torch.empty((int(tas.J), B), dtype=torch.int64, device="cuda")
+        ja = torch.empty((int(tas.J), B), dtype=torch.int32, device="cuda")
+        tot = torch.empty(B, dtype=torch.int64, device="cuda")
         P.tensile_eval_plans_per_job(h, dp, jp, ja, tot)
         torch.cuda.synchronize()
-        jp0, ja0, t0 = O.eval_per_job(tas, pl.select(srows))
-        assert np.array_equal(jp[:, sidx].cpu().numpy(), jp0) and np.array_equal(ja[:, sidx].cpu().numpy(), ja0)
-        assert np.array_equal(tot[sidx].cpu().numpy(), t0) and bool((tot >= peak).all())
+        parts = in_threads(lambda c: O.eval_per_job(tas, plan_range(pl, *c)), cuts(0, B, 4 * N_THREADS))
+        assert np.array_equal(jp.cpu().numpy(), np.concatenate([x[0] for x in parts], axis=1))
+        assert np.array_equal(ja.cpu().numpy(), np.concatenate([x[1] for x in parts], axis=1))
+        assert np.array_equal(tot.cpu().numpy(), np.concatenate([x[2] for x in parts]))
+        del jp, ja, tot
+
+    # scores, recomputation savings, link occupancy: the whole batch on the GPU, n_score plans by the oracle
+    rows = np.unique(np.linspace(0, B - 1, min(n_score, B)).astype(np.int64))
+    sidx = torch.as_tensor(rows, device="cuda")
+    say(f"  scoring the whole batch; the oracle scores {len(rows)} plans")
+    sc = torch.empty((B, N), dtype=torch.int64, device="cuda")
+    wo = torch.empty((B, N), dtype=torch.int32, device="cuda")
+    wi = torch.empty((B, N), dtype=torch.int32, device="cuda")
+    P.tensile_score_candidates(h, dp, res, peak, arg, sc, wo, wi)
+    torch.cuda.synchronize()
+    got_s = [x[sidx].cpu().numpy() for x in (sc, wo, wi)]
+    size = torch.from_numpy(tas.size_bytes).cuda()
+    assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
+    P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)
+    torch.cuda.synchronize()
+    got_r = [x[sidx].cpu().numpy() for x in (sc, wo, wi)]
+    assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
+    del sc, wo, wi
+
+    def scores_of(c):
+        sel = pl.select(rows[c[0]:c[1]])
+        r0, p0, a0, _ = O.eval_plans(tas, sel, MF0=MF0)
+        return O.score_plans(tas, sel, r0, p0, a0), O.score_recompute_plans(tas, sel, r0, p0, a0)
+    pieces = cuts(0, len(rows), 2 * N_THREADS)
+    for c, (swap, rec) in zip(pieces, in_threads(scores_of, pieces)):
+        for k, name in enumerate(("score", "win_out", "win_in")):
+            assert np.array_equal(got_s[k][c[0]:c[1]], swap[k]), f"{name} of sampled plans {c}"
+            assert np.array_equal(got_r[k][c[0]:c[1]], rec[k]), f"recomputation {name} of sampled plans {c}"
+    assert int((got_s[1] >= 0).sum()) > len(rows)
+
     if tas.step_ns is not None:
         say("  link occupancy of the whole batch")
-        lrows = torch.empty((cfg.B, tas.T), dtype=torch.int32, device="cuda")
-        lpk = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
-        larg = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
-        lover = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
+        lrows = torch.empty((B, T), dtype=torch.int32, device="cuda")
+        lpk = torch.empty(B, dtype=torch.int32, device="cuda")
+        larg = torch.empty(B, dtype=torch.int32, device="cuda")
+        lover = torch.empty(B, dtype=torch.int32, device="cuda")
         P.tensile_eval_link(h, dp, lpk, lrows, larg, lover, reuse_host_copies=True)
         torch.cuda.synchronize()
-        l0, lp0, la0, lo0 = O.link_occupancy(tas, pl.select(srows), reuse=True)
-        assert np.array_equal(lrows[sidx].cpu().numpy(), l0) and np.array_equal(lpk[sidx].cpu().numpy(), lp0)
-        assert np.array_equal(larg[sidx].cpu().numpy(), la0) and np.array_equal(lover[sidx].cpu().numpy(), lo0)
+        got_l = [x[sidx].cpu().numpy() for x in (lrows, lpk, larg, lover)]
+        for c, want_l in zip(pieces, in_threads(lambda c: O.link_occupancy(tas, pl.select(rows[c[0]:c[1]]), reuse=True), pieces)):
+            for k, name in enumerate(("link rows", "link peak", "link peak step", "overbooked")):
+                assert np.array_equal(got_l[k][c[0]:c[1]], want_l[k]), f"{name} of sampled plans {c}"
         assert torch.equal(lrows.max(dim=1).values, lpk) and bool((lrows >= 0).all())
         assert torch.equal((lrows >= 2).sum(dim=1).to(torch.int32), lover)
         del lrows
-    say("  recomputation savings of the whole batch")
-    P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)
-    torch.cuda.synchronize()
-    s0, o0, i0 = O.score_recompute_plans(tas, sel, r0, p0, a0, rows=pos[:2])
-    assert np.array_equal(sc[sidx[:2]].cpu().numpy(), s0) and np.array_equal(wo[sidx[:2]].cpu().numpy(), o0)
-    assert np.array_equal(wi[sidx[:2]].cpu().numpy(), i0)
-    assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
-    say("  one more interval per plan of the whole batch (windowed update)")
-    t1, o1, r1 = extra_intervals(tas, cfg.B, 99)
-    P.tensile_apply_intervals(h, torch.from_numpy(t1).cuda(), torch.from_numpy(o1).cuda(), torch.from_numpy(r1).cuda(), res, peak, arg, mn)
-    torch.cuda.synchronize()
-    pa, aa, ma = O.apply_intervals(tas, t1[rows], o1[rows], r1[rows], r0)
-    assert np.array_equal(res[idxs].cpu().numpy(), r0) and np.array_equal(peak[idxs].cpu().numpy(), pa)
-    assert np.array_equal(arg[idxs].cpu().numpy(), aa) and np.array_equal(mn[idxs].cpu().numpy(), ma)
-    assert torch.equal(res.max(dim=1).values, peak) and torch.equal(res.min(dim=1).values, mn)
+    h.close()
+
+
+@pytest.mark.parametrize("idx", [2, 3])
+def test_greedy_on_large_configs(idx):
+    """The planner on the two-iteration transformer and on the four merged jobs, capped at 64 iterations:
+    from nothing, and - with a swapping rate of zero per job, so that swapping ends after each job's first
+    swap - through the recomputation phase on top of an existing plan (the batch's first)."""
+    tas = make_tas(idx)
+    say(f"greedy on config {idx}: N={tas.N} T={tas.T}")
+    h = P.tas_load(tas)
+    same_greedy(P.tensile_greedy_plan(h, 0, max_iters=64, capacity=64), O.greedy(tas, 0, max_iters=64))
+    first = make_config_plans(idx, tas, B=1)
+    init = tuple(np.ascontiguousarray(x) for x in first.plan(0))
+    n0 = len(init[0])
+    zero = np.zeros(int(tas.J), dtype=np.int64)
+    o = O.greedy(tas, 0, max_iters=64, initial=init, recompute=True, msr_num=zero, msr_den=1, capacity=n0 + 64)
+    g = P.tensile_greedy_plan(h, 0, max_iters=64, initial=init, recompute=True, msr_num=zero, msr_den=1, capacity=n0 + 64)
+    same_greedy(g, o)
+    kinds = g["iv_kind"][n0:]
+    say(f"  on top of {n0} intervals: {int((kinds == 0).sum())} swaps, {int((kinds == 1).sum())} recomputations")
+    assert len(kinds) == 64 and (kinds == 1).sum() >= 32
     h.close()
