@@ -49,7 +49,7 @@
  * memory it replaces is kept until the handle is freed, since kernels enqueued
  * earlier may still use it); a caller that cannot allocate at some point (a
  * stream being captured into a graph, say) first makes one call of the largest
- * shape on that stream.  The two tables
+ * shape on that stream, or uses tensile_eval_plans_static.  The two tables
  * that are built on first use (tensile_score_recompute,
  * tensile_eval_plans_per_job) are built by whichever thread comes first while
  * the others wait.  A stream must outlive the calls enqueued on it.
@@ -155,6 +155,33 @@ typedef struct {
  * Asynchronous on hip_stream.  B == 0 is a no-op. */
 int tensile_eval_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *resident, int64_t *peak,
                        int32_t *argmax, int64_t *min_resident, void *hip_stream);
+
+/* tensile_eval_plans for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same results, same kernels; the scratch memory (per-segment
+ * partial results, the launch flag, the sorted endpoint records of batches of
+ * long plans) lives in a 16 MiB device array that is part of the library's
+ * code object instead of the handle's per-stream workspaces, and the call makes
+ * no allocation of any kind on host or device paths of the HIP runtime
+ * (no hipMalloc / hipFree / allocating library routine).  Every GPU the library
+ * runs on holds its own copy of the array until the process ends.
+ *   Limits: the per-segment partials (20 bytes per plan and segment, only when
+ *   a plan is split into several segments: batches of fewer plans than the GPU
+ *   has compute units, or rows of millions of steps) must fit the 16 MiB, else
+ *   TENSILE_E_CAPACITY with the sizes in tensile_last_error() and nothing is
+ *   enqueued.  Batches whose average plan exceeds about 5,400 intervals are
+ *   sorted by tile first when the records (16 bytes per interval + 12 bytes per
+ *   plan and 8192 steps) fit what is left; otherwise they are evaluated from
+ *   their lists as they are, exactly but more slowly.
+ *   The handle must live on the current device (TENSILE_E_INVAL otherwise).
+ *   All calls on one GPU share that GPU's array, whatever the handle or stream:
+ *   calls that may overlap in time on one GPU (different streams, or different
+ *   host threads without a common stream order) race on it and give wrong
+ *   results; order them on one stream.  Nothing in the array needs to start
+ *   at zero between calls.
+ * Asynchronous on hip_stream.  B == 0 is a no-op. */
+int tensile_eval_plans_static(const tensile_tas *tas, const tensile_plans *plans, int64_t *resident, int64_t *peak,
+                              int32_t *argmax, int64_t *min_resident, void *hip_stream);
 
 /* Per-workload peaks (section III-A: the footprint MF_j of workload W_j counts
  * the accesses and schedule events of that workload alone, MP_j is its maximum,

@@ -23,7 +23,7 @@ EXPORTS = ["tensile_last_error", "tensile_version", "tensile_tas_load", "tensile
            "tensile_tas_update_latencies",
            "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_eval_link", "tensile_apply_intervals", "tensile_score_candidates", "tensile_score_recompute",
            "tensile_validate_plans",
-           "tensile_greedy_plan", "tensile_tuning_set", "tensile_tuning_reset"]
+           "tensile_greedy_plan", "tensile_eval_plans_static", "tensile_tuning_set", "tensile_tuning_reset"]
 
 
 class TensileError(RuntimeError):
@@ -194,6 +194,16 @@ def tensile_eval_plans(h: TasHandle, plans: DevicePlans, resident: Optional[torc
     _check(_lib.tensile_eval_plans(h.ptr, ctypes.byref(st), _dp(resident, torch.int64, B * h.T, "resident"),
                                    _dp(peak, torch.int64, B, "peak"), _dp(argmax, torch.int32, B, "argmax"),
                                    _dp(min_resident, torch.int64, B, "min_resident"), _stream(stream)))
+
+
+def tensile_eval_plans_static(h: TasHandle, plans: DevicePlans, resident: Optional[torch.Tensor], peak: torch.Tensor,
+                              argmax: torch.Tensor, min_resident: Optional[torch.Tensor] = None, stream=None) -> None:
+    """tensile_eval_plans with its scratch in the library's preallocated device array (allocates nothing)."""
+    B = plans.B
+    st = plans.struct()
+    _check(_lib.tensile_eval_plans_static(h.ptr, ctypes.byref(st), _dp(resident, torch.int64, B * h.T, "resident"),
+                                          _dp(peak, torch.int64, B, "peak"), _dp(argmax, torch.int32, B, "argmax"),
+                                          _dp(min_resident, torch.int64, B, "min_resident"), _stream(stream)))
 
 
 def tensile_tuning_set(knob: str, value: int) -> None:

@@ -1603,3 +1603,62 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
 }
 
 }  // namespace tensile
+
+// ---- evaluation without any allocation ---------------------------------------------------
+// For callers that cannot allocate (HIP graph capture, serving loops, harnesses that forbid it): the same
+// kernels with their scratch in a preallocated device array instead of the handle's workspaces.  Every GPU
+// the library runs on holds its own copy of the array for the life of the process.  Layout: the first 256
+// bytes hold the launch flag of the evaluation kernels (zero when the code object is loaded, then only ever
+// raised to the number of the latest launch, so it never needs clearing); the rest is carved up anew by every
+// call (per-segment partials, the records of binned batches), all of it written before it is read.
+constexpr size_t kStaticScratchBytes = size_t{16} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticWorkspace {
+    std::once_flag once;
+    hipError_t status = hipSuccess;
+    tensile::Workspace ws;
+};
+StaticWorkspace g_static_ws[kMaxDevices];
+}  // namespace
+
+extern "C" int tensile_eval_plans_static(const tensile_tas *tas, const tensile_plans *plans, int64_t *resident, int64_t *peak,
+                                         int32_t *argmax, int64_t *min_resident, void *hip_stream) {
+    using namespace tensile;
+    int rc = check_plans(tas, plans, "eval_plans_static");
+    if (rc != TENSILE_OK) return rc;
+    if (plans->B == 0) return TENSILE_OK;
+    if (!peak || !argmax) { set_error("eval_plans_static: peak and argmax are required"); return TENSILE_E_INVAL; }
+    int dev = -1;
+    TS_HIP(hipGetDevice(&dev));
+    if (dev != tas->device) {
+        set_error("eval_plans_static: the handle lives on device %d, the current device is %d", tas->device, dev);
+        return TENSILE_E_INVAL;
+    }
+    if (dev < 0 || dev >= kMaxDevices) { set_error("eval_plans_static: device %d is beyond the %d supported", dev, kMaxDevices); return TENSILE_E_RANGE; }
+    StaticWorkspace &sw = g_static_ws[dev];
+    // once per device, with that device current: where this device keeps its copy of the array
+    std::call_once(sw.once, [&sw]() {
+        void *ptr = nullptr;
+        sw.status = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (sw.status != hipSuccess) return;
+        sw.ws.fixed_base = static_cast<char *>(ptr);
+        sw.ws.fixed_bytes = kStaticScratchBytes;
+        sw.ws.tail_flag.owned = false;
+        sw.ws.tail_flag.p = static_cast<unsigned long long *>(ptr);
+        sw.ws.tail_flag.n = 1;
+    });
+    if (sw.status != hipSuccess) return hip_fail(sw.status, "hipGetSymbolAddress(scratch)");
+    std::lock_guard<std::mutex> g(sw.ws.mu);   // (serialises the enqueueing only; see the header about overlapping calls)
+    sw.ws.stream = static_cast<hipStream_t>(hip_stream);
+    sw.ws.begin_call();
+    EvalArgs a{};
+    a.T = tas->T; a.N = tas->N; a.B = plans->B; a.o_min = 0; a.n_intervals = plans->n_intervals;
+    a.plan_offsets = plans->plan_offsets;
+    a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;
+    a.size = tas->d_size.p; a.size_units = tas->d_size_units.p; a.size_shift = tas->size_shift;
+    a.MF0 = tas->d_MF0.p; a.dMF0 = tas->d_dMF0.p; a.resident = resident;
+    return launch_eval(tas, sw.ws, a, peak, argmax, min_resident);
+}

@@ -96,6 +96,7 @@ def test_null_arguments_are_errors_not_crashes(lib):
     assert lib.tensile_validate_plans(None, None, None, None) == -1
     assert lib.tensile_greedy_plan(None, ctypes.c_int64(0), None, 0, 0, None, None, None, None, None, None, None) == -1
     assert b"NULL" in lib.tensile_last_error()
+    assert lib.tensile_eval_plans_static(None, None, None, None, None, None, None) == -1
     lib.tensile_tas_free.restype = None
     lib.tensile_tas_free(None)     # allowed
 
