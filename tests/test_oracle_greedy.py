@@ -153,3 +153,79 @@ def test_link_is_exclusive():
     # tensor 0 takes link steps 1-2 and 9-10; tensor 1 is pushed to 3-4 and 7-8
     assert ivs == [(0, 2, 11), (1, 4, 9)]
     assert g["xfer_out_start"].tolist() == [1, 3] and g["xfer_in_start"].tolist() == [9, 7]
+
+
+def _place_by_enumeration(C, busy, lo, hi, x, earliest):
+    """Every way to put a transfer of duration x on consecutive free link steps a..e inside [lo, hi], no
+    longer than needed; the earliest one (smallest a, then e) or the latest one (largest e, then a)."""
+    options = []
+    for a in range(lo, hi + 1):
+        for e in range(a, hi + 1):
+            if busy[a:e + 1].any():
+                break
+            if C[e + 1] - C[a] >= x:
+                # no longer than needed: dropping the last step (earliest form) / the first step (latest form) is too short
+                shorter = (C[e] - C[a]) if earliest else (C[e + 1] - C[a + 1])
+                if e == a or shorter < x:
+                    options.append((a, e))
+                if earliest:
+                    break
+    if not options:
+        return None
+    return min(options) if earliest else max(options, key=lambda ae: (ae[1], ae[0]))
+
+
+@pytest.mark.parametrize("seed,link", [(21, 300_000), (24, 1_000_000), (28, 3_000_000), (25, 100_000), (27, 40_000)])
+def test_every_swap_choice_rederived(seed, link):
+    """Every iteration of the swap phase, re-derived from the (pinned) scores and an independent placement
+    on a busy-step mask: the winner is the first candidate in the order (score, size descending, tensor
+    ascending) whose swap-out fits the earliest free run after the previous access and whose swap-in fits
+    the latest free run before the next one, with the peak step still strictly inside the placed window."""
+    tas = small_random_tas(700 + seed, N=50, T=140, max_acc=4, timed=True, link_bytes_per_us=link)
+    g = O.greedy(tas, 0, min_iters=1 << 30)
+    C, x = O.times(tas)
+    busy = np.zeros(tas.T, dtype=bool)
+    ivs = []
+    n_skipped = 0
+    for k in range(len(g["iv_tensor"]) + 1):
+        pl = plans_from_lists([ivs])
+        res, peak, arg, _ = O.eval_plans(tas, pl)
+        assert peak[0] == g["peak_trace"][k]
+        sc, wo, wi = O.score_plans(tas, pl, res, peak, arg)
+        tstar = int(arg[0])
+        cands = [i for i in range(tas.N) if wo[0][i] >= 0]
+        cands.sort(key=lambda i: (-int(sc[0][i]), -int(tas.size_bytes[i]), i))
+        chosen = None
+        for i in cands:
+            q = int(wi[0][i])
+            p = int(max(t for t in touch_points(tas, i) if t < q))
+            if x[i] == 0:
+                placed = (p, q, -1, -1)
+            else:
+                out = _place_by_enumeration(C, busy, p + 1, q - 1, int(x[i]), earliest=True)
+                if out is None:
+                    n_skipped += 1
+                    continue
+                back = _place_by_enumeration(C, busy, out[1] + 1, q - 1, int(x[i]), earliest=False)
+                if back is None:
+                    n_skipped += 1
+                    continue
+                placed = (out[1], back[1] + 1, out[0], back[0])
+            if placed[0] < tstar < placed[1]:
+                chosen = (i,) + placed
+                break
+            n_skipped += 1
+        if k == len(g["iv_tensor"]):
+            assert chosen is None, "the planner stopped although a candidate could still be placed"
+            break
+        assert chosen is not None
+        i, o, r, a, c = chosen
+        assert (int(g["iv_tensor"][k]), int(g["iv_out"][k]), int(g["iv_in"][k])) == (i, o, r), f"iteration {k}"
+        assert (int(g["xfer_out_start"][k]), int(g["xfer_in_start"][k])) == (a, c), f"iteration {k}: link steps"
+        if a >= 0:
+            busy[a:o + 1] = True
+            busy[c:r] = True
+        ivs.append((i, o, r))
+    assert len(ivs) >= (6 if link >= 300_000 else 3)
+    if link <= 100_000:
+        assert n_skipped > 0      # (slow links: some candidates do not fit the link any more and are passed over)
