@@ -23,23 +23,62 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "eval_kernel_c3_hbm_traffic.txt")
+TRAFFIC_FILES = {"eval": os.path.join(ROOT, "profiles", "eval_kernel_c3_hbm_traffic.txt"),
+                 "score": os.path.join(ROOT, "profiles", "score_kernel_c3_hbm_traffic.txt"),
+                 "step": os.path.join(ROOT, "profiles", "step_kernel_c3_hbm_traffic.txt")}
+KERNEL_SOURCES = ("eval.hip", "score.hip", "step.hip", "common.h", "wave_ops.h")
 
 
-def measured_traffic(config: int):
-    """HBM bytes per eval launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
-    workload (the summary under profiles/ gives the commands); None for other workloads."""
-    if config != 3 or not os.path.exists(TRAFFIC_FILE):
-        return None
-    vals = {}
-    with open(TRAFFIC_FILE) as f:
+def kernel_sources_hash() -> str:
+    """SHA-256 over the kernel sources: a counter summary under profiles/ is tied to the code it was measured on."""
+    import hashlib
+    hsh = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        path = os.path.join(ROOT, "paper_2105_13336_amd", "csrc", name)
+        if os.path.exists(path):
+            with open(path, "rb") as f:
+                hsh.update(name.encode() + b"\0" + f.read())
+    return hsh.hexdigest()[:16]
+
+
+def measured_traffic(which: str, config: int):
+    """(HBM bytes per launch, note): FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs on this workload, as
+    recorded in the summary under profiles/ (which gives the commands and the calibration).  The number is
+    REPLAYED from that file, not measured in this run, so it is reported only while the file says it was taken on
+    the kernel sources as they are now; otherwise None with the reason."""
+    path = TRAFFIC_FILES[which]
+    if config != 3:
+        return None, "counter runs exist for configs[3] only"
+    if not os.path.exists(path):
+        return None, "no counter summary for this kernel"
+    vals, stamp = {}, None
+    with open(path) as f:
         for line in f:
             if "=" in line and not line.startswith("#"):
                 k, v = line.split("=", 1)
-                vals[k.strip()] = float(v.split()[0])
+                if k.strip() == "kernel_sources_sha256":
+                    stamp = v.split()[0]
+                else:
+                    try:
+                        vals[k.strip()] = float(v.split()[0])
+                    except ValueError:
+                        pass
+    if stamp != kernel_sources_hash():
+        return None, f"stale: {os.path.basename(path)} was measured on kernel sources {stamp}, these are {kernel_sources_hash()}"
     if "fetch_bytes_per_launch" in vals and "write_bytes_per_launch" in vals:
-        return vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"]
-    return None
+        return vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"], f"replayed from profiles/{os.path.basename(path)} (kernel sources {stamp})"
+    return None, "summary holds no byte counts"
+
+
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def log(msg: str) -> None:
@@ -86,9 +125,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
-    ap.add_argument("--cpu-plans", type=int, default=4096, help="plans in the oracle's sample (about 10-20 s of CPU work)")
+    ap.add_argument("--cpu-plans", type=int, default=4096, help="plans in the oracle's sample on all threads (a quarter of them on one thread)")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the oracle's second leg (default: min(16, cores))")
+    ap.add_argument("--print-sources-hash", action="store_true", help="print the hash that ties a counter summary to the kernel sources and exit")
     ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-planner leg")
     ap.add_argument("--eval-only", action="store_true", help="steps run tensile_eval_plans alone (profiling aid)")
+    ap.add_argument("--fused", action="store_true", help="the one-call row forces the fused evaluation + scoring kernel (profiling aid)")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-job and recomputation rows (profiling aid)")
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the benchmark: time plain fill / copy / reduction kernels over 6.55 GB and print them")
@@ -96,6 +138,9 @@ def main() -> int:
                     help="before the steps, launch one plain elementwise kernel (out = in + 1) that reads 2 GiB and writes "
                          "2 GiB: the dispatch of known size that FETCH_SIZE / WRITE_SIZE of a counter run are scaled by")
     args = ap.parse_args()
+    if args.print_sources_hash:
+        print(kernel_sources_hash())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build evaluates plans on ONE GPU (plans are independent; no multi-GPU path is built); "
               "run with --gpus 1", file=sys.stderr)
@@ -169,6 +214,8 @@ def main() -> int:
     # scoring: footprint rows in, scores and windows out, intervals in
     score_bytes = 8.0 * B * T + 16.0 * B * N + 12.0 * K + 12.0 * B
 
+    eval_traffic, eval_note = measured_traffic("eval", args.config)
+    score_traffic, score_note = measured_traffic("score", args.config)
     out = {
         "metric": "plan-timesteps evaluated/sec (eval_plans + score_candidates per step) and % of peak HBM GB/s",
         "value": value, "unit": "plan-timesteps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -177,8 +224,14 @@ def main() -> int:
         "config": {"workload": f"configs[{args.config}] {cfg.name}", "B": B, "T": T, "N": N, "intervals": K,
                    "step": "eval_plans" if args.eval_only else "eval_plans+score_candidates"},
         "roofline": {"kernel": "eval_kernel (tensile_eval_plans)", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.config),
-                     "algorithmic_bytes": eval_bytes, "avg_launch_ms": eval_avg},
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": eval_traffic,
+                     "traffic_note": eval_note, "algorithmic_bytes": eval_bytes, "avg_launch_ms": eval_avg},
+        # the longest kernel of the step has its own block
+        "roofline_score": {"kernel": "score_kernel (tensile_score_candidates)", "bound": "hbm",
+                           "achieved": score_bytes / max(score_avg, 1e-9) / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": score_bytes / max(score_avg, 1e-9) / 1e6 / HBM_PEAK_GBS, "traffic": score_traffic,
+                           "traffic_note": score_note, "algorithmic_bytes": score_bytes, "avg_launch_ms": score_avg},
+        "kernel_sources": kernel_sources_hash(),
         "rows": {
             "eval_plans": {"ms": eval_avg, "ms_min": float(np.min(eval_ms)),
                            "plan_timesteps_per_s": plan_timesteps / (eval_avg * 1e-3)},
@@ -186,6 +239,59 @@ def main() -> int:
                                  "frac_of_hbm_peak": score_bytes / max(score_avg, 1e-9) / 1e6 / HBM_PEAK_GBS},
         },
     }
+
+    if not args.eval_only:
+        # the same step through the one-call entry point
+        if args.fused:
+            P.tensile_tuning_set("step_fused", 1)
+        sc1, wo1, wi1 = torch.empty_like(sc), torch.empty_like(wo), torch.empty_like(wi)
+        pk1, ar1, mn1 = torch.empty_like(peak), torch.empty_like(arg), torch.empty_like(mn)
+        res1 = torch.empty_like(res)
+        P.tensile_eval_score_plans(h, dp, res1, pk1, ar1, mn1, sc1, wo1, wi1)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            P.tensile_eval_score_plans(h, dp, res1, pk1, ar1, mn1, sc1, wo1, wi1)
+        e1.record()
+        torch.cuda.synchronize()
+        ms1 = e0.elapsed_time(e1) / 10
+        for x, y in ((res1, res), (pk1, peak), (ar1, arg), (mn1, mn), (sc1, sc), (wo1, wo), (wi1, wi)):
+            assert torch.equal(x, y)
+        out["rows"]["eval_score_plans"] = {"ms": ms1, "plan_timesteps_per_s": plan_timesteps / (ms1 * 1e-3),
+                                           "kernels": "one fused kernel (forced)" if args.fused else "evaluation, then scoring"}
+        P.tensile_tuning_reset()
+        del sc1, wo1, wi1, pk1, ar1, mn1, res1
+
+    if not args.no_extras:
+        # The same batch with the intervals of every plan in random order (seeded): the kernel lets a wavefront skip
+        # the tiles its 384 consecutive intervals cannot touch, which a list in tensor / time order favours; a caller
+        # that appends intervals in any other order (the greedy planner does) gets this number instead.
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(210513336)
+        lens = dp.plan_offsets[1:] - dp.plan_offsets[:-1]
+        owner = torch.repeat_interleave(torch.arange(B, device="cuda", dtype=torch.int64), lens)
+        keys = (owner << 32) | torch.randint(0, 1 << 31, (K,), generator=gen, device="cuda", dtype=torch.int64)
+        perm = torch.argsort(keys)
+        del keys, owner
+        dps = P.DevicePlans(dp.plan_offsets, dp.iv_tensor[perm].contiguous(), dp.iv_out[perm].contiguous(),
+                            dp.iv_in[perm].contiguous(), None if dp.iv_kind is None else dp.iv_kind[perm].contiguous())
+        del perm
+        pk_s, ar_s, mn_s = torch.empty_like(peak), torch.empty_like(arg), torch.empty_like(mn)
+        res_s = torch.empty_like(res)
+        P.tensile_eval_plans(h, dps, res_s, pk_s, ar_s, mn_s)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            P.tensile_eval_plans(h, dps, res_s, pk_s, ar_s, mn_s)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_s = e0.elapsed_time(e1) / 5
+        assert torch.equal(pk_s, peak) and torch.equal(ar_s, arg) and torch.equal(mn_s, mn) and torch.equal(res_s, res)
+        out["rows"]["eval_plans_shuffled"] = {"ms": ms_s, "frac_of_hbm_peak": eval_bytes / (ms_s * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                              "note": "intervals of every plan in random order; results identical"}
+        del dps, res_s, pk_s, ar_s, mn_s
 
     if not args.eval_only and not args.no_extras and tas.J > 1:
         # per-job peaks and their sum (one pass of the evaluation kernel per job, no rows written)
@@ -281,27 +387,48 @@ def main() -> int:
             "budget": budget, "peak_after": int(g2["final_peak"])}
 
     if not args.no_cpu:
+        # The oracle as it stands on this machine's host cores, on a bounded sample of the same batch and the same
+        # step: once on one thread, once with the plans split evenly over P threads (the C loops release the
+        # interpreter lock).  A baseline, not a target.
+        from concurrent.futures import ThreadPoolExecutor
         from oracle import oracle as O
+        n_thr = args.cpu_threads if args.cpu_threads > 0 else min(16, os.cpu_count() or 1)
         ns = min(B, args.cpu_plans)
-        sample = pl.select(np.arange(ns))
-        log(f"cpu baseline: oracle on the first {ns} plans")
+        ns1 = max(1, ns // 4)
         MF0 = O.base_timeline(tas)
+
+        def leg(b0, b1):
+            sample = pl.select(np.arange(b0, b1))
+            t_a = time.perf_counter()
+            r0, p0, a0, m0 = O.eval_plans(tas, sample, MF0=MF0)
+            t_b = time.perf_counter()
+            sco = None if args.eval_only else O.score_plans(tas, sample, r0, p0, a0)
+            return (b0, b1), t_b - t_a, time.perf_counter() - t_b, (r0[:8].copy() if b0 == 0 else None, p0, a0, sco)
+
+        log(f"cpu baseline: oracle on the first {ns1} plans, one thread")
         tc0 = time.perf_counter()
-        r0, p0, a0, m0 = O.eval_plans(tas, sample, MF0=MF0)
-        tc1 = time.perf_counter()
-        if not args.eval_only:
-            s0, o0, i0 = O.score_plans(tas, sample, r0, p0, a0)
-        tc2 = time.perf_counter()
-        cpu_s = tc2 - tc0
-        out["cpu_baseline"] = {"value": ns * float(T) / cpu_s, "unit": "plan-timesteps/s", "cores": 1, "kind": "oracle",
-                               "sample": f"first {ns} of {B} plans of the same batch, same step "
-                                         f"({'eval' if args.eval_only else 'eval + score'}), single thread",
-                               "eval_only_value": ns * float(T) / (tc1 - tc0), "seconds": cpu_s}
+        one = leg(0, ns1)
+        t_one = time.perf_counter() - tc0
+        log(f"cpu baseline: oracle on the first {ns} plans, {n_thr} threads")
+        edges = np.linspace(0, ns, n_thr + 1).astype(int)
+        tc0 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=n_thr) as pool:
+            parts = list(pool.map(lambda k: leg(int(edges[k]), int(edges[k + 1])), range(n_thr)))
+        t_all = time.perf_counter() - tc0
+        what = "eval" if args.eval_only else "eval + score"
+        out["cpu_baseline"] = {"value": ns * float(T) / t_all, "unit": "plan-timesteps/s", "cores": n_thr, "kind": "oracle",
+                               "sample": f"first {ns} of {B} plans of the same batch, same step ({what}), plans split evenly "
+                                         f"over {n_thr} threads; single thread: first {ns1} plans",
+                               "seconds": t_all, "cpu_model": cpu_model(), "host_cores": os.cpu_count(),
+                               "single_thread": {"value": ns1 * float(T) / t_one, "cores": 1, "plans": ns1, "seconds": t_one,
+                                                 "eval_only_value": ns1 * float(T) / one[1]}}
         # the GPU results for the sample agree with what the oracle just computed
-        assert np.array_equal(peak[:ns].cpu().numpy(), p0) and np.array_equal(arg[:ns].cpu().numpy(), a0)
-        assert np.array_equal(res[:8].cpu().numpy(), r0[:8])
-        if not args.eval_only:
-            assert np.array_equal(sc[:ns].cpu().numpy(), s0) and np.array_equal(wo[:ns].cpu().numpy(), o0)
+        for (b0, b1), _, _, (r8, p0, a0, sco) in parts + [one]:
+            assert np.array_equal(peak[b0:b1].cpu().numpy(), p0) and np.array_equal(arg[b0:b1].cpu().numpy(), a0)
+            if r8 is not None:
+                assert np.array_equal(res[:8].cpu().numpy(), r8)
+            if sco is not None:
+                assert np.array_equal(sc[b0:b1].cpu().numpy(), sco[0]) and np.array_equal(wo[b0:b1].cpu().numpy(), sco[1])
     h.close()
     print(json.dumps(out), flush=True)
     return 0

@@ -221,6 +221,18 @@ int tensile_score_candidates(const tensile_tas *tas, const tensile_plans *plans,
                              const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
                              int32_t *win_in, void *hip_stream);
 
+/* Peak analysis and candidate scores of B plans in one call: the body of the
+ * loop of Alg. 3, where the memory peak analysis (Alg. 1) is immediately
+ * followed by the choice among the tensors resident at the peak (section IV-C).
+ * Outputs and their meaning are exactly those of tensile_eval_plans followed by
+ * tensile_score_candidates on the same batch (resident is required here, the
+ * scores are computed from it); the two kernels are enqueued back to back
+ * under one lock of the stream's workspace.  Asynchronous on hip_stream.
+ * B == 0 is a no-op. */
+int tensile_eval_score_plans(const tensile_tas *tas, const tensile_plans *plans, int64_t *resident, int64_t *peak,
+                             int32_t *argmax, int64_t *min_resident, int64_t *score, int32_t *win_out, int32_t *win_in,
+                             void *hip_stream);
+
 /* Recomputation savings for every plan (section IV-D, "Recomputation
  * Scheduling": recomputation is applied only to tensors that have never been
  * released, and valued by the memory it saves).  Tensor i may be dropped after
@@ -346,6 +358,10 @@ int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes, const tens
  *   "eval_r"          intervals per thread kept in registers (0 = automatic)
  *   "score_blocks"    size of the scoring grid (0 = automatic)
  *   "link_packed"     0: search the cumulative latencies themselves even when their packed form exists (1 = automatic)
+ *   "step_fused"      1: tensile_eval_score_plans takes each plan through evaluation and scoring in ONE kernel when the
+ *                     batch has the shape for it (sizes in 32-bit units, T even and at most 131,072, 16-byte aligned
+ *                     rows, plans of at most about 5,400 intervals on average); measured slower than the two kernels,
+ *                     hence never chosen automatically (0 / -1: two kernels)
  * TENSILE_E_INVAL for an unknown name. */
 int tensile_tuning_set(const char *knob, int value);
 

@@ -23,7 +23,7 @@ EXPORTS = ["tensile_last_error", "tensile_version", "tensile_tas_load", "tensile
            "tensile_tas_update_latencies",
            "tensile_tas_base_timeline", "tensile_eval_plans", "tensile_eval_plans_per_job", "tensile_eval_link", "tensile_apply_intervals", "tensile_score_candidates", "tensile_score_recompute",
            "tensile_validate_plans",
-           "tensile_greedy_plan", "tensile_eval_plans_static", "tensile_tuning_set", "tensile_tuning_reset"]
+           "tensile_greedy_plan", "tensile_eval_plans_static", "tensile_eval_score_plans", "tensile_tuning_set", "tensile_tuning_reset"]
 
 
 class TensileError(RuntimeError):
@@ -256,6 +256,19 @@ def tensile_score_candidates(h: TasHandle, plans: DevicePlans, resident: torch.T
     st = plans.struct()
     _check(_lib.tensile_score_candidates(h.ptr, ctypes.byref(st), _dp(resident, torch.int64, B * h.T, "resident"),
                                          _dp(peak, torch.int64, B, "peak"), _dp(argmax, torch.int32, B, "argmax"),
+                                         _dp(score, torch.int64, B * N, "score"), _dp(win_out, torch.int32, B * N, "win_out"),
+                                         _dp(win_in, torch.int32, B * N, "win_in"), _stream(stream)))
+
+
+def tensile_eval_score_plans(h: TasHandle, plans: DevicePlans, resident: torch.Tensor, peak: torch.Tensor, argmax: torch.Tensor,
+                             min_resident: Optional[torch.Tensor], score: torch.Tensor, win_out: Optional[torch.Tensor] = None,
+                             win_in: Optional[torch.Tensor] = None, stream=None) -> None:
+    """tensile_eval_plans followed by tensile_score_candidates on the same batch, in one call (one kernel when possible)."""
+    B, N = plans.B, h.N
+    st = plans.struct()
+    _check(_lib.tensile_eval_score_plans(h.ptr, ctypes.byref(st), _dp(resident, torch.int64, B * h.T, "resident"),
+                                         _dp(peak, torch.int64, B, "peak"), _dp(argmax, torch.int32, B, "argmax"),
+                                         _dp(min_resident, torch.int64, B, "min_resident"),
                                          _dp(score, torch.int64, B * N, "score"), _dp(win_out, torch.int32, B * N, "win_out"),
                                          _dp(win_in, torch.int32, B * N, "win_in"), _stream(stream)))
 

@@ -11,7 +11,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libtensile.so")
-SOURCES = ["tas.hip", "eval.hip", "score.hip", "greedy.hip", "link.hip", "workspace.hip"]
+SOURCES = ["tas.hip", "eval.hip", "score.hip", "greedy.hip", "link.hip", "workspace.hip", "step.hip"]
 
 
 def build_library(verbose: bool = False, extra_flags=()) -> str:

@@ -143,6 +143,7 @@ struct Tuning {
     int eval_slots = 0;        // size of the persistent grid
     int score_blocks = 0;      // size of the scoring grid
     int link_packed = 1;       // 0: search C itself even when its packed form exists
+    int step_fused = -1;       // tensile_eval_score_plans: 0 = two kernels, 1 = the fused kernel whenever its shape allows
 };
 extern Tuning g_tuning;
 
@@ -268,6 +269,9 @@ int launch_score(const tensile_tas *tas, Workspace &ws, const CandIndex &ix, boo
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
                  int32_t *win_in, ScoreHeader *hdr = nullptr, ScoreCand *compact = nullptr,
                  unsigned long long *ready = nullptr, unsigned long long ready_value = 0);
+// step.hip
+int launch_step(const tensile_tas *tas, Workspace &ws, const tensile_plans *plans, int64_t *resident, int64_t *peak,
+                int32_t *argmax, int64_t *min_resident, int64_t *score, int32_t *win_out, int32_t *win_in);
 // link.hip
 int launch_link(const tensile_tas *tas, Workspace &ws, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak,
                 int32_t *argmax, int32_t *overbooked);

@@ -95,6 +95,7 @@ extern "C" int tensile_tuning_set(const char *knob, int value) {
         {"eval_threads", &Tuning::eval_threads}, {"eval_segments", &Tuning::eval_segments},
         {"eval_persistent", &Tuning::eval_persistent}, {"eval_slots", &Tuning::eval_slots},
         {"score_blocks", &Tuning::score_blocks}, {"link_packed", &Tuning::link_packed},
+        {"step_fused", &Tuning::step_fused},
     };
     for (const auto &row : table)
         if (std::strcmp(knob, row.name) == 0) {

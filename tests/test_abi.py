@@ -97,6 +97,7 @@ def test_null_arguments_are_errors_not_crashes(lib):
     assert lib.tensile_greedy_plan(None, ctypes.c_int64(0), None, 0, 0, None, None, None, None, None, None, None) == -1
     assert b"NULL" in lib.tensile_last_error()
     assert lib.tensile_eval_plans_static(None, None, None, None, None, None, None) == -1
+    assert lib.tensile_eval_score_plans(None, None, None, None, None, None, None, None, None, None) == -1
     lib.tensile_tas_free.restype = None
     lib.tensile_tas_free(None)     # allowed
 
@@ -104,7 +105,7 @@ def test_null_arguments_are_errors_not_crashes(lib):
 def test_tuning_knobs(lib):
     lib.tensile_tuning_set.argtypes = [ctypes.c_char_p, ctypes.c_int]
     for name in (b"eval_threads", b"eval_segments", b"eval_binned", b"eval_persistent", b"eval_slots", b"eval_r",
-                 b"score_blocks", b"link_packed"):
+                 b"score_blocks", b"link_packed", b"step_fused"):
         assert lib.tensile_tuning_set(name, 1) == 0
     assert lib.tensile_tuning_set(b"no_such_knob", 1) == -1 and lib.tensile_tuning_set(None, 1) == -1
     lib.tensile_tuning_reset.restype = None

@@ -665,6 +665,91 @@ def test_score_optional_windows_and_blocking():
     h.close()
 
 
+# -------------------------------------------------------------------- evaluation + scoring in one call
+
+def gpu_step(h, dp):
+    B, N = dp.B, h.N
+    res = torch.full((B, h.T), -3, dtype=torch.int64, device="cuda")
+    peak = torch.full((B,), -3, dtype=torch.int64, device="cuda")
+    arg = torch.full((B,), -3, dtype=torch.int32, device="cuda")
+    mn = torch.full((B,), -3, dtype=torch.int64, device="cuda")
+    sc = torch.full((B, N), -3, dtype=torch.int64, device="cuda")
+    wo = torch.full((B, N), -3, dtype=torch.int32, device="cuda")
+    wi = torch.full((B, N), -3, dtype=torch.int32, device="cuda")
+    P.tensile_eval_score_plans(h, dp, res, peak, arg, mn, sc, wo, wi)
+    torch.cuda.synchronize()
+    return res, peak, arg, mn, sc, wo, wi
+
+
+def check_step(tas, pl, h=None, label=""):
+    own = h is None
+    h = h or P.tas_load(tas)
+    got = gpu_step(h, upload(pl))
+    r0, p0, a0, m0 = O.eval_plans(tas, pl)
+    s0, o0, i0 = O.score_plans(tas, pl, r0, p0, a0)
+    for name, g, w in zip(("resident", "peak", "argmax", "min", "score", "win_out", "win_in"), got, (r0, p0, a0, m0, s0, o0, i0)):
+        assert np.array_equal(g.cpu().numpy(), w), f"{label}: {name}"
+    if own:
+        h.close()
+    return int((o0 >= 0).sum())
+
+
+@pytest.mark.parametrize("fused", [1, 0, -1])
+@pytest.mark.parametrize("T,B,timed", [(8, 3, False), (4096, 5, True), (8192, 300, False), (8194, 7, True), (20012, 9, True),
+                                       (50000, 4, True), (33334, 600, True)])
+def test_eval_score_in_one_call(T, B, timed, fused, tuning):
+    """The fused kernel forced onto every shape it is compiled for (one tile, tile edges, ragged last tiles,
+    fewer plans than workgroups and several plans per workgroup), the two kernels one after the other, and the
+    library's own choice: the same outputs as the oracle's evaluation followed by its scores."""
+    tuning("step_fused", fused)
+    N = max(2, min(400, T // 2))
+    tas = small_random_tas(6000 + T, N=N, T=T, max_acc=5 if T > 8 else 1, timed=timed, base_bytes=21, link_bytes_per_us=400_000)
+    pl = make_plans(tas, B, 17, p_swap=0.5)
+    say(f"eval+score T={T} B={B} timed={timed} fused={fused} K={pl.n_intervals}")
+    n = check_step(tas, pl, label=f"T={T} fused={fused}")
+    assert n > 0 or T <= 8
+
+
+def test_eval_score_in_one_call_long_and_empty_plans(tuning):
+    """Plans that do not fit the registers of the evaluation phase (it takes them through the form that re-reads
+    its list per tile), empty plans, and peaks in different buckets of the candidate index from plan to plan."""
+    tuning("step_fused", 1)
+    tas = small_random_tas(6100, N=400, T=24576, max_acc=6, timed=True, link_bytes_per_us=400_000)
+    base = make_plans(tas, 14, 19, p_swap=0.6)
+    lists = []
+    for b in range(base.B):
+        t, o, r, k = base.plan(b)
+        one = [(int(t[j]), int(o[j]), int(r[j]), int(k[j])) for j in range(len(t))]
+        if b in (2, 9):
+            one = (one * (9000 // len(one) + 1))[:2100 + 700 * b]      # 3500 and 8400 intervals
+        if b in (0, 5, 13):
+            one = []
+        lists.append(one)
+    pl = plans_from_lists(lists)
+    say(f"eval+score fused, long and empty plans: {[len(x) for x in lists]}")
+    assert check_step(tas, pl, label="long and empty") > 0
+
+
+def test_eval_score_in_one_call_falls_back(tuning):
+    """Shapes the fused kernel is not compiled for (odd T, sizes beyond 32 bits) run the two kernels even when the
+    fused one is asked for; the scoring-only outputs may be left out."""
+    tuning("step_fused", 1)
+    tas = small_random_tas(6200, N=300, T=20011, max_acc=5, timed=True, link_bytes_per_us=400_000)
+    check_step(tas, make_plans(tas, 6, 3, p_swap=0.5), label="odd T")
+    tas = small_random_tas(6201, N=300, T=20012, max_acc=5, timed=True, max_size=1 << 36, link_bytes_per_us=1 << 24)
+    check_step(tas, make_plans(tas, 6, 3, p_swap=0.5), label="wide sizes")
+    tas = small_random_tas(6202, N=300, T=20012, max_acc=5, timed=True, link_bytes_per_us=400_000)
+    pl = make_plans(tas, 5, 4, p_swap=0.5)
+    h = P.tas_load(tas)
+    dp = upload(pl)
+    res, peak, arg, mn, sc, wo, wi = gpu_step(h, dp)
+    sc2 = torch.full_like(sc, -3)
+    P.tensile_eval_score_plans(h, dp, res, peak, arg, None, sc2, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(sc, sc2)
+    h.close()
+
+
 # -------------------------------------------------------------------- latency updates
 
 def test_update_latencies_rescoring_and_greedy():
@@ -1046,6 +1131,11 @@ def test_full_size_config(idx, n_score):
     P.tensile_score_candidates(h, dp, res, peak, arg, sc, wo, wi)
     torch.cuda.synchronize()
     got_s = [x[sidx].cpu().numpy() for x in (sc, wo, wi)]
+    say("  the same batch through tensile_eval_score_plans")
+    one_call = gpu_step(h, dp)
+    for name, g, w in zip(("resident", "peak", "argmax", "min", "score", "win_out", "win_in"), one_call, (res, peak, arg, mn, sc, wo, wi)):
+        assert torch.equal(g, w), f"one call: {name}"
+    del one_call
     size = torch.from_numpy(tas.size_bytes).cuda()
     assert bool((sc >= 0).all()) and bool((sc <= size[None, :]).all()) and bool(((wo >= 0) | (sc == 0)).all())
     P.tensile_score_recompute(h, dp, res, peak, arg, sc, wo, wi)
