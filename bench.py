@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 TRAFFIC_FILES = {"eval": os.path.join(ROOT, "profiles", "eval_kernel_c3_hbm_traffic.txt"),
                  "score": os.path.join(ROOT, "profiles", "score_kernel_c3_hbm_traffic.txt"),
                  "step": os.path.join(ROOT, "profiles", "step_kernel_c3_hbm_traffic.txt")}
-KERNEL_SOURCES = ("eval.hip", "score.hip", "step.hip", "common.h", "wave_ops.h")
+KERNEL_SOURCES = ("eval.hip", "eval_body.h", "score.hip", "score_body.h", "step.hip", "common.h", "wave_ops.h")
 
 
 def kernel_sources_hash() -> str:
