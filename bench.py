@@ -368,6 +368,7 @@ def main() -> int:
 
     if not args.no_greedy:
         iters = 48
+        P.tensile_greedy_plan(h, 0, max_iters=4, capacity=8192)      # warm-up: the planner's buffers are allocated once per handle
         torch.cuda.synchronize()
         tg = time.perf_counter()
         g = P.tensile_greedy_plan(h, 0, max_iters=iters, capacity=iters)

@@ -14,6 +14,8 @@
 
 namespace tensile {
 
+struct GreedyBuffers;   // greedy.hip: what a run of the planner allocates, kept by the handle for the next run
+
 void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
 int hip_fail(hipError_t e, const char *what);
 
@@ -188,6 +190,7 @@ struct CandIndex {
     DevBuf<int4> cand;
     DevBuf<int64_t> cand_size;
     DevBuf<int32_t> cand_o;
+    DevBuf<int32_t> cand_gap;      // the entry's gap: its number among the gaps of length >= 2 in tensor order
     DevBuf<int2> qord, tord;
     DevBuf<int32_t> slice_first;   // [n_buckets + 1]
     DevBuf<int32_t> wave_ptr;      // [slices][4][kScoreWaves + 1]
@@ -220,10 +223,14 @@ struct tensile_tas {
     mutable tensile::CandIndex recompute_index;
     mutable bool recompute_index_built = false;
     std::vector<int32_t> h_gp, h_gq, h_gt;    // gaps of length >= 2 in tensor order (host)
+    std::vector<int32_t> h_gap_first;         // [N+1] first gap of every tensor in those lists
     mutable tensile::JobTables job_tables;    // built by the first tensile_eval_plans_per_job
     // host copies used by the greedy driver and the validator
     std::vector<int64_t> h_size, h_C, h_x, h_touch_off;
     std::vector<int32_t> h_touch, h_job;
+    // the buffers of the last tensile_greedy_plan on this handle, for the next one to take (or null)
+    mutable std::mutex greedy_mu;
+    mutable tensile::GreedyBuffers *greedy_cache = nullptr;
     // one workspace per stream this handle has been called with (see Workspace)
     mutable std::mutex ws_mu;
     mutable std::map<hipStream_t, std::unique_ptr<tensile::Workspace>> workspaces;
@@ -241,14 +248,8 @@ int fill_words(hipStream_t stream, void *dst, size_t n_words, uint32_t value);
 // eval.hip
 int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, int64_t *peak, int32_t *argmax,
                 int64_t *min_resident);
-struct ApplyAppend {   // see launch_apply
-    int32_t tensor, out, in, n;
-    int32_t *plan_t, *plan_o, *plan_r;
-    int64_t *plan_offs;
-};
 int launch_apply(const tensile_tas *tas, Workspace &ws, int32_t B, const int32_t *tensor, const int32_t *out,
-                 const int32_t *in, int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident,
-                 const ApplyAppend *append_to = nullptr);
+                 const int32_t *in, int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident);
 // score.hip
 // What one greedy iteration brings back from the device: the peak, its step and the tensors with a window.
 struct ScoreHeader {
@@ -257,7 +258,8 @@ struct ScoreHeader {
 };
 struct ScoreCand {
     int64_t score;
-    int32_t tensor, wo, wi, pad;
+    int32_t tensor, wo, wi;
+    int32_t gap;                   // number of the candidate's gap (planner's kernel; -1 from the batch kernel's one-plan form)
 };
 // (any_interval: an interval of the entry's tensor cancels the entry wherever it lies, not only inside the gap.
 //  compact != null, B == 1 only: instead of the dense rows, one record per tensor with a window, in no
@@ -269,12 +271,31 @@ int launch_score(const tensile_tas *tas, Workspace &ws, const CandIndex &ix, boo
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,
                  int32_t *win_in, ScoreHeader *hdr = nullptr, ScoreCand *compact = nullptr,
                  unsigned long long *ready = nullptr, unsigned long long ready_value = 0);
+// One iteration of the planner in one launch (score.hip: greedy_step_kernel).  fresh: the interval that joins the plan
+// (applied to the row, written to `position` of the plan's device arrays), or null.
+struct GreedyNew {
+    int32_t tensor, out, in, position;
+    int32_t gap;                   // number of the gap the interval lies in (as the candidate's record gave it), or -1
+    int32_t *plan_t, *plan_o, *plan_r;
+};
+// What the planner keeps on the device from iteration to iteration besides the plan and its row.
+struct GreedyTables {
+    int64_t *blk_max;              // [ceil(T / kScoreMini)] maxima of the row's blocks
+    int32_t *blk_arg;              // ... and the earliest step of each
+    uint8_t *gap_taken;            // [G] the plan holds an interval inside this gap
+    uint8_t *tensor_taken;         // [N] the plan holds an interval of this tensor
+};
+int launch_greedy_step(const tensile_tas *tas, Workspace &ws, const CandIndex &ix, bool any_interval, const tensile_plans *pl,
+                       int64_t *row, const GreedyTables &tables, bool rebuild, const GreedyNew *fresh, bool do_score,
+                       ScoreHeader *hdr, ScoreCand *compact, unsigned long long *ready, unsigned long long ready_value);
 // step.hip
 int launch_step(const tensile_tas *tas, Workspace &ws, const tensile_plans *plans, int64_t *resident, int64_t *peak,
                 int32_t *argmax, int64_t *min_resident, int64_t *score, int32_t *win_out, int32_t *win_in);
 // link.hip
 int launch_link(const tensile_tas *tas, Workspace &ws, const tensile_plans *plans, bool reuse, int32_t *link, int32_t *peak,
                 int32_t *argmax, int32_t *overbooked);
+// greedy.hip
+void drop_greedy_cache(const tensile_tas *tas);   // (at tensile_tas_free)
 // tas.hip
 int check_plans(const tensile_tas *tas, const tensile_plans *plans, const char *who);   // argument checks shared by the entry points
 int build_times_and_index(tensile_tas *tas, const int64_t *step_ns_host);

@@ -788,17 +788,13 @@ constexpr int kApplyThr = 1024, kApplyChunk = kApplyThr * 8;
 struct ApplyArgs {
     int32_t T, N, S, chunks_per_group;
     const int64_t *size;
-    const int32_t *tensor, *out, *in;      // [B] the new intervals (unless `append`)
+    const int32_t *tensor, *out, *in;      // [B] the new intervals
     int64_t *resident;
     int64_t *part_max, *part_min;          // [B*S] per-run partials when S > 1
     int32_t *part_arg;
     unsigned int *tickets;                 // [B] zero between launches: runs of a row that have finished (S > 1)
     int64_t *peak, *min_resident;          // [B] results (min may be null)
     int32_t *argmax;
-    // one plan whose new interval comes by value and is appended to the plan's device arrays on the way
-    int32_t append, one_tensor, one_out, one_in, plan_n;
-    int32_t *plan_t, *plan_o, *plan_r;
-    int64_t *plan_offs;
 };
 
 template <bool kVec16>
@@ -812,14 +808,7 @@ __global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(const ApplyAr
     const int32_t group = static_cast<int32_t>(blockIdx.x % S);     // this workgroup's run of chunks of the row
     const int32_t g_lo = group * a.chunks_per_group * kApplyChunk;  // (fits: the host keeps S * chunks_per_group * chunk near T)
     const int32_t g_hi = T - g_lo < a.chunks_per_group * kApplyChunk ? T : g_lo + a.chunks_per_group * kApplyChunk;
-    const int32_t i = a.append ? a.one_tensor : a.tensor[plan], o = a.append ? a.one_out : a.out[plan],
-                  r = a.append ? a.one_in : a.in[plan];
-    if (a.append && blockIdx.x == 0 && tid == 0) {   // the plan's own arrays learn of the interval here
-        a.plan_t[a.plan_n] = i;
-        a.plan_o[a.plan_n] = o;
-        a.plan_r[a.plan_n] = r;
-        a.plan_offs[1] = a.plan_n + 1;
-    }
+    const int32_t i = a.tensor[plan], o = a.out[plan], r = a.in[plan];
     const bool ok = static_cast<uint32_t>(i) < static_cast<uint32_t>(a.N) && o >= 0 && r <= T && r > o;
     const int64_t sz = ok ? a.size[i] : 0;
     const int32_t win_lo = ok ? o + 1 : 0, win_hi = ok ? r : 0;   // steps win_lo .. win_hi - 1 change
@@ -910,11 +899,8 @@ __global__ __launch_bounds__(kApplyThr) void apply_interval_kernel(const ApplyAr
 
 }  // namespace
 
-// append_to: null, or the device arrays {tensor, out, in} and offsets of a one-plan batch that receive the
-// interval (one_tensor, one_out, one_in) at position plan_n (B must be 1; the device arrays of intervals are not read)
 int launch_apply(const tensile_tas *tas, Workspace &ws, int32_t B, const int32_t *tensor, const int32_t *out,
-                 const int32_t *in, int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident,
-                 const ApplyAppend *append_to) {
+                 const int32_t *in, int64_t *resident, int64_t *peak, int32_t *argmax, int64_t *min_resident) {
     if (B == 0) return TENSILE_OK;
     const hipStream_t stream = ws.stream;
     const int32_t T = tas->T;
@@ -945,12 +931,6 @@ int launch_apply(const tensile_tas *tas, Workspace &ws, int32_t B, const int32_t
         if (rc != TENSILE_OK) return rc;
         a.part_max = ws.part_max.p; a.part_arg = ws.part_arg.p; a.part_min = ws.part_min.p;
         a.tickets = ws.apply_tickets.p;
-    }
-    if (append_to) {
-        if (B != 1) { set_error("apply_intervals: appending takes one plan"); return TENSILE_E_INVAL; }
-        a.append = 1;
-        a.one_tensor = append_to->tensor; a.one_out = append_to->out; a.one_in = append_to->in; a.plan_n = append_to->n;
-        a.plan_t = append_to->plan_t; a.plan_o = append_to->plan_o; a.plan_r = append_to->plan_r; a.plan_offs = append_to->plan_offs;
     }
     const bool vec16 = (T % 2 == 0) && (reinterpret_cast<uintptr_t>(resident) % 16 == 0);
     const dim3 grid(static_cast<uint32_t>(blocks)), block(kApplyThr);

@@ -41,6 +41,7 @@
 // entries, one full pass per slice; the index keeps the q order and the
 // wavefronts' start positions per slice.
 #include <atomic>
+#include <type_traits>
 
 #include "score_body.h"
 
@@ -48,7 +49,405 @@ namespace tensile {
 
 namespace {
 
+// ---- one iteration of the planner on the device --------------------------------------------------------
+// Alg. 3 analyses the peak again after every tensor it schedules.  The planner's row exists already, so an
+// iteration is: take the new interval's bytes out of its window of the row; bring the maxima (and their earliest
+// steps) of the 256-step blocks the window touches up to date - the table of block maxima is kept in global
+// memory from iteration to iteration: it is the block-level form of the prefix / suffix maxima of the row, of
+// which only the window's part changes; find the peak and its earliest step from the table; score the candidates
+// and hand the host one record per tensor with a window.  One workgroup, one launch.
+//
+// With the table, the blocks of the row are independent of each other: the maximum of everything before a block
+// and of everything after it come from prefix / suffix scans of the table (196 entries for 50,000 steps), so the
+// blocks are dealt to the wavefronts round-robin, each block is read once (from L2: the row is 400 KB), and an
+// entry whose o (q) lies in a block completes max MF[0..o] (max MF[q..T)) from the block alone.  Which candidates
+// the plan has already dealt with is not worked out from the plan's list again either (the list grows with
+// every iteration): a flag per gap and per tensor, set as intervals join, says so.  (The batch
+// kernel gives every wavefront one contiguous span instead, with boundaries balanced at load time for rows that
+// come from HBM; on one L2-resident row that left the slowest wavefront 60 % behind the first.)  Rows of more than
+// 131,072 steps, whose table does not fit in LDS next to the lists, take the batch kernel's body in its one-plan
+// form.
+struct GreedyStepArgs {
+    ScoreArgs s;                 // the scoring pass: one plan (all of the interval arrays), hdr / compact / ready set
+    int64_t *row;                // [T] the plan's footprint, in/out
+    int64_t *blk_max;            // [ceil(T / kMini)] maxima of the row's blocks, in/out
+    int32_t *blk_arg;            // [ceil(T / kMini)] earliest step of each block's maximum, in/out
+    uint8_t *gap_taken;          // [gaps] the plan holds an interval inside this gap, in/out
+    uint8_t *tensor_taken;       // [N] the plan holds an interval of this tensor, in/out
+    int32_t new_gap;             // the new interval's gap, or -1
+    const int64_t *size;         // [N]
+    int32_t rebuild;             // every block's maximum is computed afresh (first launch on a row)
+    int32_t has_new;             // an interval joins the plan: applied to the row and written to position plan_n
+    int32_t new_tensor, new_out, new_in, plan_n;
+    int32_t *plan_t, *plan_o, *plan_r;
+    int32_t do_score;            // 0: only the header {peak, peak step, 0} is produced
+};
+
+constexpr int kStageRecs = 1024;   // records staged in LDS per round before they leave for the host
+
+struct TabledLds {
+    __attribute__((aligned(16))) SpanBuf buf[kWaves];     // 48 KB; after the streaming step: staging of the records
+    int64_t pmx[kTabLds + 1];        // pmx[k] = max of the blocks before k (pmx[0] = -inf)
+    int64_t smx[kTabLds + 1];        // smx[k] = max of the blocks k .. (smx[n_blk] = -inf)
+    int64_t tb[kTabLds];             // the table itself
+    int32_t ta[kTabLds];
+    int32_t lo_ptr[kTabLds + 1];     // first entry of the o order with o in block k or later
+    int32_t hi_ptr[kTabLds + 1];     // the same for the q order
+    int64_t acc[kMaxLocal];
+    int32_t lo_list[kMaxLocal];
+    int2 hi_list[kMaxLocal];
+    int32_t n_stage, peak_block;
+};
+static_assert(sizeof(SpanBuf) * kWaves >= kStageRecs * sizeof(ScoreCand), "the staging area reuses the wavefronts' buffers");
+
+// the compact epilogue: header, then the word the host waits for
+__device__ __forceinline__ void publish_header(const ScoreArgs &a, int64_t P, int32_t tstar, int32_t count) {
+    *a.hdr = ScoreHeader{P, tstar, count};
+    if (a.ready) {
+        __threadfence_system();
+        __hip_atomic_store(a.ready, a.ready_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
+// The window of the new interval leaves the row, and the table entries of the blocks it touches (of all blocks on a
+// fresh row) are recomputed.  One block per wavefront and round, 4 steps per lane.
+template <bool kVec>
+__device__ __forceinline__ void patch_row_and_table(const GreedyStepArgs &g, int tid) {
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int32_t T = g.s.T, n_blk = g.s.n_tab;
+    int64_t *const row = g.row;
+    const int32_t i = g.new_tensor, o = g.new_out, r = g.new_in;
+    const bool ok = g.has_new && static_cast<uint32_t>(i) < static_cast<uint32_t>(g.s.N) && o >= 0 && r <= T && r > o;
+    if (g.has_new && tid == 0) {   // the plan's own arrays learn of the interval here, and so do the flags
+        g.plan_t[g.plan_n] = i;
+        g.plan_o[g.plan_n] = o;
+        g.plan_r[g.plan_n] = r;
+        if (ok) {
+            g.tensor_taken[i] = 1;
+            if (g.new_gap >= 0) g.gap_taken[g.new_gap] = 1;
+        }
+    }
+    const int64_t sz = ok ? g.size[i] : 0;
+    const int32_t win_lo = ok ? o + 1 : 0, win_hi = ok ? r : 0;   // steps win_lo .. win_hi - 1 lose sz bytes
+    const bool any = win_hi > win_lo;
+    const int32_t kb0 = g.rebuild ? 0 : (any ? win_lo / kMini : 0);
+    const int32_t kb1 = g.rebuild ? n_blk : (any ? (win_hi - 1) / kMini + 1 : 0);
+    for (int32_t k = kb0 + wave; k < kb1; k += kWaves) {   // (wave-uniform)
+        const int32_t t = k * kMini + 4 * lane;
+        int64_t x[4];
+        load_quad<kVec>(row, t, T, x);    // steps beyond T come back as INT64_MIN and lie outside every window
+        bool ch[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            ch[j] = t + j >= win_lo && t + j < win_hi;
+            x[j] -= ch[j] ? sz : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; j += 2) {
+            if (kVec && ch[j] && ch[j + 1]) {
+                *reinterpret_cast<ll2 *>(row + t + j) = ll2{x[j], x[j + 1]};
+            } else {
+                if (ch[j]) row[t + j] = x[j];
+                if (ch[j + 1]) row[t + j + 1] = x[j + 1];
+            }
+        }
+        const int64_t lm = max64(max64(x[0], x[1]), max64(x[2], x[3]));
+        int32_t lj = 3;
+#pragma unroll
+        for (int j = 2; j >= 0; --j)
+            if (x[j] == lm) lj = j;
+        const int64_t m = last_lane(wave_scan_max(lm));
+        const uint64_t holders = __builtin_amdgcn_ballot_w64(lm == m);   // (never empty)
+        if (lane == __builtin_ctzll(holders)) {
+            g.blk_max[k] = m;
+            g.blk_arg[k] = t + lj;
+        }
+    }
+}
+
+// kBigT == false: the table-driven scoring pass described above.  kBigT == true: the batch kernel's body.
+template <bool kBigT, bool kVec>
+__global__ __launch_bounds__(kThreads) void greedy_step_kernel(const GreedyStepArgs g) {
+    typedef typename std::conditional<kBigT, ScoreLds<true>, TabledLds>::type Lds;
+    __shared__ Lds lds;
+    __shared__ int64_t red_v[kWaves];
+    __shared__ int32_t red_k[kWaves];
+    __shared__ int64_t s_peak;
+    __shared__ int32_t s_step;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef TENSILE_SCORE_PROF
+    unsigned long long prof_t = wall_clock64();
+#endif
+    const ScoreArgs &a = g.s;
+    const int32_t T = a.T, n_blk = a.n_tab;
+    patch_row_and_table<kVec>(g, tid);
+    // other wavefronts of this workgroup read what these stores wrote (table entries now, the row in the scoring pass)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+    if constexpr (kBigT) {
+        // ---- the peak: largest block maximum, earliest block among equals
+        int64_t bv = INT64_MIN;
+        int32_t bk = INT32_MAX;
+        for (int32_t k = tid; k < n_blk; k += kThreads) {   // (a thread meets its blocks in ascending order)
+            const int64_t v = g.blk_max[k];
+            if (v > bv) {
+                bv = v;
+                bk = k;
+            }
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const int64_t ov = __shfl_xor(bv, d, 64);
+            const int32_t ok2 = __shfl_xor(bk, d, 64);
+            if (ov > bv || (ov == bv && ok2 < bk)) {
+                bv = ov;
+                bk = ok2;
+            }
+        }
+        if (lane == 0) {
+            red_v[wave] = bv;
+            red_k[wave] = bk;
+        }
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w)
+                if (red_v[w] > bv || (red_v[w] == bv && red_k[w] < bk)) {
+                    bv = red_v[w];
+                    bk = red_k[w];
+                }
+            s_peak = bv;
+            s_step = g.blk_arg[bk];
+        }
+        __syncthreads();
+    } else {
+        // ---- the table into LDS; its prefix and suffix maxima; the peak and the first block that holds it
+        for (int32_t k = tid; k < n_blk; k += kThreads) {
+            lds.tb[k] = g.blk_max[k];
+            lds.ta[k] = g.blk_arg[k];
+        }
+        if (tid == 0) lds.peak_block = INT32_MAX;
+        __syncthreads();
+        if (wave == 0) {          // pmx[k + 1] = max tb[0..k]
+            int64_t run = INT64_MIN;
+            if (lane == 0) lds.pmx[0] = INT64_MIN;
+            for (int32_t k0 = 0; k0 < n_blk; k0 += 64) {
+                const int32_t k = k0 + lane;
+                const int64_t incl = max64(wave_scan_max(k < n_blk ? lds.tb[k] : INT64_MIN), run);
+                if (k < n_blk) lds.pmx[k + 1] = incl;
+                run = last_lane(incl);
+            }
+            if (lane == 0) s_peak = run;
+        } else if (wave == 1) {   // smx[k] = max tb[k..]
+            int64_t run = INT64_MIN;
+            if (lane == 0) lds.smx[n_blk] = INT64_MIN;
+            for (int32_t top = n_blk; top > 0; top -= 64) {
+                const int32_t k = top - 1 - lane;
+                const int64_t incl = max64(wave_scan_max(k >= 0 ? lds.tb[k] : INT64_MIN), run);
+                if (k >= 0) lds.smx[k] = incl;
+                run = last_lane(incl);
+            }
+        }
+        __syncthreads();
+        for (int32_t k = tid; k < n_blk; k += kThreads)
+            if (lds.tb[k] == s_peak) atomicMin(&lds.peak_block, k);
+        __syncthreads();
+        if (tid == 0) s_step = lds.ta[lds.peak_block];
+        __syncthreads();
+    }
+    const int32_t tstar = __builtin_amdgcn_readfirstlane(s_step);
+    const uint32_t p_lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(s_peak));
+    const uint32_t p_hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(static_cast<uint64_t>(s_peak) >> 32));
+    const int64_t P = static_cast<int64_t>((static_cast<uint64_t>(p_hi) << 32) | p_lo);
+#ifdef TENSILE_SCORE_PROF
+#define STEP_MARK(k) do { if (tid == 0) { const unsigned long long now_ = wall_clock64(); atomicAdd(&g_score_prof[k], now_ - prof_t); prof_t = now_; } } while (0)
+#else
+#define STEP_MARK(k) do { } while (0)
+#endif
+    STEP_MARK(6);
+    if (!g.do_score) {
+        if (tid == 0) publish_header(a, P, tstar, 0);
+        return;
+    }
+    if constexpr (kBigT) {
+        ScoreCarry carry;
+#ifdef TENSILE_SCORE_PROF
+        carry.prof_t = prof_t;
+#endif
+        score_plan<true, kVec, true>(a, 0, tstar, P, lds, a.tab_scratch, carry);   // (one workgroup: its scratch table is the first)
+    } else {
+        const int64_t *const MF = g.row;
+        const int32_t bk = tstar >> a.bucket_shift;
+        const int32_t e0 = uniform_load(a.bucket_off, bk), n_e = uniform_load(a.bucket_off, bk + 1) - e0;
+        int32_t n_out = 0;     // records handed to the host so far (the same in every thread)
+        for (int32_t slice_lo = 0; slice_lo < n_e; slice_lo += kMaxLocal) {
+            const int32_t n_slice = min(kMaxLocal, n_e - slice_lo);
+            __syncthreads();   // the previous slice has finished with the lists, acc and the staging area
+            // ---- the slice's lists; per block, where its entries start in each order
+            for (int32_t k = tid; k < n_slice; k += kThreads) {
+                lds.acc[k] = INT64_MIN;
+                lds.lo_list[k] = a.cand_o[e0 + slice_lo + k];
+                lds.hi_list[k] = a.qord[e0 + slice_lo + k];
+            }
+            if (tid == 0) lds.n_stage = 0;
+            __syncthreads();
+            for (int32_t k = tid; k <= n_slice; k += kThreads) {
+                // blocks after the previous entry's block, up to this entry's block, start at this entry
+                const int32_t lo_prev = k > 0 ? lds.lo_list[k - 1] / kMini : -1, lo_cur = k < n_slice ? lds.lo_list[k] / kMini : n_blk;
+                for (int32_t bq = lo_prev + 1; bq <= lo_cur; ++bq) lds.lo_ptr[bq] = k;
+                const int32_t hi_prev = k > 0 ? lds.hi_list[k - 1].x / kMini : -1, hi_cur = k < n_slice ? lds.hi_list[k].x / kMini : n_blk;
+                for (int32_t bq = hi_prev + 1; bq <= hi_cur; ++bq) lds.hi_ptr[bq] = k;
+            }
+            __syncthreads();
+            STEP_MARK(1);
+            // ---- the row's blocks, dealt round-robin; a block without an endpoint of the slice is not even read
+            {
+                SpanBuf *const buf = &lds.buf[wave];
+                auto wanted = [&](int32_t kb) { return kb < n_blk && (lds.lo_ptr[kb + 1] > lds.lo_ptr[kb] || lds.hi_ptr[kb + 1] > lds.hi_ptr[kb]); };
+                auto next_wanted = [&](int32_t kb) {     // (wave-uniform)
+                    while (kb < n_blk && !wanted(kb)) kb += kWaves;
+                    return kb;
+                };
+                // The wavefront's blocks are requested kAhead ahead (the row sits in L2; with one request in flight
+                // per wavefront every block would cost a full round trip).  The requests live in kAhead fixed sets
+                // of registers, taken in turn - rotating them would mean waiting for the youngest - and are always
+                // issued, at clamped addresses past the end, so that every wait names an exact count.
+                constexpr int kAhead = 4;
+                int32_t kq[kAhead];            // the block each set of registers holds (>= n_blk: none)
+                int64_t x[kAhead][4];
+                int32_t cursor = wave;         // where the search for the wavefront's next block goes on
+#pragma unroll
+                for (int d = 0; d < kAhead; ++d) {
+                    kq[d] = next_wanted(cursor);
+                    cursor = kq[d] + kWaves;
+                    load_quad<kVec>(MF, (kq[d] < n_blk ? kq[d] : n_blk) * kMini + 4 * lane, T, x[d]);
+                }
+                for (bool more = true; more;) {
+#pragma unroll
+                    for (int d = 0; d < kAhead; ++d) {
+                        const int32_t kb = kq[d];
+                        if (kb >= n_blk) {     // (wave-uniform; the blocks come in ascending order: nothing is left)
+                            more = false;
+                            break;
+                        }
+                        const int64_t v0 = x[d][0], v1 = x[d][1], v2 = x[d][2], v3 = x[d][3];
+                        kq[d] = next_wanted(cursor);
+                        cursor = kq[d] + kWaves;
+                        load_quad<kVec>(MF, (kq[d] < n_blk ? kq[d] : n_blk) * kMini + 4 * lane, T, x[d]);
+                        const int32_t t0 = kb * kMini;
+                        const int64_t before_blk = lds.pmx[kb], after_blk = lds.smx[kb + 1];
+                        const int64_t m = max64(max64(v0, v1), max64(v2, v3));
+                        const int64_t incl = max64(wave_scan_max(m), before_blk);
+                        const int64_t excl = from_prev_lane(incl, before_blk);          // max MF[0 .. t0 + 4 lane - 1]
+                        const int64_t rs = wave_rscan_max(m, lane);
+                        const int64_t rs_next = max64(from_next_lane(rs, INT64_MIN), after_blk);   // max MF[t0 + 4 lane + 4 .. T)
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        reinterpret_cast<ll2 *>(buf->raw)[2 * lane] = ll2{v0, v1};
+                        reinterpret_cast<ll2 *>(buf->raw)[2 * lane + 1] = ll2{v2, v3};
+                        buf->before[lane] = excl;
+                        buf->after[lane] = rs_next;
+                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        for (int32_t k = lds.lo_ptr[kb] + lane; k < lds.lo_ptr[kb + 1]; k += 64) {
+                            const int32_t r = lds.lo_list[k] - t0, l = r >> 2, j = r & 3;
+                            int64_t v = max64(buf->before[l], buf->raw[4 * l]);
+                            if (j >= 1) v = max64(v, buf->raw[4 * l + 1]);
+                            if (j >= 2) v = max64(v, buf->raw[4 * l + 2]);
+                            if (j >= 3) v = max64(v, buf->raw[4 * l + 3]);
+                            atomicMax(reinterpret_cast<long long *>(lds.acc + k), static_cast<long long>(v));
+                        }
+                        for (int32_t k = lds.hi_ptr[kb] + lane; k < lds.hi_ptr[kb + 1]; k += 64) {
+                            const int2 it = lds.hi_list[k];
+                            const int32_t r = it.x - t0, l = r >> 2, j = r & 3;
+                            int64_t v = max64(buf->after[l], buf->raw[4 * l + 3]);
+                            if (j <= 2) v = max64(v, buf->raw[4 * l + 2]);
+                            if (j <= 1) v = max64(v, buf->raw[4 * l + 1]);
+                            if (j <= 0) v = max64(v, buf->raw[4 * l]);
+                            atomicMax(reinterpret_cast<long long *>(lds.acc + it.y), static_cast<long long>(v));
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                }
+            }
+            STEP_MARK(3);
+            __syncthreads();
+            STEP_MARK(4);
+            // ---- scores of the surviving candidates, staged in LDS (where the wavefronts' buffers were) kStageRecs
+            // at a time and sent to the host as whole lines
+            ScoreCand *const stage = reinterpret_cast<ScoreCand *>(lds.buf);
+            int32_t staged_before = 0;     // (n_stage counts the slice's records so far; it is reset at the slice's start)
+            for (int32_t r0 = 0; r0 < n_slice; r0 += kStageRecs) {
+                const int32_t k = r0 + tid;
+                if (k < n_slice) {
+                    // (a candidate the plan has already dealt with is out: an interval inside the entry's gap - or,
+                    // for recomputation, any interval of its tensor - which the flags record as the plan grows)
+                    const int4 c = a.cand[e0 + slice_lo + k];
+                    const int32_t gap = a.cand_gap[e0 + slice_lo + k];
+                    const int64_t sz = a.cand_size[e0 + slice_lo + k];
+                    const int64_t v = lds.acc[k];
+                    const bool taken = (a.any_interval ? g.tensor_taken[c.w] : g.gap_taken[gap]) != 0;
+                    if (c.z < tstar && tstar < c.y && !taken)
+                        stage[atomicAdd(&lds.n_stage, 1) - staged_before] = ScoreCand{P - max64(v, P - sz), c.w, c.z, c.y, gap};
+                }
+                __syncthreads();
+                const int32_t n_st = lds.n_stage - staged_before;
+                const int64_t *src = reinterpret_cast<const int64_t *>(stage);
+                int64_t *dst = reinterpret_cast<int64_t *>(a.compact + n_out);
+                for (int32_t w = tid; w < 3 * n_st; w += kThreads) dst[w] = src[w];
+                n_out += n_st;
+                staged_before += n_st;
+                __syncthreads();       // the staging area is free again
+            }
+        }
+        // the header travels with the records: one wait for the host's memory instead of two
+        if (tid == 0) *a.hdr = ScoreHeader{P, tstar, n_out};
+        if (a.ready) __threadfence_system();   // this thread's records (and the header), before the barrier that precedes the signal
+        __syncthreads();
+        if (tid == 0 && a.ready) __hip_atomic_store(a.ready, a.ready_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        STEP_MARK(7);
+    }
+#undef STEP_MARK
+}
+
 }  // namespace
+
+// One iteration of tensile_greedy_plan on the device (see greedy_step_kernel).  pl: the one plan INCLUDING the new
+// interval (n_intervals counts it; its slot in the device arrays is written by the kernel).
+int launch_greedy_step(const tensile_tas *tas, Workspace &ws, const CandIndex &ix, bool any_interval, const tensile_plans *pl,
+                       int64_t *row, const GreedyTables &tables, bool rebuild, const GreedyNew *fresh, bool do_score,
+                       ScoreHeader *hdr, ScoreCand *compact, unsigned long long *ready, unsigned long long ready_value) {
+    GreedyStepArgs g{};
+    g.s = make_score_args(tas, ix, any_interval, pl, row, nullptr, nullptr, nullptr, nullptr, nullptr);
+    g.s.hdr = hdr; g.s.compact = compact; g.s.ready = ready; g.s.ready_value = ready_value;
+    g.row = row; g.blk_max = tables.blk_max; g.blk_arg = tables.blk_arg; g.size = tas->d_size.p;
+    g.gap_taken = tables.gap_taken; g.tensor_taken = tables.tensor_taken; g.new_gap = -1;
+    g.rebuild = rebuild ? 1 : 0;
+    g.do_score = (do_score && tas->N > 0) ? 1 : 0;
+    if (fresh) {
+        g.has_new = 1;
+        g.new_tensor = fresh->tensor; g.new_out = fresh->out; g.new_in = fresh->in; g.plan_n = fresh->position;
+        g.new_gap = fresh->gap;
+        g.plan_t = fresh->plan_t; g.plan_o = fresh->plan_o; g.plan_r = fresh->plan_r;
+    }
+    const bool big_t = g.s.n_tab > kTabLds;
+    if (big_t && g.do_score) {
+        const int rc = ws.provide(ws.score_tab, static_cast<size_t>(g.s.n_tab), "greedy: block maxima of the scoring pass");
+        if (rc != TENSILE_OK) return rc;
+        g.s.tab_scratch = ws.score_tab.p;
+    }
+    const hipStream_t stream = ws.stream;
+    if (big_t) {
+        if (g.s.vec16) hipLaunchKernelGGL((greedy_step_kernel<true, true>), dim3(1), dim3(kThreads), 0, stream, g);
+        else hipLaunchKernelGGL((greedy_step_kernel<true, false>), dim3(1), dim3(kThreads), 0, stream, g);
+    } else {
+        if (g.s.vec16) hipLaunchKernelGGL((greedy_step_kernel<false, true>), dim3(1), dim3(kThreads), 0, stream, g);
+        else hipLaunchKernelGGL((greedy_step_kernel<false, false>), dim3(1), dim3(kThreads), 0, stream, g);
+    }
+    TS_HIP(hipGetLastError());
+    return TENSILE_OK;
+}
 
 int launch_score(const tensile_tas *tas, Workspace &ws, const CandIndex &ix, bool any_interval, const tensile_plans *plans,
                  const int64_t *resident, const int64_t *peak, const int32_t *argmax, int64_t *score, int32_t *win_out,

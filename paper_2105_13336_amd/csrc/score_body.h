@@ -35,6 +35,7 @@ struct ScoreArgs {
     const int4 *cand;
     const int64_t *cand_size;
     const int32_t *cand_o;
+    const int32_t *cand_gap;
     const int2 *qord, *tord;
     const int32_t *slice_first;
     const int32_t *wave_ptr;
@@ -252,6 +253,58 @@ __device__ __forceinline__ T uniform_load(const T *p, int64_t i) {
     return ((const_ptr)p)[i];
 }
 
+// Step 2 of the scoring pass: the plan's own intervals k0 .. k1-1 cancel candidates of the slice
+// [slice_lo, slice_lo + n_slice) of a bucket (acc = +inf): an interval inside the gap of an entry of its tensor
+// (any interval of that tensor when a.any_interval).  filter: the bucket's bit filter over tensors, in LDS;
+// hd: the bucket's {first slot, log2(slots)} in the hash table.
+__device__ __forceinline__ void cancel_by_plan(const ScoreArgs &a, const int64_t k0, const int64_t k1, const int2 hd,
+                                               const int32_t slice_lo, const int32_t n_slice, const uint32_t *filter, int64_t *acc,
+                                               const int tid) {
+    const uint32_t fmask = static_cast<uint32_t>(a.filter_words) * 32 - 1;
+    const int hshift = 32 - hd.y;
+    const uint32_t hmask = (1u << hd.y) - 1;
+    const int4 *slots = a.hash_slots + hd.x;
+    for (int64_t kb = k0 + tid; kb < k1; kb += kIvU * kThreads) {
+        int32_t i[kIvU], o[kIvU], r[kIvU];
+        uint32_t h[kIvU];
+        int4 s[kIvU];
+        bool go[kIvU];
+#pragma unroll
+        for (int u = 0; u < kIvU; ++u) {
+            const int64_t k = kb + u * kThreads;
+            const int64_t kc = k < k1 ? k : k1 - 1;
+            i[u] = a.iv_tensor[kc];
+            o[u] = a.iv_out[kc];
+            r[u] = a.iv_in[kc];
+            if (k >= k1) i[u] = -1;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < kIvU; ++u) {
+            go[u] = static_cast<uint32_t>(i[u]) < static_cast<uint32_t>(a.N) && o[u] >= 0 && r[u] <= a.T && r[u] > o[u];
+            const uint32_t fb = static_cast<uint32_t>(i[u]) & fmask;
+            go[u] = go[u] && ((filter[fb >> 5] >> (fb & 31)) & 1u);
+            h[u] = go[u] ? (static_cast<uint32_t>(i[u]) * 2654435769u) >> hshift : 0u;
+            s[u] = slots[h[u]];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < kIvU; ++u) {
+            while (go[u] && s[u].x >= 0) {      // probe until the tensor's last entry or an empty slot
+                if (s[u].x == i[u]) {
+                    if (a.any_interval || (s[u].y <= o[u] && r[u] <= s[u].z)) {
+                        const uint32_t el = static_cast<uint32_t>((s[u].w & INT32_MAX) - slice_lo);
+                        if (el < static_cast<uint32_t>(n_slice)) acc[el] = INT64_MAX;
+                    }
+                    if (s[u].w < 0) break;
+                }
+                h[u] = (h[u] + 1) & hmask;
+                s[u] = slots[h[u]];
+            }
+        }
+    }
+}
+
 // LDS of one scoring workgroup.  A struct, so that a kernel that runs other phases in the same workgroup can
 // overlay it with theirs.
 template <bool kBigT>
@@ -335,7 +388,9 @@ __device__ __forceinline__ void score_plan(const ScoreArgs &a, const int32_t b, 
         const int32_t slice0 = uniform_load(a.slice_first, bk);
         const int32_t *hash_dir = reinterpret_cast<const int32_t *>(a.hash_dir);
         const int2 hd = make_int2(uniform_load(hash_dir, 2 * bk), uniform_load(hash_dir, 2 * bk + 1));
-        int64_t k0 = uniform_load(a.plan_offsets, b), k1 = uniform_load(a.plan_offsets, b + 1);
+        // (the one plan of the compact form is the whole of the interval arrays: its offsets are not read, so a
+        // kernel may append to the plan before it calls this)
+        int64_t k0 = kCompact ? 0 : uniform_load(a.plan_offsets, b), k1 = kCompact ? a.n_intervals : uniform_load(a.plan_offsets, b + 1);
         if (k0 < 0) k0 = 0;
         if (k1 > a.n_intervals) k1 = a.n_intervals;
         PROF_MARK(0);
@@ -369,51 +424,7 @@ __device__ __forceinline__ void score_plan(const ScoreArgs &a, const int32_t b, 
             PROF_MARK(1);
 
             // ---- 2: the plan's own intervals cancel candidates
-            {
-                const uint32_t fmask = static_cast<uint32_t>(a.filter_words) * 32 - 1;
-                const int hshift = 32 - hd.y;
-                const uint32_t hmask = (1u << hd.y) - 1;
-                const int4 *slots = a.hash_slots + hd.x;
-                for (int64_t kb = k0 + tid; kb < k1; kb += kIvU * kThreads) {
-                    int32_t i[kIvU], o[kIvU], r[kIvU];
-                    uint32_t h[kIvU];
-                    int4 s[kIvU];
-                    bool go[kIvU];
-#pragma unroll
-                    for (int u = 0; u < kIvU; ++u) {
-                        const int64_t k = kb + u * kThreads;
-                        const int64_t kc = k < k1 ? k : k1 - 1;
-                        i[u] = a.iv_tensor[kc];
-                        o[u] = a.iv_out[kc];
-                        r[u] = a.iv_in[kc];
-                        if (k >= k1) i[u] = -1;
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int u = 0; u < kIvU; ++u) {
-                        go[u] = static_cast<uint32_t>(i[u]) < static_cast<uint32_t>(a.N) && o[u] >= 0 && r[u] <= a.T && r[u] > o[u];
-                        const uint32_t fb = static_cast<uint32_t>(i[u]) & fmask;
-                        go[u] = go[u] && ((filter[fb >> 5] >> (fb & 31)) & 1u);
-                        h[u] = go[u] ? (static_cast<uint32_t>(i[u]) * 2654435769u) >> hshift : 0u;
-                        s[u] = slots[h[u]];
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int u = 0; u < kIvU; ++u) {
-                        while (go[u] && s[u].x >= 0) {      // probe until the tensor's last entry or an empty slot
-                            if (s[u].x == i[u]) {
-                                if (a.any_interval || (s[u].y <= o[u] && r[u] <= s[u].z)) {
-                                    const uint32_t el = static_cast<uint32_t>((s[u].w & INT32_MAX) - slice_lo);
-                                    if (el < static_cast<uint32_t>(n_slice)) acc[el] = INT64_MAX;
-                                }
-                                if (s[u].w < 0) break;
-                            }
-                            h[u] = (h[u] + 1) & hmask;
-                            s[u] = slots[h[u]];
-                        }
-                    }
-                }
-            }
+            cancel_by_plan(a, k0, k1, hd, slice_lo, n_slice, filter, acc, tid);
             PROF_MARK(2);
 
             // ---- 3: stream the row (no barrier needed after step 2: +inf survives every max)
@@ -461,7 +472,7 @@ __device__ __forceinline__ void score_plan(const ScoreArgs &a, const int32_t b, 
                     const int64_t v = acc[k];
                     if (!(c.z < tstar && tstar < c.y) || v == INT64_MAX) continue;
                     if (kCompact) {
-                        a.compact[atomicAdd(&n_compact, 1)] = ScoreCand{final_score(c, sz, v), c.w, c.z, c.y, 0};
+                        a.compact[atomicAdd(&n_compact, 1)] = ScoreCand{final_score(c, sz, v), c.w, c.z, c.y, -1};
                         continue;
                     }
                     score[c.w] = final_score(c, sz, v);
@@ -481,7 +492,7 @@ __device__ __forceinline__ void score_plan(const ScoreArgs &a, const int32_t b, 
                         const int64_t sz = a.cand_size[e0 + k];
                         const int64_t v = acc[k];
                         if (c.z < tstar && tstar < c.y && v != INT64_MAX)
-                            a.compact[atomicAdd(&n_compact, 1)] = ScoreCand{final_score(c, sz, v), c.w, c.z, c.y, 0};
+                            a.compact[atomicAdd(&n_compact, 1)] = ScoreCand{final_score(c, sz, v), c.w, c.z, c.y, -1};
                     }
                     continue;   // (block-uniform; a staged bucket is one slice: this ends the slice loop)
                 }
@@ -604,7 +615,7 @@ inline ScoreArgs make_score_args(const tensile_tas *tas, const CandIndex &ix, bo
     a.iv_tensor = plans->iv_tensor; a.iv_out = plans->iv_out; a.iv_in = plans->iv_in;
     a.bucket_shift = ix.shift; a.filter_words = ix.filter_words;
     a.bucket_off = ix.bucket_off.p;
-    a.cand = ix.cand.p; a.cand_size = ix.cand_size.p; a.cand_o = ix.cand_o.p; a.qord = ix.qord.p; a.tord = ix.tord.p;
+    a.cand = ix.cand.p; a.cand_size = ix.cand_size.p; a.cand_o = ix.cand_o.p; a.cand_gap = ix.cand_gap.p; a.qord = ix.qord.p; a.tord = ix.tord.p;
     a.slice_first = ix.slice_first.p; a.wave_ptr = ix.wave_ptr.p; a.hash_dir = ix.hash_dir.p; a.hash_slots = ix.hash_slots.p; a.filter = ix.filter.p;
     a.resident = resident; a.peak = peak; a.argmax = argmax;
     a.score = score; a.win_out = win_out; a.win_in = win_in;

@@ -278,7 +278,7 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
                     cand[fill[b]++] = make_int4(gp[g], gq[g], gwin[g], gt[g]);
     }
     std::vector<int64_t> cand_size(E);
-    std::vector<int32_t> cand_o(E);
+    std::vector<int32_t> cand_o(E), cand_gap(E);
     std::vector<int2> qord(E), tord(E);
     std::vector<int32_t> slice_first(static_cast<size_t>(nb) + 1, 0);
     for (int32_t b = 0; b < nb; ++b)
@@ -309,6 +309,9 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
         for (int32_t k = 0; k < n; ++k) {
             cand_size[e0 + k] = h->h_size[c[k].w];
             cand_o[e0 + k] = c[k].z;
+            // the gap's number: its place among the tensor's gaps, which are listed by ascending first step
+            const int32_t *g0 = gp.data() + h->h_gap_first[c[k].w], *g1 = gp.data() + h->h_gap_first[c[k].w + 1];
+            cand_gap[e0 + k] = static_cast<int32_t>(std::lower_bound(g0, g1, c[k].x) - gp.data());
         }
         for (int32_t s0 = 0, sl = slice_first[b]; s0 < n; s0 += kScoreMaxLocal, ++sl) {
             const int32_t ns = std::min(kScoreMaxLocal, n - s0);
@@ -407,6 +410,7 @@ int build_candidate_index(const tensile_tas *h, CandIndex &ix, const std::vector
     TS_HIP(ix.cand.upload(cand.data(), E));
     TS_HIP(ix.cand_size.upload(cand_size.data(), E));
     TS_HIP(ix.cand_o.upload(cand_o.data(), E));
+    TS_HIP(ix.cand_gap.upload(cand_gap.data(), E));
     TS_HIP(ix.qord.upload(qord.data(), E));
     TS_HIP(ix.tord.upload(tord.data(), E));
     TS_HIP(ix.slice_first.upload(slice_first.data(), slice_first.size()));
@@ -490,6 +494,9 @@ int build(tensile_tas *h, const tensile_tas_desc *d) {
         if (rc != TENSILE_OK) return rc;
     }
 
+    h->h_gap_first.assign(static_cast<size_t>(N) + 1, 0);
+    for (int32_t t : gt) ++h->h_gap_first[t + 1];
+    for (int32_t i = 0; i < N; ++i) h->h_gap_first[i + 1] += h->h_gap_first[i];
     h->h_gp = std::move(gp);
     h->h_gq = std::move(gq);
     h->h_gt = std::move(gt);
@@ -674,6 +681,7 @@ int tensile_tas_load(const tensile_tas_desc *desc, tensile_tas **out) {
 void tensile_tas_free(tensile_tas *tas) {
     if (!tas) return;
     (void)hipDeviceSynchronize();
+    drop_greedy_cache(tas);
     delete tas;
 }
 
