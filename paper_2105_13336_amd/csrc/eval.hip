@@ -487,17 +487,50 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     write_result(fresh_ids());
 }
 
-// The tail kernel runs after the common one on the same stream with a small persistent grid.
-// It does nothing unless the common kernel met a plan it had to leave (flag == this launch's
-// epoch); then its workgroups walk all (plan, segment) pairs and take the long plans.
+// The tail kernel runs after the common one on the same stream with a small persistent grid.  It does nothing
+// unless the common kernel met a plan it had to leave (flag == this launch's epoch).  Then every workgroup
+// walks the batch's offsets, kThr plans at a time, numbers the long plans as it meets them (ballots: the count
+// is the same in every workgroup), and takes the (long plan, segment) pairs whose running number is its own
+// modulo the grid: the long plans are spread evenly over the workgroups wherever they sit in the batch.
 template <int kThr, bool kNarrow, int kOut>
-__global__ __launch_bounds__(kThr) void eval_tail_kernel(const EvalArgs a, const int64_t n_logical) {
+__global__ __launch_bounds__(kThr) void eval_tail_kernel(const EvalArgs a) {
     if (*a.tail_flag != a.epoch) return;
+    constexpr int kWaves = kThr / 64;
     __shared__ EvalLds<kThr> lds;
-    for (int64_t w = blockIdx.x; w < n_logical; w += gridDim.x) {
-        int32_t plan, seg;
-        if (decode_block(a, w, plan, seg)) eval_body<kThr, kCapTail / kThr, true, kNarrow, kOut>(a, plan, seg, lds);
-        __syncthreads();   // LDS is reused by the next logical workgroup
+    __shared__ unsigned long long long_mask[kWaves];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t grid = static_cast<int32_t>(gridDim.x), me = static_cast<int32_t>(blockIdx.x);
+    const int32_t s_step = a.S % grid;
+    int32_t item_mod = 0;     // (number of the long plan at hand) * S modulo the grid: block-uniform, kept without divisions
+    for (int64_t base = 0; base < a.B; base += kThr) {
+        const int64_t p = base + tid;
+        bool is_long = false;
+        if (p < a.B) {
+            int64_t k0 = a.plan_offsets[p], k1 = a.plan_offsets[p + 1];
+            if (k0 < 0) k0 = 0;
+            if (k1 > a.n_intervals) k1 = a.n_intervals;
+            is_long = k1 - k0 > a.tail_threshold;
+        }
+        const unsigned long long mine = __builtin_amdgcn_ballot_w64(is_long);
+        if (lane == 0) long_mask[wave] = mine;
+        __syncthreads();
+        for (int w = 0; w < kWaves; ++w) {
+            const unsigned long long m_any = long_mask[w];
+            unsigned long long m = (static_cast<unsigned long long>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(m_any >> 32))) << 32) |
+                                   __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(m_any));
+            while (m) {       // (block-uniform)
+                const int32_t plan = static_cast<int32_t>(base + w * 64 + __builtin_ctzll(m));
+                m &= m - 1;
+                // this workgroup's segments of the plan: those whose item number, long plan * S + seg, is its own modulo the grid
+                for (int32_t seg = me >= item_mod ? me - item_mod : me - item_mod + grid; seg < a.S; seg += grid) {
+                    eval_body<kThr, kCapTail / kThr, true, kNarrow, kOut>(a, plan, seg, lds);
+                    __syncthreads();   // LDS is reused by the next pair
+                }
+                item_mod += s_step;
+                if (item_mod >= grid) item_mod -= grid;
+            }
+        }
+        __syncthreads();   // everybody has read the masks
     }
 }
 
@@ -680,6 +713,19 @@ __global__ void eval_finalize_kernel(int32_t B, int32_t S, const int64_t *part_m
 
 constexpr int kSmallGeometryMaxT = 16384;   // rows up to this length use the 512-thread geometry
 
+// Whether a batch whose average plan holds `avg` intervals, on rows of n_tiles tiles, is sorted by tile first.
+// Sorting costs a pass of its own (two reads of the lists, 16 bytes of records per interval written and read
+// back) that is spread over the row's tiles; without it a plan's intervals beyond the 8192 a workgroup keeps
+// in registers are read again for every tile.  Per tile, in microseconds, measured on rows of 10^6 and of
+// 50,000 steps with 9,000 to 60,000 intervals per plan: re-reading 0.35 per 1024 intervals beyond the registers,
+// sorting 1.5 + 3 per 1024 intervals of the plan divided by the number of tiles.  (Long rows: sorted from about
+// 12,000 intervals per plan; rows of a few tiles: never - 16,000 intervals on 7 tiles take 1.18 ms for 4,096
+// plans re-read and 1.72 ms sorted.)
+bool binning_pays(double avg, int64_t n_tiles) {
+    if (avg <= kCapTail) return false;
+    return 0.35 * (avg - kCapTail) / 1024.0 > 1.5 + 3.0 * avg / 1024.0 / static_cast<double>(n_tiles);
+}
+
 // The launches of one geometry: common kernel (three register capacities), tail kernel.
 template <int kThr>
 int launch_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, int64_t blocks, int cap, int out, bool narrow,
@@ -728,7 +774,10 @@ int launch_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, in
     }
     if (cap == kCapSmall) TS_LAUNCH_EVAL(kCapSmall / kThr);
     else if (cap == kCapMid) TS_LAUNCH_EVAL(kCapMid / kThr);
-    else TS_LAUNCH_EVAL(kCapBig / kThr);
+    else if (cap == kCapTail && kThr == 1024) {   // (one workgroup per plan only: the host does not ask for the persistent grid here)
+        if (narrow) TS_LAUNCH_OUT(eval_kernel, 1024, kCapTail / 1024, true);
+        else TS_LAUNCH_OUT(eval_kernel, 1024, kCapTail / 1024, false);
+    } else TS_LAUNCH_EVAL(kCapBig / kThr);
     TS_HIP(hipGetLastError());
 #undef TS_LAUNCH_EVAL
 #undef TS_LAUNCH_OUT
@@ -737,9 +786,9 @@ int launch_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, in
         const dim3 tgrid(static_cast<uint32_t>(blocks < resident ? blocks : resident));
 #define TS_LAUNCH_TAIL(NARROW)                                                                                            \
     do {                                                                                                                  \
-        if (out == 2) hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 2>), tgrid, block, 0, stream, a, blocks);        \
-        else if (out == 1) hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 1>), tgrid, block, 0, stream, a, blocks);   \
-        else hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 0>), tgrid, block, 0, stream, a, blocks);                 \
+        if (out == 2) hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 2>), tgrid, block, 0, stream, a);        \
+        else if (out == 1) hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 1>), tgrid, block, 0, stream, a);   \
+        else hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 0>), tgrid, block, 0, stream, a);                 \
     } while (0)
         if (narrow) TS_LAUNCH_TAIL(true);
         else TS_LAUNCH_TAIL(false);
@@ -761,7 +810,7 @@ int launch_tiny_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &
     do {                                                                                                             \
         hipLaunchKernelGGL((eval_kernel<kThr, kCapSmall / kThr, NARROW, OUT>), grid, block, 0, stream, a);           \
         if (a.n_intervals > a.tail_threshold) /* else no plan can be longer than the registers hold */              \
-            hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, OUT>), tgrid, block, 0, stream, a, blocks);           \
+            hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, OUT>), tgrid, block, 0, stream, a);                   \
     } while (0)
     if (narrow) {
         if (out == 2) TS_LAUNCH_TINY(true, 2);
@@ -957,7 +1006,7 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
     int64_t need = avg_k + avg_k / 8;
     const int r_forced = g_tuning.eval_r;   // tuning knob: intervals per thread in registers at 1024 threads
     if (r_forced > 0) need = static_cast<int64_t>(r_forced) * 1024;
-    const int cap = need <= kCapSmall ? kCapSmall : need <= kCapMid ? kCapMid : kCapBig;
+    int cap = need <= kCapSmall ? kCapSmall : need <= kCapMid ? kCapMid : need <= kCapBig ? kCapBig : kCapTail;
     const int bin_forced = g_tuning.eval_binned;   // tuning knob: 0 = never, 1 = whenever possible
     int threads = a.T <= kSmallGeometryMaxT ? 512 : 1024;
     if (a.B > tas->num_cus && (!a.resident || a.T <= 2 * kSmallGeometryMaxT)) threads = 512;
@@ -971,6 +1020,7 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
     const bool tiny_ok = cap == kCapSmall && bin_forced != 1;
     if (tiny_ok && threads_forced == 0 && a.T <= kSmallGeometryMaxT && a.B >= 4 * static_cast<int64_t>(tas->num_cus)) threads = 256;
     if (threads_forced == 256 && tiny_ok) threads = 256;
+    if (cap == kCapTail && threads != 1024) cap = kCapBig;   // (8 intervals per thread only exist for 1024 threads)
     const bool small_for_batch = threads == 512 && a.T > kSmallGeometryMaxT;
     const int tile = threads * kVpt;
     const int64_t n_tiles = (static_cast<int64_t>(a.T) + tile - 1) / tile;
@@ -982,7 +1032,7 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
     int64_t S = 1;
     {
         const double avg = a.B > 0 ? static_cast<double>(a.n_intervals) / a.B : 0.0;
-        const bool likely_binned = a.size_units != nullptr && avg * 1.125 > kCapBig && n_tiles < kMaxBinTiles;
+        const bool likely_binned = a.size_units != nullptr && n_tiles < kMaxBinTiles && binning_pays(avg, n_tiles);
         const double p = likely_binned ? 0.25 : 0.3 + (avg < kCapBig ? avg : kCapBig) / 3500.0;
         double best = 0.0;
         const int64_t s_max = n_tiles < 1024 ? n_tiles : 1024;
@@ -1042,7 +1092,8 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
     a.tail_flag = ws.tail_flag.p;
     a.epoch = ++ws.epoch;
     // a batch whose average plan does not fit the registers is binned by tile first
-    bool binned = narrow && need > kCapBig && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2);
+    bool binned = narrow && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2) &&
+                  binning_pays(static_cast<double>(a.n_intervals) / a.B, n_tiles);
     if (bin_forced == 0) binned = false;
     if (bin_forced == 1) binned = narrow && n_tiles < kMaxBinTiles && a.n_intervals <= (INT32_MAX / 2);
     if (a.n_intervals == 0) binned = false;   // nothing to bin (and no record for the binned kernel's clamped loads)
@@ -1070,7 +1121,7 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
         a.n_tiles = static_cast<int32_t>(n_tiles);
     }
     // several plans per resident workgroup: the persistent kernel (it addresses a row's bytes with 32 bits)
-    const bool pers_ok = S == 1 && !binned && a.N > 0 && a.T <= (1 << 28);
+    const bool pers_ok = S == 1 && !binned && a.N > 0 && a.T <= (1 << 28) && cap != kCapTail;
     bool persistent = pers_ok && out == 0 && a.B >= 4 * static_cast<int64_t>(tas->num_cus);
     const int pers_forced = g_tuning.eval_persistent;   // tuning knob: 0 = never, 1 = whenever possible
     if (pers_forced == 0) persistent = false;

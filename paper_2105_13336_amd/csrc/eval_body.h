@@ -16,6 +16,7 @@ namespace {
 constexpr int kVpt = 8;   // steps per lane per tile: the scan below is written for 8
 // intervals per plan held in registers: three sizes for the common kernel, 8192 for the kernel that takes longer plans
 constexpr int kCapSmall = 2048, kCapMid = 4096, kCapBig = 6144, kCapTail = 8192;
+constexpr int kTailU = 4;   // intervals per thread and round where a long plan's list is re-read (see eval_body)
 // LDS layouts are skewed: 16-byte granule g lives at granule g + (g >> 4), i.e. cell u at
 // u + 2 * (u >> 5).  A lane's four granules stay contiguous (they never straddle a multiple of 16).
 constexpr int kStageCells = 64 * kVpt + 2 * ((64 * kVpt) >> 5) + 2;    // 546 per wave, rounded up below
@@ -356,14 +357,29 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
             }
         }
         if constexpr (kTail) {
-            for (int64_t k = k_over + tid; k < k1; k += kThr) {
-                const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
-                if (!applies(a, i, o, r)) continue;
-                const uint32_t u0 = static_cast<uint32_t>(o + 1 - tile_lo), u1 = static_cast<uint32_t>(r - tile_lo);
-                if ((u0 < tile_n) | (u1 < tile_n)) {
-                    const int64_t s = a.size[i];
-                    if (u0 < tile_n) lds_add(&delta[skew(u0)], -s);
-                    if (u1 < tile_n) lds_add(&delta[skew(u1)], s);
+            // the intervals beyond the registers, kTailU per thread and round: their loads are issued together (at
+            // clamped indices), so that a round costs one memory latency, not kTailU; the size is fetched only for
+            // the few whose endpoints fall into this tile
+            for (int64_t kb = k_over + tid; kb < k1; kb += static_cast<int64_t>(kTailU) * kThr) {
+                int32_t ti[kTailU], to[kTailU], tr[kTailU];
+#pragma unroll
+                for (int u = 0; u < kTailU; ++u) {
+                    const int64_t k = kb + static_cast<int64_t>(u) * kThr;
+                    const int64_t kc = k < k1 ? k : k1 - 1;
+                    ti[u] = a.iv_tensor[kc];
+                    to[u] = a.iv_out[kc];
+                    tr[u] = a.iv_in[kc];
+                    if (k >= k1) ti[u] = -1;
+                }
+#pragma unroll
+                for (int u = 0; u < kTailU; ++u) {
+                    if (!applies(a, ti[u], to[u], tr[u])) continue;
+                    const uint32_t u0 = static_cast<uint32_t>(to[u] + 1 - tile_lo), u1 = static_cast<uint32_t>(tr[u] - tile_lo);
+                    if ((u0 < tile_n) | (u1 < tile_n)) {
+                        const int64_t s = a.size[ti[u]];
+                        if (u0 < tile_n) lds_add(&delta[skew(u0)], -s);
+                        if (u1 < tile_n) lds_add(&delta[skew(u1)], s);
+                    }
                 }
             }
         }

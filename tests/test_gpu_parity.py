@@ -208,6 +208,42 @@ def test_eval_smallest_geometry_with_long_plans(tuning):
         h.close()
 
 
+def repeated(base, b, length):
+    t, o, r, k = base.plan(b)
+    one = [(int(t[j]), int(o[j]), int(r[j]), int(k[j])) for j in range(len(t))]
+    return (one * (length // max(1, len(one)) + 1))[:length]
+
+
+@pytest.mark.parametrize("T", [20012, 50001])
+def test_eval_mixed_batch_of_short_and_long_plans(T):
+    """A batch of short plans in which every seventh plan is long (7,000 to 20,000 intervals: beyond what the
+    common kernel keeps in registers, and beyond the 8192 of the kernel that takes the long ones, which then reads the
+    rest again per tile), under the library's own launch choices."""
+    tas = small_random_tas(4500 + T, N=400, T=T, max_acc=5, base_bytes=3)
+    B = 300
+    base = make_plans(tas, B, 23, p_swap=0.7)
+    lists = [repeated(base, b, 7000 + 331 * (b % 41)) if b % 7 == 3 else repeated(base, b, len(base.plan(b)[0]))
+             for b in range(B)]
+    pl = plans_from_lists(lists)
+    lens = np.diff(pl.plan_offsets)
+    say(f"eval mixed batch T={T}: {int((lens > 6144).sum())} of {B} plans longer than 6144 (longest {int(lens.max())})")
+    assert (lens > 6144).sum() >= B // 10 and lens.max() > 8192
+    check_eval(tas, pl, label=f"mixed T={T}")
+
+
+def test_eval_batch_of_plans_that_just_fit_eight_per_thread():
+    """Average plan between 6144 and 8192 intervals: the common kernel's largest register capacity, with a few
+    plans beyond it."""
+    tas = small_random_tas(4600, N=400, T=33001, max_acc=5, base_bytes=3)
+    B = 40
+    base = make_plans(tas, B, 29, p_swap=0.7)
+    lists = [repeated(base, b, 6500 + 37 * b if b % 9 else 8192 + 5 * b) for b in range(B)]
+    lists[7] = []
+    pl = plans_from_lists(lists)
+    say(f"eval plans of 6500-8400 intervals: average {pl.n_intervals // B}")
+    check_eval(tas, pl, label="eight per thread")
+
+
 # ---- seeded sweep over shapes and launch variants ----------------------------------------------
 
 @pytest.mark.parametrize("case", range(30))
