@@ -355,6 +355,8 @@ int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes, const tens
  *   "eval_binned"     0 never sort a batch's endpoints by tile first, 1 whenever possible (-1 = automatic)
  *   "eval_persistent" 0 never use the persistent grid, 1 whenever possible (-1 = automatic)
  *   "eval_slots"      size of the persistent grid (0 = automatic)
+ *   "eval_nt"         footprint rows written with nontemporal stores: 0 never, 1 whenever compiled for the
+ *                     kernel at hand, -1 (default) for rows whose unscheduled timeline exceeds 1 MiB
  *   "eval_r"          intervals per thread kept in registers (0 = automatic)
  *   "score_blocks"    size of the scoring grid (0 = automatic)
  *   "link_packed"     0: search the cumulative latencies themselves even when their packed form exists (1 = automatic)

@@ -143,6 +143,7 @@ struct Tuning {
     int eval_segments = 0;     // segments per plan
     int eval_persistent = -1;  // 0 never, 1 whenever possible
     int eval_slots = 0;        // size of the persistent grid
+    int eval_nt = -1;          // footprint rows written with nontemporal stores: 0 never, 1 always, -1 by row length
     int score_blocks = 0;      // size of the scoring grid
     int link_packed = 1;       // 0: search C itself even when its packed form exists
     int step_fused = -1;       // tensile_eval_score_plans: 0 = two kernels, 1 = the fused kernel whenever its shape allows

@@ -711,6 +711,14 @@ __global__ void eval_finalize_kernel(int32_t B, int32_t S, const int64_t *part_m
     if (min_resident) min_resident[b] = mn;
 }
 
+// Rows whose unscheduled timeline (8 bytes per step, read by every workgroup tile by tile) is larger than this
+// are written with nontemporal stores.  Ordinary stores allocate their lines in the L2 of the XCD, and the
+// stream of rows then pushes dMF0 out between two workgroups' reads of the same tile; every tile of every
+// workgroup ends up waiting for a miss.  Measured with a plain probe (1024 workgroups copying a shared buffer
+// into their own 8 MB rows through LDS, one tile ahead): shared buffer of 0.4 MB 5.9 TB/s with ordinary and 5.65
+// with nontemporal stores; 2 MB 4.1 and 5.6; 8 MB 3.7 and 5.85.
+constexpr int64_t kStreamRowsBytes = 1 << 20;
+
 constexpr int kSmallGeometryMaxT = 16384;   // rows up to this length use the 512-thread geometry
 
 // Whether a batch whose average plan holds `avg` intervals, on rows of n_tiles tiles, is sorted by tile first.
@@ -735,7 +743,10 @@ int launch_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, in
     if (binned) {
         hipLaunchKernelGGL(bin_kernel<kThr>, dim3(a.B), dim3(1024), 0, stream, a, ws.bin_recs.p, ws.bin_off.p, ws.bin_sum.p);
         TS_HIP(hipGetLastError());
-        if (out == 2) {
+        if (out == 3) {
+            hipLaunchKernelGGL((eval_binned_kernel<kThr, 3, true>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL((eval_binned_kernel<kThr, 3, false>), grid, block, 0, stream, a);
+        } else if (out >= 2) {
             hipLaunchKernelGGL((eval_binned_kernel<kThr, 2, true>), grid, block, 0, stream, a);
             hipLaunchKernelGGL((eval_binned_kernel<kThr, 2, false>), grid, block, 0, stream, a);
         } else if (out == 1) {
@@ -750,7 +761,7 @@ int launch_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, in
     }
 #define TS_LAUNCH_OUT(KERNEL, ...)                                                                   \
     do {                                                                                             \
-        if (out == 2) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 2>), grid, block, 0, stream, a);       \
+        if (out >= 2) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 2>), grid, block, 0, stream, a);       \
         else if (out == 1) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 1>), grid, block, 0, stream, a);  \
         else hipLaunchKernelGGL((KERNEL<__VA_ARGS__, 0>), grid, block, 0, stream, a);                \
     } while (0)
@@ -772,7 +783,18 @@ int launch_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, in
         const int64_t rounds = (blocks + slots - 1) / slots;
         grid = dim3(static_cast<uint32_t>((blocks + rounds - 1) / rounds));
     }
-    if (cap == kCapSmall) TS_LAUNCH_EVAL(kCapSmall / kThr);
+    if (out == 3 && kThr == 1024 && !persistent) {   // nontemporal rows: compiled for the large geometry only (long rows use no other)
+#define TS_LAUNCH_NT(R)                                                                                  \
+    do {                                                                                                 \
+        if (narrow) hipLaunchKernelGGL((eval_kernel<1024, R, true, 3>), grid, block, 0, stream, a);      \
+        else hipLaunchKernelGGL((eval_kernel<1024, R, false, 3>), grid, block, 0, stream, a);            \
+    } while (0)
+        if (cap == kCapSmall) TS_LAUNCH_NT(kCapSmall / 1024);
+        else if (cap == kCapMid) TS_LAUNCH_NT(kCapMid / 1024);
+        else if (cap == kCapTail) TS_LAUNCH_NT(kCapTail / 1024);
+        else TS_LAUNCH_NT(kCapBig / 1024);
+#undef TS_LAUNCH_NT
+    } else if (cap == kCapSmall) TS_LAUNCH_EVAL(kCapSmall / kThr);
     else if (cap == kCapMid) TS_LAUNCH_EVAL(kCapMid / kThr);
     else if (cap == kCapTail && kThr == 1024) {   // (one workgroup per plan only: the host does not ask for the persistent grid here)
         if (narrow) TS_LAUNCH_OUT(eval_kernel, 1024, kCapTail / 1024, true);
@@ -786,7 +808,8 @@ int launch_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, in
         const dim3 tgrid(static_cast<uint32_t>(blocks < resident ? blocks : resident));
 #define TS_LAUNCH_TAIL(NARROW)                                                                                            \
     do {                                                                                                                  \
-        if (out == 2) hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 2>), tgrid, block, 0, stream, a);        \
+        if (out == 3 && kThr == 1024) hipLaunchKernelGGL((eval_tail_kernel<1024, NARROW, 3>), tgrid, block, 0, stream, a); \
+        else if (out >= 2) hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 2>), tgrid, block, 0, stream, a);   \
         else if (out == 1) hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 1>), tgrid, block, 0, stream, a);   \
         else hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, 0>), tgrid, block, 0, stream, a);                 \
     } while (0)
@@ -813,11 +836,11 @@ int launch_tiny_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &
             hipLaunchKernelGGL((eval_tail_kernel<kThr, NARROW, OUT>), tgrid, block, 0, stream, a);                   \
     } while (0)
     if (narrow) {
-        if (out == 2) TS_LAUNCH_TINY(true, 2);
+        if (out >= 2) TS_LAUNCH_TINY(true, 2);
         else if (out == 1) TS_LAUNCH_TINY(true, 1);
         else TS_LAUNCH_TINY(true, 0);
     } else {
-        if (out == 2) TS_LAUNCH_TINY(false, 2);
+        if (out >= 2) TS_LAUNCH_TINY(false, 2);
         else if (out == 1) TS_LAUNCH_TINY(false, 1);
         else TS_LAUNCH_TINY(false, 0);
     }
@@ -1076,8 +1099,12 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
         a.out_arg = ws.part_arg.p;
         a.out_min = ws.part_min.p;
     }
-    const int out = !a.resident ? 0
-                    : ((a.T % 2 == 0) && (reinterpret_cast<uintptr_t>(a.resident) % 16 == 0)) ? 2 : 1;
+    int out = !a.resident ? 0
+              : ((a.T % 2 == 0) && (reinterpret_cast<uintptr_t>(a.resident) % 16 == 0)) ? 2 : 1;
+    // long rows: nontemporal stores (see kStreamRowsBytes; tuning knob eval_nt: 0 never, 1 always).  Compiled for the
+    // large geometry and for the binned kernels; which it is is known further down
+    const bool nt_wanted = out == 2 && (g_tuning.eval_nt >= 0 ? g_tuning.eval_nt == 1
+                                                              : static_cast<int64_t>(a.T) * 8 > kStreamRowsBytes);
     const bool narrow = a.size_units != nullptr;
     a.tail_threshold = cap;
     if (!ws.fixed_base) {   // (a fixed workspace brings its flag: zero when the code object is loaded, then monotone)
@@ -1108,6 +1135,7 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
             if (need > ws.fixed_bytes - ws.fixed_used) binned = false;
         }
     }
+    if (nt_wanted && (threads == 1024 || (binned && threads == 512))) out = 3;
     if (binned) {
         const size_t n_recs = 2 * static_cast<size_t>(a.n_intervals), n_off = static_cast<size_t>(a.B) * (n_tiles + 1),
                      n_sum = static_cast<size_t>(a.B) * n_tiles;
@@ -1199,3 +1227,14 @@ extern "C" int tensile_eval_plans_static(const tensile_tas *tas, const tensile_p
     a.MF0 = tas->d_MF0.p; a.dMF0 = tas->d_dMF0.p; a.resident = resident;
     return launch_eval(tas, sw.ws, a, peak, argmax, min_resident);
 }
+
+#ifdef TENSILE_EVAL_PROF
+extern "C" int tensile_debug_eval_prof(unsigned long long *out, int reset) {
+    if (out) (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(tensile::g_eval_prof), sizeof(tensile::g_eval_prof));
+    if (reset) {
+        unsigned long long z[16 * 8] = {};
+        (void)hipMemcpyToSymbol(HIP_SYMBOL(tensile::g_eval_prof), z, sizeof(z));
+    }
+    return 0;
+}
+#endif

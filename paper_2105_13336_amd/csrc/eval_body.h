@@ -94,6 +94,20 @@ struct SizeReg<true> {
     }
 };
 
+// Phase timing for tuning, compiled in with -DTENSILE_EVAL_PROF only: thread 0 of every workgroup adds the
+// 100 MHz ticks it spent in each part of a tile to g_eval_prof (lane 0 of every wavefront, per wavefront).
+#ifdef TENSILE_EVAL_PROF
+__device__ unsigned long long g_eval_prof[16 * 8];   // [wavefront][part]
+#define EVAL_MARK(k)                                              \
+    do {                                                          \
+        const unsigned long long now_ = wall_clock64();           \
+        prof_acc[k] += now_ - prof_t;                             \
+        prof_t = now_;                                            \
+    } while (0)
+#else
+#define EVAL_MARK(k) do { } while (0)
+#endif
+
 __device__ __forceinline__ void opaque(uint32_t &x) { asm volatile("" : "+v"(x)); }
 __device__ __forceinline__ void opaque(int64_t &x) { asm volatile("" : "+v"(x)); }
 
@@ -115,8 +129,10 @@ __device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o,
 // the intervals beyond the registers from memory for every tile.  Both are launched for every
 // batch; a workgroup whose plan belongs to the other kernel exits at once.
 // kOut: 0 = no footprint rows are written (peaks only), 1 = rows written with 8-byte stores
-// (odd T or unaligned buffer), 2 = with 16-byte stores.  A compile-time property so that
-// every path through the tile loop issues the same memory operations.
+// (odd T or unaligned buffer), 2 = with 16-byte stores, 3 = with nontemporal 16-byte stores (long rows,
+// see launch_eval).  A compile-time property so that every path through the tile loop issues the
+// same memory operations: the compiler's waits for the loop's loads count the stores issued after
+// them only when no branch surrounds those stores.
 // kBinned: the batch went through bin_kernel first; nothing is kept in registers (R is 1 and unused),
 // every tile reads its own records.  Every plan of the batch is taken.
 // kBinFast (with kBinned): no tile of the segment holds more than kBinFastRecs * kThr records, so a tile's
@@ -130,7 +146,7 @@ template <int kThr, int R, bool kTail, bool kNarrow, int kOut, bool kBinned = fa
 __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan, const int32_t seg, EvalLds<kThr> &L,
                                           Best *result = nullptr) {
     static_assert(!kBinFast || kBinned, "kBinFast is a form of the binned kernel");
-    constexpr bool kStore = kOut != 0, kVec16 = kOut == 2;
+    constexpr bool kStore = kOut != 0, kVec16 = kOut >= 2;
     constexpr int kWaves = Geom<kThr>::kWaves, kTile = Geom<kThr>::kTile, kTileCells = Geom<kThr>::kTileCells;
     int64_t *const delta = L.delta, *const stage_all = L.stage_all, *const wave_tot = L.wave_tot, *const carry_part = L.carry_part;
     int64_t *const red_mx = L.red_mx, *const red_mn = L.red_mn;
@@ -277,13 +293,31 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
     const uint32_t n_rec = static_cast<uint32_t>(2 * (k1 - k0));
     const int2 *plan_recs = (kBinFast && n_rec) ? a.recs + 2 * k0 : a.recs;
     auto rec_at = [&](uint32_t k) { return plan_recs[k < n_rec ? k : (n_rec ? n_rec - 1 : 0)]; };
-    int2 rec_cur[kBinFastRecs];
-    int32_t rec_lo = 0, rec_hi = 0;   // (uniform)
-    if constexpr (kBinFast) {
-        rec_lo = tile_off[seg_lo / kTile];
-        rec_hi = tile_off[seg_lo / kTile + 1];
+    // Two register sets, for the even and the odd tiles of the segment.  A set is used in its tile's scatter and
+    // requested again, for the tile after the next, at the END of that tile: a request then has two tiles' time to
+    // come back from HBM, and the wavefronts reach that point spread out in time (they leave the tile's last
+    // barrier together but drain their stores one after the other), so their requests do not arrive in one
+    // burst on the CU's queue of outstanding misses, behind which the stores of all wavefronts would wait.
+    int2 rec_set[2][kBinFastRecs];
+    auto off_at = [&](int32_t tile_index) { return tile_off[tile_index < a.n_tiles ? tile_index : a.n_tiles]; };
+    auto load_recs = [&](int32_t lo, int32_t hi, int2 (&dst)[kBinFastRecs]) {   // the records [lo, hi) of one tile
 #pragma unroll
-        for (int j = 0; j < kBinFastRecs; ++j) rec_cur[j] = rec_at(static_cast<uint32_t>(rec_lo + j * kThr + tid));
+        for (int j = 0; j < kBinFastRecs; ++j) {
+            // (a slot past the tile's last record reads what slot j - 1 reads: a line that is on its way already)
+            const int32_t k = lo + j * kThr + tid;
+            dst[j] = rec_at(static_cast<uint32_t>(j > 0 && k >= hi ? k - kThr : k));
+        }
+    };
+    // (uniform) where the records of this tile, the next and the one after it start; a tile reads one more offset
+    // at its top, through the scalar unit, and needs it at its end
+    int32_t off0 = 0, off1 = 0, off2 = 0, off3 = 0;
+    if constexpr (kBinFast) {
+        const int32_t t0 = seg_lo / kTile;
+        off0 = off_at(t0);
+        off1 = off_at(t0 + 1);
+        off2 = off_at(t0 + 2);
+        load_recs(off0, off1, rec_set[0]);
+        load_recs(off1, off2, rec_set[1]);
     }
     __syncthreads();   // the first tile's cells are in place
 
@@ -294,7 +328,9 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
         const int32_t wave_t0 = t_lo + wave_u * (64 * kVpt);
         const ll2 x = (reinterpret_cast<const ll2 *>(stage) + lane + (lane >> 4))[68 * j];
         if (kVec16 && t_hi - t_lo == kTile) {
-            (reinterpret_cast<ll2 *>(row + wave_t0) + lane)[64 * j] = x;   // plain store: nontemporal ones measured slower
+            ll2 *const at = reinterpret_cast<ll2 *>(row + wave_t0) + lane + 64 * j;
+            if constexpr (kOut == 3) __builtin_nontemporal_store(x, at);
+            else *at = x;
         } else {
             const int32_t t = wave_t0 + 2 * (j * 64 + lane);
             if (t + 2 <= t_hi) {
@@ -314,8 +350,14 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
     // of every wavefront's stores at one point of the iteration backs it up and the wavefronts
     // behind arrive late at the next barrier.  The first tile has no previous one and is a
     // separate instantiation so that the same operations are issued on every path.
-    auto do_tile = [&](int32_t tile_lo, auto first_tag) {
+#ifdef TENSILE_EVAL_PROF
+    unsigned long long prof_t = wall_clock64();
+    unsigned long long prof_acc[8] = {};
+#endif
+    auto do_tile = [&](int32_t tile_lo, auto first_tag, auto set_tag) {
+        EVAL_MARK(7);
         constexpr bool kFirst = decltype(first_tag)::value;
+        constexpr int kSet = decltype(set_tag)::value;   // (kBinFast) the register set that holds this tile's records
         const int32_t tile_hi = tile_lo + kTile < seg_hi ? tile_lo + kTile : seg_hi;
         const uint32_t tile_n = static_cast<uint32_t>(tile_hi - tile_lo);
         // delta holds dMF0 of this tile: written before the loop, or by the scan of the previous
@@ -324,20 +366,15 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
 #pragma unroll
         for (int j = 0; j < kVpt / 2; ++j)
             fill[j] = *reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kTile + fill_at + 128 * j);
-        int2 rec_next[kBinFastRecs];
-        int32_t next_hi = 0;
-        if constexpr (kBinFast) {   // the next tile's records (none past the last tile: its offsets are equal)
-            const int32_t t_next = tile_lo / kTile + 2;
-            next_hi = tile_off[t_next < a.n_tiles ? t_next : a.n_tiles];
-#pragma unroll
-            for (int j = 0; j < kBinFastRecs; ++j) rec_next[j] = rec_at(static_cast<uint32_t>(rec_hi + j * kThr + tid));
-        }
+        const int32_t rec_lo = off0, rec_hi = off1;   // this tile's records within the plan's
+        if constexpr (kBinFast) off3 = off_at(tile_lo / kTile + 3);
         constexpr bool kPrev = !kFirst && kStore;
         if constexpr (kPrev) {
             __builtin_amdgcn_wave_barrier();
             store_part(tile_lo - kTile, tile_lo, 0);
         }
 
+        EVAL_MARK(0);
         // ---- scatter: endpoints of this plan that fall into [tile_lo, tile_hi); a wavefront none
         // of whose lanes holds an endpoint in the tile's range skips its registers
         const bool mine = hi_t >= tile_lo && lo_t < tile_hi;
@@ -387,14 +424,11 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
             const uint32_t trash = kTileCells + lane;
 #pragma unroll
             for (int j = 0; j < kBinFastRecs; ++j) {
-                const int2 rec = rec_cur[j];
+                const int2 rec = rec_set[kSet][j];
                 const bool valid = rec_lo + j * kThr + tid < rec_hi;
                 const int64_t bytes = static_cast<int64_t>(static_cast<uint64_t>(static_cast<uint32_t>(rec.y)) << a.size_shift);
                 lds_add(&delta[valid ? static_cast<uint32_t>(rec.x) & 0x7fffffffu : trash], !valid ? 0 : rec.x < 0 ? -bytes : bytes);
-                rec_cur[j] = rec_next[j];
             }
-            rec_lo = rec_hi;
-            rec_hi = next_hi;
         } else if constexpr (kBinned) {
             const int32_t *off = a.tile_off + static_cast<int64_t>(plan) * (a.n_tiles + 1) + tile_lo / kTile;
             const int2 *recs = a.recs + 2 * k0;
@@ -406,7 +440,9 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
             }
         }
         if constexpr (kPrev) store_part(tile_lo - kTile, tile_lo, 1);
+        EVAL_MARK(1);
         __syncthreads();
+        EVAL_MARK(2);
 
         // ---- local scan of this lane's 8 cells; the cells receive the next tile's dMF0.  In the
         // ragged last tile of a row a wavefront whose 512 steps all lie past the end has nothing
@@ -432,7 +468,9 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
         }
         if (lane == 63) wave_tot[wave] = incl;
         if constexpr (kPrev) store_part(tile_lo - kTile, tile_lo, 2);
+        EVAL_MARK(3);
         __syncthreads();
+        EVAL_MARK(4);
         if (!wave_live) {   // (the ragged tile is the last one of its row: no later tile needs carry)
             if constexpr (kPrev) store_part(tile_lo - kTile, tile_lo, 3);
             return;
@@ -510,13 +548,43 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
 #pragma unroll
             for (int j = 0; j < kVpt / 2; ++j) mine_out[j] = ll2{v[2 * j], v[2 * j + 1]};
         }
+        EVAL_MARK(5);
+        if constexpr (kBinFast) {
+            load_recs(off2, off3, rec_set[kSet]);
+            off0 = off1;
+            off1 = off2;
+            off2 = off3;
+        }
+        EVAL_MARK(6);
     };
 
-    do_tile(seg_lo, std::true_type{});
+    typedef std::integral_constant<int, 0> Set0;
+    typedef std::integral_constant<int, 1> Set1;
+    do_tile(seg_lo, std::true_type{}, Set0{});
     int32_t last_lo = seg_lo;
-    for (int32_t tile_lo = seg_lo + kTile; tile_lo < seg_hi; tile_lo += kTile) {
-        do_tile(tile_lo, std::false_type{});
-        last_lo = tile_lo;
+    if constexpr (kBinFast) {
+        // The second tile stands outside the loop as well: the loop is then entered from a tile that, like the
+        // tiles inside it, issues its four quarters of stores after requesting the next tile's records.  The
+        // compiler's wait for those records counts the operations issued after them on the SHORTEST path into the
+        // loop; entered from the first tile (which has no stores), every iteration waited for all stores of the
+        // tile before it to complete.
+        if (seg_lo + kTile < seg_hi) {
+            do_tile(seg_lo + kTile, std::false_type{}, Set1{});
+            last_lo = seg_lo + kTile;
+            for (int32_t tile_lo = seg_lo + 2 * kTile; tile_lo < seg_hi; tile_lo += kTile) {
+                do_tile(tile_lo, std::false_type{}, Set0{});
+                last_lo = tile_lo;
+                tile_lo += kTile;
+                if (tile_lo >= seg_hi) break;
+                do_tile(tile_lo, std::false_type{}, Set1{});
+                last_lo = tile_lo;
+            }
+        }
+    } else {
+        for (int32_t tile_lo = seg_lo + kTile; tile_lo < seg_hi; tile_lo += kTile) {
+            do_tile(tile_lo, std::false_type{}, Set0{});
+            last_lo = tile_lo;
+        }
     }
     if constexpr (kStore) {
         __builtin_amdgcn_wave_barrier();
@@ -524,6 +592,12 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
         for (int j = 0; j < kVpt / 2; ++j) store_part(last_lo, seg_hi, j);
     }
 
+#ifdef TENSILE_EVAL_PROF
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) atomicAdd(&g_eval_prof[wave * 8 + k], prof_acc[k]);
+    }
+#endif
     // ---- (max, earliest argmax, min) of the segment
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {

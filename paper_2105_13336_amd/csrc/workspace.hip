@@ -93,7 +93,7 @@ extern "C" int tensile_tuning_set(const char *knob, int value) {
     struct { const char *name; int Tuning::*field; } const table[] = {
         {"eval_r", &Tuning::eval_r},           {"eval_binned", &Tuning::eval_binned},
         {"eval_threads", &Tuning::eval_threads}, {"eval_segments", &Tuning::eval_segments},
-        {"eval_persistent", &Tuning::eval_persistent}, {"eval_slots", &Tuning::eval_slots},
+        {"eval_persistent", &Tuning::eval_persistent}, {"eval_slots", &Tuning::eval_slots}, {"eval_nt", &Tuning::eval_nt},
         {"score_blocks", &Tuning::score_blocks}, {"link_packed", &Tuning::link_packed},
         {"step_fused", &Tuning::step_fused},
     };

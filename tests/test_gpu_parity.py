@@ -156,6 +156,41 @@ def test_eval_binned_tiles_with_many_records(threads, T, segs, tuning):
     check_eval(tas, pl, label=f"binned crowded threads={threads}")
 
 
+@pytest.mark.parametrize("threads,binned,T,segs,r", [(1024, 0, 20012, 0, 0), (1024, 0, 8192, 0, 2), (1024, 0, 16390, 2, 8), (1024, 1, 20012, 0, 0),
+                                                      (1024, 1, 50002, 3, 0), (512, 1, 12292, 0, 0), (512, 1, 20012, 2, 0)])
+def test_eval_rows_written_with_nontemporal_stores(threads, binned, T, segs, r, tuning):
+    """Long rows are written with nontemporal stores (a kernel variant of its own); forced here on rows of a few
+    tiles: the common kernel with several register capacities and the tail kernel behind it (one plan is longer
+    than the registers hold), several segments per plan, and the binned kernels in both geometries."""
+    tuning("eval_nt", 1)
+    tuning("eval_threads", threads)
+    tuning("eval_binned", binned)
+    if segs:
+        tuning("eval_segments", segs)
+    if r:
+        tuning("eval_r", r)
+    tas = small_random_tas(2300 + T, N=400, T=T, max_acc=4, base_bytes=3)
+    base = make_plans(tas, 7, 11, p_swap=0.8)
+    lists = []
+    for b in range(7):
+        t, o, rr, k = base.plan(b)
+        one = [(int(t[j]), int(o[j]), int(rr[j]), int(k[j])) for j in range(len(t))]
+        lists.append(one * (1, 0, 2, 1, 40, 1, 3)[b])      # (x 40: more than 8192 intervals, the tail kernel's plan)
+    pl = plans_from_lists(lists)
+    say(f"eval nontemporal rows: threads={threads} binned={binned} T={T} segs={segs} r={r} lengths={[len(x) for x in lists]}")
+    check_eval(tas, pl, label=f"nontemporal threads={threads} binned={binned}")
+
+
+def test_eval_long_rows_take_nontemporal_stores_by_default():
+    """A row of more than 131,072 steps (its unscheduled timeline exceeds 1 MiB) with short plans: the default
+    path, which writes such rows with nontemporal stores, against the oracle; ragged last tile."""
+    T = 150_002
+    tas = small_random_tas(2400, N=300, T=T, max_acc=4, base_bytes=9)
+    pl = make_plans(tas, 5, 13, p_swap=0.7)
+    say(f"eval long rows: T={T} K={pl.n_intervals}")
+    check_eval(tas, pl, label="long rows")
+
+
 @pytest.mark.parametrize("threads,T,B,slots,tail", [(1024, 20011, 23, 3, False), (512, 12291, 40, 7, False), (1024, 4097, 9, 2, False),
                                                      (512, 7, 33, 4, False), (1024, 8192, 12, 5, False), (512, 20012, 21, 2, True),
                                                      (1024, 50001, 11, 3, True), (512, 4096, 5, 8, False)])
