@@ -160,7 +160,12 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
     asm volatile("" : "+v"(tid_now));
     const int tid = tid_now, lane = tid & 63, wave = tid >> 6;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // the same number, known to be wave-uniform
-    int64_t k0 = a.plan_offsets[plan], k1 = a.plan_offsets[plan + 1];
+    // The offsets are read through the constant address space (the batch is not written during the launch), so
+    // that they come through the scalar unit: a vector load would queue behind whatever stores the workgroup
+    // that had this CU before has left in the CU's memory pipeline, and the interval loads depend on it.
+    typedef const int64_t __attribute__((address_space(4))) *const_i64_ptr;
+    const const_i64_ptr plan_offsets = (const_i64_ptr)(a.plan_offsets);
+    int64_t k0 = plan_offsets[plan], k1 = plan_offsets[plan + 1];
     if (k0 < 0) k0 = 0;
     if (k1 > a.n_intervals) k1 = a.n_intervals;
     if (k1 < k0) k1 = k0;

@@ -19,11 +19,7 @@
 // One workgroup walks a plan at a time (persistent workgroups, plans dealt
 // round-robin).  Per plan, with acc[] one word per bucket entry in LDS:
 //   1. the plan's output rows are cleared (score 0, windows -1); acc = -inf;
-//   2. the plan's own intervals cancel candidates: an interval inside the gap of
-//      an entry of its tensor sets acc = +inf (Alg. 2 of the paper only takes tensors
-//      that are not swapped out yet).  A per-bucket bit filter over tensors, kept in LDS,
-//      turns most intervals away; the others probe the bucket's hash table;
-//   3. every wavefront streams its own contiguous span of the row, 256 steps at a
+//   2. every wavefront streams its own contiguous span of the row, 256 steps at a
 //      time, four consecutive steps per lane.  With two wave-level scans it forms,
 //      per lane, the running maximum from the span's start up to the lane's steps
 //      and the maximum from after them to the end of the 256, and puts both, with
@@ -33,8 +29,16 @@
 //      the bucket is sorted by o, and a second list is sorted by q; both lists sit
 //      in LDS (reloaded only when the bucket changes) and the wavefront takes them
 //      up 64 at a time.  The maxima of the 256-step pieces go to a table
-//      (LDS), suffix-scanned within the span at the end.  The waves of a workgroup
-//      meet at one barrier after this step; nothing inside it needs one;
+//      (LDS), suffix-scanned within the span at the end;
+//   3. the plan's own intervals cancel candidates: an interval inside the gap of
+//      an entry of its tensor sets acc = +inf (Alg. 2 of the paper only takes tensors
+//      that are not swapped out yet).  A per-bucket bit filter over tensors, kept in LDS,
+//      turns most intervals away; the others probe the bucket's hash table.  (After
+//      the streaming, not before it: +inf survives every max and overwrites one that
+//      came first, so the order is free, and the streaming's many independent loads
+//      make better use of the time in which the output rows of the plan before are
+//      still leaving the CU than this chain of short dependent ones.)  The waves of a
+//      workgroup meet at one barrier after this step; nothing before it needs one;
 //   4. an entry with o < t* < q and acc != +inf scores
 //      P - max( acc, pieces after q's in its span, spans before o's, spans after q's, P - size ).
 // Buckets with more entries than acc holds are processed in slices of kMaxLocal
@@ -502,7 +506,7 @@ int launch_score(const tensile_tas *tas, Workspace &ws, const CandIndex &ix, boo
 extern "C" int tensile_debug_score_prof(unsigned long long *out, int reset) {
     if (out) (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_score_prof), sizeof(g_score_prof));
     if (reset) {
-        unsigned long long z[8] = {};
+        unsigned long long z[8 + 2 * 16] = {};
         (void)hipMemcpyToSymbol(HIP_SYMBOL(g_score_prof), z, sizeof(z));
     }
     return 0;

@@ -229,7 +229,7 @@ __device__ __forceinline__ int64_t stream_span(const ScoreArgs &a, const int64_t
 // Phase timing for tuning, compiled in with -DTENSILE_SCORE_PROF only: thread 0 of every
 // workgroup adds the 100 MHz ticks it spent in each phase to g_score_prof.
 #ifdef TENSILE_SCORE_PROF
-__device__ unsigned long long g_score_prof[8];
+__device__ unsigned long long g_score_prof[8 + 2 * 16];   // phases of thread 0; then per wavefront: streaming, cancelling
 #define PROF_MARK(k)                                              \
     do {                                                          \
         if (tid == 0) {                                           \
@@ -253,7 +253,17 @@ __device__ __forceinline__ T uniform_load(const T *p, int64_t i) {
     return ((const_ptr)p)[i];
 }
 
-// Step 2 of the scoring pass: the plan's own intervals k0 .. k1-1 cancel candidates of the slice
+// A 16-byte piece of an output row.  On long rows (kStream: those of more than 131,072 steps) the store is
+// nontemporal: the lines are not read again by this kernel, and left out of the L2 they leave it to the
+// candidate index and the sub-span maxima (rows of 10^6 steps: 2.58 -> 2.49 ms per batch of 1024 plans; on rows
+// of 50,000 steps it costs 5 %, so short rows keep ordinary stores).
+template <bool kStream, typename V>
+__device__ __forceinline__ void store_out(V *at, const V v) {
+    if constexpr (kStream) __builtin_nontemporal_store(v, at);
+    else *at = v;
+}
+
+// Step 3 of the scoring pass: the plan's own intervals k0 .. k1-1 cancel candidates of the slice
 // [slice_lo, slice_lo + n_slice) of a bucket (acc = +inf): an interval inside the gap of an entry of its tensor
 // (any interval of that tensor when a.any_interval).  filter: the bucket's bit filter over tensors, in LDS;
 // hd: the bucket's {first slot, log2(slots)} in the hash table.
@@ -401,7 +411,8 @@ __device__ __forceinline__ void score_plan(const ScoreArgs &a, const int32_t b, 
             const int32_t *wp = a.wave_ptr + static_cast<int64_t>(slice_id) * 4 * (kWaves + 1);
             // the wavefronts' spans of the row: the slice's own boundaries (multiples of kMini, the last one T),
             // chosen when the index is built so that steps and entries together are spread evenly
-            const int32_t span_lo = uniform_load(wp, 3 * (kWaves + 1) + wave), span_hi = uniform_load(wp, 3 * (kWaves + 1) + wave + 1);
+            const int span = wave;   // (which wavefront takes which span is free: span_max is indexed by span)
+            const int32_t span_lo = uniform_load(wp, 3 * (kWaves + 1) + span), span_hi = uniform_load(wp, 3 * (kWaves + 1) + span + 1);
             __syncthreads();   // the previous plan or slice has finished with acc, tab, span_max, the filter, the lists
             for (int32_t k = tid; k < n_slice; k += kThreads) acc[k] = INT64_MIN;
             if (lists_of != slice_id) {
@@ -423,14 +434,17 @@ __device__ __forceinline__ void score_plan(const ScoreArgs &a, const int32_t b, 
             __syncthreads();
             PROF_MARK(1);
 
-            // ---- 2: the plan's own intervals cancel candidates
-            cancel_by_plan(a, k0, k1, hd, slice_lo, n_slice, filter, acc, tid);
-            PROF_MARK(2);
-
-            // ---- 3: stream the row (no barrier needed after step 2: +inf survives every max)
+            // ---- 2: stream the row.  It comes before the cancelling because its loads are many and independent: they
+            // queue behind the output rows of the plan before (stores that are still leaving the CU) and keep the
+            // memory pipeline busy from the moment those are gone, whereas the cancelling is a chain of short
+            // dependent loads that would only wait there.  The order does not matter to the result: +inf survives
+            // every max, and a max that lands before the +inf is overwritten by it; no barrier in between.
+#ifdef TENSILE_SCORE_PROF
+            const unsigned long long wave_t0 = wall_clock64();
+#endif
             {
-                const int32_t lo_begin = uniform_load(wp, wave), lo_end = uniform_load(wp, wave + 1);
-                const int32_t hi_begin = uniform_load(wp, kWaves + 1 + wave), hi_end = uniform_load(wp, kWaves + 1 + wave + 1);
+                const int32_t lo_begin = uniform_load(wp, span), lo_end = uniform_load(wp, span + 1);
+                const int32_t hi_begin = uniform_load(wp, kWaves + 1 + span), hi_end = uniform_load(wp, kWaves + 1 + span + 1);
                 int64_t m;
                 if (kBigT)
                     m = stream_span<kVec>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
@@ -438,8 +452,19 @@ __device__ __forceinline__ void score_plan(const ScoreArgs &a, const int32_t b, 
                 else
                     m = stream_span<kVec>(a, MF, span_lo, span_hi, lo_list, hi_list, lo_begin, lo_end, hi_begin, hi_end,
                                           acc, &span_buf[wave], tab_lds, lane);
-                if (lane == 0) span_max[wave] = m;
+                if (lane == 0) span_max[span] = m;
             }
+#ifdef TENSILE_SCORE_PROF
+            const unsigned long long wave_t1 = wall_clock64();
+            if (lane == 0) atomicAdd(&g_score_prof[8 + wave], wave_t1 - wave_t0);
+#endif
+            PROF_MARK(2);
+
+            // ---- 3: the plan's own intervals cancel candidates
+            cancel_by_plan(a, k0, k1, hd, slice_lo, n_slice, filter, acc, tid);
+#ifdef TENSILE_SCORE_PROF
+            if (lane == 0) atomicAdd(&g_score_prof[24 + wave], wall_clock64() - wave_t1);
+#endif
             PROF_MARK(3);
             __syncthreads();
             PROF_MARK(4);
@@ -544,13 +569,13 @@ __device__ __forceinline__ void score_plan(const ScoreArgs &a, const int32_t b, 
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
                             const int v = j * 64 + lane;            // two scores per vector
-                            if (2 * v + 1 < n_t) reinterpret_cast<ll2 *>(score + t0)[v] = reinterpret_cast<const ll2 *>(st_score)[v];
+                            if (2 * v + 1 < n_t) store_out<kBigT>(reinterpret_cast<ll2 *>(score + t0) + v, reinterpret_cast<const ll2 *>(st_score)[v]);
                             else if (2 * v < n_t) score[t0 + 2 * v] = st_score[2 * v];
                         }
                         if (lane < kScoreStage / 4) {               // four window values per vector
                             if (4 * lane + 3 < n_t) {
-                                if (wout) reinterpret_cast<i4 *>(wout + t0)[lane] = reinterpret_cast<const i4 *>(st_wo)[lane];
-                                if (win) reinterpret_cast<i4 *>(win + t0)[lane] = reinterpret_cast<const i4 *>(st_wi)[lane];
+                                if (wout) store_out<kBigT>(reinterpret_cast<i4 *>(wout + t0) + lane, reinterpret_cast<const i4 *>(st_wo)[lane]);
+                                if (win) store_out<kBigT>(reinterpret_cast<i4 *>(win + t0) + lane, reinterpret_cast<const i4 *>(st_wi)[lane]);
                             } else {
                                 for (int32_t k = 4 * lane; k < n_t; ++k) {
                                     if (wout) wout[t0 + k] = st_wo[k];
