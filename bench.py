@@ -329,17 +329,18 @@ def main() -> int:
         larg = torch.empty(B, dtype=torch.int32, device="cuda")
         lover = torch.empty(B, dtype=torch.int32, device="cuda")
         link_ms = {}
-        for name, rows_out in (("rows", lrows), ("peaks_only", None)):
-            P.tensile_eval_link(h, dp, lpk, rows_out, larg, lover)
+        for name, rows_out, reuse in (("reuse", lrows, True), ("peaks_only", None, False), ("rows", lrows, False)):
+            P.tensile_eval_link(h, dp, lpk, rows_out, larg, lover, reuse_host_copies=reuse)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(3):
-                P.tensile_eval_link(h, dp, lpk, rows_out, larg, lover)
+                P.tensile_eval_link(h, dp, lpk, rows_out, larg, lover, reuse_host_copies=reuse)
             e1.record()
             torch.cuda.synchronize()
             link_ms[name] = e0.elapsed_time(e1) / 3
         out["rows"]["eval_link"] = {"ms": link_ms["rows"], "ms_peaks_only": link_ms["peaks_only"],
+                                    "ms_with_host_copy_reuse": link_ms["reuse"],
                                     "max_link_peak": int(lpk.max()), "plans_within_one": int((lpk <= 1).sum())}
         del lrows, lpk, larg, lover
 

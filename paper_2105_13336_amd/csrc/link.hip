@@ -30,8 +30,9 @@
 //    reduce (max, earliest argmax, steps occupied twice) and the row leaves through a per-wavefront
 //    staging area as 16 contiguous bytes per lane.  Large tiles matter because every tile tests every
 //    endpoint held in registers: the scatter of a 50,000-step row costs two rounds instead of seven;
-//  * reuse: a table of the earliest swap-out step per tensor (one row of N entries per workgroup in
-//    global memory, L2 atomics) is filled before a plan's first pass and cleaned after its last.
+//  * reuse: a table of the earliest swap-out step per tensor is filled before a plan's first pass and cleaned
+//    after its last: in LDS (over the tile and the staging areas, idle at that point) for plans of one pass on
+//    sequences of up to 25,088 tensors, else one row of N entries per workgroup in global memory, L2 atomics.
 #include "common.h"
 #include "wave_ops.h"
 
@@ -114,8 +115,13 @@ __device__ unsigned long long g_link_prof[8];
 // one lane's cache line per cycle), not by their latency.
 template <bool kPacked>
 __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
-    __shared__ __attribute__((aligned(16))) uint32_t delta[kTileWords];
-    __shared__ __attribute__((aligned(16))) int32_t stage_all[kWaves * kStageCells];
+    // the difference tile and the staging areas, one array: between two plans it also serves as the table of
+    // the earliest swap-out step per tensor (host copy reuse) when the sequence has few enough tensors
+    __shared__ __attribute__((aligned(16))) uint32_t work[kTileWords + kWaves * kStageCells];
+    uint32_t *const delta = work;
+    int32_t *const stage_all = reinterpret_cast<int32_t *>(work + kTileWords);
+    int32_t *const first_lds = reinterpret_cast<int32_t *>(work);
+    constexpr int32_t kFirstLds = kTileWords + kWaves * kStageCells;   // tensors the LDS table has room for
     __shared__ int64_t tab[kTabMax];
     __shared__ int32_t wave_tot[kWaves];
     __shared__ int32_t red_mx[kWaves], red_arg[kWaves], red_over[kWaves];
@@ -139,7 +145,10 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
         int tid_now = threadIdx.x;
         asm volatile("" : "+v"(tid_now));
         const int tid = tid_now, lane = tid & 63, wave = tid >> 6;
-        int64_t k0 = a.plan_offsets[plan], k1 = a.plan_offsets[plan + 1];
+        // (the offsets through the constant address space, i.e. the scalar unit: as a vector load they would queue
+        // behind the row stores of the plan before, and the interval loads depend on them)
+        typedef const int64_t __attribute__((address_space(4))) *const_i64_ptr;
+        int64_t k0 = ((const_i64_ptr)a.plan_offsets)[plan], k1 = ((const_i64_ptr)a.plan_offsets)[plan + 1];
         if (k0 < 0) k0 = 0;
         if (k1 > a.n_intervals) k1 = a.n_intervals;
         if (k1 < k0) k1 = k0;
@@ -150,7 +159,11 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
             const bool kind0 = a.iv_kind ? a.iv_kind[k] == 0 : true;
             return kind0 && static_cast<uint32_t>(i) < static_cast<uint32_t>(a.N) && o >= 0 && r <= a.T && r > o;
         };
-        if (a.reuse) {   // the earliest swap-out step of every tensor of the plan
+        // Host copy reuse needs the earliest swap-out step of every tensor of the plan.  A plan of one pass on a
+        // sequence of at most kFirstLds tensors collects them in LDS (below, once its intervals are in registers);
+        // any other plan in a table in global memory, with L2 atomics - six times the time of the whole rest.
+        const bool reuse_lds = a.reuse && a.N <= kFirstLds && k1 - k0 <= kPass;   // (block-uniform)
+        if (a.reuse && !reuse_lds) {
             for (int64_t k = k0 + tid; k < k1; k += kThr) {
                 int32_t i, o, r;
                 if (swap_at(k, i, o, r)) atomicMin(&first_out[i], o);
@@ -200,13 +213,34 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
                     }
                 }
             }
+            if (reuse_lds) {
+                // only the entries this plan touches are set up, and put back to zero afterwards: the rest of the
+                // tile is zero already (the scan clears what it reads) and the staging areas may hold anything
+#pragma unroll
+                for (int j = 0; j < kR; ++j)
+                    if (ok[j]) first_lds[iv_i[j]] = INT32_MAX;
+                __syncthreads();
+#pragma unroll
+                for (int j = 0; j < kR; ++j)
+                    if (ok[j]) atomicMin(&first_lds[iv_i[j]], iv_o[j]);
+                __syncthreads();
+#pragma unroll
+                for (int j = 0; j < kR; ++j) charged[j] = ok[j] && first_lds[iv_i[j]] == iv_o[j];
+                __syncthreads();
+#pragma unroll
+                for (int j = 0; j < kR; ++j)
+                    if (ok[j]) first_lds[iv_i[j]] = 0;
+                __syncthreads();
+            }
             LINK_MARK(1);
             int64_t v[kR][2];     // C at the transfer's end minus its duration: the transfer starts inside the last step that begins at or before v
 #pragma unroll
             for (int j = 0; j < kR; ++j) {
                 const int64_t x = a.x[iv_i[j]];
-                charged[j] = true;
-                if (a.reuse) charged[j] = __hip_atomic_load(&first_out[iv_i[j]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == iv_o[j];
+                if (!reuse_lds) {
+                    charged[j] = true;
+                    if (a.reuse) charged[j] = __hip_atomic_load(&first_out[iv_i[j]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == iv_o[j];
+                }
                 v[j][0] = c_at(static_cast<uint32_t>(iv_o[j] + 1)) - x;
                 v[j][1] = c_at(static_cast<uint32_t>(iv_r[j])) - x;
                 ok[j] = ok[j] && x > 0;
@@ -487,7 +521,7 @@ __global__ __launch_bounds__(kThr) void link_kernel(const LinkArgs a) {
             if (a.argmax) a.argmax[plan] = arg;
             if (a.overbooked) a.overbooked[plan] = ov;
         }
-        if (a.reuse) {   // leave the table as it was found
+        if (a.reuse && !reuse_lds) {   // leave the table as it was found
             for (int64_t k = k0 + tid; k < k1; k += kThr) {
                 int32_t i, o, r;
                 if (swap_at(k, i, o, r)) __hip_atomic_store(&first_out[i], INT32_MAX, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
