@@ -544,7 +544,10 @@ __global__ __launch_bounds__(kThr) void eval_tail_kernel(const EvalArgs a) {
 constexpr int kMaxBinTiles = 4096;
 constexpr int kBinU = 4;   // intervals per thread and round of bin_kernel's passes
 
-template <int kThr>
+// kSums: the tiles' delta sums are wanted (rows cut into several segments take their entering sums from them).
+// Without them the first pass needs no sizes: it reads the steps only, and an interval whose tensor index is
+// out of range is counted there like any other and gets records of size zero in the second pass.
+template <int kThr, bool kSums>
 __global__ __launch_bounds__(1024) void bin_kernel(const EvalArgs a, int2 *recs_all, int32_t *tile_off, int64_t *tile_sum) {
     constexpr int kTile = Geom<kThr>::kTile;
     __shared__ int32_t cnt[kMaxBinTiles + 1];
@@ -592,28 +595,42 @@ __global__ __launch_bounds__(1024) void bin_kernel(const EvalArgs a, int2 *recs_
             todo &= ~group;
         }
     };
+    // which intervals the passes take when the sizes are not looked at: those whose steps can be applied
+    auto steps_apply = [&](int32_t o, int32_t r) { return o >= a.o_min && r <= a.T && r > o; };
     for (int64_t base = wave * 64; base < n_iv; base += kBinU * 1024) {
         int32_t i[kBinU], o[kBinU], r[kBinU];
         uint32_t units[kBinU];
-        load_round(k0 + base + lane, i, o, r, units);
+        if constexpr (kSums) {
+            load_round(k0 + base + lane, i, o, r, units);
+        } else {
+#pragma unroll
+            for (int u = 0; u < kBinU; ++u) {
+                const int64_t k = k0 + base + lane + u * 1024;
+                const int64_t kc = k < k1 ? k : k1 - 1;
+                o[u] = a.iv_out[kc];
+                r[u] = a.iv_in[kc];
+                i[u] = (k < k1 && steps_apply(o[u], r[u])) ? 0 : -1;
+                units[u] = 0;
+            }
+        }
 #pragma unroll
         for (int u = 0; u < kBinU; ++u) {
             const int64_t bytes = static_cast<int64_t>(static_cast<uint64_t>(units[u]) << a.size_shift);
             const bool has_out = i[u] >= 0 && o[u] + 1 < a.T, has_in = i[u] >= 0 && r[u] < a.T;
             const int32_t tl_out = (o[u] + 1) / kTile, tl_in = r[u] / kTile;
             for_each_tile(has_out, tl_out, [&](int32_t t, uint64_t group, int leader) {
-                const int64_t tot = last_lane(wave_scan_add(has_out && tl_out == t ? bytes : 0));
-                if (lane == leader) {
-                    atomicAdd(&cnt[t], __popcll(group));
-                    lds_sub(&sum[t], tot);
+                if constexpr (kSums) {
+                    const int64_t tot = last_lane(wave_scan_add(has_out && tl_out == t ? bytes : 0));
+                    if (lane == leader) lds_sub(&sum[t], tot);
                 }
+                if (lane == leader) atomicAdd(&cnt[t], __popcll(group));
             });
             for_each_tile(has_in, tl_in, [&](int32_t t, uint64_t group, int leader) {
-                const int64_t tot = last_lane(wave_scan_add(has_in && tl_in == t ? bytes : 0));
-                if (lane == leader) {
-                    atomicAdd(&cnt[t], __popcll(group));
-                    lds_add(&sum[t], tot);
+                if constexpr (kSums) {
+                    const int64_t tot = last_lane(wave_scan_add(has_in && tl_in == t ? bytes : 0));
+                    if (lane == leader) lds_add(&sum[t], tot);
                 }
+                if (lane == leader) atomicAdd(&cnt[t], __popcll(group));
             });
         }
     }
@@ -650,6 +667,15 @@ __global__ __launch_bounds__(1024) void bin_kernel(const EvalArgs a, int2 *recs_
         int32_t i[kBinU], o[kBinU], r[kBinU];
         uint32_t units[kBinU];
         load_round(k0 + base + lane, i, o, r, units);
+        if constexpr (!kSums) {   // (the first pass counted by the steps alone)
+#pragma unroll
+            for (int u = 0; u < kBinU; ++u) {
+                if (i[u] < 0 && base + lane + u * 1024 < n_iv && steps_apply(o[u], r[u])) {
+                    i[u] = 0;
+                    units[u] = 0;
+                }
+            }
+        }
 #pragma unroll
         for (int u = 0; u < kBinU; ++u) {
             const bool has_out = i[u] >= 0 && o[u] + 1 < a.T, has_in = i[u] >= 0 && r[u] < a.T;
@@ -741,7 +767,8 @@ int launch_geometry(const tensile_tas *tas, Workspace &ws, const EvalArgs &a, in
     const hipStream_t stream = ws.stream;
     dim3 grid(static_cast<uint32_t>(blocks)), block(kThr);
     if (binned) {
-        hipLaunchKernelGGL(bin_kernel<kThr>, dim3(a.B), dim3(1024), 0, stream, a, ws.bin_recs.p, ws.bin_off.p, ws.bin_sum.p);
+        if (a.S > 1) hipLaunchKernelGGL((bin_kernel<kThr, true>), dim3(a.B), dim3(1024), 0, stream, a, ws.bin_recs.p, ws.bin_off.p, ws.bin_sum.p);
+        else hipLaunchKernelGGL((bin_kernel<kThr, false>), dim3(a.B), dim3(1024), 0, stream, a, ws.bin_recs.p, ws.bin_off.p, ws.bin_sum.p);
         TS_HIP(hipGetLastError());
         if (out == 3) {
             hipLaunchKernelGGL((eval_binned_kernel<kThr, 3, true>), grid, block, 0, stream, a);

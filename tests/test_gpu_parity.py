@@ -566,16 +566,31 @@ def test_eval_optional_outputs_and_empty_batches(configs_small):
     h.close()
 
 
-def test_eval_inapplicable_intervals_and_clamped_offsets():
+@pytest.mark.parametrize("binned,segs", [(-1, 0), (1, 0), (1, 2)])
+def test_eval_inapplicable_intervals_and_clamped_offsets(binned, segs, tuning):
+    """Intervals that cannot be applied are skipped, offsets outside the arrays are clamped: on the default path and
+    on the binned one, whose counting pass looks at the steps alone when the rows are not cut into segments (an
+    interval with a tensor index out of range then gets records of size zero)."""
+    tuning("eval_binned", binned)
+    if segs:
+        tuning("eval_segments", segs)
     tas = tas_from_lists(8, [5, 7], [0, 1], [[6], [7]])
     good = [(0, 1, 5, 0)]
     bad = [(2, 1, 5, 0), (-1, 1, 5, 0), (0, -1, 5, 0), (0, 1, 9, 0), (0, 5, 5, 0), (0, 5, 3, 0), (1, 3, 8, 0), (0, 2, 3, 0)]
     pl = plans_from_lists([good, good + bad, bad])
-    say("eval inapplicable intervals")
+    say(f"eval inapplicable intervals binned={binned} segs={segs}")
     check_eval(tas, pl)
     pl2 = plans_from_lists([good, good])
     pl2 = Plans(2, np.array([-5, 1, 99], dtype=np.int64), pl2.iv_tensor, pl2.iv_out, pl2.iv_in, pl2.iv_kind)
     check_eval(tas, pl2)
+    # the same on rows of several tiles, many intervals, a third of them with a tensor index out of range
+    tas2 = small_random_tas(2500, N=300, T=20012, max_acc=4, base_bytes=3)
+    base = make_plans(tas2, 5, 17, p_swap=0.8)
+    lists = []
+    for b in range(5):
+        t, o, r, k = base.plan(b)
+        lists.append([((int(t[j]) if j % 3 else tas2.N + j), int(o[j]), int(r[j]), int(k[j])) for j in range(len(t))] * (1 + 3 * b))
+    check_eval(tas2, plans_from_lists(lists), label="out-of-range tensors")
 
 
 def test_eval_order_invariance(configs_small):
