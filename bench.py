@@ -125,7 +125,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
-    ap.add_argument("--cpu-plans", type=int, default=4096, help="plans in the oracle's sample on all threads (a quarter of them on one thread)")
+    ap.add_argument("--cpu-plans", type=int, default=16384, help="plans in the oracle's sample on all threads (a quarter of them on one thread)")
     ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the oracle's second leg (default: min(16, cores))")
     ap.add_argument("--print-sources-hash", action="store_true", help="print the hash that ties a counter summary to the kernel sources and exit")
     ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-planner leg")
