@@ -296,17 +296,50 @@ __global__ __launch_bounds__(kThreads) void greedy_step_kernel(const GreedyStepA
                 lds.hi_list[k] = a.qord[e0 + slice_lo + k];
             }
             if (tid == 0) lds.n_stage = 0;
-            __syncthreads();
-            for (int32_t k = tid; k <= n_slice; k += kThreads) {
-                // blocks after the previous entry's block, up to this entry's block, start at this entry
-                const int32_t lo_prev = k > 0 ? lds.lo_list[k - 1] / kMini : -1, lo_cur = k < n_slice ? lds.lo_list[k] / kMini : n_blk;
-                for (int32_t bq = lo_prev + 1; bq <= lo_cur; ++bq) lds.lo_ptr[bq] = k;
-                const int32_t hi_prev = k > 0 ? lds.hi_list[k - 1].x / kMini : -1, hi_cur = k < n_slice ? lds.hi_list[k].x / kMini : n_blk;
-                for (int32_t bq = hi_prev + 1; bq <= hi_cur; ++bq) lds.hi_ptr[bq] = k;
+            // this thread's entries for the last step (three at most), requested now: what they are scored from is
+            // static, and the flags were set before the barrier above; all of it is on its way while the row streams
+            constexpr int kPer = kMaxLocal / kThreads;
+            static_assert(kPer * kThreads == kMaxLocal && kStageRecs == kThreads, "one entry per thread and round of the last step");
+            int4 my_c[kPer];
+            int32_t my_gap[kPer];
+            int64_t my_sz[kPer];
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) {
+                const int32_t k = j * kThreads + tid;
+                const int32_t e = e0 + slice_lo + (k < n_slice ? k : 0);
+                my_c[j] = a.cand[e];
+                my_gap[j] = a.cand_gap[e];
+                my_sz[j] = a.cand_size[e];
             }
             __syncthreads();
+            STEP_MARK(0);
+            // lo_ptr[b] / hi_ptr[b]: the first entry of the o / q order whose step lies in block b or later - one
+            // binary search per block and order, all blocks at once.  (Walking the entries and filling in the blocks
+            // between two of them left the ~100 blocks before the first entry, and as many after the last, to a
+            // single thread: 6.7 us of every iteration.)
+            for (int32_t bq = tid; bq <= 2 * n_blk + 1; bq += kThreads) {
+                const bool hi_order = bq > n_blk;
+                const int32_t blk = hi_order ? bq - n_blk - 1 : bq;
+                const int32_t bound = blk * kMini;                 // (blk == n_blk: past every step)
+                int32_t lo = 0, hi = n_slice;                      // first k with step(k) >= bound
+                while (lo < hi) {
+                    const int32_t mid = (lo + hi) >> 1;
+                    const int32_t step = hi_order ? lds.hi_list[mid].x : lds.lo_list[mid];
+                    if (step < bound) lo = mid + 1;
+                    else hi = mid;
+                }
+                if (hi_order) lds.hi_ptr[blk] = lo;
+                else lds.lo_ptr[blk] = lo;
+            }
+            uint8_t my_taken[kPer];
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) my_taken[j] = a.any_interval ? g.tensor_taken[my_c[j].w] : g.gap_taken[my_gap[j] < 0 ? 0 : my_gap[j]];
+            __syncthreads();
             STEP_MARK(1);
-            // ---- the row's blocks, dealt round-robin; a block without an endpoint of the slice is not even read
+            // ---- the row's blocks, dealt round-robin; a block without an endpoint of the slice is not even read.
+            // (Taken one by one from a common counter instead - the entries are spread unevenly over the blocks, and
+            // the first wavefront waits 3 us for the last - the wait shrinks to 2 us and the step grows by 2: the
+            // atomic and its way back into a scalar register sit in front of every request.)
             {
                 SpanBuf *const buf = &lds.buf[wave];
                 auto wanted = [&](int32_t kb) { return kb < n_blk && (lds.lo_ptr[kb + 1] > lds.lo_ptr[kb] || lds.hi_ptr[kb + 1] > lds.hi_ptr[kb]); };
@@ -343,9 +376,21 @@ __global__ __launch_bounds__(kThreads) void greedy_step_kernel(const GreedyStepA
                         const int32_t t0 = kb * kMini;
                         const int64_t before_blk = lds.pmx[kb], after_blk = lds.smx[kb + 1];
                         const int64_t m = max64(max64(v0, v1), max64(v2, v3));
-                        const int64_t incl = max64(wave_scan_max(m), before_blk);
+                        // (this pass is bound by its instructions - one CU for the whole row - and the two scans are
+                        // most of them: where the block's values share their upper halves, as they nearly always do,
+                        // the scans run on the lower ones)
+                        int64_t fwd, rs;
+                        const int32_t m_hi = static_cast<int32_t>(m >> 32);
+                        if (__builtin_amdgcn_ballot_w64(m_hi != __builtin_amdgcn_readfirstlane(m_hi)) == 0) {   // (wave-uniform)
+                            const int64_t top = static_cast<int64_t>(static_cast<uint64_t>(static_cast<uint32_t>(m_hi)) << 32);
+                            fwd = top | wave_scan_umax32(static_cast<uint32_t>(m));
+                            rs = top | wave_rscan_umax32(static_cast<uint32_t>(m), lane);
+                        } else {
+                            fwd = wave_scan_max(m);
+                            rs = wave_rscan_max(m, lane);
+                        }
+                        const int64_t incl = max64(fwd, before_blk);
                         const int64_t excl = from_prev_lane(incl, before_blk);          // max MF[0 .. t0 + 4 lane - 1]
-                        const int64_t rs = wave_rscan_max(m, lane);
                         const int64_t rs_next = max64(from_next_lane(rs, INT64_MIN), after_blk);   // max MF[t0 + 4 lane + 4 .. T)
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         reinterpret_cast<ll2 *>(buf->raw)[2 * lane] = ll2{v0, v1};
@@ -382,20 +427,24 @@ __global__ __launch_bounds__(kThreads) void greedy_step_kernel(const GreedyStepA
             // at a time and sent to the host as whole lines
             ScoreCand *const stage = reinterpret_cast<ScoreCand *>(lds.buf);
             int32_t staged_before = 0;     // (n_stage counts the slice's records so far; it is reset at the slice's start)
-            for (int32_t r0 = 0; r0 < n_slice; r0 += kStageRecs) {
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) {
+                const int32_t r0 = j * kStageRecs;
+                if (r0 >= n_slice) break;      // (block-uniform)
                 const int32_t k = r0 + tid;
                 if (k < n_slice) {
                     // (a candidate the plan has already dealt with is out: an interval inside the entry's gap - or,
                     // for recomputation, any interval of its tensor - which the flags record as the plan grows)
-                    const int4 c = a.cand[e0 + slice_lo + k];
-                    const int32_t gap = a.cand_gap[e0 + slice_lo + k];
-                    const int64_t sz = a.cand_size[e0 + slice_lo + k];
+                    const int4 c = my_c[j];
+                    const int32_t gap = my_gap[j];
+                    const int64_t sz = my_sz[j];
                     const int64_t v = lds.acc[k];
-                    const bool taken = (a.any_interval ? g.tensor_taken[c.w] : g.gap_taken[gap]) != 0;
+                    const bool taken = my_taken[j] != 0;
                     if (c.z < tstar && tstar < c.y && !taken)
                         stage[atomicAdd(&lds.n_stage, 1) - staged_before] = ScoreCand{P - max64(v, P - sz), c.w, c.z, c.y, gap};
                 }
                 __syncthreads();
+                STEP_MARK(2);
                 const int32_t n_st = lds.n_stage - staged_before;
                 const int64_t *src = reinterpret_cast<const int64_t *>(stage);
                 int64_t *dst = reinterpret_cast<int64_t *>(a.compact + n_out);
@@ -403,11 +452,14 @@ __global__ __launch_bounds__(kThreads) void greedy_step_kernel(const GreedyStepA
                 n_out += n_st;
                 staged_before += n_st;
                 __syncthreads();       // the staging area is free again
+                STEP_MARK(5);
             }
         }
-        // the header travels with the records: one wait for the host's memory instead of two
+        // the header travels with the records: one wait for the host's memory instead of two.  The barrier orders every
+        // thread's records before thread 0's store of the signal, and that store releases at system scope - which
+        // covers what happened before it in other threads too (a system-scope fence in each of the 1024 threads,
+        // as it was first written, cost 2 us per iteration more)
         if (tid == 0) *a.hdr = ScoreHeader{P, tstar, n_out};
-        if (a.ready) __threadfence_system();   // this thread's records (and the header), before the barrier that precedes the signal
         __syncthreads();
         if (tid == 0 && a.ready) __hip_atomic_store(a.ready, a.ready_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         STEP_MARK(7);

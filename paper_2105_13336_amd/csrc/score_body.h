@@ -105,6 +105,34 @@ __device__ __forceinline__ int64_t wave_rscan_max(int64_t x, int lane) {
     return max64(x, later);
 }
 
+// The same two scans over unsigned 32-bit values (a single instruction per step instead of a 64-bit compare and
+// two selects): for values that share their upper halves, the maximum is decided by the lower ones.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ uint32_t dpp_umax32(uint32_t x) {
+    const uint32_t y = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kCtrl, kRowMask, 0xf, true));
+    return x > y ? x : y;
+}
+__device__ __forceinline__ uint32_t wave_scan_umax32(uint32_t x) {
+    x = dpp_umax32<0x111, 0xf>(x);
+    x = dpp_umax32<0x112, 0xf>(x);
+    x = dpp_umax32<0x114, 0xf>(x);
+    x = dpp_umax32<0x118, 0xf>(x);
+    x = dpp_umax32<0x142, 0xa>(x);
+    x = dpp_umax32<0x143, 0xc>(x);
+    return x;
+}
+__device__ __forceinline__ uint32_t wave_rscan_umax32(uint32_t x, int lane) {
+    x = dpp_umax32<0x101, 0xf>(x);
+    x = dpp_umax32<0x102, 0xf>(x);
+    x = dpp_umax32<0x104, 0xf>(x);
+    x = dpp_umax32<0x108, 0xf>(x);
+    const uint32_t r3 = __builtin_amdgcn_readlane(static_cast<int>(x), 48);
+    const uint32_t q2 = __builtin_amdgcn_readlane(static_cast<int>(x), 32), r2 = q2 > r3 ? q2 : r3;
+    const uint32_t q1 = __builtin_amdgcn_readlane(static_cast<int>(x), 16), r1 = q1 > r2 ? q1 : r2;
+    const uint32_t later = lane < 16 ? r1 : (lane < 32 ? r2 : (lane < 48 ? r3 : 0u));
+    return x > later ? x : later;
+}
+
 // value of the previous / next lane; the first / last lane receives `edge`
 __device__ __forceinline__ int64_t from_prev_lane(int64_t x, int64_t edge) { return dpp_move<0x138, 0xf>(x, edge); }   // wave_shr:1
 __device__ __forceinline__ int64_t from_next_lane(int64_t x, int64_t edge) { return dpp_move<0x130, 0xf>(x, edge); }   // wave_shl:1
