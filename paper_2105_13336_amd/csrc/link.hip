@@ -583,7 +583,8 @@ int launch_link(const tensile_tas *tas, Workspace &ws, const tensile_plans *plan
     }
     a.n_tab = static_cast<int32_t>(static_cast<int64_t>(T) / a.tab_stride + 1);   // entries k with k * stride <= T: at most kTabReal
     const int32_t grid = B < tas->num_cus ? B : tas->num_cus;
-    if (reuse) {
+    // (the table in global memory is only for plans the kernel cannot serve from LDS: see reuse_lds there)
+    if (reuse && (tas->N > kTileWords + kWaves * kStageCells || plans->n_intervals > kPass)) {
         const size_t need = static_cast<size_t>(grid) * static_cast<size_t>(tas->N);
         bool fresh = false;
         const int rc = ws.provide(ws.link_first, need, "eval_link: earliest swap-out table", &fresh);
