@@ -68,16 +68,16 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
 // A persistent grid: one workgroup per resident slot walks the plans slot, slot + grid, ... as ONE
 // stream of tiles.  A workgroup that starts pays three dependent load latencies (offsets, intervals,
 // sizes) before its first tile; here
-//  * the next plan's intervals are loaded right after the current plan's last scatter (into the
-//    registers that its own intervals leave) and their sizes after that tile's scan, each ahead of
-//    later stores, so that neither wait includes younger stores;
+//  * the next plan's intervals are requested during the current plan's first tile and their sizes during
+//    its last, into registers of their own (a row of one tile: after its scatter and after its scan);
 //  * the last tile's scan refills the cells with the next plan's first tile;
 //  * a tile's results are stored during the next tile, whichever plan that belongs to;
 //  * the wavefronts' (max, argmax, min) of a plan are combined after the next tile's first barrier.
-// Measured on rows of 50,000 steps with 5,400 intervals per plan: 8 % faster than one workgroup per
-// plan when no rows are written (peaks only), no faster when they are (there the start of the next
-// workgroup already overlaps the draining stores of the last one), so the host picks it for
-// peaks-only batches.
+// Measured on rows of 50,000 steps with 5,400 intervals per plan, 16,384 plans, 1024 threads: 11 % faster than
+// one workgroup per plan when no rows are written (1.19 -> 1.05 ms; two workgroups of 512 threads per CU, one per
+// plan, take 0.86 there and are what the host picks) and 6 % when they are (1.66 -> 1.55 ms), where the lists'
+// way from HBM is the part a starting workgroup cannot hide; with the lists requested only one tile ahead it was no
+// faster than one workgroup per plan.
 // Plans with more intervals than the registers hold are left to the tail kernel as before.
 template <int kThr, int R, bool kNarrow, int kOut>
 __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) void eval_stream_kernel(const EvalArgs a) {
@@ -161,9 +161,19 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         for (int j = 0; j < R; ++j) {
             const uint32_t k = static_cast<uint32_t>(L.wave) * (64 * R) + j * 64 + L.lane;   // (as in eval_body)
             const uint32_t kc = k < len ? k : len - 1;
-            nti[j] = pt[kc];
-            nvo[j] = po[kc];
-            nvr[j] = pr[kc];
+            // (when rows are written the lists are read past the L2's allocation: they are used once, and the lines
+            // they would take are the unscheduled timeline's, which every workgroup of the XCD reads - c3 1.575 ->
+            // 1.547 ms; without row stores it is 1 % slower, and in the kernel with one workgroup per plan, which
+            // waits for the lists at once, 3 % on 24,000-step rows and 40 % on 6,000-step ones)
+            if constexpr (kStore) {
+                nti[j] = __builtin_nontemporal_load(pt + kc);
+                nvo[j] = __builtin_nontemporal_load(po + kc);
+                nvr[j] = __builtin_nontemporal_load(pr + kc);
+            } else {
+                nti[j] = pt[kc];
+                nvo[j] = po[kc];
+                nvr[j] = pr[kc];
+            }
         }
     };
     auto load_sizes = [&](const Ids &L, int64_t k0, int64_t k1) {
@@ -188,14 +198,14 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         for (int j = 0; j < R; ++j) {
             if (nvr[j] < 0) {
                 sz[j] = 0;
-                e0[j] = UINT32_MAX;
-                e1[j] = UINT32_MAX;
+                e0[j] = kNoCell;
+                e1[j] = kNoCell;
             } else {
                 sz[j] = nsz[j];
                 lo_t = nvo[j] + 1 < lo_t ? nvo[j] + 1 : lo_t;
                 hi_t = nvr[j] > hi_t ? nvr[j] : hi_t;
-                e0[j] = skew(static_cast<uint32_t>(nvo[j] + 1));
-                e1[j] = skew(static_cast<uint32_t>(nvr[j]));
+                e0[j] = cell_bytes(nvo[j] + 1, 0, a.T);
+                e1[j] = cell_bytes(nvr[j], 0, a.T);
             }
         }
     };
@@ -309,7 +319,6 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         constexpr bool kFirst = decltype(first_tag)::value, kLast = decltype(last_tag)::value;
         const std::integral_constant<bool, !kFirst> prev_full{};
         const int32_t tile_hi = tile_lo + kTile < a.T ? tile_lo + kTile : a.T;
-        const uint32_t tile_n = static_cast<uint32_t>(tile_hi - tile_lo);
         // loads first: the cells of the tile that follows (the next plan's first one after a last
         // tile; dMF0 is padded to whole tiles), then the next plan's intervals
         {   // (uniform base plus a 32-bit byte offset: no 64-bit address is kept per L.lane)
@@ -318,26 +327,35 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
 #pragma unroll
             for (int j = 0; j < kVpt / 2; ++j) fill[j] = *reinterpret_cast<const ll2 *>(cells + 1024 * j);
         }
+        // The next plan's intervals are requested in this plan's first tile and their sizes (which come from the
+        // L2) in its last, into registers of their own: every vector memory instruction of the CU queues behind
+        // the stores that have not left it yet (most of a tile's worth when the rows are written) and the lists
+        // then come from HBM while it is busy with those stores.  Requested where this plan's registers become
+        // free (after the last scatter) they were waited for during most of a tile; one tile ahead changed little
+        // (c3 with rows 1.745 ms either way), a whole row ahead does (1.57).
+        if constexpr (kFirst && !kLast) load_list(L, nk0, nk1);
+        if constexpr (kLast && !kFirst) load_sizes(L, nk0, nk1);
         __builtin_amdgcn_wave_barrier();
         store_part(L, 0, prev_full);
 
         // ---- scatter
         const bool mine = hi_t >= tile_lo && lo_t < tile_hi;
         if (__builtin_amdgcn_ballot_w64(mine) != 0) {
-            const uint32_t base_cell = skew(static_cast<uint32_t>(tile_lo)), n_cell = skew(tile_n);
-            const uint32_t trash = kTileCells + L.lane;
+            const uint32_t tile_bytes = __builtin_amdgcn_readfirstlane(skew(static_cast<uint32_t>(tile_lo)) * 8u);
+            const uint32_t trash = (kTileCells + L.lane) * 8u;
+            char *const cells = reinterpret_cast<char *>(delta);
 #pragma unroll
-            for (int j = 0; j < R; ++j) {
-                const uint32_t u0 = e0[j] - base_cell, u1 = e1[j] - base_cell;
+            for (int j = 0; j < R; ++j) {   // (as in eval_body)
+                const uint32_t u0 = e0[j] - tile_bytes, u1 = e1[j] - tile_bytes;
                 typename SR::type s = sz[j];
                 opaque(s);
                 const int64_t bytes = SR::bytes(a, s);
-                lds_sub(&delta[u0 < n_cell ? u0 : trash], bytes);
-                lds_add(&delta[u1 < n_cell ? u1 : trash], bytes);
+                lds_sub(reinterpret_cast<int64_t *>(cells + (u0 < trash ? u0 : trash)), bytes);
+                lds_add(reinterpret_cast<int64_t *>(cells + (u1 < trash ? u1 : trash)), bytes);
             }
         }
-        // the registers of this plan's intervals are free after its last scatter: the next plan's move in
-        if constexpr (kLast) load_list(L, nk0, nk1);
+        // (a row of one tile: the next plan's intervals as soon as this plan's have been scattered)
+        if constexpr (kLast && kFirst) load_list(L, nk0, nk1);
         store_part(L, 1, prev_full);
         __syncthreads();
         if constexpr (kFirst) {
@@ -372,7 +390,7 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
             }
         }
         if (L.lane == 63) wave_tot[L.wave] = incl;
-        if constexpr (kLast) load_sizes(L, nk0, nk1);
+        if constexpr (kLast && kFirst) load_sizes(L, nk0, nk1);
         store_part(L, 2, prev_full);
         __syncthreads();
         if (wave_live) {
@@ -1100,6 +1118,9 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
     const int forced = g_tuning.eval_segments;   // tuning knob
     if (forced > 0) S = forced;
     if (S < 1) S = 1;
+    // (the kernels keep an interval's endpoints as 32-bit byte offsets into the segment's cells: at most 2^28 steps
+    // and a tile per segment)
+    if (S < ((static_cast<int64_t>(a.T) + (1 << 28) - 1) >> 28)) S = (static_cast<int64_t>(a.T) + (1 << 28) - 1) >> 28;
     if (S > n_tiles) S = n_tiles;
     const int64_t tps = (n_tiles + S - 1) / S;
     S = (n_tiles + tps - 1) / tps;
@@ -1177,7 +1198,12 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
     }
     // several plans per resident workgroup: the persistent kernel (it addresses a row's bytes with 32 bits)
     const bool pers_ok = S == 1 && !binned && a.N > 0 && a.T <= (1 << 28) && cap != kCapTail;
-    bool persistent = pers_ok && out == 0 && a.B >= 4 * static_cast<int64_t>(tas->num_cus);
+    // Without rows: batches of at least four plans per CU (where the host has not chosen two small workgroups per
+    // CU, which are ahead there).  With rows, in the large geometry: the same batches when a row has at least three
+    // tiles - the next plan's lists are then requested most of a row ahead (50,000-step rows, 5,400 intervals per
+    // plan: 16,384 plans 1.66 -> 1.55 ms, 4,096 plans 0.423 -> 0.401, 512 plans 0.051 -> 0.052).
+    bool persistent = pers_ok && a.B >= 4 * static_cast<int64_t>(tas->num_cus) &&
+                      (out == 0 || (threads == 1024 && out != 3 && n_tiles >= 3));
     const int pers_forced = g_tuning.eval_persistent;   // tuning knob: 0 = never, 1 = whenever possible
     if (pers_forced == 0) persistent = false;
     if (pers_forced == 1) persistent = pers_ok;

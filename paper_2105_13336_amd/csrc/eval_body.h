@@ -30,6 +30,16 @@ struct Geom {
     static_assert(kWaves <= 16 && kTile <= kEvalTile, "wave totals are scanned by 16 lanes; dMF0 is padded for kEvalTile");
 };
 __device__ __forceinline__ uint32_t skew(uint32_t u) { return u + ((u >> 5) << 1); }
+// An interval's endpoints are kept as BYTE offsets of their cells from the segment's first cell (skew is monotone, and
+// additive over multiples of 32, so the offset inside a tile is this minus the tile's own).  Segments have at most
+// 2^28 + one tile of steps (the host cuts longer rows), so an offset stays below 2.3e9, and kNoCell - for an endpoint
+// outside the segment, an interval that is not applied or an empty slot - minus any tile's offset, like the
+// wrapped difference of an endpoint before the tile, lies far above the 70 KB of a tile: one unsigned minimum
+// with the lane's trash cell sends all of them there.
+constexpr uint32_t kNoCell = 0xfffffff8u;
+__device__ __forceinline__ uint32_t cell_bytes(int32_t step, int32_t seg_lo, int32_t seg_hi) {
+    return step >= seg_lo && step < seg_hi ? skew(static_cast<uint32_t>(step - seg_lo)) * 8u : kNoCell;
+}
 
 // LDS of one workgroup of the evaluation body.  A struct, so that a kernel that runs other phases in the
 // same workgroup can overlay it with theirs.
@@ -199,9 +209,9 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
     // ---- the plan's first R*threads intervals live in registers for the whole segment, R per
     // thread: (first step without the bytes, first step with them again, size).  An interval that cannot be applied, or a slot past the end of the list, gets
     // endpoints no tile contains.  [lo_t, hi_t] spans this thread's endpoints.
-    // e0/e1 hold the endpoints in the skewed cell numbering of the LDS tile (skew is monotone and
-    // additive over multiples of 32, so skew(e) - skew(tile_lo) is the cell inside the tile)
+    // e0/e1 hold the endpoints as byte offsets into the segment's skewed cells (see kNoCell)
     uint32_t e0[R], e1[R];
+    int64_t before = 0;   // (segments after the first) this thread's part of the plan's deltas before the segment
     typename SR::type sz[R];
     int32_t lo_t = INT32_MAX, hi_t = -1;
     if (!kBinned && k1 > k0) {   // block-uniform
@@ -234,20 +244,24 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
         for (int j = 0; j < R; ++j) {
             if (ti[j] < 0) {
                 sz[j] = 0;
-                e0[j] = UINT32_MAX;
-                e1[j] = UINT32_MAX;
+                e0[j] = kNoCell;
+                e1[j] = kNoCell;
             } else {
                 lo_t = vo[j] + 1 < lo_t ? vo[j] + 1 : lo_t;
                 hi_t = vr[j] > hi_t ? vr[j] : hi_t;
-                e0[j] = skew(static_cast<uint32_t>(vo[j] + 1));
-                e1[j] = skew(static_cast<uint32_t>(vr[j]));
+                e0[j] = cell_bytes(vo[j] + 1, seg_lo, seg_hi);
+                e1[j] = cell_bytes(vr[j], seg_lo, seg_hi);
+                if (seg_lo > 0) {   // (block-uniform)
+                    const int64_t s = SR::bytes(a, sz[j]);
+                    before += (vr[j] < seg_lo ? s : 0) - (vo[j] + 1 < seg_lo ? s : 0);
+                }
             }
         }
     } else {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            e0[j] = UINT32_MAX;
-            e1[j] = UINT32_MAX;
+            e0[j] = kNoCell;
+            e1[j] = kNoCell;
             sz[j] = 0;
         }
     }
@@ -259,14 +273,7 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
     // ---- footprint just before the segment: MF0 there plus the plan's deltas before it
     int64_t carry = 0;   // same value in every thread
     if (seg_lo > 0) {
-        int64_t c = 0;
-#pragma unroll
-        for (int j = 0; j < R; ++j) {
-            typename SR::type s32 = sz[j];
-            opaque(s32);
-            const int64_t s = SR::bytes(a, s32);
-            c += (e1[j] < skew(seg_lo) ? s : 0) - (e0[j] < skew(seg_lo) ? s : 0);
-        }
+        int64_t c = before;
         if constexpr (kTail) {
             for (int64_t k = k_over + tid; k < k1; k += kThr) {
                 const int32_t i = a.iv_tensor[k], o = a.iv_out[k], r = a.iv_in[k];
@@ -384,18 +391,23 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
         // of whose lanes holds an endpoint in the tile's range skips its registers
         const bool mine = hi_t >= tile_lo && lo_t < tile_hi;
         if (__builtin_amdgcn_ballot_w64(mine) != 0) {
-            const uint32_t base_cell = skew(static_cast<uint32_t>(tile_lo)), n_cell = skew(tile_n);
-            const uint32_t trash = kTileCells + lane;
+            // (three instructions per endpoint: subtract the tile's offset, a scalar; minimum with the trash cell;
+            // the atomic.  With cell numbers, a comparison against the tile's length and a shift: five, and the
+            // scatter was 40 % of the tile loop's vector instructions - 8 % of a peaks-only pass, nothing where the
+            // row stores set the pace)
+            const uint32_t tile_bytes = __builtin_amdgcn_readfirstlane(skew(static_cast<uint32_t>(tile_lo - seg_lo)) * 8u);
+            const uint32_t trash = (kTileCells + lane) * 8u;
+            char *const cells = reinterpret_cast<char *>(delta);
 #pragma unroll
             for (int j = 0; j < R; ++j) {
-                const uint32_t u0 = e0[j] - base_cell, u1 = e1[j] - base_cell;
+                const uint32_t u0 = e0[j] - tile_bytes, u1 = e1[j] - tile_bytes;
                 // keep the compact register form across tiles: without this the widened (and a
                 // negated) size is hoisted out of the tile loop and held in extra registers
                 typename SR::type s = sz[j];
                 opaque(s);
                 const int64_t bytes = SR::bytes(a, s);
-                lds_sub(&delta[u0 < n_cell ? u0 : trash], bytes);
-                lds_add(&delta[u1 < n_cell ? u1 : trash], bytes);
+                lds_sub(reinterpret_cast<int64_t *>(cells + (u0 < trash ? u0 : trash)), bytes);
+                lds_add(reinterpret_cast<int64_t *>(cells + (u1 < trash ? u1 : trash)), bytes);
             }
         }
         if constexpr (kTail) {

@@ -193,12 +193,14 @@ def test_eval_long_rows_take_nontemporal_stores_by_default():
 
 @pytest.mark.parametrize("threads,T,B,slots,tail", [(1024, 20011, 23, 3, False), (512, 12291, 40, 7, False), (1024, 4097, 9, 2, False),
                                                      (512, 7, 33, 4, False), (1024, 8192, 12, 5, False), (512, 20012, 21, 2, True),
-                                                     (1024, 50001, 11, 3, True), (512, 4096, 5, 8, False)])
+                                                     (1024, 50001, 11, 3, True), (512, 4096, 5, 8, False),
+                                                     (1024, 16384, 10, 3, False), (1024, 8193, 14, 4, True), (512, 8191, 17, 3, False)])
 def test_eval_persistent_grid(threads, T, B, slots, tail, tuning):
-    """The persistent kernel (several plans per workgroup, the next plan's intervals loaded during the
-    current plan's last tile) with a grid forced small: ragged and whole last tiles, one tile per row,
-    plans without intervals in the middle and at the end of a workgroup's walk, more workgroups than
-    plans, and (tail) plans too long for the registers, which it must leave to the tail kernel."""
+    """The persistent kernel (several plans per workgroup, the next plan's intervals requested during the
+    current plan's first tile and their sizes during its last) with a grid forced small: ragged and whole last
+    tiles, one, two and more tiles per row, plans without intervals in the middle and at the end of a workgroup's
+    walk, more workgroups than plans, and (tail) plans too long for the registers, which it must leave to the
+    tail kernel."""
     tuning("eval_threads", threads)
     tuning("eval_persistent", 1)
     tuning("eval_segments", 1)
