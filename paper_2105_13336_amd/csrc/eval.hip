@@ -88,6 +88,7 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     __shared__ int64_t wave_tot[kWaves];
     __shared__ int64_t red_mx[kWaves], red_mn[kWaves];
     __shared__ int32_t red_arg[kWaves];
+    __shared__ int64_t ahead_off[2][2];   // where the list of the plan after the next starts and ends (see the plan loop)
     typedef SizeReg<kNarrow> SR;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -242,6 +243,8 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     int32_t prev_lo = 0, prev_hi = 0;
     int64_t done_plan = -1;      // the plan whose per-wavefront results wait in red_*
     int64_t nk0 = 0, nk1 = 0;    // the next plan's list
+    int64_t ahead = a.B;         // the plan after the next (a.B: none), whose offsets the first wavefront fetches
+    int ahead_slot = 0;          // ... into ahead_off[ahead_slot]
     __syncthreads();
 
     // Every path through a tile issues the same memory instructions, so that the waits for its loads
@@ -356,6 +359,18 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         }
         // (a row of one tile: the next plan's intervals as soon as this plan's have been scattered)
         if constexpr (kLast && kFirst) load_list(L, nk0, nk1);
+        // The offsets of the plan after the next come through the scalar unit, whose loads every wait for an LDS
+        // operation waits for as well: the first wavefront, which is the one with time to spare before this barrier,
+        // fetches them for all.
+        if constexpr (kFirst) {
+            if (L.wave_u == 0 && ahead < a.B) {
+                const int64_t c0 = plan_offsets[ahead], c1 = plan_offsets[ahead + 1];
+                if (L.lane == 0) {
+                    ahead_off[ahead_slot][0] = c0;
+                    ahead_off[ahead_slot][1] = c1;
+                }
+            }
+        }
         store_part(L, 1, prev_full);
         __syncthreads();
         if constexpr (kFirst) {
@@ -465,11 +480,10 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         prev_hi = tile_hi;
     };
 
+    int64_t next = next_mine(plan + stride);
+    if (next < a.B) list_of(next, nk0, nk1);
     for (;;) {
-        const int64_t next = next_mine(plan + stride);
-        nk0 = 0;
-        nk1 = 0;
-        if (next < a.B) list_of(next, nk0, nk1);
+        ahead = next < a.B && next + stride < a.B ? next + stride : a.B;
         row = kStore ? a.resident + plan * a.T : nullptr;
         carry = 0;
         best = Best{INT64_MIN, INT64_MAX, INT32_MAX};
@@ -497,6 +511,27 @@ __global__ __launch_bounds__(kThr) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         if (next >= a.B) break;
         take_list();
         plan = next;
+        // the plan after it: the one whose offsets were fetched during the first tile (the last barrier lies
+        // between that write and this read, and the slots alternate, so the first wavefront's write for the plan
+        // after cannot overtake a wavefront that still reads here), unless it is left to the tail kernel
+        next = a.B;
+        nk0 = 0;
+        nk1 = 0;
+        if (ahead < a.B) {
+            int64_t c0 = uniform(ahead_off[ahead_slot][0]), c1 = uniform(ahead_off[ahead_slot][1]);
+            if (c0 < 0) c0 = 0;
+            if (c1 > a.n_intervals) c1 = a.n_intervals;
+            if (c1 < c0) c1 = c0;
+            if (c1 - c0 <= a.tail_threshold) {
+                next = ahead;
+                nk0 = c0;
+                nk1 = c1;
+            } else {
+                next = next_mine(ahead);
+                if (next < a.B) list_of(next, nk0, nk1);
+            }
+        }
+        ahead_slot ^= 1;
     }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -1200,10 +1235,11 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
     const bool pers_ok = S == 1 && !binned && a.N > 0 && a.T <= (1 << 28) && cap != kCapTail;
     // Without rows: batches of at least four plans per CU (where the host has not chosen two small workgroups per
     // CU, which are ahead there).  With rows, in the large geometry: the same batches when a row has at least three
-    // tiles - the next plan's lists are then requested most of a row ahead (50,000-step rows, 5,400 intervals per
-    // plan: 16,384 plans 1.66 -> 1.55 ms, 4,096 plans 0.423 -> 0.401, 512 plans 0.051 -> 0.052).
-    bool persistent = pers_ok && a.B >= 4 * static_cast<int64_t>(tas->num_cus) &&
-                      (out == 0 || (threads == 1024 && out != 3 && n_tiles >= 3));
+    // tiles, from three plans per CU - the next plan's lists are then requested most of a row ahead (50,000-step
+    // rows, 5,400 intervals per plan: 16,384 plans 1.66 -> 1.52 ms, 4,096 plans 0.423 -> 0.391, 768 plans 87 -> 78 us,
+    // 512 plans 53 -> 55 us).
+    const int64_t per_cu = a.B / tas->num_cus;
+    bool persistent = pers_ok && ((out == 0 && per_cu >= 4) || (out != 0 && out != 3 && threads == 1024 && n_tiles >= 3 && per_cu >= 3));
     const int pers_forced = g_tuning.eval_persistent;   // tuning knob: 0 = never, 1 = whenever possible
     if (pers_forced == 0) persistent = false;
     if (pers_forced == 1) persistent = pers_ok;
