@@ -150,6 +150,7 @@ __device__ __forceinline__ bool applies(const EvalArgs &a, int32_t i, int32_t o,
 // through the scalar unit: the tile loop then issues a fixed set of memory instructions like the common
 // kernel's, instead of waiting for two dependent loads (and with them for every store) in every tile.
 constexpr int kBinFastRecs = 2;
+constexpr int kBinAhead = 4;   // tiles between the request for a tile's records and their use
 // result (may be null): an LDS word triple that receives the segment's (max, earliest argmax, min) as well; it
 // is complete after the next workgroup barrier.
 template <int kThr, int R, bool kTail, bool kNarrow, int kOut, bool kBinned = false, bool kBinFast = false>
@@ -304,15 +305,21 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
         kBinFast ? (const_i32_ptr)(a.tile_off + static_cast<int64_t>(plan) * (a.n_tiles + 1)) : nullptr;
     const uint32_t n_rec = static_cast<uint32_t>(2 * (k1 - k0));
     const int2 *plan_recs = (kBinFast && n_rec) ? a.recs + 2 * k0 : a.recs;
-    auto rec_at = [&](uint32_t k) { return plan_recs[k < n_rec ? k : (n_rec ? n_rec - 1 : 0)]; };
-    // Two register sets, for the even and the odd tiles of the segment.  A set is used in its tile's scatter and
-    // requested again, for the tile after the next, at the END of that tile: a request then has two tiles' time to
-    // come back from HBM, and the wavefronts reach that point spread out in time (they leave the tile's last
-    // barrier together but drain their stores one after the other), so their requests do not arrive in one
-    // burst on the CU's queue of outstanding misses, behind which the stores of all wavefronts would wait.
-    int2 rec_set[2][kBinFastRecs];
+    // (a record travels as ONE 64-bit value, cell and sign in the lower half, size units in the upper: as a pair of
+    // 32-bit values the two halves become loop-carried values of their own, the register allocator gives one of
+    // them a register that is not the load's, and the copy it inserts right after the request waits for the
+    // records - and with them for every store before them - at the end of every tile)
+    auto rec_at = [&](uint32_t k) { return reinterpret_cast<const uint64_t *>(plan_recs)[k < n_rec ? k : (n_rec ? n_rec - 1 : 0)]; };
+    // kBinAhead register sets, taken in turn by the tiles of the segment.  A set is used in its tile's scatter and
+    // requested again, for the tile kBinAhead tiles on, at the END of that tile: a request then has that many
+    // tiles' time to come back from HBM (behind the CU's queue of row stores two tiles were not enough: the wait
+    // for them still took a third of a tile), and the wavefronts reach that point spread out in time (they
+    // leave the tile's last barrier together but drain their stores one after the other), so their requests do
+    // not arrive in one burst on the CU's queue of outstanding misses, behind which the stores of all wavefronts
+    // would wait.
+    uint64_t rec_set[kBinAhead][kBinFastRecs];
     auto off_at = [&](int32_t tile_index) { return tile_off[tile_index < a.n_tiles ? tile_index : a.n_tiles]; };
-    auto load_recs = [&](int32_t lo, int32_t hi, int2 (&dst)[kBinFastRecs]) {   // the records [lo, hi) of one tile
+    auto load_recs = [&](int32_t lo, int32_t hi, uint64_t (&dst)[kBinFastRecs]) {   // the records [lo, hi) of one tile
 #pragma unroll
         for (int j = 0; j < kBinFastRecs; ++j) {
             // (a slot past the tile's last record reads what slot j - 1 reads: a line that is on its way already)
@@ -320,16 +327,15 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
             dst[j] = rec_at(static_cast<uint32_t>(j > 0 && k >= hi ? k - kThr : k));
         }
     };
-    // (uniform) where the records of this tile, the next and the one after it start; a tile reads one more offset
-    // at its top, through the scalar unit, and needs it at its end
-    int32_t off0 = 0, off1 = 0, off2 = 0, off3 = 0;
+    // (uniform) where the records of this tile and of the kBinAhead tiles after it start; a tile reads one more
+    // offset at its top, through the scalar unit, and needs it at its end
+    int32_t offs[kBinAhead + 1] = {}, off_new = 0;
     if constexpr (kBinFast) {
         const int32_t t0 = seg_lo / kTile;
-        off0 = off_at(t0);
-        off1 = off_at(t0 + 1);
-        off2 = off_at(t0 + 2);
-        load_recs(off0, off1, rec_set[0]);
-        load_recs(off1, off2, rec_set[1]);
+#pragma unroll
+        for (int d = 0; d <= kBinAhead; ++d) offs[d] = off_at(t0 + d);
+#pragma unroll
+        for (int d = 0; d < kBinAhead; ++d) load_recs(offs[d], offs[d + 1], rec_set[d]);
     }
     __syncthreads();   // the first tile's cells are in place
 
@@ -378,8 +384,8 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
 #pragma unroll
         for (int j = 0; j < kVpt / 2; ++j)
             fill[j] = *reinterpret_cast<const ll2 *>(a.dMF0 + tile_lo + kTile + fill_at + 128 * j);
-        const int32_t rec_lo = off0, rec_hi = off1;   // this tile's records within the plan's
-        if constexpr (kBinFast) off3 = off_at(tile_lo / kTile + 3);
+        const int32_t rec_lo = offs[0], rec_hi = offs[1];   // this tile's records within the plan's
+        if constexpr (kBinFast) off_new = off_at(tile_lo / kTile + kBinAhead + 1);
         constexpr bool kPrev = !kFirst && kStore;
         if constexpr (kPrev) {
             __builtin_amdgcn_wave_barrier();
@@ -441,10 +447,11 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
             const uint32_t trash = kTileCells + lane;
 #pragma unroll
             for (int j = 0; j < kBinFastRecs; ++j) {
-                const int2 rec = rec_set[kSet][j];
+                const uint64_t rec = rec_set[kSet][j];
+                const int32_t rec_x = static_cast<int32_t>(static_cast<uint32_t>(rec));
                 const bool valid = rec_lo + j * kThr + tid < rec_hi;
-                const int64_t bytes = static_cast<int64_t>(static_cast<uint64_t>(static_cast<uint32_t>(rec.y)) << a.size_shift);
-                lds_add(&delta[valid ? static_cast<uint32_t>(rec.x) & 0x7fffffffu : trash], !valid ? 0 : rec.x < 0 ? -bytes : bytes);
+                const int64_t bytes = static_cast<int64_t>((rec >> 32) << a.size_shift);
+                lds_add(&delta[valid ? static_cast<uint32_t>(rec_x) & 0x7fffffffu : trash], !valid ? 0 : rec_x < 0 ? -bytes : bytes);
             }
         } else if constexpr (kBinned) {
             const int32_t *off = a.tile_off + static_cast<int64_t>(plan) * (a.n_tiles + 1) + tile_lo / kTile;
@@ -567,16 +574,28 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
         }
         EVAL_MARK(5);
         if constexpr (kBinFast) {
-            load_recs(off2, off3, rec_set[kSet]);
-            off0 = off1;
-            off1 = off2;
-            off2 = off3;
+            load_recs(offs[kBinAhead], off_new, rec_set[kSet]);
+            // With rows the wavefront now waits for everything it has in flight, these records included (s_waitcnt
+            // vmcnt(0): bits 3:0 and 15:14 of the operand; the other counters at their maxima).  Measured on rows of
+            // 10^6 steps, 60,000 intervals per plan: 2.61 ms; without the wait 3.14 ms, with a wait that leaves just
+            // the records in flight 3.15, with the wait before the request 3.17, with the request after the scatter
+            // and the wait here 3.02.  A request that is still on its way to HBM while the CU's wavefronts issue row
+            // stores holds those stores up; made last in the tile and waited for, it has the queue to itself (the
+            // wavefronts get here one after the other).  Without rows nothing is held up, and the requests run
+            // kBinAhead tiles ahead (1.43 -> 1.28 ms).
+            if constexpr (kStore) __builtin_amdgcn_s_waitcnt(0x0f70);
+#pragma unroll
+            for (int d = 0; d < kBinAhead; ++d) offs[d] = offs[d + 1];
+            offs[kBinAhead] = off_new;
         }
         EVAL_MARK(6);
     };
 
     typedef std::integral_constant<int, 0> Set0;
     typedef std::integral_constant<int, 1> Set1;
+    typedef std::integral_constant<int, 2> Set2;
+    typedef std::integral_constant<int, 3> Set3;
+    static_assert(kBinAhead == 4, "the tile loop below names the register sets");
     do_tile(seg_lo, std::true_type{}, Set0{});
     int32_t last_lo = seg_lo;
     if constexpr (kBinFast) {
@@ -588,13 +607,30 @@ __device__ __forceinline__ void eval_body(const EvalArgs &a, const int32_t plan,
         if (seg_lo + kTile < seg_hi) {
             do_tile(seg_lo + kTile, std::false_type{}, Set1{});
             last_lo = seg_lo + kTile;
-            for (int32_t tile_lo = seg_lo + 2 * kTile; tile_lo < seg_hi; tile_lo += kTile) {
-                do_tile(tile_lo, std::false_type{}, Set0{});
+            // Whole groups of kBinAhead tiles in the loop, the rest after it: a way out of the middle of the loop's
+            // body would give the compiler a path from the end of one tile straight back to the top of the loop
+            // (never taken, but it counts the operations issued after a request on the shortest path), and the wait
+            // for a tile's records would again include the stores of the tile before.
+            const std::false_type later{};
+            int32_t tile_lo = seg_lo + 2 * kTile;
+            for (; tile_lo + 3 * kTile < seg_hi; tile_lo += 4 * kTile) {
+                do_tile(tile_lo, later, Set2{});
+                do_tile(tile_lo + kTile, later, Set3{});
+                do_tile(tile_lo + 2 * kTile, later, Set0{});
+                do_tile(tile_lo + 3 * kTile, later, Set1{});
+            }
+            last_lo = tile_lo - kTile;
+            if (tile_lo < seg_hi) {
+                do_tile(tile_lo, later, Set2{});
                 last_lo = tile_lo;
-                tile_lo += kTile;
-                if (tile_lo >= seg_hi) break;
-                do_tile(tile_lo, std::false_type{}, Set1{});
-                last_lo = tile_lo;
+                if (tile_lo + kTile < seg_hi) {
+                    do_tile(tile_lo + kTile, later, Set3{});
+                    last_lo = tile_lo + kTile;
+                    if (tile_lo + 2 * kTile < seg_hi) {
+                        do_tile(tile_lo + 2 * kTile, later, Set0{});
+                        last_lo = tile_lo + 2 * kTile;
+                    }
+                }
             }
         }
     } else {
