@@ -23,7 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-TRAFFIC_FILES = {"eval": os.path.join(ROOT, "profiles", "eval_kernel_c3_hbm_traffic.txt"),
+TRAFFIC_FILES = {"eval": os.path.join(ROOT, "profiles", "eval_stream_kernel_c3_hbm_traffic.txt"),
                  "score": os.path.join(ROOT, "profiles", "score_kernel_c3_hbm_traffic.txt"),
                  "step": os.path.join(ROOT, "profiles", "step_kernel_c3_hbm_traffic.txt")}
 KERNEL_SOURCES = ("eval.hip", "eval_body.h", "score.hip", "score_body.h", "step.hip", "common.h", "wave_ops.h")
@@ -223,7 +223,7 @@ def main() -> int:
         "dtype": "int64", "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg.name}", "B": B, "T": T, "N": N, "intervals": K,
                    "step": "eval_plans" if args.eval_only else "eval_plans+score_candidates"},
-        "roofline": {"kernel": "eval_kernel (tensile_eval_plans)", "bound": "hbm", "achieved": achieved,
+        "roofline": {"kernel": "eval_stream_kernel (tensile_eval_plans)" if args.config == 3 else "evaluation kernel (tensile_eval_plans)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": eval_traffic,
                      "traffic_note": eval_note, "algorithmic_bytes": eval_bytes, "avg_launch_ms": eval_avg},
         # the longest kernel of the step has its own block
