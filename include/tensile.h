@@ -352,6 +352,8 @@ int tensile_greedy_plan(const tensile_tas *tas, int64_t budget_bytes, const tens
  * while no call is in flight.  The library never reads the environment.
  *   "eval_threads"    256 / 512 / 1024: workgroup geometry of the evaluation kernel (0 = automatic)
  *   "eval_segments"   segments per plan (0 = automatic)
+ *   "eval_seg_steps"  most steps a segment may hold: rows longer than this are cut, whatever else was chosen
+ *                     (0 = 2^28, the kernels' limit; a smaller value only serves to exercise the rule)
  *   "eval_binned"     0 never sort a batch's endpoints by tile first, 1 whenever possible (-1 = automatic)
  *   "eval_persistent" 0 never use the persistent grid, 1 whenever possible (-1 = automatic)
  *   "eval_slots"      size of the persistent grid (0 = automatic)

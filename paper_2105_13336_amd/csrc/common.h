@@ -141,6 +141,7 @@ struct Tuning {
     int eval_binned = -1;      // 0 never bin, 1 bin whenever possible
     int eval_threads = 0;      // 256 / 512 / 1024
     int eval_segments = 0;     // segments per plan
+    int eval_seg_steps = 0;    // most steps a segment may hold (0: 2^28, what the kernels' 32-bit cell offsets allow)
     int eval_persistent = -1;  // 0 never, 1 whenever possible
     int eval_slots = 0;        // size of the persistent grid
     int eval_nt = -1;          // footprint rows written with nontemporal stores: 0 never, 1 always, -1 by row length

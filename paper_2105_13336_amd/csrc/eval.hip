@@ -1155,7 +1155,11 @@ int launch_eval(const tensile_tas *tas, Workspace &ws, const EvalArgs &proto, in
     if (S < 1) S = 1;
     // (the kernels keep an interval's endpoints as 32-bit byte offsets into the segment's cells: at most 2^28 steps
     // and a tile per segment)
-    if (S < ((static_cast<int64_t>(a.T) + (1 << 28) - 1) >> 28)) S = (static_cast<int64_t>(a.T) + (1 << 28) - 1) >> 28;
+    {
+        const int64_t most = g_tuning.eval_seg_steps > 0 && g_tuning.eval_seg_steps < (1 << 28) ? g_tuning.eval_seg_steps : (1 << 28);
+        const int64_t s_min = (static_cast<int64_t>(a.T) + most - 1) / most;
+        if (S < s_min) S = s_min;
+    }
     if (S > n_tiles) S = n_tiles;
     const int64_t tps = (n_tiles + S - 1) / S;
     S = (n_tiles + tps - 1) / tps;

@@ -94,6 +94,7 @@ extern "C" int tensile_tuning_set(const char *knob, int value) {
         {"eval_r", &Tuning::eval_r},           {"eval_binned", &Tuning::eval_binned},
         {"eval_threads", &Tuning::eval_threads}, {"eval_segments", &Tuning::eval_segments},
         {"eval_persistent", &Tuning::eval_persistent}, {"eval_slots", &Tuning::eval_slots}, {"eval_nt", &Tuning::eval_nt},
+        {"eval_seg_steps", &Tuning::eval_seg_steps},
         {"score_blocks", &Tuning::score_blocks}, {"link_packed", &Tuning::link_packed},
         {"step_fused", &Tuning::step_fused},
     };

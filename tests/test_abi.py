@@ -105,7 +105,7 @@ def test_null_arguments_are_errors_not_crashes(lib):
 def test_tuning_knobs(lib):
     lib.tensile_tuning_set.argtypes = [ctypes.c_char_p, ctypes.c_int]
     for name in (b"eval_threads", b"eval_segments", b"eval_binned", b"eval_persistent", b"eval_slots", b"eval_r",
-                 b"score_blocks", b"link_packed", b"step_fused", b"eval_nt"):
+                 b"score_blocks", b"link_packed", b"step_fused", b"eval_nt", b"eval_seg_steps"):
         assert lib.tensile_tuning_set(name, 1) == 0
     assert lib.tensile_tuning_set(b"no_such_knob", 1) == -1 and lib.tensile_tuning_set(None, 1) == -1
     lib.tensile_tuning_reset.restype = None

@@ -132,10 +132,28 @@ def test_eval_geometries_and_binning(threads, binned, T, segs, tuning):
     check_eval(tas, pl, label=f"threads={threads} binned={binned}")
 
 
+@pytest.mark.parametrize("threads,binned,persistent,most,T", [(1024, 0, 0, 9000, 50001), (512, 0, 0, 5000, 20011),
+                                                               (1024, 1, 0, 17000, 50001), (1024, 0, 1, 30000, 29999),
+                                                               (256, 0, 0, 2048, 12291)])
+def test_eval_rows_cut_by_the_segment_limit(threads, binned, persistent, most, T, tuning):
+    """The kernels keep endpoints as 32-bit byte offsets into a segment's cells, so the host cuts rows into segments of
+    at most 2^28 steps whatever else it chose; here the limit is lowered (tuning knob) so that the rule, and endpoints
+    before, inside, at the edge of and after a segment, are exercised on rows a test can hold.  Where a persistent
+    grid is asked for, the cut wins (that grid takes whole rows only)."""
+    tuning("eval_threads", threads)
+    tuning("eval_binned", binned)
+    tuning("eval_persistent", persistent)
+    tuning("eval_seg_steps", most)
+    tas = small_random_tas(2300 + T, N=min(400, T // 2), T=T, max_acc=4, base_bytes=17)
+    pl = make_plans(tas, 7, 11, p_swap=0.7)
+    say(f"eval segment limit: threads={threads} binned={binned} persistent={persistent} most={most} T={T}")
+    check_eval(tas, pl, label=f"segment limit {most}")
+
+
 @pytest.mark.parametrize("threads,T,segs", [(512, 4097, 0), (1024, 20011, 2), (1024, 8192, 0)])
 def test_eval_binned_tiles_with_many_records(threads, T, segs, tuning):
-    """The binned path takes a tile's records two per thread, one tile ahead; plans with a tile that holds
-    more go through its general form.  One batch with plans of both kinds, with empty plans, and with every
+    """The binned path takes a tile's records two per thread, requested ahead of the tile; plans with a tile that
+    holds more go through its general form.  One batch with plans of both kinds, with empty plans, and with every
     endpoint of a plan in one tile."""
     tuning("eval_threads", threads)
     tuning("eval_binned", 1)
