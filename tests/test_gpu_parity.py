@@ -117,7 +117,12 @@ def test_eval_shapes_and_segments(T, B, segs, tuning):
 @pytest.mark.parametrize("threads,binned,T,segs", [(512, 0, 20011, 0), (1024, 0, 4097, 0), (512, 1, 12291, 0),
                                                     (1024, 1, 20011, 2), (512, 1, 7, 0), (1024, 1, 50001, 3),
                                                     (256, 0, 20011, 0), (256, 0, 4097, 2), (256, 0, 2048, 0), (256, 0, 7, 0),
-                                                    (256, 0, 12291, 4)])
+                                                    (256, 0, 12291, 4),
+                                                    # binned rows of 4 ... 10 tiles: the tile loop takes groups of four
+                                                    # and then the rest, so every remainder, with and without a group
+                                                    (1024, 1, 24581, 0), (1024, 1, 32868, 0), (1024, 1, 40961, 0),
+                                                    (1024, 1, 57347, 0), (1024, 1, 65545, 0), (1024, 1, 73730, 0),
+                                                    (512, 1, 40962, 0), (512, 1, 36865, 2)])
 def test_eval_geometries_and_binning(threads, binned, T, segs, tuning):
     """The workgroup geometries on rows they would not get by default, and the binned path (endpoints
     sorted by tile first) on short and ragged rows, with and without several segments per plan."""
